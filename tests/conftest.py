@@ -1,0 +1,30 @@
+import os
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (runs the HIP library)")
+
+
+@pytest.fixture(scope="session")
+def tiny():
+    """Tiny workload: vectors, queries and an oracle-built index."""
+    from workloads import CONFIGS, tiny_mixture
+    from oracle import pqt_build
+    cfg = CONFIGS["tiny"]
+    X = tiny_mixture(cfg.N, d=cfg.D, seed=cfg.data_seed)
+    Y = tiny_mixture(cfg.nq, d=cfg.D, seed=cfg.query_seed)
+    ix = pqt_build.build_index(X, cfg.P, cfg.k1, cfg.k2, cfg.M, H=cfg.H, T=cfg.T, C=cfg.C)
+    return cfg, X, Y, ix
+
+
+@pytest.fixture(scope="session")
+def rng():
+    return np.random.default_rng(12345)

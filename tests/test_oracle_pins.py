@@ -1,0 +1,302 @@
+"""Pins for the CPU oracle: every check compares it with something other than itself --
+brute force (Eq. 1), closed forms, hand-computed fixtures, library routines, invariants."""
+import os
+
+import numpy as np
+import pytest
+from scipy.spatial.distance import cdist
+
+from oracle import pqt_build as B
+from oracle import pqt_index_io as IO
+from oracle import pqt_query as Q
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---- P1: exhaustive visit + exact re-ranking reproduces brute force (Eq. 1) ----------------
+def test_exhaustive_exact_rerank_equals_brute_force(tiny):
+    cfg, X, Y, ix = tiny
+    for q in range(8):
+        tr = Q.query(ix, Y[q], k=10, w=cfg.k1, T=ix.K, C=cfg.N, X=X, exact_rerank=True)
+        # textbook routine, not the oracle's own brute force
+        d = cdist(Y[q:q + 1].astype(np.float64), X.astype(np.float64), "sqeuclidean")[0]
+        want = np.lexsort((np.arange(cfg.N), d))[:10]
+        assert np.array_equal(tr.out_ids, want)
+        np.testing.assert_allclose(tr.out_dists, d[want], rtol=1e-12)
+        ids, dd = Q.brute_force(Y[q], X, 10)
+        assert np.array_equal(ids, want)
+        np.testing.assert_allclose(dd, d[want], rtol=1e-12)
+
+
+# ---- P2: bins are a partition of the database; every id sits in slot m(x) -------------------
+def test_bins_partition_the_database(tiny):
+    cfg, X, Y, ix = tiny
+    tr = Q.query(ix, Y[3], k=10, w=cfg.k1, T=ix.K, C=cfg.N)
+    assert np.array_equal(np.sort(tr.cand_ids), np.arange(cfg.N))
+    off = ix.offsets.astype(np.int64)
+    assert off[0] == 0 and off[-1] == cfg.N and np.all(np.diff(off) >= 0)
+    slot_of_pos = np.repeat(np.arange(ix.H), np.diff(off))
+    hist = np.bincount(slot_of_pos, minlength=ix.H)
+    assert np.array_equal(np.cumsum(hist), off[1:])          # pointer array = prefix sum (Sec. 4)
+    for t in range(0, cfg.N, 97):
+        assert slot_of_pos[t] == B.bin_slot(X[ix.ids[t]], ix.C1, ix.C2, ix.H)
+    for s in np.nonzero(hist > 1)[0][:50]:
+        run = ix.ids[off[s]:off[s + 1]]
+        assert np.all(np.diff(run.astype(np.int64)) > 0)     # ids ascending inside a slot
+
+
+def test_leaf_is_nearest_child_of_nearest_cell(tiny):
+    """m(x) by a library routine: per part, argmin over level-1 then over that cell's children."""
+    cfg, X, Y, ix = tiny
+    dp = cfg.D // cfg.P
+    for n in range(0, 200, 7):
+        leaf = B.leaf_of(X[n], ix.C1, ix.C2)
+        for p in range(cfg.P):
+            xp = X[n:n + 1, p * dp:(p + 1) * dp].astype(np.float64)
+            i = int(np.argmin(cdist(xp, ix.C1[p].astype(np.float64), "sqeuclidean")[0]))
+            j = int(np.argmin(cdist(xp, ix.C2[p, i].astype(np.float64), "sqeuclidean")[0]))
+            assert leaf[p] == i * cfg.k2 + j
+
+
+# ---- P3: Eq. 9 is the exact distance to the reconstructed (line-quantised) vector -----------
+def test_adc_score_equals_distance_to_reconstruction(tiny):
+    cfg, X, Y, ix = tiny
+    cc64 = B.pair_table(ix.C1, ix.M)
+    for q in range(5):
+        a = Q.level1_subpart_distances(Y[q], ix.C1, ix.M)
+        lut = Q.build_lut(a, ix.tbl_i, ix.tbl_j, ix.tbl_lam, cc64)
+        pos = np.arange(q, cfg.N, 211)
+        s = Q.score_codes(lut, ix.codes[pos])
+        for t, ps in enumerate(pos):
+            xr = Q.reconstruct(ix, ix.codes[ps])
+            want = float(np.sum((Y[q].astype(np.float64) - xr) ** 2))
+            assert abs(s[t] - want) <= 1e-9 * max(want, 1e-30)
+
+
+def test_codes_are_nearest_code_points(tiny):
+    cfg, X, Y, ix = tiny
+    ds = cfg.D // cfg.M
+    for t in range(0, cfg.N, 503):
+        x = X[ix.ids[t]].astype(np.float64)
+        assert np.array_equal(ix.codes[t], B.encode_vector(X[ix.ids[t]], ix.C1, ix.M, ix.tbl_i, ix.tbl_j, ix.tbl_lam))
+        for m in range(cfg.M):
+            # brute force over explicit reconstructions of all 256 code points
+            best, bestc = np.inf, -1
+            for c in range(256):
+                code = ix.codes[t].copy()
+                code[m] = c
+                xr = Q.reconstruct(ix, code)[m * ds:(m + 1) * ds]
+                e = float(np.sum((x[m * ds:(m + 1) * ds] - xr) ** 2))
+                if e < best:
+                    best, bestc = e, c
+            assert bestc == ix.codes[t, m]
+
+
+# ---- P4: Eq. 9 special cases and hand-computed triangle -------------------------------------
+def test_eq9_hand_computed_triangle():
+    rows = np.loadtxt(os.path.join(GOLD, "eq9_triangle.txt"))
+    for lam, b2, a2, c2, h2 in rows:
+        a = np.array([[b2, a2]])
+        cc = np.array([[[0.0, c2], [c2, 0.0]]])
+        lut = Q.build_lut(a, np.array([[0]], np.uint8), np.array([[1]], np.uint8),
+                          np.array([[lam]], np.float32), cc)
+        assert lut[0, 0] == pytest.approx(h2, rel=1e-12)
+
+
+def test_eq9_closed_forms(rng):
+    for _ in range(20):
+        ci, cj, y = rng.normal(size=(3, 6))
+        b2, a2, c2 = np.sum((y - ci) ** 2), np.sum((y - cj) ** 2), np.sum((ci - cj) ** 2)
+        a = np.array([[b2, a2]])
+        cc = np.array([[[0.0, c2], [c2, 0.0]]])
+        ti, tj = np.zeros((1, 3), np.uint8), np.ones((1, 3), np.uint8)
+        lut = Q.build_lut(a, ti, tj, np.array([[0.0, 1.0, 0.5]], np.float32), cc)
+        assert lut[0, 0] == pytest.approx(b2, rel=1e-12)                      # lambda = 0: the c_i end
+        assert lut[0, 1] == pytest.approx(a2, rel=1e-12)                      # lambda = 1: the c_j end
+        assert lut[0, 2] == pytest.approx((a2 + b2) / 2 - c2 / 4, rel=1e-12)  # median of a triangle
+        # swapping the roles of i and j must NOT give the same value for lambda != 1/2
+        lam = np.float32(0.3)
+        l_ij = Q.build_lut(a, ti[:, :1], tj[:, :1], np.array([[lam]], np.float32), cc)[0, 0]
+        want = np.sum((y - ((1 - float(lam)) * ci + float(lam) * cj)) ** 2)
+        assert l_ij == pytest.approx(want, rel=1e-10)
+
+
+def test_line_projection_is_orthogonal(rng):
+    for _ in range(10):
+        ci, cj, x = rng.normal(size=(3, 5))
+        lam, err = B.line_projection(x, ci, cj)
+        proj = (1 - lam) * ci + lam * cj
+        assert abs(np.dot(x - proj, cj - ci)) < 1e-12
+        assert err == pytest.approx(np.sum((x - proj) ** 2))
+        # Pythagoras on the right triangle (x, proj, ci)
+        assert err == pytest.approx(np.sum((x - ci) ** 2) - lam ** 2 * np.sum((cj - ci) ** 2), abs=1e-10)
+
+
+# ---- P5: bin order ---------------------------------------------------------------------------
+def _sorted_lists(rng, P, R, integer):
+    if integer:
+        return [np.sort(rng.integers(0, 12, size=R)).astype(np.float32) for _ in range(P)]
+    return [np.sort(rng.random(R)).astype(np.float32) for _ in range(P)]
+
+
+@pytest.mark.parametrize("integer", [False, True])
+def test_bin_order_fullsort_equals_priority_queue(rng, integer):
+    for R in (1, 5, 16):
+        L = _sorted_lists(rng, 2, R, integer)
+        for T in (1, 7, R * R, R * R + 5):
+            t1, k1_ = Q.bin_order(L, T, "fullsort")
+            t2, k2_ = Q.bin_order(L, T, "pq")
+            assert np.array_equal(t1, t2) and np.array_equal(k1_, k2_)
+            assert t1.shape[0] == min(T, R * R)
+            assert tuple(t1[0]) == (0, 0)
+            assert np.all(np.diff(k1_) >= 0)
+            # brute-force definition: python sort of (fl32 sum, r1, r2)
+            ref = sorted((np.float32(L[0][a] + L[1][b]), a, b) for a in range(R) for b in range(R))[:T]
+            assert [tuple(x) for x in t1] == [(a, b) for _, a, b in ref]
+
+
+@pytest.mark.parametrize("integer", [False, True])
+def test_bin_order_four_parts_truncation_is_exact(rng, integer):
+    L = _sorted_lists(rng, 4, 6, integer)
+    for T in (1, 10, 100, 6 ** 4):
+        full, kf = Q.bin_order(L, T, "fullsort", truncate_pairs=False)
+        trunc, kt = Q.bin_order(L, T, "fullsort", truncate_pairs=True)
+        pq, kp = Q.bin_order(L, T, "pq", truncate_pairs=True)
+        assert np.array_equal(full, trunc) and np.array_equal(full, pq)
+        assert np.array_equal(kf, kt) and np.array_equal(kf, kp)
+        assert tuple(full[0]) == (0, 0, 0, 0) and np.all(np.diff(kf) >= 0)
+
+
+def test_bin_order_on_tiny_lists(tiny):
+    cfg, X, Y, ix = tiny
+    for q in range(10):
+        tr = Q.query(ix, Y[q], cfg.k, cfg.w, order_method="pq")
+        tr2 = Q.query(ix, Y[q], cfg.k, cfg.w, order_method="fullsort")
+        assert np.array_equal(tr.tuples, tr2.tuples) and np.array_equal(tr.out_ids, tr2.out_ids)
+        # the first proposed bin is the combination of the per-part best leaves (Sec. 3.2)
+        assert [tr.Lid[p][0] for p in range(cfg.P)] == [tr.Lid[p][tr.tuples[0, p]] for p in range(cfg.P)]
+
+
+# ---- P6: counts printed in the paper ----------------------------------------------------------
+def test_distance_evaluation_counts_and_bin_count():
+    rows = np.loadtxt(os.path.join(GOLD, "paper_counts.txt"), dtype=np.int64)
+    for k1, k2, w, P, evals, bins in rows:
+        if k1 > 64:      # closed form only (building an 8192-centroid tree is not needed)
+            assert k1 + w * k2 == evals and (k1 * k2) ** P == bins
+            continue
+        rng = np.random.default_rng(1)
+        dp = 3
+        C1 = rng.normal(size=(P, k1, dp)).astype(np.float32)
+        C2 = rng.normal(size=(P, k1, k2, dp)).astype(np.float32)
+        y = rng.normal(size=P * dp)
+        a = Q.level1_subpart_distances(y, C1, P)
+        sel = Q.select_clusters(Q.part_distances(a, P), w)
+        d2, ids2 = Q.level2_distances(y, C2, sel)
+        assert a.shape[1] + d2.shape[1] == evals          # per part: k1 + w*k2
+        ix = Q.PQTIndex(D=P * dp, P=P, k1=k1, k2=k2, M=P, N=0, H=1, T=1, C=1, C1=C1, C2=C2,
+                        tbl_i=None, tbl_j=None, tbl_lam=None, cc=None, offsets=None, ids=None, codes=None)
+        assert ix.K == bins
+        assert len(set(ids2[0].tolist())) == w * k2 and ids2.max() < k1 * k2
+
+
+# ---- P7: elementary steps against library routines ---------------------------------------------
+def test_level1_distances_match_cdist(tiny):
+    cfg, X, Y, ix = tiny
+    ds, dp = cfg.D // cfg.M, cfg.D // cfg.P
+    a = Q.level1_subpart_distances(Y[0], ix.C1, cfg.M)
+    for m in range(cfg.M):
+        p = (m * ds) // dp
+        lo = m * ds - p * dp
+        want = cdist(Y[0:1, m * ds:(m + 1) * ds].astype(np.float64),
+                     ix.C1[p, :, lo:lo + ds].astype(np.float64), "sqeuclidean")[0]
+        np.testing.assert_allclose(a[m], want, rtol=1e-12)
+    d1 = Q.part_distances(a, cfg.P)
+    for p in range(cfg.P):
+        want = cdist(Y[0:1, p * dp:(p + 1) * dp].astype(np.float64), ix.C1[p].astype(np.float64), "sqeuclidean")[0]
+        np.testing.assert_allclose(d1[p], want, rtol=1e-12)
+
+
+def test_level2_distances_match_cdist(tiny):
+    cfg, X, Y, ix = tiny
+    dp = cfg.D // cfg.P
+    sel = np.array([[3, 0, 5], [7, 2, 1]])
+    d2, ids2 = Q.level2_distances(Y[1], ix.C2, sel)
+    for p in range(cfg.P):
+        for s, i in enumerate(sel[p]):
+            want = cdist(Y[1:2, p * dp:(p + 1) * dp].astype(np.float64), ix.C2[p, i].astype(np.float64), "sqeuclidean")[0]
+            np.testing.assert_allclose(d2[p, s * cfg.k2:(s + 1) * cfg.k2], want, rtol=1e-12)
+            assert ids2[p, s * cfg.k2:(s + 1) * cfg.k2].tolist() == [i * cfg.k2 + j for j in range(cfg.k2)]
+
+
+def test_sorts_match_python_sorted(rng):
+    v = rng.integers(0, 5, size=40).astype(np.float64)      # many ties
+    ids = rng.permutation(40)
+    o = Q.order_by_value_then_id(v, ids)
+    assert [(v[t], ids[t]) for t in o] == sorted(zip(v.tolist(), ids.tolist()))
+    sel = Q.select_clusters(v[None, :16], 5)[0]
+    assert sel.tolist() == [i for _, i in sorted(zip(v[:16].tolist(), range(16)))[:5]]
+    Ld, Lid = Q.sort_level2(v[None], ids[None])
+    assert list(zip(Ld[0].tolist(), Lid[0].tolist())) == sorted(zip(v.tolist(), ids.tolist()))
+    oi, od = Q.top_k(v, ids, 45)
+    ref = sorted(zip(v.tolist(), ids.tolist()))
+    assert oi[:40].tolist() == [i for _, i in ref] and np.all(oi[40:] == -1) and np.all(np.isinf(od[40:]))
+
+
+def test_score_is_sum_of_table_entries(rng):
+    lut = rng.random((4, 256))
+    codes = rng.integers(0, 256, size=(50, 4)).astype(np.uint8)
+    s = Q.score_codes(lut, codes)
+    for n in range(50):
+        assert s[n] == pytest.approx(sum(lut[m, codes[n, m]] for m in range(4)), rel=1e-14)
+
+
+# ---- P8: P=1, k2=1 degenerates to a plain inverted file over k1 Voronoi cells -----------------
+def test_single_part_single_child_is_inverted_file(rng):
+    X = rng.normal(size=(600, 8)).astype(np.float32)
+    ix = B.build_index(X, P=1, k1=8, k2=1, M=1, T=8, C=600, iters=5)
+    y = rng.normal(size=8)
+    d = cdist(y[None], ix.C1[0].astype(np.float64), "sqeuclidean")[0]
+    cells = np.argsort(d, kind="stable")
+    lab = np.argmin(cdist(X.astype(np.float64), ix.C1[0].astype(np.float64), "sqeuclidean"), axis=1)
+    for w in (1, 3, 8):
+        tr = Q.query(ix, y, k=5, w=w)
+        want = np.concatenate([np.nonzero(lab == c)[0] for c in cells[:w]])
+        assert np.array_equal(tr.cand_ids, want)
+
+
+# ---- P10: recall bookkeeping --------------------------------------------------------------------
+def test_exact_rerank_finds_nn_iff_its_bin_was_visited(tiny):
+    cfg, X, Y, ix = tiny
+    for q in range(20):
+        gt = int(np.argmin(cdist(Y[q:q + 1].astype(np.float64), X.astype(np.float64), "sqeuclidean")[0]))
+        tr = Q.query(ix, Y[q], cfg.k, cfg.w, X=X, exact_rerank=True)
+        assert (gt in tr.cand_ids) == (tr.out_ids[0] == gt)
+        assert len(tr.cand_ids) <= cfg.C and len(set(tr.cand_ids.tolist())) == len(tr.cand_ids)
+
+
+# ---- hashing: colliding bins share one list, a slot is proposed once ---------------------------
+def test_modulo_hash_dedupes_slots(tiny):
+    cfg, X, Y, _ = tiny
+    ixh = B.build_index(X[:2000], cfg.P, cfg.k1, cfg.k2, cfg.M, H=97, T=1024, C=2000, iters=5)
+    tr = Q.query(ixh, Y[0], k=10, w=cfg.k1, T=ixh.K, C=2000)
+    assert len(set(tr.slots.tolist())) == len(tr.slots)
+    assert np.array_equal(np.sort(tr.cand_ids), np.arange(2000))   # still a partition
+    for t in range(0, 2000, 131):
+        slot = int(np.searchsorted(ixh.offsets, t, side="right")) - 1
+        assert slot == B.bin_slot(X[ixh.ids[t]], ixh.C1, ixh.C2, 97)
+
+
+# ---- index file round trip -----------------------------------------------------------------------
+def test_index_file_roundtrip(tiny, tmp_path):
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    ix2 = IO.read_index(path)
+    for name in ("C1", "C2", "tbl_i", "tbl_j", "tbl_lam", "cc", "offsets", "ids", "codes"):
+        assert np.array_equal(getattr(ix, name), getattr(ix2, name))
+    assert (ix2.D, ix2.P, ix2.k1, ix2.k2, ix2.M, ix2.N, ix2.H, ix2.T, ix2.C) == \
+        (ix.D, ix.P, ix.k1, ix.k2, ix.M, ix.N, ix.H, ix.T, ix.C)
+    with open(path, "r+b") as f:
+        f.truncate(os.path.getsize(path) - 10)
+    with pytest.raises(ValueError):
+        IO.read_index(path)
