@@ -1,0 +1,164 @@
+/*
+ * pqt.h -- C ABI of the Product Quantization Tree (PQT) query library for AMD MI355X (gfx950).
+ *
+ * The library answers the nearest-neighbour problem of Eq. 1 of the paper,
+ *     N(y) = argmin_{x in X} ||y - x||^2 ,
+ * approximately, with the online phase of Sec. 3.2 / 3.3: tree traversal (level-1
+ * distances, Eq. 6; level-2 refinement of the w best clusters), bin proposal, vector
+ * proposal from the inverted lists of Sec. 4, re-ranking by line quantisation
+ * (Eq. 8-9) and a final sort.  Every query-dependent step runs inside
+ * pqt_query_batch on the GPU (Sec. 1: all query-dependent work belongs to the online phase).
+ *
+ * Conventions
+ *   - plain C, no exceptions cross this boundary; every function that can fail returns
+ *     0 (PQT_OK) or a negative PQT_E* code and leaves a message for pqt_last_error();
+ *   - "device" pointers are HIP device addresses on the index's GPU, "host" pointers are
+ *     ordinary process memory; the library never takes ownership of caller memory;
+ *   - all distances are squared Euclidean distances (Sec. 1: d(.) := ||.||^2);
+ *   - symbols: D dimension, P tree parts, k1/k2 level-1/level-2 centroids per part,
+ *     M re-rank sub-parts = code bytes per vector ("P_line", Sec. 3.3), H bin slots,
+ *     T bin tuples examined per query, C candidate budget per query, w clusters refined
+ *     per part, k results per query, R = w*k2.
+ */
+#ifndef PQT_H
+#define PQT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PQT_OK            0
+#define PQT_EINVAL       (-1)  /* null pointer, size or parameter out of range               */
+#define PQT_EIO          (-2)  /* file missing or unreadable                                 */
+#define PQT_EFORMAT      (-3)  /* bad magic/version, truncated file, inconsistent arrays     */
+#define PQT_ENOMEM       (-4)  /* host or device allocation failed                           */
+#define PQT_EHIP         (-5)  /* a HIP runtime call or kernel launch failed                 */
+#define PQT_EUNSUPPORTED (-6)  /* valid request outside the implemented limits               */
+
+/* Limits of the kernels (requests beyond them return PQT_EUNSUPPORTED or PQT_EINVAL). */
+#define PQT_MAX_K1      256    /* code table stores centroid numbers in one byte             */
+#define PQT_MAX_R      1024    /* w*k2 level-2 entries per part                              */
+#define PQT_MAX_T      8192
+#define PQT_MAX_C     16384
+#define PQT_MAX_K      1024
+
+typedef struct pqt_index pqt_index;   /* opaque; owns all device and host memory of one index */
+
+typedef struct pqt_info {
+    uint64_t N, H;
+    uint32_t D, P, k1, k2, M;
+    uint32_t T, C;               /* current budgets (defaults come from the index file)      */
+    int32_t  device;
+    uint64_t bytes_index;        /* device bytes held by the index arrays                    */
+    uint64_t bytes_workspace;    /* device bytes held by the per-batch workspace             */
+} pqt_info;
+
+/*
+ * pqt_index_load -- read an index file (host path) and place it in the memory of GPU
+ * `device`.  The file holds what the offline phase produces (Sec. 3.1, 3.3, 4): the
+ * two-level codebooks, the line-code table (i, j, lambda) per code byte value (Eq. 7),
+ * the centroid-pair distance table of Sec. 3.3, the pointer array over the H hashed bin
+ * slots, the ids sorted by slot, and the codes stored in the same order as the ids.
+ * Layout: 256-byte header  "PQTIDX1\0", u32 version=1, D, P, k1, k2, M, u64 N, u64 H,
+ * u32 T, u32 C, u32 offset_bits=32; then, each at the next multiple of 256 bytes:
+ * C1 f32[P][k1][D/P], C2 f32[P][k1][k2][D/P], tbl_i u8[M][256], tbl_j u8[M][256],
+ * tbl_lambda f32[M][256], cc f32[M][k1][k1], offsets u32[H+1], ids u32[N], codes u8[N][M].
+ * On success *out is a handle the caller releases with pqt_index_free.
+ * Errors: PQT_EINVAL (null), PQT_EIO, PQT_EFORMAT (also: offsets not monotone,
+ * offsets[H] != N, table entries >= k1), PQT_EUNSUPPORTED (P not in {1,2,4}, sizes beyond
+ * the limits above), PQT_ENOMEM, PQT_EHIP.
+ */
+int pqt_index_load(const char* path, int device, pqt_index** out);
+
+/* Releases the index, its device arrays and its workspace.  NULL is allowed. */
+void pqt_index_free(pqt_index* index);
+
+/* Fills *out.  PQT_EINVAL on null arguments. */
+int pqt_index_info(const pqt_index* index, pqt_info* out);
+
+/*
+ * pqt_set_budget -- how far the bin proposal goes (Sec. 3.2 "until a sufficient number
+ * of vectors ... is generated"; Table 1: the first 2^12 proposed vectors are used):
+ * T_bins rank tuples are examined per query (empty and repeated slots count), and the
+ * candidate list is cut after C_candidates vectors.  1 <= T <= PQT_MAX_T,
+ * 1 <= C <= PQT_MAX_C, else PQT_EINVAL.
+ */
+int pqt_set_budget(pqt_index* index, uint32_t T_bins, uint32_t C_candidates);
+
+/*
+ * pqt_query_batch -- the online phase for nq queries.
+ *   queries   device, nq x D row-major fp32
+ *   k         results per query, 1 <= k <= min(C, PQT_MAX_K)
+ *   w         level-1 clusters refined per part, 1 <= w <= k1, w*k2 <= PQT_MAX_R
+ *   out_ids   device, nq x k int64: database ids ascending by (distance, id); when fewer
+ *             than k candidates exist the tail is -1
+ *   out_dists device, nq x k fp32: the Eq. 8-9 approximation of ||y-x||^2 for each id
+ *             (i.e. the exact squared distance to the line-quantised vector); tail +inf
+ *   hip_stream  a hipStream_t (NULL = the default stream).  The call only enqueues work:
+ *             it returns before the results exist and never synchronises the device,
+ *             except when the library's workspace has to grow for a larger nq than seen
+ *             before (one hipMalloc).  Same inputs give the same bytes.
+ * Calls on one index must not overlap (they share the workspace).
+ * Errors: PQT_EINVAL (null pointers with nq > 0, nq < 0, k or w out of range),
+ * PQT_EUNSUPPORTED (LDS budget exceeded for this D/M/k1/R/T/C), PQT_ENOMEM, PQT_EHIP.
+ */
+int pqt_query_batch(pqt_index* index, const float* queries, int64_t nq, int k, int w,
+                    int64_t* out_ids, float* out_dists, void* hip_stream);
+
+/*
+ * Optional device buffers that receive every intermediate of the path, for checking it
+ * stage by stage.  Any pointer may be NULL (that tap is skipped).  Shapes are per batch:
+ *   a          nq x M x k1   fp32   level-1 sub-part distances (Eq. 6 per sub-part)
+ *   sel        nq x P x w    int32  kept level-1 clusters, closest first
+ *   L_d, L_id  nq x P x R    fp32 / uint32  sorted level-2 lists (distance, leaf id i*k2+j)
+ *   n_tuples   nq            uint32 rank tuples examined (min(T, R^P))
+ *   tuples     nq x T x 4    uint16 examined rank tuples in bin order (unused parts 0)
+ *   tuple_keys nq x T        fp32   their summed level-2 distances
+ *   n_slots    nq            uint32 proposed (non-empty, first-seen, before the C cut) slots
+ *   slots      nq x T        uint64 those slots in visit order
+ *   n_cand     nq            uint32 candidates gathered (<= C)
+ *   cand_ids   nq x C        int64  candidate ids in visit order
+ *   scores     nq x C        fp32   their Eq. 8-9 scores
+ *   lut        nq x M x 256  fp32   per-query table of Eq. 9 summands
+ */
+typedef struct pqt_debug_taps {
+    float*    a;
+    int32_t*  sel;
+    float*    L_d;
+    uint32_t* L_id;
+    uint32_t* n_tuples;
+    uint16_t* tuples;
+    float*    tuple_keys;
+    uint32_t* n_slots;
+    uint64_t* slots;
+    uint32_t* n_cand;
+    int64_t*  cand_ids;
+    float*    scores;
+    float*    lut;
+} pqt_debug_taps;
+
+/* pqt_query_batch plus the taps above (taps may be NULL: then identical to pqt_query_batch). */
+int pqt_query_batch_debug(pqt_index* index, const float* queries, int64_t nq, int k, int w,
+                          int64_t* out_ids, float* out_dists, void* hip_stream,
+                          const pqt_debug_taps* taps);
+
+/*
+ * Per-stage device timing.  With profiling enabled every pqt_query_batch records HIP events
+ * on its stream around its three kernels: [0] traversal (level-1 + level-2 distances and
+ * sorts), [1] bin ranking and run list, [2] gather + re-rank + top-k.
+ * pqt_stage_times synchronises on the recorded events, adds up the elapsed milliseconds of
+ * all calls since the last pqt_stage_times (at most 256 are kept) into ms[3], stores the
+ * number of calls in *calls, and resets.  PQT_EINVAL on null arguments.
+ */
+int pqt_set_profiling(pqt_index* index, int enabled);
+int pqt_stage_times(pqt_index* index, float ms[3], int* calls);
+
+/* Message of the last failing call on this thread ("" if none).  Static storage. */
+const char* pqt_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PQT_H */

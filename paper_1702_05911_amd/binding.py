@@ -1,0 +1,207 @@
+"""Thin Python binding of the PQT C ABI (include/pqt.h): argument marshalling only.
+
+Every step of the query path runs inside libpqt.so's HIP kernels.  PyTorch is used for
+device memory (tensors own the query/result buffers) and for the stream handle; there is
+no CPU fallback -- if the library is missing, importing this module raises.
+"""
+import ctypes
+import os
+
+import torch  # noqa: F401  (loads the HIP runtime the library binds to)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpqt.so")
+
+PQT_OK = 0
+PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -2, -3, -4, -5, -6
+
+EXPORTS = (
+    "pqt_index_load", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
+    "pqt_query_batch_debug", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
+)
+
+
+class PqtError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"pqt error {code}: {message}")
+        self.code = code
+
+
+class _Info(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_uint64), ("H", ctypes.c_uint64),
+                ("D", ctypes.c_uint32), ("P", ctypes.c_uint32), ("k1", ctypes.c_uint32),
+                ("k2", ctypes.c_uint32), ("M", ctypes.c_uint32), ("T", ctypes.c_uint32),
+                ("C", ctypes.c_uint32), ("device", ctypes.c_int32),
+                ("bytes_index", ctypes.c_uint64), ("bytes_workspace", ctypes.c_uint64)]
+
+
+_TAP_FIELDS = ("a", "sel", "L_d", "L_id", "n_tuples", "tuples", "tuple_keys", "n_slots", "slots",
+               "n_cand", "cand_ids", "scores", "lut")
+
+
+class _Taps(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_void_p) for name in _TAP_FIELDS]
+
+
+def load_library(path=LIB_PATH):
+    if not os.path.exists(path):
+        raise ImportError(f"{path} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(path)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.pqt_index_load.argtypes = [ctypes.c_char_p, ci, ctypes.POINTER(vp)]
+    lib.pqt_index_load.restype = ci
+    lib.pqt_index_free.argtypes = [vp]
+    lib.pqt_index_free.restype = None
+    lib.pqt_index_info.argtypes = [vp, ctypes.POINTER(_Info)]
+    lib.pqt_index_info.restype = ci
+    lib.pqt_set_budget.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32]
+    lib.pqt_set_budget.restype = ci
+    lib.pqt_query_batch.argtypes = [vp, vp, i64, ci, ci, vp, vp, vp]
+    lib.pqt_query_batch.restype = ci
+    lib.pqt_query_batch_debug.argtypes = [vp, vp, i64, ci, ci, vp, vp, vp, ctypes.POINTER(_Taps)]
+    lib.pqt_query_batch_debug.restype = ci
+    lib.pqt_set_profiling.argtypes = [vp, ci]
+    lib.pqt_set_profiling.restype = ci
+    lib.pqt_stage_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 3), ctypes.POINTER(ci)]
+    lib.pqt_stage_times.restype = ci
+    lib.pqt_last_error.argtypes = []
+    lib.pqt_last_error.restype = ctypes.c_char_p
+    return lib
+
+
+_lib = load_library()
+
+
+def _check(rc):
+    if rc != PQT_OK:
+        raise PqtError(rc, _lib.pqt_last_error().decode("utf-8", "replace"))
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+class Index:
+    """Handle of an index resident on one GPU (pqt_index_load / pqt_index_free)."""
+
+    def __init__(self, path, device=0):
+        self._h = ctypes.c_void_p()
+        _check(_lib.pqt_index_load(os.fsencode(path), int(device), ctypes.byref(self._h)))
+        self.device = torch.device("cuda", int(device))
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib.pqt_index_free(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def info(self):
+        out = _Info()
+        _check(_lib.pqt_index_info(self._h, ctypes.byref(out)))
+        return {name: getattr(out, name) for name, _ in _Info._fields_}
+
+    def set_budget(self, T, C):
+        _check(_lib.pqt_set_budget(self._h, int(T), int(C)))
+
+    def _buffers(self, queries, k):
+        if queries.dtype != torch.float32 or not queries.is_cuda or not queries.is_contiguous() or queries.dim() != 2:
+            raise ValueError("queries must be a contiguous 2-D float32 CUDA tensor")
+        nq = queries.shape[0]
+        out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+        out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+        return nq, out_ids, out_dists
+
+    def query_batch(self, queries, k, w, out_ids=None, out_dists=None, stream=None):
+        """pqt_query_batch.  queries: (nq, D) float32 CUDA tensor.  Returns (ids int64, dists float32)."""
+        info_d = self.info()["D"]
+        if queries.dim() == 2 and queries.shape[1] != info_d:
+            raise ValueError(f"queries have dimension {queries.shape[1]}, index has D={info_d}")
+        nq, ids_, dists_ = self._buffers(queries, k)
+        out_ids = ids_ if out_ids is None else out_ids
+        out_dists = dists_ if out_dists is None else out_dists
+        _check(_lib.pqt_query_batch(self._h, queries.data_ptr(), nq, int(k), int(w), out_ids.data_ptr(),
+                                    out_dists.data_ptr(), _stream_handle(stream)))
+        return out_ids, out_dists
+
+    def query_batch_debug(self, queries, k, w, taps=_TAP_FIELDS, stream=None):
+        """pqt_query_batch_debug.  Returns (ids, dists, dict of tap tensors)."""
+        inf = self.info()
+        if queries.dim() == 2 and queries.shape[1] != inf["D"]:
+            raise ValueError(f"queries have dimension {queries.shape[1]}, index has D={inf['D']}")
+        nq, out_ids, out_dists = self._buffers(queries, k)
+        P, M, k1, T, C, R = inf["P"], inf["M"], inf["k1"], inf["T"], inf["C"], w * inf["k2"]
+        dev = queries.device
+        shapes = {
+            "a": ((nq, M, k1), torch.float32), "sel": ((nq, P, w), torch.int32),
+            "L_d": ((nq, P, R), torch.float32), "L_id": ((nq, P, R), torch.int32),
+            "n_tuples": ((nq,), torch.int32), "tuples": ((nq, T, 4), torch.int16),
+            "tuple_keys": ((nq, T), torch.float32), "n_slots": ((nq,), torch.int32),
+            "slots": ((nq, T), torch.int64), "n_cand": ((nq,), torch.int32),
+            "cand_ids": ((nq, C), torch.int64), "scores": ((nq, C), torch.float32),
+            "lut": ((nq, M, 256), torch.float32),
+        }
+        bufs = {name: torch.zeros(shapes[name][0], dtype=shapes[name][1], device=dev) for name in taps}
+        ct = _Taps(**{name: bufs[name].data_ptr() for name in taps})
+        _check(_lib.pqt_query_batch_debug(self._h, queries.data_ptr(), nq, int(k), int(w), out_ids.data_ptr(),
+                                          out_dists.data_ptr(), _stream_handle(stream), ctypes.byref(ct)))
+        return out_ids, out_dists, bufs
+
+    def set_profiling(self, enabled):
+        _check(_lib.pqt_set_profiling(self._h, 1 if enabled else 0))
+
+    def stage_times(self):
+        """(ms per stage summed over the calls since the last read, number of calls)."""
+        ms = (ctypes.c_float * 3)()
+        calls = ctypes.c_int()
+        _check(_lib.pqt_stage_times(self._h, ctypes.byref(ms), ctypes.byref(calls)))
+        return [float(v) for v in ms], int(calls.value)
+
+
+def last_error():
+    return _lib.pqt_last_error().decode("utf-8", "replace")
+
+
+# ---- the C ABI's names, one to one ---------------------------------------------------------------
+def pqt_index_load(path, device=0):
+    return Index(path, device)
+
+
+def pqt_index_free(index):
+    index.close()
+
+
+def pqt_index_info(index):
+    return index.info()
+
+
+def pqt_set_budget(index, T_bins, C_candidates):
+    index.set_budget(T_bins, C_candidates)
+
+
+def pqt_query_batch(index, queries, k, w, out_ids=None, out_dists=None, stream=None):
+    return index.query_batch(queries, k, w, out_ids, out_dists, stream)
+
+
+def pqt_query_batch_debug(index, queries, k, w, taps=_TAP_FIELDS, stream=None):
+    return index.query_batch_debug(queries, k, w, taps, stream)
+
+
+def pqt_set_profiling(index, enabled):
+    index.set_profiling(enabled)
+
+
+def pqt_stage_times(index):
+    return index.stage_times()
+
+
+def pqt_last_error():
+    return last_error()

@@ -1,0 +1,415 @@
+// C ABI of the PQT query library: index loading, budgets, the batched query and stage timing.
+// Host code only; the three kernels live in traverse.hip, rank_bins.hip and rerank.hip.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/pqt.h"
+#include "pqt_kernels.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(e_ == hipErrorOutOfMemory ? PQT_ENOMEM : PQT_EHIP, "%s: %s", #expr,    \
+                        hipGetErrorString(e_));                                                \
+    } while (0)
+
+struct DeviceGuard {   // make the index's GPU current for the duration of a call
+    int prev = -1;
+    bool ok = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true;
+    }
+    ~DeviceGuard() {
+        if (prev >= 0) (void)hipSetDevice(prev);
+    }
+};
+
+constexpr int kMaxProfiledCalls = 256;
+
+// Dynamic LDS a kernel may ask for: 160 KB once the runtime has accepted that ceiling for all
+// three kernels, else the 64 KB every HIP device grants without asking.
+size_t g_lds_limit = 64 * 1024;
+
+}  // namespace
+
+struct pqt_index {
+    uint32_t D = 0, P = 0, k1 = 0, k2 = 0, M = 0, T = 0, C = 0;
+    uint64_t N = 0, H = 0;
+    int device = 0;
+    bool hashed = false;
+    // index arrays (device)
+    float* C1 = nullptr;
+    float* c1n = nullptr;
+    float* C2 = nullptr;
+    pqt::CodeEntry* table = nullptr;
+    uint32_t* offsets = nullptr;
+    uint32_t* ids = nullptr;
+    uint8_t* codes = nullptr;
+    uint64_t bytes_index = 0;
+    // workspace (device), sized for ws_nq queries at ws_R list entries and ws_T tuples
+    int64_t ws_nq = 0;
+    int ws_R = 0, ws_T = 0;
+    float* ws_a = nullptr;
+    float* ws_Ld = nullptr;
+    uint32_t* ws_Lid = nullptr;
+    uint2* ws_runs = nullptr;
+    uint2* ws_meta = nullptr;
+    uint64_t bytes_workspace = 0;
+    // stage timing
+    bool profiling = false;
+    int prof_calls = 0;
+    std::vector<hipEvent_t> events;   // 4 per profiled call
+
+    void free_workspace() {
+        (void)hipFree(ws_a); (void)hipFree(ws_Ld); (void)hipFree(ws_Lid);
+        (void)hipFree(ws_runs); (void)hipFree(ws_meta);
+        ws_a = ws_Ld = nullptr; ws_Lid = nullptr; ws_runs = ws_meta = nullptr;
+        ws_nq = 0; bytes_workspace = 0;
+    }
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+struct FileHeader {
+    char magic[8];
+    uint32_t version, D, P, k1, k2, M;
+    uint64_t N, H;
+    uint32_t T, C, offset_bits, reserved;
+};
+static_assert(sizeof(FileHeader) == 64, "header prefix is 64 bytes");
+
+struct FileCloser {
+    void operator()(FILE* f) const {
+        if (f) fclose(f);
+    }
+};
+
+// Reads `bytes` at the next 256-byte boundary of the file.
+bool read_section(FILE* f, void* dst, size_t bytes) {
+    long pos = ftell(f);
+    if (pos < 0) return false;
+    long pad = (long)((kAlign - (size_t)pos % kAlign) % kAlign);
+    if (pad && fseek(f, pad, SEEK_CUR) != 0) return false;
+    return bytes == 0 || fread(dst, 1, bytes, f) == bytes;
+}
+
+template <typename Tp>
+int upload(Tp** dev, const void* host, size_t bytes, uint64_t* account) {
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(dev), bytes ? bytes : 1));
+    if (bytes) HIP_TRY(hipMemcpy(*dev, host, bytes, hipMemcpyHostToDevice));
+    *account += bytes;
+    return PQT_OK;
+}
+
+int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
+    const int R = w * (int)ix->k2;
+    const size_t l1 = pqt::traverse_lds_bytes(ix->D, ix->P, ix->k1, ix->k2, ix->M, w);
+    const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed);
+    const int threads = ix->C > 4096 ? 512 : 256;
+    const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads);
+    if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)
+        return fail(PQT_EUNSUPPORTED,
+                    "LDS budget exceeded (traverse %zu, rank %zu, rerank %zu bytes of %zu) for D=%u M=%u k1=%u R=%d T=%u C=%u",
+                    l1, l2, l3, g_lds_limit, ix->D, ix->M, ix->k1, R, ix->T, ix->C);
+    if (lds_out) { lds_out[0] = l1; lds_out[1] = l2; lds_out[2] = l3; }
+    return PQT_OK;
+}
+
+int ensure_workspace(pqt_index* ix, int64_t nq, int R) {
+    if (nq <= ix->ws_nq && R <= ix->ws_R && (int)ix->T <= ix->ws_T) return PQT_OK;
+    ix->free_workspace();
+    const int64_t n = nq > ix->ws_nq ? nq : ix->ws_nq;
+    const int r = R > ix->ws_R ? R : ix->ws_R;
+    const int t = (int)ix->T > ix->ws_T ? (int)ix->T : ix->ws_T;
+    const size_t ba = sizeof(float) * (size_t)n * ix->M * ix->k1;
+    const size_t bl = sizeof(float) * (size_t)n * ix->P * r;
+    const size_t br = sizeof(uint2) * (size_t)n * t;
+    const size_t bm = sizeof(uint2) * (size_t)n;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_a), ba));
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_Ld), bl));
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_Lid), bl));
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_runs), br));
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_meta), bm));
+    ix->ws_nq = n; ix->ws_R = r; ix->ws_T = t;
+    ix->bytes_workspace = ba + 2 * bl + br + bm;
+    return PQT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pqt_last_error(void) { return g_err; }
+
+int pqt_index_load(const char* path, int device, pqt_index** out) {
+    if (!path || !out) return fail(PQT_EINVAL, "pqt_index_load: null argument");
+    *out = nullptr;
+    std::unique_ptr<FILE, FileCloser> f(fopen(path, "rb"));
+    if (!f) return fail(PQT_EIO, "cannot open '%s'", path);
+    unsigned char hdr[kAlign];
+    if (fread(hdr, 1, kAlign, f.get()) != kAlign) return fail(PQT_EFORMAT, "'%s': truncated header", path);
+    FileHeader h;
+    memcpy(&h, hdr, sizeof(h));
+    if (memcmp(h.magic, "PQTIDX1\0", 8) != 0) return fail(PQT_EFORMAT, "'%s': bad magic", path);
+    if (h.version != 1 || h.offset_bits != 32) return fail(PQT_EFORMAT, "'%s': unsupported version", path);
+    if (h.D == 0 || h.P == 0 || h.k1 == 0 || h.k2 == 0 || h.M == 0 || h.H == 0 || h.D % h.P || h.D % h.M ||
+        h.M % h.P)
+        return fail(PQT_EFORMAT, "'%s': inconsistent sizes D=%u P=%u k1=%u k2=%u M=%u", path, h.D, h.P, h.k1,
+                    h.k2, h.M);
+    if (!(h.P == 1 || h.P == 2 || h.P == 4)) return fail(PQT_EUNSUPPORTED, "P=%u: only 1, 2 or 4 tree parts", h.P);
+    if (h.P == 4) return fail(PQT_EUNSUPPORTED, "P=4 bin ranking is not available in this build");
+    if (h.k1 > PQT_MAX_K1 || h.k2 > PQT_MAX_R || h.M > 64 || h.D > 8192)
+        return fail(PQT_EUNSUPPORTED, "k1=%u k2=%u M=%u D=%u beyond the kernel limits", h.k1, h.k2, h.M, h.D);
+    if (h.N >= 0xffffffffull || h.H >= 0xffffffffull)
+        return fail(PQT_EUNSUPPORTED, "N=%llu H=%llu: 32-bit ids and slots only", (unsigned long long)h.N,
+                    (unsigned long long)h.H);
+    long double K = 1;
+    for (uint32_t p = 0; p < h.P; ++p) K *= (long double)h.k1 * h.k2;
+    if ((long double)h.H > K) return fail(PQT_EFORMAT, "'%s': H exceeds the number of bins", path);
+    if (h.T < 1 || h.T > PQT_MAX_T || h.C < 1 || h.C > PQT_MAX_C)
+        return fail(PQT_EFORMAT, "'%s': default budgets T=%u C=%u out of range", path, h.T, h.C);
+
+    const size_t dp = h.D / h.P, ds = h.D / h.M;
+    std::vector<float> C1, C2, lam, cc;
+    std::vector<uint8_t> ti, tj, codes;
+    std::vector<uint32_t> offsets, ids;
+    try {
+        C1.resize((size_t)h.P * h.k1 * dp);
+        C2.resize((size_t)h.P * h.k1 * h.k2 * dp);
+        ti.resize((size_t)h.M * 256); tj.resize((size_t)h.M * 256); lam.resize((size_t)h.M * 256);
+        cc.resize((size_t)h.M * h.k1 * h.k1);
+        offsets.resize((size_t)h.H + 1);
+        ids.resize((size_t)h.N);
+        codes.resize((size_t)h.N * h.M);
+    } catch (const std::bad_alloc&) {
+        return fail(PQT_ENOMEM, "host allocation failed while reading '%s'", path);
+    }
+    if (!read_section(f.get(), C1.data(), C1.size() * 4) || !read_section(f.get(), C2.data(), C2.size() * 4) ||
+        !read_section(f.get(), ti.data(), ti.size()) || !read_section(f.get(), tj.data(), tj.size()) ||
+        !read_section(f.get(), lam.data(), lam.size() * 4) || !read_section(f.get(), cc.data(), cc.size() * 4) ||
+        !read_section(f.get(), offsets.data(), offsets.size() * 4) || !read_section(f.get(), ids.data(), ids.size() * 4) ||
+        !read_section(f.get(), codes.data(), codes.size()))
+        return fail(PQT_EFORMAT, "'%s': truncated", path);
+
+    if (offsets[0] != 0 || offsets[h.H] != h.N) return fail(PQT_EFORMAT, "'%s': offsets do not span the ids", path);
+    for (size_t s = 0; s < h.H; ++s)
+        if (offsets[s + 1] < offsets[s]) return fail(PQT_EFORMAT, "'%s': offsets not monotone at slot %zu", path, s);
+    for (size_t e = 0; e < ti.size(); ++e)
+        if (ti[e] >= h.k1 || tj[e] >= h.k1) return fail(PQT_EFORMAT, "'%s': code table names centroid >= k1", path);
+
+    // squared norms of the centroid sub-parts, and the code table with its pair distance folded in
+    std::vector<float> c1n((size_t)h.M * h.k1);
+    const size_t per = h.M / h.P;
+    for (size_t m = 0; m < h.M; ++m) {
+        const size_t p = m / per, lo = m * ds - p * dp;
+        for (size_t i = 0; i < h.k1; ++i) {
+            double s = 0;
+            for (size_t d = 0; d < ds; ++d) {
+                const double v = C1[(p * h.k1 + i) * dp + lo + d];
+                s += v * v;
+            }
+            c1n[m * h.k1 + i] = (float)s;
+        }
+    }
+    std::vector<pqt::CodeEntry> table((size_t)h.M * 256);
+    for (size_t m = 0; m < h.M; ++m)
+        for (size_t c = 0; c < 256; ++c) {
+            const size_t e = m * 256 + c;
+            table[e].ij = (uint32_t)ti[e] | ((uint32_t)tj[e] << 8);
+            table[e].lam = lam[e];
+            table[e].cc = cc[(m * h.k1 + ti[e]) * h.k1 + tj[e]];
+        }
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev)
+        return fail(PQT_EHIP, "GPU %d is not available (%d visible)", device, ndev);
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", device);
+    if (pqt::configure_traverse(pqt::kMaxLds) == hipSuccess && pqt::configure_rank(pqt::kMaxLds) == hipSuccess &&
+        pqt::configure_rerank(pqt::kMaxLds) == hipSuccess) {
+        g_lds_limit = pqt::kMaxLds;
+    } else {
+        (void)hipGetLastError();
+        g_lds_limit = 64 * 1024;
+        HIP_TRY(pqt::configure_traverse(g_lds_limit));
+        HIP_TRY(pqt::configure_rank(g_lds_limit));
+        HIP_TRY(pqt::configure_rerank(g_lds_limit));
+    }
+
+    pqt_index* ix = new (std::nothrow) pqt_index();
+    if (!ix) return fail(PQT_ENOMEM, "host allocation failed");
+    ix->D = h.D; ix->P = h.P; ix->k1 = h.k1; ix->k2 = h.k2; ix->M = h.M; ix->T = h.T; ix->C = h.C;
+    ix->N = h.N; ix->H = h.H; ix->device = device;
+    ix->hashed = (long double)h.H != K;
+    int rc = PQT_OK;
+    if ((rc = upload(&ix->C1, C1.data(), C1.size() * 4, &ix->bytes_index)) ||
+        (rc = upload(&ix->c1n, c1n.data(), c1n.size() * 4, &ix->bytes_index)) ||
+        (rc = upload(&ix->C2, C2.data(), C2.size() * 4, &ix->bytes_index)) ||
+        (rc = upload(&ix->table, table.data(), table.size() * sizeof(pqt::CodeEntry), &ix->bytes_index)) ||
+        (rc = upload(&ix->offsets, offsets.data(), offsets.size() * 4, &ix->bytes_index)) ||
+        (rc = upload(&ix->ids, ids.data(), ids.size() * 4, &ix->bytes_index)) ||
+        (rc = upload(&ix->codes, codes.data(), codes.size(), &ix->bytes_index))) {
+        pqt_index_free(ix);
+        return rc;
+    }
+    *out = ix;
+    return PQT_OK;
+}
+
+void pqt_index_free(pqt_index* ix) {
+    if (!ix) return;
+    DeviceGuard guard(ix->device);
+    (void)hipFree(ix->C1); (void)hipFree(ix->c1n); (void)hipFree(ix->C2); (void)hipFree(ix->table);
+    (void)hipFree(ix->offsets); (void)hipFree(ix->ids); (void)hipFree(ix->codes);
+    ix->free_workspace();
+    for (hipEvent_t e : ix->events) (void)hipEventDestroy(e);
+    delete ix;
+}
+
+int pqt_index_info(const pqt_index* ix, pqt_info* out) {
+    if (!ix || !out) return fail(PQT_EINVAL, "pqt_index_info: null argument");
+    out->N = ix->N; out->H = ix->H; out->D = ix->D; out->P = ix->P; out->k1 = ix->k1; out->k2 = ix->k2;
+    out->M = ix->M; out->T = ix->T; out->C = ix->C; out->device = ix->device;
+    out->bytes_index = ix->bytes_index; out->bytes_workspace = ix->bytes_workspace;
+    return PQT_OK;
+}
+
+int pqt_set_budget(pqt_index* ix, uint32_t T_bins, uint32_t C_candidates) {
+    if (!ix) return fail(PQT_EINVAL, "pqt_set_budget: null index");
+    if (T_bins < 1 || T_bins > PQT_MAX_T || C_candidates < 1 || C_candidates > PQT_MAX_C)
+        return fail(PQT_EINVAL, "budget T=%u C=%u out of range (T<=%d, C<=%d)", T_bins, C_candidates, PQT_MAX_T,
+                    PQT_MAX_C);
+    ix->T = T_bins;
+    ix->C = C_candidates;
+    return PQT_OK;
+}
+
+int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int64_t* out_ids,
+                          float* out_dists, void* hip_stream, const pqt_debug_taps* taps) {
+    if (!ix) return fail(PQT_EINVAL, "pqt_query_batch: null index");
+    if (nq < 0) return fail(PQT_EINVAL, "pqt_query_batch: nq=%lld < 0", (long long)nq);
+    if (k < 1 || k > PQT_MAX_K || (uint32_t)k > ix->C)
+        return fail(PQT_EINVAL, "pqt_query_batch: k=%d outside 1..min(C=%u, %d)", k, ix->C, PQT_MAX_K);
+    if (w < 1 || (uint32_t)w > ix->k1) return fail(PQT_EINVAL, "pqt_query_batch: w=%d outside 1..k1=%u", w, ix->k1);
+    if ((int64_t)w * ix->k2 > PQT_MAX_R)
+        return fail(PQT_EINVAL, "pqt_query_batch: w*k2=%lld exceeds %d", (long long)w * ix->k2, PQT_MAX_R);
+    if (nq == 0) return PQT_OK;
+    if (!queries || !out_ids || !out_dists) return fail(PQT_EINVAL, "pqt_query_batch: null buffer");
+    int rc = check_query_limits(ix, k, w, nullptr);
+    if (rc) return rc;
+
+    DeviceGuard guard(ix->device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
+    const int R = w * (int)ix->k2;
+    if ((rc = ensure_workspace(ix, nq, R))) return rc;
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    static const pqt_debug_taps no_taps = {};
+    const pqt_debug_taps& tp = taps ? *taps : no_taps;
+
+    hipEvent_t* ev = nullptr;
+    if (ix->profiling && ix->prof_calls < kMaxProfiledCalls) {
+        while ((int)ix->events.size() < 4 * (ix->prof_calls + 1)) {
+            hipEvent_t e;
+            HIP_TRY(hipEventCreate(&e));
+            ix->events.push_back(e);
+        }
+        ev = &ix->events[4 * ix->prof_calls];
+        ix->prof_calls++;
+    }
+
+    pqt::TraverseArgs ta;
+    ta.queries = queries; ta.nq = nq;
+    ta.D = ix->D; ta.P = ix->P; ta.k1 = ix->k1; ta.k2 = ix->k2; ta.M = ix->M; ta.w = w;
+    ta.C1 = ix->C1; ta.c1n = ix->c1n; ta.C2 = ix->C2;
+    ta.a = ix->ws_a; ta.L_d = ix->ws_Ld; ta.L_id = ix->ws_Lid; ta.sel_tap = tp.sel;
+    if (ev) HIP_TRY(hipEventRecord(ev[0], stream));
+    HIP_TRY(pqt::launch_traverse(ta, stream));
+    if (ev) HIP_TRY(hipEventRecord(ev[1], stream));
+
+    pqt::RankArgs ra;
+    ra.nq = nq; ra.P = ix->P; ra.R = R; ra.T = ix->T; ra.C = ix->C;
+    ra.k1k2 = ix->k1 * ix->k2; ra.H = ix->H; ra.hashed = ix->hashed ? 1 : 0;
+    ra.offsets = ix->offsets; ra.L_d = ix->ws_Ld; ra.L_id = ix->ws_Lid;
+    ra.runs = ix->ws_runs; ra.meta = ix->ws_meta;
+    ra.n_tuples = tp.n_tuples; ra.tuples = tp.tuples; ra.tuple_keys = tp.tuple_keys; ra.slots = tp.slots;
+    HIP_TRY(pqt::launch_rank(ra, stream));
+    if (ev) HIP_TRY(hipEventRecord(ev[2], stream));
+
+    pqt::RerankArgs ca;
+    ca.nq = nq; ca.M = ix->M; ca.k1 = ix->k1; ca.T = ix->T; ca.C = ix->C; ca.k = k;
+    ca.threads = ix->C > 4096 ? 512 : 256;
+    ca.a = ix->ws_a; ca.table = ix->table; ca.runs = ix->ws_runs; ca.meta = ix->ws_meta;
+    ca.ids = ix->ids; ca.codes = ix->codes; ca.out_ids = out_ids; ca.out_dists = out_dists;
+    ca.n_cand = tp.n_cand; ca.cand_ids = tp.cand_ids; ca.scores = tp.scores; ca.lut = tp.lut;
+    HIP_TRY(pqt::launch_rerank(ca, stream));
+    if (ev) HIP_TRY(hipEventRecord(ev[3], stream));
+
+    // taps that are plain copies of workspace arrays
+    if (tp.a)
+        HIP_TRY(hipMemcpyAsync(tp.a, ix->ws_a, sizeof(float) * (size_t)nq * ix->M * ix->k1, hipMemcpyDeviceToDevice, stream));
+    if (tp.L_d)
+        HIP_TRY(hipMemcpyAsync(tp.L_d, ix->ws_Ld, sizeof(float) * (size_t)nq * ix->P * R, hipMemcpyDeviceToDevice, stream));
+    if (tp.L_id)
+        HIP_TRY(hipMemcpyAsync(tp.L_id, ix->ws_Lid, sizeof(uint32_t) * (size_t)nq * ix->P * R, hipMemcpyDeviceToDevice, stream));
+    if (tp.n_slots) {
+        // number of proposed slots = meta.x; strided copy of the first word of every meta pair
+        HIP_TRY(hipMemcpy2DAsync(tp.n_slots, sizeof(uint32_t), ix->ws_meta, sizeof(uint2), sizeof(uint32_t), (size_t)nq,
+                                 hipMemcpyDeviceToDevice, stream));
+    }
+    return PQT_OK;
+}
+
+int pqt_query_batch(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int64_t* out_ids,
+                    float* out_dists, void* hip_stream) {
+    return pqt_query_batch_debug(ix, queries, nq, k, w, out_ids, out_dists, hip_stream, nullptr);
+}
+
+int pqt_set_profiling(pqt_index* ix, int enabled) {
+    if (!ix) return fail(PQT_EINVAL, "pqt_set_profiling: null index");
+    ix->profiling = enabled != 0;
+    ix->prof_calls = 0;
+    return PQT_OK;
+}
+
+int pqt_stage_times(pqt_index* ix, float ms[3], int* calls) {
+    if (!ix || !ms || !calls) return fail(PQT_EINVAL, "pqt_stage_times: null argument");
+    DeviceGuard guard(ix->device);
+    ms[0] = ms[1] = ms[2] = 0.0f;
+    for (int c = 0; c < ix->prof_calls; ++c) {
+        hipEvent_t* ev = &ix->events[4 * c];
+        HIP_TRY(hipEventSynchronize(ev[3]));
+        for (int s = 0; s < 3; ++s) {
+            float t = 0.0f;
+            HIP_TRY(hipEventElapsedTime(&t, ev[s], ev[s + 1]));
+            ms[s] += t;
+        }
+    }
+    *calls = ix->prof_calls;
+    ix->prof_calls = 0;
+    return PQT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+// Device-side helpers shared by the PQT query kernels (gfx950, 64-lane wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pqt {
+
+constexpr int kWave = 64;
+
+// Order-preserving map float -> uint32 (ascending floats give ascending keys).
+// Adding +0.0f first turns -0.0 into +0.0 so that equal floats get equal keys.
+__device__ __forceinline__ uint32_t mono_key(float f) {
+    uint32_t u = __float_as_uint(f + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float mono_inv(uint32_t k) {
+    uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __uint_as_float(u);
+}
+
+// In-place ascending bitonic sort of n (a power of two) keys in LDS by `nthreads`
+// cooperating threads numbered tid.  Every thread of the workgroup must call it with the
+// same n (it uses workgroup barriers), but different groups of threads may sort
+// different arrays.
+template <typename K>
+__device__ __forceinline__ void bitonic_sort_lds(K* keys, int n, int tid, int nthreads) {
+    for (int size = 2; size <= n; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (int e = tid; e < (n >> 1); e += nthreads) {
+                int i = 2 * e - (e & (stride - 1));
+                int j = i + stride;
+                bool asc = (i & size) == 0;
+                K x = keys[i], y = keys[j];
+                if ((x > y) == asc) {
+                    keys[i] = y;
+                    keys[j] = x;
+                }
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// Exclusive prefix sum over data[0..n) in LDS, in place, by the whole workgroup.
+// part needs blockDim.x entries.  Returns the total.  Ends with a barrier.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t* data, int n, uint32_t* part) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int chunk = (n + nt - 1) / nt;
+    const int lo = min(tid * chunk, n), hi = min(lo + chunk, n);
+    uint32_t s = 0;
+    for (int e = lo; e < hi; ++e) s += data[e];
+    part[tid] = s;
+    __syncthreads();
+    for (int off = 1; off < nt; off <<= 1) {
+        uint32_t v = (tid >= off) ? part[tid - off] : 0u;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    const uint32_t total = part[nt - 1];
+    s = (tid > 0) ? part[tid - 1] : 0u;
+    for (int e = lo; e < hi; ++e) {
+        uint32_t v = data[e];
+        data[e] = s;
+        s += v;
+    }
+    __syncthreads();
+    return total;
+}
+
+// Inclusive running maximum over data[0..n) in LDS (uint16 payload), in place.
+__device__ __forceinline__ void block_inclusive_max_u16(uint16_t* data, int n, uint32_t* part) {
+    const int tid = threadIdx.x, nt = blockDim.x;
+    const int chunk = (n + nt - 1) / nt;
+    const int lo = min(tid * chunk, n), hi = min(lo + chunk, n);
+    uint32_t s = 0;
+    for (int e = lo; e < hi; ++e) s = max(s, (uint32_t)data[e]);
+    part[tid] = s;
+    __syncthreads();
+    for (int off = 1; off < nt; off <<= 1) {
+        uint32_t v = (tid >= off) ? part[tid - off] : 0u;
+        __syncthreads();
+        part[tid] = max(part[tid], v);
+        __syncthreads();
+    }
+    s = (tid > 0) ? part[tid - 1] : 0u;
+    for (int e = lo; e < hi; ++e) {
+        s = max(s, (uint32_t)data[e]);
+        data[e] = (uint16_t)s;
+    }
+    __syncthreads();
+}
+
+__host__ __device__ inline int next_pow2(int v) {
+    int p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+}  // namespace pqt

@@ -1,0 +1,85 @@
+// Launch interface of the three query kernels.  Host code fills the argument structs,
+// checks sizes against the kernels' limits and calls launch_*; nothing here allocates.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pqt {
+
+constexpr int kQueryTile = 16;          // queries per workgroup of the traversal kernel (MFMA rows)
+constexpr int kTraverseThreads = 256;
+constexpr int kRankThreads = 256;
+constexpr size_t kMaxLds = 160 * 1024;  // LDS per workgroup on gfx950
+
+// One entry of the folded line-code table: centroid numbers i | j<<8, lambda, and
+// ||c_i - c_j||^2 of the sub-part (the pair table of Sec. 3.3 gathered per code value).
+struct CodeEntry {
+    uint32_t ij;
+    float lam;
+    float cc;
+};
+
+struct TraverseArgs {
+    const float* queries;   // nq x D
+    int64_t nq;
+    int D, P, k1, k2, M, w;
+    const float* C1;        // P x k1 x dp
+    const float* c1n;       // M x k1   squared norms of the centroid sub-parts
+    const float* C2;        // P x k1 x k2 x dp
+    float* a;               // nq x M x k1
+    float* L_d;             // nq x P x R
+    uint32_t* L_id;         // nq x P x R
+    int32_t* sel_tap;       // nq x P x w or null
+};
+size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w);
+hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s);
+
+struct RankArgs {
+    int64_t nq;
+    int P, R, T, C;
+    uint32_t k1k2;
+    uint64_t H;
+    int hashed;               // H != (k1*k2)^P: slots may repeat within a query
+    const uint32_t* offsets;  // H+1
+    const float* L_d;
+    const uint32_t* L_id;
+    uint2* runs;              // nq x T   (.x = first position in ids/codes, .y = start in candidate list)
+    uint2* meta;              // nq       (.x = number of runs, .y = number of candidates)
+    // taps (nullable)
+    uint32_t* n_tuples;
+    uint16_t* tuples;         // nq x T x 4
+    float* tuple_keys;        // nq x T
+    uint64_t* slots;          // nq x T
+};
+// number of (r1, r2) pairs that can be among the first T of an R x R sum table
+int rank_region_size(int R, int T);
+size_t rank_lds_bytes(int P, int R, int T, int hashed);
+hipError_t launch_rank(const RankArgs& a, hipStream_t s);
+
+struct RerankArgs {
+    int64_t nq;
+    int M, k1, T, C, k;
+    int threads;              // workgroup size (multiple of 64)
+    const float* a;           // nq x M x k1
+    const CodeEntry* table;   // M x 256
+    const uint2* runs;
+    const uint2* meta;
+    const uint32_t* ids;
+    const uint8_t* codes;     // N x M
+    int64_t* out_ids;         // nq x k
+    float* out_dists;         // nq x k
+    // taps (nullable)
+    uint32_t* n_cand;
+    int64_t* cand_ids;        // nq x C
+    float* scores;            // nq x C
+    float* lut;               // nq x M x 256
+};
+size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads);
+hipError_t launch_rerank(const RerankArgs& a, hipStream_t s);
+
+// raise the dynamic-LDS ceiling of each kernel (once per device)
+hipError_t configure_traverse(size_t max_dynamic_lds);
+hipError_t configure_rank(size_t max_dynamic_lds);
+hipError_t configure_rerank(size_t max_dynamic_lds);
+
+}  // namespace pqt

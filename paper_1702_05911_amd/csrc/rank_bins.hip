@@ -1,0 +1,194 @@
+// Bin proposal (Sec. 3.2 "Bin Proposal Heuristic", Sec. 4): rank the combinations of the
+// per-part sorted level-2 lists by their summed distance -- the order the paper calls optimal
+// and re-sorts by on SIFT1B (Sec. 5.1) -- map each rank tuple to its bin number (Eq. 5),
+// hash it (modulo H, Sec. 4), drop repeated and empty slots, and lay the surviving runs of
+// the inverted lists end to end until the candidate budget C is reached.
+//
+// One workgroup per query.  The first T tuples of the order (sum, r1, r2) are found without
+// a priority queue: a pair (r1, r2) can only be among the first T if (r1+1)(r2+1) <= T,
+// because every pair that is component-wise smaller precedes it.  Only that hyperbolic
+// region is evaluated, packed as 64-bit keys (ordered sum bits, r1, r2) and sorted in LDS.
+#include "pqt_device.hpp"
+#include "pqt_kernels.hpp"
+
+namespace pqt {
+
+__host__ __device__ inline int region_row_count(int a, int R, int T) {
+    const int c = T / (a + 1);
+    return c < R ? c : R;
+}
+
+int rank_region_size(int R, int T) {
+    long n = 0;
+    for (int a = 0; a < R; ++a) n += region_row_count(a, R, T);
+    return (int)n;
+}
+
+struct RankLds {
+    int npad;   // sort width
+    int Tcap;   // examined tuples (upper bound)
+    int Tpad;
+    size_t off_Ld, off_Lid, off_keys, off_rowbase, off_len, off_o0, off_flag, off_part, off_dkeys, total;
+};
+
+static RankLds rank_layout(int P, int R, int T, int hashed) {
+    RankLds L;
+    long total_tuples = 1;
+    for (int p = 0; p < P; ++p) total_tuples = (total_tuples * R > (1L << 40)) ? (1L << 40) : total_tuples * R;
+    L.Tcap = (int)((long)T < total_tuples ? (long)T : total_tuples);
+    L.Tpad = next_pow2(L.Tcap);
+    int nreg = (P == 1) ? L.Tcap : rank_region_size(R, T);
+    L.npad = next_pow2(nreg);
+    size_t o = 0;
+    L.off_keys = o;    o += sizeof(unsigned long long) * L.npad;
+    L.off_dkeys = o;   o += hashed ? sizeof(unsigned long long) * L.Tpad : 0;
+    L.off_Ld = o;      o += sizeof(float) * P * R;
+    L.off_Lid = o;     o += sizeof(uint32_t) * P * R;
+    L.off_rowbase = o; o += sizeof(uint32_t) * (R + 1);
+    L.off_len = o;     o += sizeof(uint32_t) * L.Tcap;
+    L.off_o0 = o;      o += sizeof(uint32_t) * L.Tcap;
+    L.off_flag = o;    o += sizeof(uint32_t) * L.Tcap;
+    L.off_part = o;    o += sizeof(uint32_t) * kRankThreads;
+    L.total = o;
+    return L;
+}
+
+size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed).total; }
+
+struct RankOffsets {   // byte offsets handed to the kernel (computed once on the host)
+    int npad, Tcap, Tpad;
+    uint32_t keys, dkeys, Ld, Lid, rowbase, len, o0, flag, part;
+};
+
+__global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + L.keys);
+    unsigned long long* dkeys = reinterpret_cast<unsigned long long*>(smem + L.dkeys);
+    float* sLd = reinterpret_cast<float*>(smem + L.Ld);
+    uint32_t* sLid = reinterpret_cast<uint32_t*>(smem + L.Lid);
+    uint32_t* rowbase = reinterpret_cast<uint32_t*>(smem + L.rowbase);
+    uint32_t* slen = reinterpret_cast<uint32_t*>(smem + L.len);
+    uint32_t* so0 = reinterpret_cast<uint32_t*>(smem + L.o0);
+    uint32_t* sflag = reinterpret_cast<uint32_t*>(smem + L.flag);
+    uint32_t* part = reinterpret_cast<uint32_t*>(smem + L.part);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    constexpr int nwaves = kRankThreads / kWave;
+    const int64_t q = blockIdx.x;
+    const int P = g.P, R = g.R, T = g.T;
+    const int Tn = L.Tcap;                       // tuples examined: min(T, R^P)
+
+    for (int e = tid; e < P * R; e += kRankThreads) {
+        sLd[e] = g.L_d[q * P * R + e];
+        sLid[e] = g.L_id[q * P * R + e];
+    }
+    __syncthreads();
+
+    // ---- keys of the candidate tuples ------------------------------------------------------------
+    if (P == 1) {
+        for (int e = tid; e < L.npad; e += kRankThreads)
+            keys[e] = (e < Tn) ? (((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e) : ~0ull;
+        __syncthreads();                         // the list is already sorted by (distance, id)
+    } else {                                     // P == 2
+        for (int a = tid; a < R; a += kRankThreads) rowbase[a] = (uint32_t)region_row_count(a, R, T);
+        __syncthreads();
+        const uint32_t nreg = block_exclusive_scan(rowbase, R, part);
+        for (int a = wave; a < R; a += nwaves) {
+            const int cnt = region_row_count(a, R, T);
+            const uint32_t base = rowbase[a];
+            const float da = sLd[a];
+            for (int b = lane; b < cnt; b += kWave) {
+                const float s = da + sLd[R + b];
+                keys[base + b] = ((unsigned long long)mono_key(s) << 32) | ((unsigned)a << 16) | (unsigned)b;
+            }
+        }
+        for (int e = (int)nreg + tid; e < L.npad; e += kRankThreads) keys[e] = ~0ull;
+        bitonic_sort_lds(keys, L.npad, tid, kRankThreads);
+    }
+
+    // ---- tuple -> bin number -> slot -> run of the inverted list -----------------------------------
+    for (int t = tid; t < Tn; t += kRankThreads) {
+        const unsigned long long key = keys[t];
+        unsigned long long lin;
+        unsigned r1, r2 = 0;
+        if (P == 1) {
+            r1 = (unsigned)key & 0xffffu;
+            lin = sLid[r1];
+        } else {
+            r1 = ((unsigned)key >> 16) & 0xffffu;
+            r2 = (unsigned)key & 0xffffu;
+            lin = (unsigned long long)sLid[r1] * g.k1k2 + sLid[R + r2];
+        }
+        const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+        const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
+        so0[t] = o0;
+        slen[t] = o1 - o0;
+        if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;
+        if (g.tuples) {
+            uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
+            tp[0] = (uint16_t)r1; tp[1] = (uint16_t)r2; tp[2] = 0; tp[3] = 0;
+        }
+        if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
+    }
+    if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
+    __syncthreads();
+
+    // ---- a slot proposed earlier in the order is skipped (hashed indexes only) ----------------------
+    if (g.hashed) {
+        for (int e = Tn + tid; e < L.Tpad; e += kRankThreads) dkeys[e] = ~0ull;
+        bitonic_sort_lds(dkeys, L.Tpad, tid, kRankThreads);
+        for (int e = tid + 1; e < Tn; e += kRankThreads) {
+            const unsigned long long cur = dkeys[e], prev = dkeys[e - 1];
+            if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
+        }
+        __syncthreads();
+    }
+
+    // ---- lay the runs end to end, cut at C, compact ----------------------------------------------------
+    for (int t = tid; t < Tn; t += kRankThreads) sflag[t] = slen[t];
+    __syncthreads();
+    const uint32_t total = block_exclusive_scan(sflag, Tn, part);        // sflag[t] = start position
+    const uint32_t C = (uint32_t)g.C;
+    for (int t = tid; t < Tn; t += kRankThreads) {
+        const uint32_t start = sflag[t];
+        slen[t] = (slen[t] > 0 && start < C) ? 1u : 0u;                  // run is proposed
+    }
+    __syncthreads();
+    const uint32_t nruns = block_exclusive_scan(slen, Tn, part);        // slen[t] = run index
+    for (int t = tid; t < Tn; t += kRankThreads) {
+        const uint32_t start = sflag[t];
+        const uint32_t idx = slen[t];
+        const bool emit = (t + 1 < Tn ? slen[t + 1] : nruns) != idx;     // its flag was 1
+        if (emit) {
+            g.runs[(size_t)q * T + idx] = make_uint2(so0[t], start);
+            if (g.slots) {
+                const unsigned long long key = keys[t];
+                unsigned long long lin;
+                if (P == 1) lin = sLid[(unsigned)key & 0xffffu];
+                else lin = (unsigned long long)sLid[((unsigned)key >> 16) & 0xffffu] * g.k1k2 + sLid[R + ((unsigned)key & 0xffffu)];
+                g.slots[(size_t)q * T + idx] = g.hashed ? (lin % g.H) : lin;
+            }
+        }
+    }
+    if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
+}
+
+hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
+    if (a.nq <= 0) return hipSuccess;
+    const RankLds L = rank_layout(a.P, a.R, a.T, a.hashed);
+    RankOffsets o;
+    o.npad = L.npad; o.Tcap = L.Tcap; o.Tpad = L.Tpad;
+    o.keys = (uint32_t)L.off_keys; o.dkeys = (uint32_t)L.off_dkeys; o.Ld = (uint32_t)L.off_Ld;
+    o.Lid = (uint32_t)L.off_Lid; o.rowbase = (uint32_t)L.off_rowbase; o.len = (uint32_t)L.off_len;
+    o.o0 = (uint32_t)L.off_o0; o.flag = (uint32_t)L.off_flag; o.part = (uint32_t)L.off_part;
+    hipLaunchKernelGGL(rank_kernel, dim3((unsigned)a.nq), dim3(kRankThreads), L.total, s, a, o);
+    return hipGetLastError();
+}
+
+hipError_t configure_rank(size_t max_dynamic_lds) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+}
+
+}  // namespace pqt

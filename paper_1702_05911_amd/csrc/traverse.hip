@@ -1,0 +1,189 @@
+// Tree traversal (Sec. 3.2 "Tree Traversal"): level-1 distances of every query sub-part to
+// all k1 centroids (Eq. 6, kept per re-rank sub-part as Sec. 3.3's last paragraph asks),
+// the w closest clusters per part, the level-2 distances to their children, and the sorted
+// (distance, leaf) lists per part.
+//
+// One workgroup of 256 threads handles a tile of 16 queries.
+//   * level 1 is a dense contraction [16 x ds] . [ds x k1] per sub-part on the matrix cores
+//     (v_mfma_f32_16x16x4_f32, fp32 in, fp32 accumulate) with ||q||^2 + ||c||^2 - 2 q.c;
+//   * the per-part distance is the sum of its sub-part distances in ascending sub-part order;
+//   * cluster selection ranks the k1 keys (distance, id) by counting;
+//   * level 2 is a gathered set of small matrix-vector products (every query picks its own
+//     w clusters), done on the vector ALU with direct squared differences: one wavefront
+//     per (query, part), one lane per child;
+//   * each list is sorted as 64-bit keys (ordered distance bits, leaf id) by a bitonic
+//     network in LDS.
+#include "pqt_device.hpp"
+#include "pqt_kernels.hpp"
+
+namespace pqt {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct TraverseLds {
+    int qs;          // row stride of the query tile (floats)
+    int k1p;         // k1 rounded up to a multiple of 16
+    int Rpad;        // R rounded up to a power of two
+    size_t off_q, off_a, off_d1, off_qn, off_sel, off_key, total;
+};
+
+__host__ __device__ inline TraverseLds traverse_layout(int D, int P, int k1, int k2, int M, int w) {
+    TraverseLds L;
+    L.qs = D + 1;
+    L.k1p = (k1 + 15) & ~15;
+    L.Rpad = next_pow2(w * k2);
+    size_t o = 0;
+    L.off_q = o;   o += sizeof(float) * kQueryTile * L.qs;
+    L.off_a = o;   o += sizeof(float) * kQueryTile * M * k1;
+    L.off_d1 = o;  o += sizeof(float) * kQueryTile * P * k1;
+    L.off_qn = o;  o += sizeof(float) * kQueryTile * M;
+    L.off_sel = o; o += sizeof(int) * kQueryTile * P * w;
+    o = (o + 7) & ~size_t(7);
+    L.off_key = o; o += sizeof(unsigned long long) * (kTraverseThreads / kWave) * L.Rpad;
+    L.total = o;
+    return L;
+}
+
+size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w) {
+    return traverse_layout(D, P, k1, k2, M, w).total;
+}
+
+__global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs g) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const TraverseLds L = traverse_layout(g.D, g.P, g.k1, g.k2, g.M, g.w);
+    float* sq = reinterpret_cast<float*>(smem + L.off_q);
+    float* sa = reinterpret_cast<float*>(smem + L.off_a);
+    float* sd1 = reinterpret_cast<float*>(smem + L.off_d1);
+    float* sqn = reinterpret_cast<float*>(smem + L.off_qn);
+    int* ssel = reinterpret_cast<int*>(smem + L.off_sel);
+    unsigned long long* skey = reinterpret_cast<unsigned long long*>(smem + L.off_key);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    constexpr int nwaves = kTraverseThreads / kWave;
+    const int D = g.D, P = g.P, k1 = g.k1, k2 = g.k2, M = g.M, w = g.w;
+    const int dp = D / P, ds = D / M, per = M / P, R = w * k2;
+    const int64_t q0 = (int64_t)blockIdx.x * kQueryTile;
+
+    // ---- stage the query tile in LDS (rows past nq are zero) -------------------------------
+    for (int e = tid; e < kQueryTile * D; e += kTraverseThreads) {
+        int q = e / D, d = e - q * D;
+        int64_t gq = q0 + q;
+        sq[q * L.qs + d] = (gq < g.nq) ? g.queries[gq * D + d] : 0.0f;
+    }
+    __syncthreads();
+    for (int e = tid; e < kQueryTile * M; e += kTraverseThreads) {
+        int q = e / M, m = e - q * M;
+        const float* row = sq + q * L.qs + m * ds;
+        float s = 0.0f;
+        for (int d = 0; d < ds; ++d) s = fmaf(row[d], row[d], s);
+        sqn[e] = s;
+    }
+    __syncthreads();
+
+    // ---- level 1 on the matrix cores: one job = (sub-part m, tile of 16 centroids) -------------
+    // A operand: lane holds A[row = lane%16][k = lane/16]; B operand: B[k = lane/16][col = lane%16];
+    // result: lane holds D[row = 4*(lane/16) + r][col = lane%16] in register r.
+    {
+        const int ntiles = L.k1p / 16;
+        const int row = lane & 15, kq = lane >> 4;
+        for (int job = wave; job < M * ntiles; job += nwaves) {
+            const int m = job / ntiles, nt = job - m * ntiles;
+            const int p = m / per, lo = m * ds - p * dp;
+            const int col = nt * 16 + row;            // centroid this lane feeds as B column
+            const float* arow = sq + row * L.qs + m * ds;
+            const float* brow = g.C1 + ((size_t)p * k1 + (col < k1 ? col : 0)) * dp + lo;
+            v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+            for (int kk = 0; kk < ds; kk += 4) {
+                const int kd = kk + kq;
+                const float av = (kd < ds) ? arow[kd] : 0.0f;
+                const float bv = (kd < ds && col < k1) ? brow[kd] : 0.0f;
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc, 0, 0, 0);
+            }
+            if (col < k1) {
+                const float cn = g.c1n[m * k1 + col];
+                for (int r = 0; r < 4; ++r) {
+                    const int q = 4 * kq + r;
+                    const float v = (sqn[q * M + m] + cn) - 2.0f * acc[r];
+                    sa[(q * M + m) * k1 + col] = v;
+                    const int64_t gq = q0 + q;
+                    if (gq < g.nq) g.a[(gq * M + m) * k1 + col] = v;
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- per-part distances and the w closest clusters ------------------------------------------
+    for (int e = tid; e < kQueryTile * P * k1; e += kTraverseThreads) {
+        const int i = e % k1, qp = e / k1, p = qp % P, q = qp / P;
+        float s = sa[(q * M + p * per) * k1 + i];
+        for (int m = p * per + 1; m < (p + 1) * per; ++m) s += sa[(q * M + m) * k1 + i];
+        sd1[e] = s;
+    }
+    __syncthreads();
+    for (int e = tid; e < kQueryTile * P * k1; e += kTraverseThreads) {
+        const int i = e % k1, qp = e / k1;
+        const float* row = sd1 + qp * k1;
+        const unsigned long long me = ((unsigned long long)mono_key(row[i]) << 32) | (unsigned)i;
+        int rank = 0;
+        for (int j = 0; j < k1; ++j) {
+            const unsigned long long other = ((unsigned long long)mono_key(row[j]) << 32) | (unsigned)j;
+            rank += (other < me) ? 1 : 0;
+        }
+        if (rank < w) {
+            ssel[qp * w + rank] = i;
+            const int64_t gq = q0 + qp / P;
+            if (g.sel_tap && gq < g.nq) g.sel_tap[(gq * P + (qp % P)) * w + rank] = i;
+        }
+    }
+    __syncthreads();
+
+    // ---- level 2: one wavefront per (query, part), one lane per child ---------------------------
+    unsigned long long* mykeys = skey + (size_t)wave * L.Rpad;
+    for (int job = wave; job < kQueryTile * P; job += nwaves) {   // same trip count for every wave
+        const int q = job / P, p = job - q * P;
+        const float* yp = sq + q * L.qs + p * dp;
+        for (int e = lane; e < L.Rpad; e += kWave) {
+            unsigned long long key = ~0ull;
+            if (e < R) {
+                const int s = e / k2, j = e - s * k2;
+                const int i = ssel[(q * P + p) * w + s];
+                const float* c = g.C2 + (((size_t)p * k1 + i) * k2 + j) * dp;
+                float acc = 0.0f;
+                for (int d = 0; d < dp; ++d) {
+                    const float diff = yp[d] - c[d];
+                    acc = fmaf(diff, diff, acc);
+                }
+                key = ((unsigned long long)mono_key(acc) << 32) | (unsigned)(i * k2 + j);
+            }
+            mykeys[e] = key;
+        }
+        bitonic_sort_lds(mykeys, L.Rpad, lane, kWave);
+        const int64_t gq = q0 + q;
+        if (gq < g.nq) {
+            for (int e = lane; e < R; e += kWave) {
+                const unsigned long long key = mykeys[e];
+                g.L_d[(gq * P + p) * R + e] = mono_inv((uint32_t)(key >> 32));
+                g.L_id[(gq * P + p) * R + e] = (uint32_t)key;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s) {
+    if (a.nq <= 0) return hipSuccess;
+    const size_t lds = traverse_lds_bytes(a.D, a.P, a.k1, a.k2, a.M, a.w);
+    const unsigned blocks = (unsigned)((a.nq + kQueryTile - 1) / kQueryTile);
+    hipLaunchKernelGGL(traverse_kernel, dim3(blocks), dim3(kTraverseThreads), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t configure_traverse(size_t max_dynamic_lds) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(traverse_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+}
+
+}  // namespace pqt

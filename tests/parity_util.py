@@ -1,0 +1,107 @@
+"""Stage-by-stage comparison of the HIP path (through the C ABI's debug taps) with the oracle.
+
+Float stages (level-1 distances, level-2 distances, LUT, scores, output distances) are
+compared within a tolerance.  Discrete stages are replayed: the oracle's selection /
+sorting / bin ordering / gathering / top-k logic is run ON THE GPU'S OWN fp32 VALUES (in
+fp32, the kernel's precision) and must reproduce the GPU's decisions bit for bit.
+"""
+import numpy as np
+
+from oracle import pqt_query as Q
+
+RTOL = 1e-4          # relative tolerance on fp32 distances
+ATOL_SCALE = 2e-6    # absolute floor, times (||y||^2 + max ||c||^2): fp32 cancellation in ||q||^2+||c||^2-2q.c
+
+
+def close(g, o, scale):
+    g = np.asarray(g, dtype=np.float64)
+    o = np.asarray(o, dtype=np.float64)
+    return np.all(np.abs(g - o) <= RTOL * np.abs(o) + ATOL_SCALE * scale)
+
+
+def to_np(t):
+    return t.detach().cpu().numpy()
+
+
+def check_query_stages(ix, y, taps, q, k, w, T, C, out_ids, out_dists, exact=False):
+    """ix: oracle PQTIndex (same file the GPU loaded); taps: dict of numpy arrays for the batch;
+    q: row in the batch.  Raises AssertionError naming the stage.  Returns the oracle trace of the
+    pure float64 run."""
+    P, M, k1, k2 = ix.P, ix.M, ix.k1, ix.k2
+    R = w * k2
+    y64 = np.asarray(y, dtype=np.float64)
+    scale = float(np.dot(y64, y64) + np.max(np.sum(ix.C1.astype(np.float64) ** 2, axis=2)) * P)
+    tr = Q.query(ix, y, k, w, T=T, C=C)
+
+    # ---- S1 level-1 sub-part distances (float) ---------------------------------------------------
+    a_g = taps["a"][q]
+    if exact:
+        assert np.array_equal(a_g.astype(np.float64), tr.a), "S1 a (exact)"
+    assert close(a_g, tr.a, scale), f"S1 a: max abs err {np.max(np.abs(a_g - tr.a))}"
+
+    # ---- S2 selection replayed on the GPU's a (fp32 sums, ascending sub-part) -------------------------
+    d1_g = Q.part_distances(a_g.astype(np.float32), P)
+    sel_r = Q.select_clusters(d1_g, w)
+    assert np.array_equal(sel_r, taps["sel"][q]), "S2 sel replay"
+
+    # ---- S3 level-2 lists ---------------------------------------------------------------------------
+    Ld_g, Lid_g = taps["L_d"][q], taps["L_id"][q].astype(np.int64)
+    d2_o, ids_o = Q.level2_distances(y, ix.C2, sel_r)
+    for p in range(P):
+        assert sorted(Lid_g[p].tolist()) == sorted(ids_o[p].tolist()), "S3 leaf id set"
+        lookup = dict(zip(ids_o[p].tolist(), d2_o[p].tolist()))
+        want = np.array([lookup[i] for i in Lid_g[p].tolist()])
+        if exact:
+            assert np.array_equal(Ld_g[p].astype(np.float64), want), "S3 d2 (exact)"
+        assert close(Ld_g[p], want, scale), "S3 d2"
+        o = Q.order_by_value_then_id(Ld_g[p], Lid_g[p])
+        assert np.array_equal(o, np.arange(R)), "S3 list not sorted by (d2, id)"
+
+    # ---- S4 bin order replayed on the GPU's lists (fp32 sums) ------------------------------------------
+    tup_r, keys_r = Q.bin_order([Ld_g[p].astype(np.float32) for p in range(P)], T)
+    nt = int(taps["n_tuples"][q])
+    assert nt == tup_r.shape[0], "S4 number of tuples"
+    assert np.array_equal(taps["tuples"][q][:nt, :P].astype(np.int64), tup_r), "S4 tuple order"
+    assert np.array_equal(taps["tuple_keys"][q][:nt], keys_r.astype(np.float32)), "S4 tuple keys"
+    slots_r = Q.propose_bins(tup_r, Lid_g, k1 * k2, ix.H, ix.offsets)
+    pos_r = Q.gather_candidates(slots_r, ix.offsets, C)
+    # slots that contribute at least one candidate before the cut
+    lens = ix.offsets[slots_r + 1].astype(np.int64) - ix.offsets[slots_r].astype(np.int64) if slots_r.size else np.zeros(0, np.int64)
+    used = int(np.sum(np.cumsum(lens) - lens < C))
+    ns = int(taps["n_slots"][q])
+    assert ns == used, f"S4 number of proposed slots {ns} vs {used}"
+    assert np.array_equal(taps["slots"][q][:ns], slots_r[:ns]), "S4 proposed slots"
+
+    # ---- S5 candidate list ---------------------------------------------------------------------------
+    nc = int(taps["n_cand"][q])
+    assert nc == pos_r.shape[0], "S5 candidate count"
+    cand_r = ix.ids[pos_r].astype(np.int64)
+    assert np.array_equal(taps["cand_ids"][q][:nc], cand_r), "S5 candidate ids"
+
+    # ---- S6 LUT (float), S7 scores replayed on the GPU's LUT (fp32, ascending m) ------------------------
+    lut_g = taps["lut"][q]
+    lut_o = Q.build_lut(a_g.astype(np.float64), ix.tbl_i, ix.tbl_j, ix.tbl_lam, ix.cc.astype(np.float64))
+    assert close(lut_g, lut_o, scale), "S6 LUT vs oracle formula on the GPU's a"
+    assert close(lut_g, tr.lut, scale), "S6 LUT vs oracle"
+    if exact:
+        assert np.array_equal(lut_g.astype(np.float64), tr.lut), "S6 LUT (exact)"
+    sc_r = Q.score_codes(lut_g.astype(np.float32), ix.codes[pos_r])
+    assert np.array_equal(taps["scores"][q][:nc], sc_r), "S7 scores replay"
+
+    # ---- S8 top-k replayed on the GPU's scores -------------------------------------------------------------
+    ids_r, d_r = Q.top_k(sc_r, cand_r, k)
+    assert np.array_equal(out_ids[q], ids_r), "S8 ids replay"
+    assert np.array_equal(out_dists[q], d_r.astype(np.float32)), "S8 distances replay"
+    return tr
+
+
+def end_to_end_agreement(tr, out_ids_q, out_dists_q, scale, margin_thr=1e-5):
+    """Compares the final answer with the pure float64 oracle run.  Returns (ids_equal, decided):
+    `decided` says whether every set-changing decision of the oracle had a relative margin above
+    margin_thr, in which case the ids MUST be equal."""
+    same = bool(np.array_equal(out_ids_q, tr.out_ids))
+    if same:
+        have = tr.out_ids >= 0
+        assert close(out_dists_q[have], tr.out_dists[have], scale), "output distances"
+    decided = tr.margins["min"] > margin_thr
+    return same, decided

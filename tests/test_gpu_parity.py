@@ -1,0 +1,260 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bit-exact on selected clusters, bin order, proposed slots, candidate lists and
+top-k ids (by replaying the oracle's discrete logic on the GPU's fp32 values); fp32 distances
+within 1e-4 relative (plus the cancellation floor stated in parity_util)."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+sys.path.insert(0, os.path.dirname(__file__))
+import parity_util as PU  # noqa: E402
+from oracle import pqt_build as B  # noqa: E402
+from oracle import pqt_index_io as IO  # noqa: E402
+from oracle import pqt_query as Q  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pqt():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: no silent fallback")
+    import paper_1702_05911_amd.binding as binding
+    return binding
+
+
+def _run_debug(pqt, gix, Y, k, w):
+    import torch
+    yq = torch.from_numpy(np.ascontiguousarray(Y)).cuda()
+    ids, dists, taps = pqt.pqt_query_batch_debug(gix, yq, k, w)
+    torch.cuda.synchronize()
+    ids2, dists2 = pqt.pqt_query_batch(gix, yq, k, w)
+    torch.cuda.synchronize()
+    assert torch.equal(ids, ids2) and torch.equal(dists.view(torch.int32), dists2.view(torch.int32)), \
+        "debug and plain entry points disagree"
+    return PU.to_np(ids), PU.to_np(dists), {n: PU.to_np(t) for n, t in taps.items()}
+
+
+def _stagewise(pqt, ix, path, Y, k, w, T, C, exact=False, must_match_all=False):
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        pqt.pqt_set_budget(gix, T, C)
+        ids, dists, taps = _run_debug(pqt, gix, Y, k, w)
+    finally:
+        pqt.pqt_index_free(gix)
+    same = decided = 0
+    for q in range(Y.shape[0]):
+        print(f"query {q}", flush=True)
+        tr = PU.check_query_stages(ix, Y[q], taps, q, k, w, T, C, ids, dists, exact=exact)
+        y64 = Y[q].astype(np.float64)
+        scale = float(np.dot(y64, y64) + np.max(np.sum(ix.C1.astype(np.float64) ** 2, axis=2)) * ix.P)
+        s, d = PU.end_to_end_agreement(tr, ids[q], dists[q], scale)
+        if exact or must_match_all:
+            assert s, f"query {q}: ids differ from the float64 oracle"
+        if exact:
+            assert np.array_equal(dists[q].astype(np.float64), tr.out_dists), f"query {q}: distances not bit-exact"
+        if d:
+            assert s, f"query {q}: all decision margins > 1e-5 but ids differ from the oracle"
+        same += s
+        decided += d
+    return same, decided
+
+
+def test_tiny_stagewise(pqt, tiny, tmp_path):
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    same, decided = _stagewise(pqt, ix, path, Y, cfg.k, cfg.w, cfg.T, cfg.C)
+    print(f"tiny: {same}/{cfg.nq} queries identical to the float64 oracle end to end, {decided} decided by margin")
+    assert same >= 0.9 * cfg.nq
+
+
+def test_tiny_ragged_batches_and_determinism(pqt, tiny, tmp_path):
+    import torch
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        yq = torch.from_numpy(Y).cuda()
+        full_ids, full_d = pqt.pqt_query_batch(gix, yq, cfg.k, cfg.w)
+        torch.cuda.synchronize()
+        for n in (1, 15, 16, 17, 33):
+            ids, d = pqt.pqt_query_batch(gix, yq[:n].contiguous(), cfg.k, cfg.w)
+            torch.cuda.synchronize()
+            assert torch.equal(ids, full_ids[:n]) and torch.equal(d.view(torch.int32), full_d[:n].view(torch.int32))
+        ids0, d0 = pqt.pqt_query_batch(gix, yq[:0].contiguous(), cfg.k, cfg.w)
+        assert ids0.shape == (0, cfg.k)
+        info = pqt.pqt_index_info(gix)
+        assert (info["N"], info["D"], info["P"], info["k1"], info["k2"], info["M"], info["H"]) == \
+            (cfg.N, cfg.D, cfg.P, cfg.k1, cfg.k2, cfg.M, cfg.H)
+    finally:
+        pqt.pqt_index_free(gix)
+
+
+def test_tiny_exhaustive_visits_everything(pqt, tiny, tmp_path):
+    """w = k1, T = K, C >= N: every bin is visited, the candidate list is the whole database."""
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    Ys = Y[:6]
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        pqt.pqt_set_budget(gix, ix.K, cfg.N)
+        ids, dists, taps = _run_debug(pqt, gix, Ys, 10, cfg.k1)
+    finally:
+        pqt.pqt_index_free(gix)
+    for q in range(Ys.shape[0]):
+        assert int(taps["n_cand"][q]) == cfg.N
+        assert np.array_equal(np.sort(taps["cand_ids"][q]), np.arange(cfg.N))
+        PU.check_query_stages(ix, Ys[q], taps, q, 10, cfg.k1, ix.K, cfg.N, ids, dists)
+
+
+def _exact_arithmetic_index(N=3000, seed=5):
+    """Integer codebooks, integer data and dyadic lambdas: every fp32 operation of the path is
+    exact, so the GPU must equal the float64 oracle bit for bit, distances included."""
+    from workloads import small_integer_vectors
+    rng = np.random.default_rng(seed)
+    D, P, k1, k2, M = 16, 2, 4, 2, 4
+    dp = D // P
+    C1 = rng.integers(0, 8, size=(P, k1, dp)).astype(np.float32)
+    C2 = np.clip(C1[:, :, None, :] + rng.integers(-1, 2, size=(P, k1, k2, dp)), 0, 7).astype(np.float32)
+    lams = [0.0, 0.25, 0.5, 0.75, 1.0, -0.25, 1.25, 0.125]
+    ent = [(i, j, lam) for i in range(k1) for j in range(i + 1, k1) for lam in lams]
+    ti = np.array([[ent[c % len(ent)][0] for c in range(256)]] * M, np.uint8)
+    tj = np.array([[ent[c % len(ent)][1] for c in range(256)]] * M, np.uint8)
+    tl = np.array([[ent[c % len(ent)][2] for c in range(256)]] * M, np.float32)
+    X = small_integer_vectors(N, D, 0, 8, seed=seed, clusters=40)
+    Y = small_integer_vectors(64, D, 0, 8, seed=seed + 1, clusters=40)
+    ix = B.build_index(X, P, k1, k2, M, T=64, C=512, codebooks=(C1, C2), line_table=(ti, tj, tl))
+    return ix, X, Y
+
+
+def test_exact_arithmetic_index_is_bit_exact(pqt, tmp_path):
+    ix, X, Y = _exact_arithmetic_index()
+    path = str(tmp_path / "exact.pqt")
+    IO.write_index(path, ix)
+    for (k, w, T, C) in ((10, 2, 16, 200), (50, 4, 64, 512), (7, 1, 4, 64)):
+        same, _ = _stagewise(pqt, ix, path, Y, k, w, T, C, exact=True)
+        assert same == Y.shape[0]
+
+
+def test_duplicate_database_ties_broken_by_id(pqt, tmp_path):
+    """All vectors identical: one bin, every score tied -> the k smallest ids."""
+    ix, X, Y = _exact_arithmetic_index(N=64)
+    Xd = np.repeat(X[:1], 1500, axis=0)
+    ixd = B.build_index(Xd, ix.P, ix.k1, ix.k2, ix.M, T=16, C=1000, codebooks=(ix.C1, ix.C2),
+                        line_table=(ix.tbl_i, ix.tbl_j, ix.tbl_lam))
+    path = str(tmp_path / "dup.pqt")
+    IO.write_index(path, ixd)
+    same, _ = _stagewise(pqt, ixd, path, np.ascontiguousarray(Xd[:3] + 0), 100, ix.k1, 16, 1000, exact=True)
+    assert same == 3
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        import torch
+        ids, d = pqt.pqt_query_batch(gix, torch.from_numpy(Xd[:1].copy()).cuda(), 100, ix.k1)
+        assert ids[0].tolist() == list(range(100))
+    finally:
+        pqt.pqt_index_free(gix)
+
+
+def test_fewer_candidates_than_k_pads(pqt, tiny, tmp_path):
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    Xs = X[:40]
+    ixs = B.build_index(Xs, cfg.P, cfg.k1, cfg.k2, cfg.M, T=4, C=64, codebooks=(ix.C1, ix.C2),
+                        line_table=(ix.tbl_i, ix.tbl_j, ix.tbl_lam))
+    p2 = str(tmp_path / "small.pqt")
+    IO.write_index(p2, ixs)
+    gix = pqt.pqt_index_load(p2, 0)
+    try:
+        ids, dists, taps = _run_debug(pqt, gix, Y[:20], 50, 1)
+    finally:
+        pqt.pqt_index_free(gix)
+    for q in range(20):
+        PU.check_query_stages(ixs, Y[q], taps, q, 50, 1, 4, 64, ids, dists)
+        nc = int(taps["n_cand"][q])
+        assert nc < 50 and np.all(ids[q][nc:] == -1) and np.all(np.isinf(dists[q][nc:]))
+
+
+def test_hashed_index_dedupes_slots(pqt, tiny, tmp_path):
+    cfg, X, Y, ix = tiny
+    ixh = B.build_index(X[:3000], cfg.P, cfg.k1, cfg.k2, cfg.M, H=97, T=256, C=1024, codebooks=(ix.C1, ix.C2),
+                        line_table=(ix.tbl_i, ix.tbl_j, ix.tbl_lam))
+    path = str(tmp_path / "hashed.pqt")
+    IO.write_index(path, ixh)
+    _stagewise(pqt, ixh, path, Y[:24], 10, 4, 256, 1024)
+    _stagewise(pqt, ixh, path, Y[:8], 10, cfg.k1, 1024, 3000)
+
+
+def test_single_part_index(pqt, tmp_path, rng):
+    X = rng.normal(size=(2000, 8)).astype(np.float32)
+    Y = rng.normal(size=(20, 8)).astype(np.float32)
+    ix1 = B.build_index(X, P=1, k1=8, k2=2, M=2, T=16, C=512, iters=5)
+    path = str(tmp_path / "p1.pqt")
+    IO.write_index(path, ix1)
+    _stagewise(pqt, ix1, path, Y, 10, 3, 16, 512)
+    _stagewise(pqt, ix1, path, Y, 10, 8, 3, 100)
+
+
+def test_wide_selection_two_elements_per_lane(pqt, tmp_path, rng):
+    """R = w*k2 = 128 > 64 lanes, k1 = 32 (two MFMA column tiles), ragged last tile."""
+    X = rng.random(size=(6000, 24)).astype(np.float32)
+    Y = rng.random(size=(19, 24)).astype(np.float32)
+    ixw = B.build_index(X, P=2, k1=32, k2=16, M=6, T=300, C=700, iters=4)
+    path = str(tmp_path / "wide.pqt")
+    IO.write_index(path, ixw)
+    _stagewise(pqt, ixw, path, Y, 20, 8, 300, 700)
+
+
+def test_error_codes(pqt, tiny, tmp_path):
+    import torch
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    with pytest.raises(pqt.PqtError) as e:
+        pqt.pqt_index_load(str(tmp_path / "missing.pqt"), 0)
+    assert e.value.code == pqt.PQT_EIO
+    bad = str(tmp_path / "bad.pqt")
+    with open(path, "rb") as f:
+        blob = f.read()
+    with open(bad, "wb") as f:
+        f.write(b"NOTANIDX" + blob[8:])
+    with pytest.raises(pqt.PqtError) as e:
+        pqt.pqt_index_load(bad, 0)
+    assert e.value.code == pqt.PQT_EFORMAT
+    with open(bad, "wb") as f:
+        f.write(blob[:-100])
+    with pytest.raises(pqt.PqtError) as e:
+        pqt.pqt_index_load(bad, 0)
+    assert e.value.code == pqt.PQT_EFORMAT
+    broken = IO.read_index(path)
+    broken.offsets = broken.offsets.copy()
+    broken.offsets[5] = broken.offsets[-1] + 7          # not monotone
+    IO.write_index(bad, broken)
+    with pytest.raises(pqt.PqtError) as e:
+        pqt.pqt_index_load(bad, 0)
+    assert e.value.code == pqt.PQT_EFORMAT
+
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        yq = torch.from_numpy(Y).cuda()
+        for k, w in ((0, 2), (cfg.C + 1, 2), (10, 0), (10, cfg.k1 + 1)):
+            with pytest.raises(pqt.PqtError) as e:
+                pqt.pqt_query_batch(gix, yq, k, w)
+            assert e.value.code == pqt.PQT_EINVAL
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_set_budget(gix, 0, 10)
+        assert e.value.code == pqt.PQT_EINVAL
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_set_budget(gix, 10, 1 << 20)
+        assert e.value.code == pqt.PQT_EINVAL
+        ids, d = pqt.pqt_query_batch(gix, yq, cfg.k, cfg.w)     # still usable after errors
+        torch.cuda.synchronize()
+        assert ids.shape == (cfg.nq, cfg.k)
+    finally:
+        pqt.pqt_index_free(gix)
