@@ -347,7 +347,8 @@ def _rel_gap(lo, hi):
     return (float(hi) - float(lo)) / scale
 
 
-def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_method="fullsort"):
+def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_method="fullsort",
+          with_margins=True):
     """One query through O1..O8.  With exact_rerank (needs the raw vectors X) the scores
     of O6-O7 are replaced by exact squared distances (step (3) of the PQ pipelines in
     Sec. 1; the paper's PQT_2 of Table 1)."""
@@ -370,7 +371,8 @@ def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_meth
         tr.lut = build_lut(tr.a, index.tbl_i, index.tbl_j, index.tbl_lam, index.cc.astype(np.float64))
         tr.scores = score_codes(tr.lut, index.codes[tr.cand_pos])
     tr.out_ids, tr.out_dists = top_k(tr.scores, tr.cand_ids, k)
-    tr.margins = decision_margins(index, tr, k, w, T, C)
+    if with_margins:
+        tr.margins = decision_margins(index, tr, k, w, T, C)
     return tr
 
 

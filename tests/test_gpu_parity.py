@@ -258,3 +258,74 @@ def test_error_codes(pqt, tiny, tmp_path):
         assert ids.shape == (cfg.nq, cfg.k)
     finally:
         pqt.pqt_index_free(gix)
+
+
+# ---- full size, in the launch configuration bench.py times -------------------------------------------
+@pytest.fixture(scope="module")
+def sift_full(pqt, tmp_path_factory):
+    """SIFT-shaped 1M x 128 database, 10,000 queries, index built by the package's builder on the
+    GPU (the index is input data for both sides; its validity is checked below)."""
+    import torch
+    from workloads import CONFIGS, sift_like_tables, sift_like_torch
+    from paper_1702_05911_amd import builder
+    cfg = CONFIGS["sift"]
+    tables = sift_like_tables(cfg.D)
+    dev = torch.device("cuda", 0)
+    X = sift_like_torch(0, cfg.N, d=cfg.D, seed=cfg.data_seed, tables=tables, device=dev)
+    Y = sift_like_torch(0, cfg.nq, d=cfg.D, seed=cfg.query_seed, tables=tables, device=dev)
+    path = str(tmp_path_factory.mktemp("sift") / "sift.pqt")
+    builder.build_index(path, X, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M, H=cfg.H, T=cfg.T, C=cfg.C,
+                        train_n=cfg.train_n, device=dev)
+    return cfg, X.cpu().numpy(), Y.cpu().numpy(), path, IO.read_index(path)
+
+
+def test_sift_full_size_index_is_valid(sift_full):
+    cfg, X, Y, path, ix = sift_full
+    off = ix.offsets.astype(np.int64)
+    assert off[0] == 0 and off[-1] == cfg.N and np.all(np.diff(off) >= 0)
+    assert np.array_equal(np.sort(ix.ids), np.arange(cfg.N, dtype=np.uint32))
+    rng = np.random.default_rng(0)
+    mism = 0
+    for t in rng.integers(0, cfg.N, size=200):
+        slot = int(np.searchsorted(off, t, side="right")) - 1
+        x = X[ix.ids[t]]
+        mism += slot != B.bin_slot(x, ix.C1, ix.C2, ix.H)
+        mism += not np.array_equal(ix.codes[t], B.encode_vector(x, ix.C1, ix.M, ix.tbl_i, ix.tbl_j, ix.tbl_lam))
+        if t > 0 and np.searchsorted(off, t - 1, side="right") - 1 == slot:
+            assert ix.ids[t - 1] < ix.ids[t]
+    assert mism <= 4          # the fp32 builder may settle a near-tie differently from float64
+
+
+@pytest.mark.parametrize("w", [8, 1])
+def test_sift_full_size_parity(pqt, sift_full, w):
+    import torch
+    cfg, X, Y, path, ix = sift_full
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        ids, dists, taps = _run_debug(pqt, gix, Y, cfg.k, w)
+    finally:
+        pqt.pqt_index_free(gix)
+    # properties on every query
+    nc = taps["n_cand"].astype(np.int64)
+    assert np.all(nc <= cfg.C) and np.all(nc > 0)
+    for q in range(cfg.nq):
+        n = int(nc[q])
+        sc, cid = taps["scores"][q][:n], taps["cand_ids"][q][:n]
+        o = np.lexsort((cid, sc))[:cfg.k]
+        assert np.array_equal(ids[q][:len(o)], cid[o]), f"query {q}: top-k is not the k smallest (score, id)"
+        assert np.array_equal(dists[q][:len(o)], sc[o])
+        assert len(set(cid.tolist())) == n
+    # the oracle, stage by stage, on a sample
+    same = decided = 0
+    sample = list(range(0, cfg.nq, 417))
+    for q in sample:
+        print(f"w={w} query {q}", flush=True)
+        tr = PU.check_query_stages(ix, Y[q], taps, q, cfg.k, w, cfg.T, cfg.C, ids, dists)
+        y64 = Y[q].astype(np.float64)
+        scale = float(np.dot(y64, y64) + np.max(np.sum(ix.C1.astype(np.float64) ** 2, axis=2)) * ix.P)
+        s, d = PU.end_to_end_agreement(tr, ids[q], dists[q], scale)
+        assert s or not d, f"query {q}: margins above threshold but ids differ"
+        same += s
+        decided += d
+    print(f"sift w={w}: {same}/{len(sample)} sampled queries identical to the float64 oracle, {decided} decided")
+    assert same >= 0.8 * len(sample)

@@ -300,3 +300,13 @@ def test_index_file_roundtrip(tiny, tmp_path):
         f.truncate(os.path.getsize(path) - 10)
     with pytest.raises(ValueError):
         IO.read_index(path)
+
+
+# ---- input generators: the torch port of the SIFT-shaped stream is bit-identical ----------------
+def test_sift_like_numpy_and_torch_agree():
+    from workloads import sift_like, sift_like_torch
+    a = sift_like(987654, 3000, seed=1)
+    b = sift_like_torch(987654, 3000, seed=1).numpy()
+    assert np.array_equal(a, b)
+    assert a.min() >= 0 and a.max() <= 255 and np.array_equal(a, np.round(a))
+    assert np.array_equal(sift_like(987654 + 100, 50, seed=1), a[100:150])     # counter based: any chunk

@@ -10,6 +10,7 @@ from .synth import (  # noqa: F401
     tiny_mixture,
     sift_like,
     sift_like_tables,
+    sift_like_torch,
     gist_like,
     small_integer_vectors,
 )

@@ -151,3 +151,53 @@ def small_integer_vectors(n, d, lo=0, hi=8, seed=0, clusters=0):
         x = cen[rng.integers(0, clusters, size=n)] + rng.integers(-1, 2, size=(n, d))
         x = np.clip(x, lo, hi - 1)
     return np.ascontiguousarray(x, dtype=np.float32)
+
+
+# --------------------------------------------------------------------------
+# the same SIFT-shaped stream computed with torch integer ops (any device)
+# --------------------------------------------------------------------------
+def sift_like_torch(start, count, d=128, seed=0, tables=None, device="cpu", chunk=1 << 20):
+    """Bit-identical to sift_like(): int64 tensors hold the 32-bit hash state (products wrap
+    modulo 2**64, the low 32 bits are what the uint64 NumPy version keeps)."""
+    import torch
+    if tables is None:
+        tables = sift_like_tables(d)
+    dev = torch.device(device)
+    centres = torch.from_numpy(tables["centres"]).to(dev)
+    basis = torch.from_numpy(tables["basis"]).to(dev)
+    thr = torch.from_numpy(tables["thresholds"].astype(np.int64)).to(dev)
+    mask = 0xFFFFFFFF
+
+    def mix32(x):
+        x = x & mask
+        x = x ^ (x >> 16)
+        x = (x * 0x7FEB352D) & mask
+        x = x ^ (x >> 15)
+        x = (x * 0x846CA68B) & mask
+        x = x ^ (x >> 16)
+        return x
+
+    s = (int(seed) * 0x9E3779B1 + 0x7F4A7C15) & mask
+
+    def stream(ids, lane):
+        h = mix32(ids ^ s)
+        h = mix32(h + (ids >> 32) * 0x85EBCA6B + 0x165667B1)
+        return mix32(h ^ ((lane * 0x9E3779B1) & mask))
+
+    out = torch.empty((count, d), dtype=torch.float32, device=dev)
+    dims = torch.arange(d, dtype=torch.int64, device=dev)[None, :]
+    for c0 in range(0, count, chunk):
+        n = min(chunk, count - c0)
+        ids = torch.arange(start + c0, start + c0 + n, dtype=torch.int64, device=dev)
+        zero = torch.zeros((), dtype=torch.int64, device=dev)
+        cl = torch.searchsorted(thr, stream(ids, zero), right=False).clamp_(max=N_CLUSTERS - 1)
+        gain = 104 + (stream(ids, zero + 1) & 63)
+        x = (centres[cl] * gain[:, None]) >> 7
+        for f in range(N_LATENT):
+            h = stream(ids, zero + 2 + f)
+            z = (h & 0xFF) + ((h >> 8) & 0xFF) - 255
+            x += (z[:, None] * basis[f][None, :]) >> 9
+        h = stream(ids[:, None], 16 + dims)
+        x += ((h & 15) - ((h >> 4) & 15)) >> 1
+        out[c0:c0 + n] = x.clamp_(0, 255).to(torch.float32)
+    return out
