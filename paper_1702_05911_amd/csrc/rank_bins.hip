@@ -57,9 +57,149 @@ size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R
 
 struct RankOffsets {   // byte offsets handed to the kernel (computed once on the host)
     int npad, Tcap, Tpad;
+    int force;             // 1: rank every query over all T tuples (taps wanted, or no head pass ran)
     uint32_t keys, dkeys, Ld, Lid, rowbase, len, o0, flag, part;
 };
 
+constexpr uint32_t kNotRanked = 0xffffffffu;   // meta.y of a query the head pass could not finish
+constexpr int kHeadT = 64;                     // tuples the head pass ranks
+constexpr int kMidT = 256;                     // first attempt of the full pass
+constexpr int kHeadKeys = 320;                 // >= region size for R = T = 64 (280), in blocks of 64
+
+// ------------------------------------------------------------------------------------------------
+// Head pass.  Most queries reach the candidate budget C within the first few dozen tuples of the
+// order (the later ones cannot change the result: their runs would start beyond C).  One wavefront
+// per query ranks only the first min(T, 64) tuples exactly and, if their runs already fill C (or
+// there are no more tuples), writes the final run list; otherwise it marks the query for the full
+// pass.  Wave-synchronous: no workgroup barrier, LDS accesses of one wave execute in program order.
+// ------------------------------------------------------------------------------------------------
+struct HeadLds {
+    float A[kHeadT], B[kHeadT];
+    uint32_t Aid[kHeadT], Bid[kHeadT];
+    unsigned long long keys[kHeadKeys];
+    uint32_t slot[kHeadT];
+};
+
+#define PQT_WAVE_LDS_ORDER()                                   \
+    do {                                                       \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); \
+        __builtin_amdgcn_wave_barrier();                       \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront"); \
+    } while (0)
+
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int lane) {
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t n = __shfl_up(v, off, kWave);
+        if (lane >= off) v += n;
+    }
+    return v;
+}
+
+__device__ __forceinline__ void wave_compare_exchange(unsigned long long* keys, int i, int j, bool asc) {
+    const unsigned long long x = keys[i], y = keys[j];
+    if ((x > y) == asc) {
+        keys[i] = y;
+        keys[j] = x;
+    }
+}
+
+__global__ __launch_bounds__(kRankThreads) void rank_head_kernel(RankArgs g, int Tn) {
+    __shared__ HeadLds lds[kRankThreads / kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int64_t q = (int64_t)blockIdx.x * (kRankThreads / kWave) + wave;
+    if (q >= g.nq) return;
+    HeadLds& S = lds[wave];
+    const int R = g.R, T = g.T;
+    const int R1 = R < kHeadT ? R : kHeadT;
+    const int T1 = Tn < kHeadT ? Tn : kHeadT;
+
+    if (lane < R1) {
+        S.A[lane] = g.L_d[q * 2 * R + lane];
+        S.Aid[lane] = g.L_id[q * 2 * R + lane];
+        S.B[lane] = g.L_d[q * 2 * R + R + lane];
+        S.Bid[lane] = g.L_id[q * 2 * R + R + lane];
+    }
+    PQT_WAVE_LDS_ORDER();
+
+    // keys of the pairs with (r1+1)(r2+1) <= T1: lane = row r1
+    const int cnt = (lane < R1) ? region_row_count(lane, R1, T1) : 0;
+    const uint32_t incl = wave_inclusive_sum((uint32_t)cnt, lane);
+    const int base = (int)incl - cnt;
+    const int nreg = (int)__shfl(incl, kWave - 1, kWave);
+    const int nblk = (nreg + kWave - 1) / kWave;
+    {
+        const float da = (lane < R1) ? S.A[lane] : 0.0f;
+        for (int b = 0; b < cnt; ++b)
+            S.keys[base + b] = ((unsigned long long)mono_key(da + S.B[b]) << 32) | ((unsigned)lane << 16) | (unsigned)b;
+        for (int e = nreg + lane; e < nblk * kWave; e += kWave) S.keys[e] = ~0ull;
+    }
+    PQT_WAVE_LDS_ORDER();
+
+    // sort every block of 64 keys ascending
+    for (int size = 2; size <= kWave; size <<= 1)
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int c = lane; c < nblk * (kWave / 2); c += kWave) {
+                const int blk = c / (kWave / 2), e = c % (kWave / 2);
+                const int il = 2 * e - (e & (stride - 1));
+                wave_compare_exchange(S.keys + blk * kWave, il, il + stride, (il & size) == 0);
+            }
+            PQT_WAVE_LDS_ORDER();
+        }
+    // fold the other blocks into block 0, keeping the 64 smallest each time: the lower half of the
+    // union of two ascending runs is min(x[i], y[63-i]) (a bitonic sequence), then a bitonic merge
+    for (int blk = 1; blk < nblk; ++blk) {
+        const unsigned long long x = S.keys[lane], y = S.keys[blk * kWave + (kWave - 1 - lane)];
+        S.keys[lane] = x < y ? x : y;
+        PQT_WAVE_LDS_ORDER();
+        for (int stride = kWave / 2; stride > 0; stride >>= 1) {
+            if (lane < kWave / 2) {
+                const int il = 2 * lane - (lane & (stride - 1));
+                wave_compare_exchange(S.keys, il, il + stride, true);
+            }
+            PQT_WAVE_LDS_ORDER();
+        }
+    }
+
+    // probe the first T1 tuples
+    uint32_t o0 = 0, len = 0;
+    if (lane < T1) {
+        const unsigned long long key = S.keys[lane];
+        const unsigned r1 = ((unsigned)key >> 16) & 0xffffu, r2 = (unsigned)key & 0xffffu;
+        const unsigned long long lin = (unsigned long long)S.Aid[r1] * g.k1k2 + S.Bid[r2];
+        const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+        o0 = g.offsets[slot];
+        len = g.offsets[slot + 1] - o0;
+        S.slot[lane] = (uint32_t)slot;
+    }
+    if (g.hashed) {
+        PQT_WAVE_LDS_ORDER();
+        if (lane < T1) {
+            const uint32_t mine = S.slot[lane];
+            for (int t = 0; t < lane; ++t)
+                if (S.slot[t] == mine) len = 0;          // proposed earlier in the order
+        }
+    }
+    const uint32_t incl_len = wave_inclusive_sum(len, lane);
+    const uint32_t start = incl_len - len;
+    const uint32_t total = __shfl(incl_len, kWave - 1, kWave);
+    const uint32_t C = (uint32_t)g.C;
+    if (total < C && T1 < Tn) {                          // not enough yet and more tuples exist
+        if (lane == 0) g.meta[q] = make_uint2(0u, kNotRanked);
+        return;
+    }
+    const bool emit = len > 0 && start < C;
+    const unsigned long long mask = __ballot(emit);
+    if (emit) {
+        const int idx = __popcll(mask & ((1ull << lane) - 1ull));
+        g.runs[(size_t)q * T + idx] = make_uint2(o0, start);
+    }
+    if (lane == 0) g.meta[q] = make_uint2((uint32_t)__popcll(mask), total < C ? total : C);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Full pass: one workgroup per query that the head pass left open (or every query when forced).
+// Ranks the first Tcur tuples for Tcur = 256, then T, stopping as soon as the budget is reached.
+// ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + L.keys);
@@ -76,8 +216,10 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     constexpr int nwaves = kRankThreads / kWave;
     const int64_t q = blockIdx.x;
+    if (!L.force && g.meta[q].y != kNotRanked) return;      // finished by the head pass (uniform)
     const int P = g.P, R = g.R, T = g.T;
-    const int Tn = L.Tcap;                       // tuples examined: min(T, R^P)
+    const int Tall = L.Tcap;                                // min(T, R^P)
+    const uint32_t C = (uint32_t)g.C;
 
     for (int e = tid; e < P * R; e += kRankThreads) {
         sLd[e] = g.L_d[q * P * R + e];
@@ -85,71 +227,80 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
     }
     __syncthreads();
 
-    // ---- keys of the candidate tuples ------------------------------------------------------------
-    if (P == 1) {
-        for (int e = tid; e < L.npad; e += kRankThreads)
-            keys[e] = (e < Tn) ? (((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e) : ~0ull;
-        __syncthreads();                         // the list is already sorted by (distance, id)
-    } else {                                     // P == 2
-        for (int a = tid; a < R; a += kRankThreads) rowbase[a] = (uint32_t)region_row_count(a, R, T);
-        __syncthreads();
-        const uint32_t nreg = block_exclusive_scan(rowbase, R, part);
-        for (int a = wave; a < R; a += nwaves) {
-            const int cnt = region_row_count(a, R, T);
-            const uint32_t base = rowbase[a];
-            const float da = sLd[a];
-            for (int b = lane; b < cnt; b += kWave) {
-                const float s = da + sLd[R + b];
-                keys[base + b] = ((unsigned long long)mono_key(s) << 32) | ((unsigned)a << 16) | (unsigned)b;
-            }
-        }
-        for (int e = (int)nreg + tid; e < L.npad; e += kRankThreads) keys[e] = ~0ull;
-        bitonic_sort_lds(keys, L.npad, tid, kRankThreads);
-    }
-
-    // ---- tuple -> bin number -> slot -> run of the inverted list -----------------------------------
-    for (int t = tid; t < Tn; t += kRankThreads) {
-        const unsigned long long key = keys[t];
-        unsigned long long lin;
-        unsigned r1, r2 = 0;
+    int Tn = (L.force || P == 1 || Tall <= kMidT) ? Tall : kMidT;   // tuples ranked in this attempt
+    uint32_t total = 0;
+    while (true) {
+        // ---- keys of the candidate tuples --------------------------------------------------------
         if (P == 1) {
-            r1 = (unsigned)key & 0xffffu;
-            lin = sLid[r1];
-        } else {
-            r1 = ((unsigned)key >> 16) & 0xffffu;
-            r2 = (unsigned)key & 0xffffu;
-            lin = (unsigned long long)sLid[r1] * g.k1k2 + sLid[R + r2];
+            for (int e = tid; e < Tn; e += kRankThreads)
+                keys[e] = ((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e;
+            __syncthreads();                     // the list is already sorted by (distance, id)
+        } else {                                 // P == 2
+            for (int a = tid; a < R; a += kRankThreads) rowbase[a] = (uint32_t)region_row_count(a, R, Tn);
+            __syncthreads();
+            const uint32_t nreg = block_exclusive_scan(rowbase, R, part);
+            const int npad = next_pow2((int)nreg);
+            for (int a = wave; a < R; a += nwaves) {
+                const int cnt = region_row_count(a, R, Tn);
+                const uint32_t base = rowbase[a];
+                const float da = sLd[a];
+                for (int b = lane; b < cnt; b += kWave) {
+                    const float s = da + sLd[R + b];
+                    keys[base + b] = ((unsigned long long)mono_key(s) << 32) | ((unsigned)a << 16) | (unsigned)b;
+                }
+            }
+            for (int e = (int)nreg + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
+            bitonic_sort_lds(keys, npad, tid, kRankThreads);
         }
-        const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
-        const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
-        so0[t] = o0;
-        slen[t] = o1 - o0;
-        if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;
-        if (g.tuples) {
-            uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
-            tp[0] = (uint16_t)r1; tp[1] = (uint16_t)r2; tp[2] = 0; tp[3] = 0;
-        }
-        if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
-    }
-    if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
-    __syncthreads();
 
-    // ---- a slot proposed earlier in the order is skipped (hashed indexes only) ----------------------
-    if (g.hashed) {
-        for (int e = Tn + tid; e < L.Tpad; e += kRankThreads) dkeys[e] = ~0ull;
-        bitonic_sort_lds(dkeys, L.Tpad, tid, kRankThreads);
-        for (int e = tid + 1; e < Tn; e += kRankThreads) {
-            const unsigned long long cur = dkeys[e], prev = dkeys[e - 1];
-            if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
+        // ---- tuple -> bin number -> slot -> run of the inverted list -------------------------------
+        for (int t = tid; t < Tn; t += kRankThreads) {
+            const unsigned long long key = keys[t];
+            unsigned long long lin;
+            unsigned r1, r2 = 0;
+            if (P == 1) {
+                r1 = (unsigned)key & 0xffffu;
+                lin = sLid[r1];
+            } else {
+                r1 = ((unsigned)key >> 16) & 0xffffu;
+                r2 = (unsigned)key & 0xffffu;
+                lin = (unsigned long long)sLid[r1] * g.k1k2 + sLid[R + r2];
+            }
+            const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+            const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
+            so0[t] = o0;
+            slen[t] = o1 - o0;
+            if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;
+            if (g.tuples) {
+                uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
+                tp[0] = (uint16_t)r1; tp[1] = (uint16_t)r2; tp[2] = 0; tp[3] = 0;
+            }
+            if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
         }
+        if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
         __syncthreads();
+
+        // ---- a slot proposed earlier in the order is skipped (hashed indexes only) ------------------
+        if (g.hashed) {
+            const int Tpad = next_pow2(Tn);
+            for (int e = Tn + tid; e < Tpad; e += kRankThreads) dkeys[e] = ~0ull;
+            bitonic_sort_lds(dkeys, Tpad, tid, kRankThreads);
+            for (int e = tid + 1; e < Tn; e += kRankThreads) {
+                const unsigned long long cur = dkeys[e], prev = dkeys[e - 1];
+                if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
+            }
+            __syncthreads();
+        }
+
+        // ---- lay the runs end to end -------------------------------------------------------------------
+        for (int t = tid; t < Tn; t += kRankThreads) sflag[t] = slen[t];
+        __syncthreads();
+        total = block_exclusive_scan(sflag, Tn, part);               // sflag[t] = start position
+        if (total >= C || Tn >= Tall) break;                         // uniform: total comes from LDS
+        Tn = Tall;
     }
 
-    // ---- lay the runs end to end, cut at C, compact ----------------------------------------------------
-    for (int t = tid; t < Tn; t += kRankThreads) sflag[t] = slen[t];
-    __syncthreads();
-    const uint32_t total = block_exclusive_scan(sflag, Tn, part);        // sflag[t] = start position
-    const uint32_t C = (uint32_t)g.C;
+    // ---- cut at C, compact -------------------------------------------------------------------------------
     for (int t = tid; t < Tn; t += kRankThreads) {
         const uint32_t start = sflag[t];
         slen[t] = (slen[t] > 0 && start < C) ? 1u : 0u;                  // run is proposed
@@ -182,6 +333,16 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
     o.keys = (uint32_t)L.off_keys; o.dkeys = (uint32_t)L.off_dkeys; o.Ld = (uint32_t)L.off_Ld;
     o.Lid = (uint32_t)L.off_Lid; o.rowbase = (uint32_t)L.off_rowbase; o.len = (uint32_t)L.off_len;
     o.o0 = (uint32_t)L.off_o0; o.flag = (uint32_t)L.off_flag; o.part = (uint32_t)L.off_part;
+    const bool taps = a.n_tuples || a.tuples || a.tuple_keys || a.slots;
+    const bool head = (a.P == 2) && !taps;
+    o.force = head ? 0 : 1;
+    if (head) {
+        constexpr int per = kRankThreads / kWave;
+        hipLaunchKernelGGL(rank_head_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kRankThreads), 0, s, a,
+                           L.Tcap);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)a.nq), dim3(kRankThreads), L.total, s, a, o);
     return hipGetLastError();
 }
