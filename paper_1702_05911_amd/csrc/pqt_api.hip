@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -124,11 +125,22 @@ int upload(Tp** dev, const void* host, size_t bytes, uint64_t* account) {
     return PQT_OK;
 }
 
+// workgroup size of the re-rank kernel (PQT_RERANK_THREADS overrides: 256, 512 or 1024)
+int rerank_threads(const pqt_index* ix) {
+    static const int forced = [] {
+        const char* e = getenv("PQT_RERANK_THREADS");
+        const int v = e ? atoi(e) : 0;
+        return (v == 256 || v == 512 || v == 1024) ? v : 0;
+    }();
+    if (forced) return forced;
+    return ix->C >= 2048 ? 512 : 256;
+}
+
 int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
     const int R = w * (int)ix->k2;
     const size_t l1 = pqt::traverse_lds_bytes(ix->D, ix->P, ix->k1, ix->k2, ix->M, w);
     const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed);
-    const int threads = ix->C > 4096 ? 512 : 256;
+    const int threads = rerank_threads(ix);
     const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads);
     if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)
         return fail(PQT_EUNSUPPORTED,
@@ -360,7 +372,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
 
     pqt::RerankArgs ca;
     ca.nq = nq; ca.M = ix->M; ca.k1 = ix->k1; ca.T = ix->T; ca.C = ix->C; ca.k = k;
-    ca.threads = ix->C > 4096 ? 512 : 256;
+    ca.threads = rerank_threads(ix);
     ca.a = ix->ws_a; ca.table = ix->table; ca.runs = ix->ws_runs; ca.meta = ix->ws_meta;
     ca.ids = ix->ids; ca.codes = ix->codes; ca.out_ids = out_ids; ca.out_dists = out_dists;
     ca.n_cand = tp.n_cand; ca.cand_ids = tp.cand_ids; ca.scores = tp.scores; ca.lut = tp.lut;

@@ -42,6 +42,36 @@ __device__ __forceinline__ void bitonic_sort_lds(K* keys, int n, int tid, int nt
     __syncthreads();
 }
 
+// Orders the LDS accesses of ONE wavefront: LDS instructions of a wave execute in program order,
+// so only the compiler has to be kept from moving them across this point.
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Ascending bitonic sort of n (a power of two) keys in LDS by the 64 lanes of one wavefront;
+// no workgroup barrier, other wavefronts may do anything else meanwhile.
+template <typename K>
+__device__ __forceinline__ void wave_bitonic_sort_lds(K* keys, int n, int lane) {
+    wave_lds_order();
+    for (int size = 2; size <= n; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int e = lane; e < (n >> 1); e += kWave) {
+                const int i = 2 * e - (e & (stride - 1));
+                const int j = i + stride;
+                const bool asc = (i & size) == 0;
+                const K x = keys[i], y = keys[j];
+                if ((x > y) == asc) {
+                    keys[i] = y;
+                    keys[j] = x;
+                }
+            }
+            wave_lds_order();
+        }
+    }
+}
+
 // Exclusive prefix sum over data[0..n) in LDS, in place, by the whole workgroup.
 // part needs blockDim.x entries.  Returns the total.  Ends with a barrier.
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t* data, int n, uint32_t* part) {

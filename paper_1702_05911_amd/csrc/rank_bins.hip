@@ -80,12 +80,7 @@ struct HeadLds {
     uint32_t slot[kHeadT];
 };
 
-#define PQT_WAVE_LDS_ORDER()                                   \
-    do {                                                       \
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront"); \
-        __builtin_amdgcn_wave_barrier();                       \
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront"); \
-    } while (0)
+#define PQT_WAVE_LDS_ORDER() wave_lds_order()
 
 __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int lane) {
     for (int off = 1; off < kWave; off <<= 1) {

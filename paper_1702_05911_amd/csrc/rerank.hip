@@ -119,6 +119,8 @@ __device__ __forceinline__ void radix_select_pass(int n, uint32_t prefix, uint32
 // misc words
 enum { kMin = 0, kMax = 1, kBucket = 2, kCountLe = 3, kNumSurv = 4, kRadix = 8 };
 
+// MW = 32-bit words per code (M/4) for M in {4, 8, 16, 32}; 0 = any other M (byte loads).
+template <int MW>
 __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* surv = reinterpret_cast<unsigned long long*>(smem + L.surv);
@@ -158,41 +160,83 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
     __syncthreads();
 
     // ---- LUT of Eq. 9 summands: b^2 + lam^2 c^2 + lam (a^2 - b^2 - c^2) ----------------------------
-    for (int e = tid; e < M * 256; e += nt) {
-        const CodeEntry ent = g.table[e];
-        const int m = e >> 8;
-        const float b2 = sa[m * k1 + (ent.ij & 0xffu)];
-        const float a2 = sa[m * k1 + ((ent.ij >> 8) & 0xffu)];
-        const float v = (b2 + (ent.lam * ent.lam) * ent.cc) + ent.lam * ((a2 - b2) - ent.cc);
-        lut[e] = v;
-        if (g.lut) g.lut[(size_t)q * M * 256 + e] = v;
+    for (int base = 0; base < M * 256; base += nt * 4) {
+        CodeEntry ent[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = base + u * nt + tid;
+            ent[u] = g.table[e < M * 256 ? e : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = base + u * nt + tid;
+            if (e >= M * 256) continue;
+            const int m = e >> 8;
+            const float b2 = sa[m * k1 + (ent[u].ij & 0xffu)];
+            const float a2 = sa[m * k1 + ((ent[u].ij >> 8) & 0xffu)];
+            const float v = (b2 + (ent[u].lam * ent[u].lam) * ent[u].cc) + ent[u].lam * ((a2 - b2) - ent[u].cc);
+            lut[e] = v;
+            if (g.lut) g.lut[(size_t)q * M * 256 + e] = v;
+        }
     }
     __syncthreads();
 
-    // ---- scores --------------------------------------------------------------------------------------
+    // ---- scores: kUnroll candidate positions per thread in flight (code loads issued before use) ----
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-    for (int p = tid; p < nc; p += nt) {
-        const uint32_t src = source_of((uint32_t)p, nr, steps, run_src, run_start);
-        const uint8_t* code = g.codes + (size_t)src * M;
-        float s = 0.0f;
-        if ((M & 3) == 0) {
-            const uint32_t* cw = reinterpret_cast<const uint32_t*>(code);
-            for (int m4 = 0; m4 < M / 4; ++m4) {
-                const uint32_t wv = cw[m4];
-                s += lut[(m4 * 4 + 0) * 256 + (wv & 0xffu)];
-                s += lut[(m4 * 4 + 1) * 256 + ((wv >> 8) & 0xffu)];
-                s += lut[(m4 * 4 + 2) * 256 + ((wv >> 16) & 0xffu)];
-                s += lut[(m4 * 4 + 3) * 256 + (wv >> 24)];
-            }
-        } else {
-            for (int m = 0; m < M; ++m) s += lut[m * 256 + code[m]];
+    constexpr int kUnroll = 4;
+    for (int base = 0; base < nc; base += nt * kUnroll) {
+        uint32_t src[kUnroll];
+        uint32_t cw[kUnroll][MW > 0 ? MW : 1];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int p = base + u * nt + tid;
+            src[u] = (p < nc) ? source_of((uint32_t)p, nr, steps, run_src, run_start) : run_src[0];
         }
-        const uint32_t key = mono_key(s);
-        skey[p] = key;
-        kmin = min(kmin, key);
-        kmax = max(kmax, key);
-        if (g.scores) g.scores[(size_t)q * C + p] = s;
-        if (g.cand_ids) g.cand_ids[(size_t)q * C + p] = (int64_t)g.ids[src];
+        if (MW > 0) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint32_t* c = reinterpret_cast<const uint32_t*>(g.codes + (size_t)src[u] * M);
+                if (MW == 2) {
+                    const uint2 v = *reinterpret_cast<const uint2*>(c);
+                    cw[u][0] = v.x;
+                    cw[u][MW > 1 ? 1 : 0] = v.y;
+                } else if (MW == 4) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(c);
+                    cw[u][0] = v.x;
+                    cw[u][MW > 1 ? 1 : 0] = v.y;
+                    cw[u][MW > 2 ? 2 : 0] = v.z;
+                    cw[u][MW > 3 ? 3 : 0] = v.w;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < MW; ++j) cw[u][j] = c[j];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int p = base + u * nt + tid;
+            if (p >= nc) continue;
+            float s = 0.0f;
+            if (MW > 0) {
+#pragma unroll
+                for (int j = 0; j < MW; ++j) {
+                    const uint32_t wv = cw[u][j];
+                    s += lut[(j * 4 + 0) * 256 + (wv & 0xffu)];
+                    s += lut[(j * 4 + 1) * 256 + ((wv >> 8) & 0xffu)];
+                    s += lut[(j * 4 + 2) * 256 + ((wv >> 16) & 0xffu)];
+                    s += lut[(j * 4 + 3) * 256 + (wv >> 24)];
+                }
+            } else {
+                const uint8_t* code = g.codes + (size_t)src[u] * M;
+                for (int m = 0; m < M; ++m) s += lut[m * 256 + code[m]];
+            }
+            const uint32_t key = mono_key(s);
+            skey[p] = key;
+            kmin = min(kmin, key);
+            kmax = max(kmax, key);
+            if (g.scores) g.scores[(size_t)q * C + p] = s;
+            if (g.cand_ids) g.cand_ids[(size_t)q * C + p] = (int64_t)g.ids[src[u]];
+        }
     }
     if (g.n_cand && tid == 0) g.n_cand[q] = (uint32_t)nc;
     for (int off = kWave / 2; off > 0; off >>= 1) {
@@ -329,13 +373,26 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
 hipError_t launch_rerank(const RerankArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
     const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads);
-    hipLaunchKernelGGL(rerank_kernel, dim3((unsigned)a.nq), dim3(a.threads), L.total, s, a, L);
+    const dim3 grid((unsigned)a.nq), block(a.threads);
+    switch ((a.M % 4 == 0) ? a.M / 4 : 0) {
+        case 1: hipLaunchKernelGGL(rerank_kernel<1>, grid, block, L.total, s, a, L); break;
+        case 2: hipLaunchKernelGGL(rerank_kernel<2>, grid, block, L.total, s, a, L); break;
+        case 4: hipLaunchKernelGGL(rerank_kernel<4>, grid, block, L.total, s, a, L); break;
+        case 8: hipLaunchKernelGGL(rerank_kernel<8>, grid, block, L.total, s, a, L); break;
+        default: hipLaunchKernelGGL(rerank_kernel<0>, grid, block, L.total, s, a, L); break;
+    }
     return hipGetLastError();
 }
 
 hipError_t configure_rerank(size_t max_dynamic_lds) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(rerank_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+    const void* kernels[] = {reinterpret_cast<const void*>(rerank_kernel<0>), reinterpret_cast<const void*>(rerank_kernel<1>),
+                             reinterpret_cast<const void*>(rerank_kernel<2>), reinterpret_cast<const void*>(rerank_kernel<4>),
+                             reinterpret_cast<const void*>(rerank_kernel<8>)};
+    for (const void* kfn : kernels) {
+        hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace pqt

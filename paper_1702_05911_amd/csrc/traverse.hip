@@ -152,7 +152,31 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
                 const int i = ssel[(q * P + p) * w + s];
                 const float* c = g.C2 + (((size_t)p * k1 + i) * k2 + j) * dp;
                 float acc = 0.0f;
-                for (int d = 0; d < dp; ++d) {
+                int d = 0;
+                if ((dp & 3) == 0) {
+                    // 16 dimensions per step: four 16-byte loads in flight, then 16 dependent FMAs
+                    const float4* c4 = reinterpret_cast<const float4*>(c);
+                    for (; d + 16 <= dp; d += 16) {
+                        const float4 v0 = c4[d / 4], v1 = c4[d / 4 + 1], v2 = c4[d / 4 + 2], v3 = c4[d / 4 + 3];
+                        const float cv[16] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w,
+                                              v2.x, v2.y, v2.z, v2.w, v3.x, v3.y, v3.z, v3.w};
+#pragma unroll
+                        for (int u = 0; u < 16; ++u) {
+                            const float diff = yp[d + u] - cv[u];
+                            acc = fmaf(diff, diff, acc);
+                        }
+                    }
+                    for (; d + 4 <= dp; d += 4) {
+                        const float4 v = c4[d / 4];
+                        const float cv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const float diff = yp[d + u] - cv[u];
+                            acc = fmaf(diff, diff, acc);
+                        }
+                    }
+                }
+                for (; d < dp; ++d) {
                     const float diff = yp[d] - c[d];
                     acc = fmaf(diff, diff, acc);
                 }
@@ -160,7 +184,7 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
             }
             mykeys[e] = key;
         }
-        bitonic_sort_lds(mykeys, L.Rpad, lane, kWave);
+        wave_bitonic_sort_lds(mykeys, L.Rpad, lane);
         const int64_t gq = q0 + q;
         if (gq < g.nq) {
             for (int e = lane; e < R; e += kWave) {
@@ -169,7 +193,7 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
                 g.L_id[(gq * P + p) * R + e] = (uint32_t)key;
             }
         }
-        __syncthreads();
+        wave_lds_order();
     }
 }
 
