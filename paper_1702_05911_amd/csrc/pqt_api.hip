@@ -132,8 +132,10 @@ int rerank_threads(const pqt_index* ix) {
         const int v = e ? atoi(e) : 0;
         return (v == 256 || v == 512 || v == 1024) ? v : 0;
     }();
-    if (forced) return forced;
-    return ix->C >= 2048 ? 512 : 256;
+    // the exact-selection fallback borrows the LUT area (M*1024 bytes) for one word per thread
+    const int cap = (int)ix->M * 256 < 256 ? 256 : (int)ix->M * 256;
+    int t = forced ? forced : (ix->C >= 2048 ? 512 : 256);
+    return t < cap ? t : cap;
 }
 
 int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {

@@ -10,8 +10,8 @@ constexpr int kWave = 64;
 // Order-preserving map float -> uint32 (ascending floats give ascending keys).
 // Adding +0.0f first turns -0.0 into +0.0 so that equal floats get equal keys.
 __device__ __forceinline__ uint32_t mono_key(float f) {
-    uint32_t u = __float_as_uint(f + 0.0f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    const uint32_t u = __float_as_uint(f + 0.0f);
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);   // negative: ~u, else u | sign bit
 }
 __device__ __forceinline__ float mono_inv(uint32_t k) {
     uint32_t u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
@@ -40,6 +40,36 @@ __device__ __forceinline__ void bitonic_sort_lds(K* keys, int n, int tid, int nt
         }
     }
     __syncthreads();
+}
+
+// ---- cross-lane helpers on the data-parallel-primitive path (no LDS traffic) ---------------------
+// dpp_ctrl codes: quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141,
+// row_mirror = 0x140, row_bcast15 = 0x142 (lane 15 of a row to the next row), row_bcast31 = 0x143.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_take(uint32_t keep, uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)keep, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ uint32_t quad_swap1(uint32_t v) { return dpp_take<0xB1, 0xf>(v, v); }   // lane ^ 1
+__device__ __forceinline__ uint32_t quad_swap2(uint32_t v) { return dpp_take<0x4E, 0xf>(v, v); }   // lane ^ 2
+
+// Minimum / maximum over the 64 lanes of a wavefront, returned in every lane.
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, dpp_take<0xB1, 0xf>(v, v));
+    v = min(v, dpp_take<0x4E, 0xf>(v, v));
+    v = min(v, dpp_take<0x141, 0xf>(v, v));
+    v = min(v, dpp_take<0x140, 0xf>(v, v));      // every lane of a row holds the row minimum
+    v = min(v, dpp_take<0x142, 0xa>(v, v));      // rows 1 and 3 fold in rows 0 and 2
+    v = min(v, dpp_take<0x143, 0xc>(v, v));      // rows 2 and 3 fold in rows 0-1: lane 63 has all
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, dpp_take<0xB1, 0xf>(v, v));
+    v = max(v, dpp_take<0x4E, 0xf>(v, v));
+    v = max(v, dpp_take<0x141, 0xf>(v, v));
+    v = max(v, dpp_take<0x140, 0xf>(v, v));
+    v = max(v, dpp_take<0x142, 0xa>(v, v));
+    v = max(v, dpp_take<0x143, 0xc>(v, v));
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 // Orders the LDS accesses of ONE wavefront: LDS instructions of a wave execute in program order,
