@@ -76,6 +76,7 @@ struct pqt_index {
     uint32_t* ws_Lid = nullptr;
     uint2* ws_runs = nullptr;
     uint2* ws_meta = nullptr;
+    uint32_t* ws_todo = nullptr;
     uint64_t bytes_workspace = 0;
     // stage timing
     bool profiling = false;
@@ -84,8 +85,8 @@ struct pqt_index {
 
     void free_workspace() {
         (void)hipFree(ws_a); (void)hipFree(ws_Ld); (void)hipFree(ws_Lid);
-        (void)hipFree(ws_runs); (void)hipFree(ws_meta);
-        ws_a = ws_Ld = nullptr; ws_Lid = nullptr; ws_runs = ws_meta = nullptr;
+        (void)hipFree(ws_runs); (void)hipFree(ws_meta); (void)hipFree(ws_todo);
+        ws_a = ws_Ld = nullptr; ws_Lid = nullptr; ws_runs = ws_meta = nullptr; ws_todo = nullptr;
         ws_nq = 0; bytes_workspace = 0;
     }
 };
@@ -167,8 +168,9 @@ int ensure_workspace(pqt_index* ix, int64_t nq, int R) {
     HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_Lid), bl));
     HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_runs), br));
     HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_meta), bm));
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_todo), sizeof(uint32_t) * ((size_t)n + 1)));
     ix->ws_nq = n; ix->ws_R = r; ix->ws_T = t;
-    ix->bytes_workspace = ba + 2 * bl + br + bm;
+    ix->bytes_workspace = ba + 2 * bl + br + bm + sizeof(uint32_t) * ((size_t)n + 1);
     return PQT_OK;
 }
 
@@ -358,7 +360,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ta.queries = queries; ta.nq = nq;
     ta.D = ix->D; ta.P = ix->P; ta.k1 = ix->k1; ta.k2 = ix->k2; ta.M = ix->M; ta.w = w;
     ta.C1 = ix->C1; ta.c1n = ix->c1n; ta.C2 = ix->C2;
-    ta.a = ix->ws_a; ta.L_d = ix->ws_Ld; ta.L_id = ix->ws_Lid; ta.sel_tap = tp.sel;
+    ta.a = ix->ws_a; ta.L_d = ix->ws_Ld; ta.L_id = ix->ws_Lid; ta.sel_tap = tp.sel; ta.todo = ix->ws_todo;
     if (ev) HIP_TRY(hipEventRecord(ev[0], stream));
     HIP_TRY(pqt::launch_traverse(ta, stream));
     if (ev) HIP_TRY(hipEventRecord(ev[1], stream));
@@ -367,7 +369,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ra.nq = nq; ra.P = ix->P; ra.R = R; ra.T = ix->T; ra.C = ix->C;
     ra.k1k2 = ix->k1 * ix->k2; ra.H = ix->H; ra.hashed = ix->hashed ? 1 : 0;
     ra.offsets = ix->offsets; ra.L_d = ix->ws_Ld; ra.L_id = ix->ws_Lid;
-    ra.runs = ix->ws_runs; ra.meta = ix->ws_meta;
+    ra.runs = ix->ws_runs; ra.meta = ix->ws_meta; ra.todo = ix->ws_todo;
     ra.n_tuples = tp.n_tuples; ra.tuples = tp.tuples; ra.tuple_keys = tp.tuple_keys; ra.slots = tp.slots;
     HIP_TRY(pqt::launch_rank(ra, stream));
     if (ev) HIP_TRY(hipEventRecord(ev[2], stream));

@@ -30,6 +30,7 @@ struct TraverseArgs {
     float* L_d;             // nq x P x R
     uint32_t* L_id;         // nq x P x R
     int32_t* sel_tap;       // nq x P x w or null
+    uint32_t* todo;         // [0] = number of queries left to the full ranking pass (reset here), or null
 };
 size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w);
 hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s);
@@ -45,6 +46,7 @@ struct RankArgs {
     const uint32_t* L_id;
     uint2* runs;              // nq x T   (.x = first position in ids/codes, .y = start in candidate list)
     uint2* meta;              // nq       (.x = number of runs, .y = number of candidates)
+    uint32_t* todo;           // [0] = count, [1..] = queries the head pass left to the full pass
     // taps (nullable)
     uint32_t* n_tuples;
     uint16_t* tuples;         // nq x T x 4

@@ -61,7 +61,6 @@ struct RankOffsets {   // byte offsets handed to the kernel (computed once on th
     uint32_t keys, dkeys, Ld, Lid, rowbase, len, o0, flag, part;
 };
 
-constexpr uint32_t kNotRanked = 0xffffffffu;   // meta.y of a query the head pass could not finish
 constexpr int kHeadT = 64;                     // tuples the head pass ranks
 constexpr int kMidT = 256;                     // first attempt of the full pass
 constexpr int kHeadKeys = 320;                 // >= region size for R = T = 64 (280), in blocks of 64
@@ -179,7 +178,7 @@ __global__ __launch_bounds__(kRankThreads) void rank_head_kernel(RankArgs g, int
     const uint32_t total = __shfl(incl_len, kWave - 1, kWave);
     const uint32_t C = (uint32_t)g.C;
     if (total < C && T1 < Tn) {                          // not enough yet and more tuples exist
-        if (lane == 0) g.meta[q] = make_uint2(0u, kNotRanked);
+        if (lane == 0) g.todo[1 + atomicAdd(&g.todo[0], 1u)] = (uint32_t)q;
         return;
     }
     const bool emit = len > 0 && start < C;
@@ -192,7 +191,7 @@ __global__ __launch_bounds__(kRankThreads) void rank_head_kernel(RankArgs g, int
 }
 
 // ------------------------------------------------------------------------------------------------
-// Full pass: one workgroup per query that the head pass left open (or every query when forced).
+// Full pass: workgroups take the queries the head pass listed (or every query when forced).
 // Ranks the first Tcur tuples for Tcur = 256, then T, stopping as soon as the budget is reached.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
@@ -210,11 +209,12 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     constexpr int nwaves = kRankThreads / kWave;
-    const int64_t q = blockIdx.x;
-    if (!L.force && g.meta[q].y != kNotRanked) return;      // finished by the head pass (uniform)
     const int P = g.P, R = g.R, T = g.T;
     const int Tall = L.Tcap;                                // min(T, R^P)
     const uint32_t C = (uint32_t)g.C;
+    const uint32_t count = L.force ? (uint32_t)g.nq : g.todo[0];
+    for (uint32_t item = blockIdx.x; item < count; item += gridDim.x) {
+    const int64_t q = L.force ? (int64_t)item : (int64_t)g.todo[1 + item];
 
     for (int e = tid; e < P * R; e += kRankThreads) {
         sLd[e] = g.L_d[q * P * R + e];
@@ -318,6 +318,8 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
         }
     }
     if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
+    __syncthreads();
+    }   // next query of the list
 }
 
 hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
@@ -338,7 +340,8 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(rank_kernel, dim3((unsigned)a.nq), dim3(kRankThreads), L.total, s, a, o);
+    const unsigned grid = head ? (unsigned)(a.nq < 1024 ? a.nq : 1024) : (unsigned)a.nq;
+    hipLaunchKernelGGL(rank_kernel, dim3(grid), dim3(kRankThreads), L.total, s, a, o);
     return hipGetLastError();
 }
 
