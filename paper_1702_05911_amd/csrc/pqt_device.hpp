@@ -72,6 +72,43 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// Inclusive prefix sum across the 64 lanes of a wavefront.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int lane) {
+    for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t n = __shfl_up(v, off, kWave);
+        if (lane >= off) v += n;
+    }
+    return v;
+}
+
+// In a 1024-bin histogram held in LDS, find the bin that holds the item of 1-based rank `need`
+// (need <= total count): digit = that bin, before = items in lower bins, count = items in it.
+// Read-only and wave-local: every wavefront may call it at the same time and all lanes of all
+// callers get the same answer.
+__device__ __forceinline__ void hist_locate(const uint32_t* hist, uint32_t need, int lane, uint32_t& digit,
+                                            uint32_t& before, uint32_t& count) {
+    constexpr int cb = 1024 / kWave;                         // bins per lane
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < cb; ++j) s += hist[lane * cb + ((j + lane) & (cb - 1))];   // rotated: no bank conflicts
+    const uint32_t incl = wave_inclusive_sum(s, lane);
+    uint32_t c = incl - s;
+    const bool mine = c < need && need <= incl;              // exactly one lane
+    uint32_t d = 0, bf = 0, ct = 0;
+    if (mine) {
+        int b = lane * cb;
+        while (c + hist[b] < need) c += hist[b++];
+        d = (uint32_t)b;
+        bf = c;
+        ct = hist[b];
+    }
+    const unsigned long long who = __ballot(mine);
+    const int owner = who ? __ffsll((long long)who) - 1 : 0;
+    digit = (uint32_t)__shfl((int)d, owner, kWave);
+    before = (uint32_t)__shfl((int)bf, owner, kWave);
+    count = (uint32_t)__shfl((int)ct, owner, kWave);
+}
+
 // Orders the LDS accesses of ONE wavefront: LDS instructions of a wave execute in program order,
 // so only the compiler has to be kept from moving them across this point.
 __device__ __forceinline__ void wave_lds_order() {

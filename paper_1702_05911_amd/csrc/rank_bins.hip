@@ -4,10 +4,14 @@
 // hash it (modulo H, Sec. 4), drop repeated and empty slots, and lay the surviving runs of
 // the inverted lists end to end until the candidate budget C is reached.
 //
-// One workgroup per query.  The first T tuples of the order (sum, r1, r2) are found without
-// a priority queue: a pair (r1, r2) can only be among the first T if (r1+1)(r2+1) <= T,
-// because every pair that is component-wise smaller precedes it.  Only that hyperbolic
-// region is evaluated, packed as 64-bit keys (ordered sum bits, r1, r2) and sorted in LDS.
+// The first T tuples of the order (sum, r1, r2) are found without a priority queue: a pair
+// (r1, r2) can only be among the first T if (r1+1)(r2+1) <= T, because every pair that is
+// component-wise smaller precedes it.  Only that hyperbolic region (about T ln T pairs) is ever
+// evaluated.  A head pass (one wavefront per query) ranks the first 64 tuples, which is enough
+// for most queries to fill the candidate budget; the full pass handles the rest: if the region
+// fits the sort buffer it is sorted directly, otherwise the T-th smallest key is found by a
+// radix select over the region (keys recomputed on the fly, never stored) and only the T
+// smallest are collected and sorted.
 #include "pqt_device.hpp"
 #include "pqt_kernels.hpp"
 
@@ -24,11 +28,15 @@ int rank_region_size(int R, int T) {
     return (int)n;
 }
 
+constexpr int kSelBits = 10;
+constexpr int kSelBins = 1 << kSelBits;
+
 struct RankLds {
-    int npad;   // sort width
-    int Tcap;   // examined tuples (upper bound)
-    int Tpad;
-    size_t off_Ld, off_Lid, off_keys, off_rowbase, off_len, off_o0, off_flag, off_part, off_dkeys, total;
+    int Tcap;   // tuples examined: min(T, R^P)
+    int cap;    // sort buffer entries: next_pow2(Tcap)
+    int nreg;   // size of the hyperbolic region (P = 2)
+    size_t off_keys, off_dkeys, off_hist, off_Ld, off_Lid, off_rowbase, off_len, off_o0, off_flag, off_part,
+        off_misc, total;
 };
 
 static RankLds rank_layout(int P, int R, int T, int hashed) {
@@ -36,12 +44,12 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     long total_tuples = 1;
     for (int p = 0; p < P; ++p) total_tuples = (total_tuples * R > (1L << 40)) ? (1L << 40) : total_tuples * R;
     L.Tcap = (int)((long)T < total_tuples ? (long)T : total_tuples);
-    L.Tpad = next_pow2(L.Tcap);
-    int nreg = (P == 1) ? L.Tcap : rank_region_size(R, T);
-    L.npad = next_pow2(nreg);
+    L.cap = next_pow2(L.Tcap) < 64 ? 64 : next_pow2(L.Tcap);
+    L.nreg = (P == 1) ? L.Tcap : rank_region_size(R, L.Tcap);
     size_t o = 0;
-    L.off_keys = o;    o += sizeof(unsigned long long) * L.npad;
-    L.off_dkeys = o;   o += hashed ? sizeof(unsigned long long) * L.Tpad : 0;
+    L.off_keys = o;    o += sizeof(unsigned long long) * L.cap;
+    L.off_dkeys = o;   o += hashed ? sizeof(unsigned long long) * L.cap : 0;
+    L.off_hist = o;    o += sizeof(uint32_t) * kSelBins;
     L.off_Ld = o;      o += sizeof(float) * P * R;
     L.off_Lid = o;     o += sizeof(uint32_t) * P * R;
     L.off_rowbase = o; o += sizeof(uint32_t) * (R + 1);
@@ -49,20 +57,20 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     L.off_o0 = o;      o += sizeof(uint32_t) * L.Tcap;
     L.off_flag = o;    o += sizeof(uint32_t) * L.Tcap;
     L.off_part = o;    o += sizeof(uint32_t) * kRankThreads;
+    L.off_misc = o;    o += sizeof(uint32_t) * 16;
     L.total = o;
     return L;
 }
 
 size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed).total; }
 
-struct RankOffsets {   // byte offsets handed to the kernel (computed once on the host)
-    int npad, Tcap, Tpad;
-    int force;             // 1: rank every query over all T tuples (taps wanted, or no head pass ran)
-    uint32_t keys, dkeys, Ld, Lid, rowbase, len, o0, flag, part;
+struct RankOffsets {   // layout handed to the kernel (computed once on the host)
+    int Tcap, cap, nreg;
+    int force;             // 1: rank every query (taps wanted, or no head pass ran)
+    uint32_t keys, dkeys, hist, Ld, Lid, rowbase, len, o0, flag, part, misc;
 };
 
 constexpr int kHeadT = 64;                     // tuples the head pass ranks
-constexpr int kMidT = 256;                     // first attempt of the full pass
 constexpr int kHeadKeys = 320;                 // >= region size for R = T = 64 (280), in blocks of 64
 
 // ------------------------------------------------------------------------------------------------
@@ -80,14 +88,6 @@ struct HeadLds {
 };
 
 #define PQT_WAVE_LDS_ORDER() wave_lds_order()
-
-__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int lane) {
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t n = __shfl_up(v, off, kWave);
-        if (lane >= off) v += n;
-    }
-    return v;
-}
 
 __device__ __forceinline__ void wave_compare_exchange(unsigned long long* keys, int i, int j, bool asc) {
     const unsigned long long x = keys[i], y = keys[j];
@@ -192,12 +192,12 @@ __global__ __launch_bounds__(kRankThreads) void rank_head_kernel(RankArgs g, int
 
 // ------------------------------------------------------------------------------------------------
 // Full pass: workgroups take the queries the head pass listed (or every query when forced).
-// Ranks the first Tcur tuples for Tcur = 256, then T, stopping as soon as the budget is reached.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + L.keys);
     unsigned long long* dkeys = reinterpret_cast<unsigned long long*>(smem + L.dkeys);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
     float* sLd = reinterpret_cast<float*>(smem + L.Ld);
     uint32_t* sLid = reinterpret_cast<uint32_t*>(smem + L.Lid);
     uint32_t* rowbase = reinterpret_cast<uint32_t*>(smem + L.rowbase);
@@ -205,32 +205,30 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
     uint32_t* so0 = reinterpret_cast<uint32_t*>(smem + L.o0);
     uint32_t* sflag = reinterpret_cast<uint32_t*>(smem + L.flag);
     uint32_t* part = reinterpret_cast<uint32_t*>(smem + L.part);
+    uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
     constexpr int nwaves = kRankThreads / kWave;
     const int P = g.P, R = g.R, T = g.T;
-    const int Tall = L.Tcap;                                // min(T, R^P)
+    const int Tn = L.Tcap;                                  // min(T, R^P)
     const uint32_t C = (uint32_t)g.C;
     const uint32_t count = L.force ? (uint32_t)g.nq : g.todo[0];
     for (uint32_t item = blockIdx.x; item < count; item += gridDim.x) {
-    const int64_t q = L.force ? (int64_t)item : (int64_t)g.todo[1 + item];
+        const int64_t q = L.force ? (int64_t)item : (int64_t)g.todo[1 + item];
 
-    for (int e = tid; e < P * R; e += kRankThreads) {
-        sLd[e] = g.L_d[q * P * R + e];
-        sLid[e] = g.L_id[q * P * R + e];
-    }
-    __syncthreads();
+        for (int e = tid; e < P * R; e += kRankThreads) {
+            sLd[e] = g.L_d[q * P * R + e];
+            sLid[e] = g.L_id[q * P * R + e];
+        }
+        __syncthreads();
 
-    int Tn = (L.force || P == 1 || Tall <= kMidT) ? Tall : kMidT;   // tuples ranked in this attempt
-    uint32_t total = 0;
-    while (true) {
-        // ---- keys of the candidate tuples --------------------------------------------------------
+        // ---- the first Tn tuples, sorted, as keys (ordered sum bits, r1, r2) -----------------------
         if (P == 1) {
             for (int e = tid; e < Tn; e += kRankThreads)
                 keys[e] = ((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e;
             __syncthreads();                     // the list is already sorted by (distance, id)
-        } else {                                 // P == 2
+        } else if (L.nreg <= L.cap) {            // the whole region fits: sort it
             for (int a = tid; a < R; a += kRankThreads) rowbase[a] = (uint32_t)region_row_count(a, R, Tn);
             __syncthreads();
             const uint32_t nreg = block_exclusive_scan(rowbase, R, part);
@@ -239,12 +237,75 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
                 const int cnt = region_row_count(a, R, Tn);
                 const uint32_t base = rowbase[a];
                 const float da = sLd[a];
-                for (int b = lane; b < cnt; b += kWave) {
-                    const float s = da + sLd[R + b];
-                    keys[base + b] = ((unsigned long long)mono_key(s) << 32) | ((unsigned)a << 16) | (unsigned)b;
-                }
+                for (int b = lane; b < cnt; b += kWave)
+                    keys[base + b] = ((unsigned long long)mono_key(da + sLd[R + b]) << 32) | ((unsigned)a << 16) | (unsigned)b;
             }
             for (int e = (int)nreg + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
+            bitonic_sort_lds(keys, npad, tid, kRankThreads);
+        } else {
+            // radix select of the Tn-th smallest sum over the region, keys recomputed in every pass
+            const int rows = R < Tn ? R : Tn;
+            auto for_region = [&](auto&& f) {
+                for (int a = wave; a < rows; a += nwaves) {
+                    const int cnt = region_row_count(a, R, Tn);
+                    const float da = sLd[a];
+                    for (int b = lane; b < cnt; b += kWave) f(mono_key(da + sLd[R + b]), (uint32_t)a, (uint32_t)b);
+                }
+            };
+            uint32_t prefix = 0, mask = 0, need = (uint32_t)Tn, less = 0, neq = 0;
+            const int shifts[4] = {22, 12, 2, 0};
+            const int nbits[4] = {10, 10, 10, 2};
+            for (int pass = 0; pass < 4; ++pass) {
+                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
+                __syncthreads();
+                const int sh = shifts[pass];
+                const uint32_t dm = (1u << nbits[pass]) - 1u;
+                for_region([&](uint32_t k32, uint32_t, uint32_t) {
+                    if ((k32 & mask) == prefix) atomicAdd(&hist[(k32 >> sh) & dm], 1u);
+                });
+                __syncthreads();
+                uint32_t digit, before, cnt;
+                hist_locate(hist, need, lane, digit, before, cnt);
+                less += before;
+                need -= before;
+                neq = cnt;
+                prefix |= digit << sh;
+                mask |= dm << sh;
+                __syncthreads();
+            }
+            const uint32_t tau = prefix;                     // Tn-th smallest sum key; `need` of the neq ties count
+            uint32_t a_cut = 0xffffffffu, b_cut = 0xffffffffu;
+            if (less + neq > (uint32_t)L.cap) {              // too many ties: cut them by (r1, r2)
+                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
+                __syncthreads();
+                for_region([&](uint32_t k32, uint32_t a, uint32_t) {
+                    if (k32 == tau) atomicAdd(&hist[a], 1u);
+                });
+                __syncthreads();
+                uint32_t before, cnt;
+                hist_locate(hist, need, lane, a_cut, before, cnt);
+                need -= before;
+                __syncthreads();
+                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
+                __syncthreads();
+                for_region([&](uint32_t k32, uint32_t a, uint32_t b) {
+                    if (k32 == tau && a == a_cut) atomicAdd(&hist[b], 1u);
+                });
+                __syncthreads();
+                hist_locate(hist, need, lane, b_cut, before, cnt);
+                __syncthreads();
+            }
+            if (tid == 0) misc[0] = 0;
+            __syncthreads();
+            for_region([&](uint32_t k32, uint32_t a, uint32_t b) {
+                bool take = k32 < tau;
+                if (k32 == tau) take = a_cut == 0xffffffffu || a < a_cut || (a == a_cut && b <= b_cut);
+                if (take) keys[atomicAdd(&misc[0], 1u)] = ((unsigned long long)k32 << 32) | (a << 16) | b;
+            });
+            __syncthreads();
+            const int n = (int)misc[0];
+            const int npad = next_pow2(n);
+            for (int e = n + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
             bitonic_sort_lds(keys, npad, tid, kRankThreads);
         }
 
@@ -287,38 +348,33 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
             __syncthreads();
         }
 
-        // ---- lay the runs end to end -------------------------------------------------------------------
+        // ---- lay the runs end to end, cut at C, compact ------------------------------------------------
         for (int t = tid; t < Tn; t += kRankThreads) sflag[t] = slen[t];
         __syncthreads();
-        total = block_exclusive_scan(sflag, Tn, part);               // sflag[t] = start position
-        if (total >= C || Tn >= Tall) break;                         // uniform: total comes from LDS
-        Tn = Tall;
-    }
-
-    // ---- cut at C, compact -------------------------------------------------------------------------------
-    for (int t = tid; t < Tn; t += kRankThreads) {
-        const uint32_t start = sflag[t];
-        slen[t] = (slen[t] > 0 && start < C) ? 1u : 0u;                  // run is proposed
-    }
-    __syncthreads();
-    const uint32_t nruns = block_exclusive_scan(slen, Tn, part);        // slen[t] = run index
-    for (int t = tid; t < Tn; t += kRankThreads) {
-        const uint32_t start = sflag[t];
-        const uint32_t idx = slen[t];
-        const bool emit = (t + 1 < Tn ? slen[t + 1] : nruns) != idx;     // its flag was 1
-        if (emit) {
-            g.runs[(size_t)q * T + idx] = make_uint2(so0[t], start);
-            if (g.slots) {
-                const unsigned long long key = keys[t];
-                unsigned long long lin;
-                if (P == 1) lin = sLid[(unsigned)key & 0xffffu];
-                else lin = (unsigned long long)sLid[((unsigned)key >> 16) & 0xffffu] * g.k1k2 + sLid[R + ((unsigned)key & 0xffffu)];
-                g.slots[(size_t)q * T + idx] = g.hashed ? (lin % g.H) : lin;
+        const uint32_t total = block_exclusive_scan(sflag, Tn, part);    // sflag[t] = start position
+        for (int t = tid; t < Tn; t += kRankThreads) {
+            const uint32_t start = sflag[t];
+            slen[t] = (slen[t] > 0 && start < C) ? 1u : 0u;              // run is proposed
+        }
+        __syncthreads();
+        const uint32_t nruns = block_exclusive_scan(slen, Tn, part);    // slen[t] = run index
+        for (int t = tid; t < Tn; t += kRankThreads) {
+            const uint32_t start = sflag[t];
+            const uint32_t idx = slen[t];
+            const bool emit = (t + 1 < Tn ? slen[t + 1] : nruns) != idx; // its flag was 1
+            if (emit) {
+                g.runs[(size_t)q * T + idx] = make_uint2(so0[t], start);
+                if (g.slots) {
+                    const unsigned long long key = keys[t];
+                    unsigned long long lin;
+                    if (P == 1) lin = sLid[(unsigned)key & 0xffffu];
+                    else lin = (unsigned long long)sLid[((unsigned)key >> 16) & 0xffffu] * g.k1k2 + sLid[R + ((unsigned)key & 0xffffu)];
+                    g.slots[(size_t)q * T + idx] = g.hashed ? (lin % g.H) : lin;
+                }
             }
         }
-    }
-    if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
-    __syncthreads();
+        if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
+        __syncthreads();
     }   // next query of the list
 }
 
@@ -326,10 +382,11 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
     const RankLds L = rank_layout(a.P, a.R, a.T, a.hashed);
     RankOffsets o;
-    o.npad = L.npad; o.Tcap = L.Tcap; o.Tpad = L.Tpad;
-    o.keys = (uint32_t)L.off_keys; o.dkeys = (uint32_t)L.off_dkeys; o.Ld = (uint32_t)L.off_Ld;
-    o.Lid = (uint32_t)L.off_Lid; o.rowbase = (uint32_t)L.off_rowbase; o.len = (uint32_t)L.off_len;
-    o.o0 = (uint32_t)L.off_o0; o.flag = (uint32_t)L.off_flag; o.part = (uint32_t)L.off_part;
+    o.Tcap = L.Tcap; o.cap = L.cap; o.nreg = L.nreg;
+    o.keys = (uint32_t)L.off_keys; o.dkeys = (uint32_t)L.off_dkeys; o.hist = (uint32_t)L.off_hist;
+    o.Ld = (uint32_t)L.off_Ld; o.Lid = (uint32_t)L.off_Lid; o.rowbase = (uint32_t)L.off_rowbase;
+    o.len = (uint32_t)L.off_len; o.o0 = (uint32_t)L.off_o0; o.flag = (uint32_t)L.off_flag;
+    o.part = (uint32_t)L.off_part; o.misc = (uint32_t)L.off_misc;
     const bool taps = a.n_tuples || a.tuples || a.tuple_keys || a.slots;
     const bool head = (a.P == 2) && !taps;
     o.force = head ? 0 : 1;

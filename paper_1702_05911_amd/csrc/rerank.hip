@@ -68,14 +68,6 @@ __device__ __forceinline__ uint32_t source_of(uint32_t p, int nr, int steps, con
     return run_src[lo] + (p - run_start[lo]);
 }
 
-__device__ __forceinline__ uint32_t wave_sum_inclusive(uint32_t v, int lane) {
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t n = __shfl_up(v, off, kWave);
-        if (lane >= off) v += n;
-    }
-    return v;
-}
-
 // One pass of a most-significant-digit radix select (exact fallback).  Counts, among the n items
 // whose key agrees with `prefix` on the bits of `mask`, the digit (key >> shift) & (2^bits - 1);
 // finds the digit holding the item of 1-based rank `need`.  out[0] = digit, out[1] = rank inside
@@ -306,26 +298,10 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
             atomicAdd(&hist[b], 1u);
         }
         __syncthreads();
-        // every wavefront: bin b with count(< b) < kk <= count(<= b); 16 bins per lane
-        uint32_t bsel, count_le;
-        {
-            constexpr int cb = kHistSize / kWave;
-            uint32_t s = 0;
-#pragma unroll
-            for (int j = 0; j < cb; ++j) s += hist[lane * cb + ((j + lane) & (cb - 1))];
-            const uint32_t incl = wave_sum_inclusive(s, lane);
-            uint32_t c = incl - s;
-            const bool mine = c < (uint32_t)kk && (uint32_t)kk <= incl;   // exactly one lane
-            uint32_t b = 0, cle = 0;
-            if (mine) {
-                b = (uint32_t)lane * cb;
-                while (c + hist[b] < (uint32_t)kk) c += hist[b++];
-                cle = c + hist[b];
-            }
-            const int owner = __ffsll((long long)__ballot(mine)) - 1;
-            bsel = (uint32_t)__shfl((int)b, owner, kWave);
-            count_le = (uint32_t)__shfl((int)cle, owner, kWave);
-        }
+        // every wavefront: bin bsel with count(< bsel) < kk <= count(<= bsel)
+        uint32_t bsel, below, inbin;
+        hist_locate(hist, (uint32_t)kk, lane, bsel, below, inbin);
+        const uint32_t count_le = below + inbin;
         if (count_le <= (uint32_t)L.scap) {
             for (int p = tid; p < nc; p += nt) {
                 const uint32_t key = skey[p];

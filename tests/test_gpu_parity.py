@@ -113,12 +113,12 @@ def test_tiny_exhaustive_visits_everything(pqt, tiny, tmp_path):
         PU.check_query_stages(ix, Ys[q], taps, q, 10, cfg.k1, ix.K, cfg.N, ids, dists)
 
 
-def _exact_arithmetic_index(N=3000, seed=5):
+def _exact_arithmetic_index(N=3000, seed=5, k1=4, k2=2):
     """Integer codebooks, integer data and dyadic lambdas: every fp32 operation of the path is
     exact, so the GPU must equal the float64 oracle bit for bit, distances included."""
     from workloads import small_integer_vectors
     rng = np.random.default_rng(seed)
-    D, P, k1, k2, M = 16, 2, 4, 2, 4
+    D, P, M = 16, 2, 4
     dp = D // P
     C1 = rng.integers(0, 8, size=(P, k1, dp)).astype(np.float32)
     C2 = np.clip(C1[:, :, None, :] + rng.integers(-1, 2, size=(P, k1, k2, dp)), 0, 7).astype(np.float32)
@@ -140,6 +140,17 @@ def test_exact_arithmetic_index_is_bit_exact(pqt, tmp_path):
     for (k, w, T, C) in ((10, 2, 16, 200), (50, 4, 64, 512), (7, 1, 4, 64)):
         same, _ = _stagewise(pqt, ix, path, Y, k, w, T, C, exact=True)
         assert same == Y.shape[0]
+
+
+def test_exact_arithmetic_wide_lists_heavily_tied_bin_keys(pqt, tmp_path):
+    """Integer level-2 distances over wide lists: thousands of bin keys tie, so the ranking pass must cut
+    the ties at the T-th tuple by (r1, r2) exactly (region larger than the sort buffer)."""
+    ix, X, Y = _exact_arithmetic_index(N=20000, seed=11, k1=16, k2=8)
+    path = str(tmp_path / "exact_wide.pqt")
+    IO.write_index(path, ix)
+    for (k, w, T, C) in ((20, 8, 1020, 4096), (20, 16, 2040, 2000), (10, 8, 510, 512), (10, 4, 300, 512)):
+        same, _ = _stagewise(pqt, ix, path, Y[:24], k, w, T, C, exact=True)
+        assert same == 24
 
 
 def test_duplicate_database_ties_broken_by_id(pqt, tmp_path):
