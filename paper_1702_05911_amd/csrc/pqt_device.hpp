@@ -18,23 +18,51 @@ __device__ __forceinline__ float mono_inv(uint32_t k) {
     return __uint_as_float(u);
 }
 
-// In-place ascending bitonic sort of n (a power of two) keys in LDS by `nthreads`
-// cooperating threads numbered tid.  Every thread of the workgroup must call it with the
-// same n (it uses workgroup barriers), but different groups of threads may sort
-// different arrays.
+// Orders the LDS accesses of ONE wavefront: LDS instructions of a wave execute in program order,
+// so only the compiler has to be kept from moving them across this point.
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// In-place ascending bitonic sort of n (a power of two) keys in LDS by the `nthreads` threads of
+// the workgroup (tid = threadIdx.x; nthreads a power-of-two multiple of 64).  Every thread must
+// call it with the same arguments.  Each wavefront owns a contiguous chunk of n / (nthreads/64)
+// keys: compare-exchange steps whose stride stays inside a chunk need no workgroup barrier, only
+// the steps that cross chunks do.
 template <typename K>
 __device__ __forceinline__ void bitonic_sort_lds(K* keys, int n, int tid, int nthreads) {
+    const int nwaves = nthreads / kWave, wave = tid / kWave, lane = tid & (kWave - 1);
+    const int chunk = n / nwaves;                 // 0 or 1 when n is small: every step is a workgroup step
+    bool crossed = true;                          // the previous step touched other wavefronts' keys
     for (int size = 2; size <= n; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (int e = tid; e < (n >> 1); e += nthreads) {
-                int i = 2 * e - (e & (stride - 1));
-                int j = i + stride;
-                bool asc = (i & size) == 0;
-                K x = keys[i], y = keys[j];
-                if ((x > y) == asc) {
-                    keys[i] = y;
-                    keys[j] = x;
+            if (stride < chunk) {
+                if (crossed) __syncthreads(); else wave_lds_order();
+                crossed = false;
+                for (int e = wave * (chunk >> 1) + lane; e < (wave + 1) * (chunk >> 1); e += kWave) {
+                    const int i = 2 * e - (e & (stride - 1));
+                    const int j = i + stride;
+                    const bool asc = (i & size) == 0;
+                    const K x = keys[i], y = keys[j];
+                    if ((x > y) == asc) {
+                        keys[i] = y;
+                        keys[j] = x;
+                    }
+                }
+            } else {
+                __syncthreads();
+                crossed = true;
+                for (int e = tid; e < (n >> 1); e += nthreads) {
+                    const int i = 2 * e - (e & (stride - 1));
+                    const int j = i + stride;
+                    const bool asc = (i & size) == 0;
+                    const K x = keys[i], y = keys[j];
+                    if ((x > y) == asc) {
+                        keys[i] = y;
+                        keys[j] = x;
+                    }
                 }
             }
         }
@@ -109,14 +137,6 @@ __device__ __forceinline__ void hist_locate(const uint32_t* hist, uint32_t need,
     count = (uint32_t)__shfl((int)ct, owner, kWave);
 }
 
-// Orders the LDS accesses of ONE wavefront: LDS instructions of a wave execute in program order,
-// so only the compiler has to be kept from moving them across this point.
-__device__ __forceinline__ void wave_lds_order() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Ascending bitonic sort of n (a power of two) keys in LDS by the 64 lanes of one wavefront;
 // no workgroup barrier, other wavefronts may do anything else meanwhile.
 template <typename K>
@@ -140,53 +160,38 @@ __device__ __forceinline__ void wave_bitonic_sort_lds(K* keys, int n, int lane) 
 }
 
 // Exclusive prefix sum over data[0..n) in LDS, in place, by the whole workgroup.
-// part needs blockDim.x entries.  Returns the total.  Ends with a barrier.
+// part needs blockDim.x + 1 entries.  Returns the total.  Ends with a barrier.
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t* data, int n, uint32_t* part) {
-    const int tid = threadIdx.x, nt = blockDim.x;
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & (kWave - 1);
     const int chunk = (n + nt - 1) / nt;
     const int lo = min(tid * chunk, n), hi = min(lo + chunk, n);
     uint32_t s = 0;
     for (int e = lo; e < hi; ++e) s += data[e];
     part[tid] = s;
     __syncthreads();
-    for (int off = 1; off < nt; off <<= 1) {
-        uint32_t v = (tid >= off) ? part[tid - off] : 0u;
-        __syncthreads();
-        part[tid] += v;
-        __syncthreads();
+    if (tid < kWave) {                            // the first wavefront scans the per-thread sums
+        const int per = nt / kWave;
+        uint32_t ls = 0;
+        for (int i = 0; i < per; ++i) ls += part[lane * per + i];
+        const uint32_t incl = wave_inclusive_sum(ls, lane);
+        uint32_t run = incl - ls;
+        for (int i = 0; i < per; ++i) {
+            const uint32_t v = part[lane * per + i];
+            part[lane * per + i] = run;           // exclusive prefix of thread lane*per+i
+            run += v;
+        }
+        if (lane == kWave - 1) part[nt] = incl;   // grand total
     }
-    const uint32_t total = part[nt - 1];
-    s = (tid > 0) ? part[tid - 1] : 0u;
+    __syncthreads();
+    s = part[tid];
+    const uint32_t total = part[nt];
     for (int e = lo; e < hi; ++e) {
-        uint32_t v = data[e];
+        const uint32_t v = data[e];
         data[e] = s;
         s += v;
     }
     __syncthreads();
     return total;
-}
-
-// Inclusive running maximum over data[0..n) in LDS (uint16 payload), in place.
-__device__ __forceinline__ void block_inclusive_max_u16(uint16_t* data, int n, uint32_t* part) {
-    const int tid = threadIdx.x, nt = blockDim.x;
-    const int chunk = (n + nt - 1) / nt;
-    const int lo = min(tid * chunk, n), hi = min(lo + chunk, n);
-    uint32_t s = 0;
-    for (int e = lo; e < hi; ++e) s = max(s, (uint32_t)data[e]);
-    part[tid] = s;
-    __syncthreads();
-    for (int off = 1; off < nt; off <<= 1) {
-        uint32_t v = (tid >= off) ? part[tid - off] : 0u;
-        __syncthreads();
-        part[tid] = max(part[tid], v);
-        __syncthreads();
-    }
-    s = (tid > 0) ? part[tid - 1] : 0u;
-    for (int e = lo; e < hi; ++e) {
-        s = max(s, (uint32_t)data[e]);
-        data[e] = (uint16_t)s;
-    }
-    __syncthreads();
 }
 
 __host__ __device__ inline int next_pow2(int v) {

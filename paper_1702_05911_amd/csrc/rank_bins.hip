@@ -56,7 +56,7 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     L.off_len = o;     o += sizeof(uint32_t) * L.Tcap;
     L.off_o0 = o;      o += sizeof(uint32_t) * L.Tcap;
     L.off_flag = o;    o += sizeof(uint32_t) * L.Tcap;
-    L.off_part = o;    o += sizeof(uint32_t) * kRankThreads;
+    L.off_part = o;    o += sizeof(uint32_t) * (kRankThreads + 1);
     L.off_misc = o;    o += sizeof(uint32_t) * 16;
     L.total = o;
     return L;
