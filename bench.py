@@ -45,8 +45,8 @@ def make_data(cfg, device):
         X = chunks(0, cfg.N) if cfg.N <= 4_000_000 else None
         return X, Y, (chunks if X is None else (lambda s, n: X[s:s + n]))
     if cfg.kind == "gist":
-        X = torch.from_numpy(synth.gist_like(0, cfg.N, d=cfg.D, seed=cfg.data_seed)).to(device)
-        Y = torch.from_numpy(synth.gist_like(0, cfg.nq, d=cfg.D, seed=cfg.query_seed + 100)).to(device)
+        X = synth.gist_like_torch(0, cfg.N, d=cfg.D, seed=cfg.data_seed, device=device)
+        Y = synth.gist_like_torch(0, cfg.nq, d=cfg.D, seed=cfg.query_seed + 100, device=device)
         return X, Y, (lambda s, n: X[s:s + n])
     raise ValueError(cfg.kind)
 

@@ -196,7 +196,6 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
         return fail(PQT_EFORMAT, "'%s': inconsistent sizes D=%u P=%u k1=%u k2=%u M=%u", path, h.D, h.P, h.k1,
                     h.k2, h.M);
     if (!(h.P == 1 || h.P == 2 || h.P == 4)) return fail(PQT_EUNSUPPORTED, "P=%u: only 1, 2 or 4 tree parts", h.P);
-    if (h.P == 4) return fail(PQT_EUNSUPPORTED, "P=4 bin ranking is not available in this build");
     if (h.k1 > PQT_MAX_K1 || h.k2 > PQT_MAX_R || h.M > 64 || h.D > 8192)
         return fail(PQT_EUNSUPPORTED, "k1=%u k2=%u M=%u D=%u beyond the kernel limits", h.k1, h.k2, h.M, h.D);
     if (h.N >= 0xffffffffull || h.H >= 0xffffffffull)
@@ -204,6 +203,8 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
                     (unsigned long long)h.H);
     long double K = 1;
     for (uint32_t p = 0; p < h.P; ++p) K *= (long double)h.k1 * h.k2;
+    if (K >= 18446744073709551616.0L)
+        return fail(PQT_EUNSUPPORTED, "(k1*k2)^P = %Lg bins do not fit 64-bit bin numbers", K);
     if ((long double)h.H > K) return fail(PQT_EFORMAT, "'%s': H exceeds the number of bins", path);
     if (h.T < 1 || h.T > PQT_MAX_T || h.C < 1 || h.C > PQT_MAX_C)
         return fail(PQT_EFORMAT, "'%s': default budgets T=%u C=%u out of range", path, h.T, h.C);

@@ -22,42 +22,65 @@ __host__ __device__ inline int region_row_count(int a, int R, int T) {
     return c < R ? c : R;
 }
 
-int rank_region_size(int R, int T) {
+// Number of pairs (a, b), a < nA, b < nB, with (a+1)(b+1) <= Tn.
+static long region_size(int nA, int nB, int Tn) {
     long n = 0;
-    for (int a = 0; a < R; ++a) n += region_row_count(a, R, T);
-    return (int)n;
+    for (int a = 0; a < nA && a < Tn; ++a) n += region_row_count(a, nB, Tn);
+    return n;
 }
+
+int rank_region_size(int R, int T) { return (int)region_size(R, R, T); }
 
 constexpr int kSelBits = 10;
 constexpr int kSelBins = 1 << kSelBits;
+constexpr int kRegionSplit = 64;   // rows below it are walked along b, the rest of the region along a
 
 struct RankLds {
-    int Tcap;   // tuples examined: min(T, R^P)
-    int cap;    // sort buffer entries: next_pow2(Tcap)
-    int nreg;   // size of the hyperbolic region (P = 2)
-    size_t off_keys, off_dkeys, off_hist, off_Ld, off_Lid, off_rowbase, off_len, off_o0, off_flag, off_part,
+    int Tcap;    // tuples examined: min(T, R^P)
+    int cap;     // sort buffer entries: next_pow2(Tcap), at least 64
+    int npair;   // P = 4: length of each of the two pair lists, min(T, R^2)
+    int nreg;    // size of the hyperbolic region of the final ranking (P = 2, 4)
+    int nreg_pair;   // P = 4: region size of each pair ranking
+    size_t off_keys, off_hist, off_Ld, off_Lid, off_ps, off_pt, off_len, off_o0, off_slot, off_flag, off_part,
         off_misc, total;
 };
 
 static RankLds rank_layout(int P, int R, int T, int hashed) {
+    (void)hashed;                      // the de-duplication keys reuse the sort buffer
     RankLds L;
     long total_tuples = 1;
     for (int p = 0; p < P; ++p) total_tuples = (total_tuples * R > (1L << 40)) ? (1L << 40) : total_tuples * R;
     L.Tcap = (int)((long)T < total_tuples ? (long)T : total_tuples);
     L.cap = next_pow2(L.Tcap) < 64 ? 64 : next_pow2(L.Tcap);
-    L.nreg = (P == 1) ? L.Tcap : rank_region_size(R, L.Tcap);
+    L.npair = 0;
+    L.nreg_pair = 0;
+    if (P == 1) {
+        L.nreg = L.Tcap;
+    } else if (P == 2) {
+        L.nreg = (int)region_size(R, R, L.Tcap);
+    } else {
+        L.npair = (int)((long)T < (long)R * R ? (long)T : (long)R * R);
+        L.nreg_pair = (int)region_size(R, R, L.npair);
+        L.nreg = (int)region_size(L.npair, L.npair, L.Tcap);
+    }
     size_t o = 0;
-    L.off_keys = o;    o += sizeof(unsigned long long) * L.cap;
-    L.off_dkeys = o;   o += hashed ? sizeof(unsigned long long) * L.cap : 0;
-    L.off_hist = o;    o += sizeof(uint32_t) * kSelBins;
-    L.off_Ld = o;      o += sizeof(float) * P * R;
-    L.off_Lid = o;     o += sizeof(uint32_t) * P * R;
-    L.off_rowbase = o; o += sizeof(uint32_t) * (R + 1);
-    L.off_len = o;     o += sizeof(uint32_t) * L.Tcap;
-    L.off_o0 = o;      o += sizeof(uint32_t) * L.Tcap;
-    L.off_flag = o;    o += sizeof(uint32_t) * L.Tcap;
-    L.off_part = o;    o += sizeof(uint32_t) * (kRankThreads + 1);
-    L.off_misc = o;    o += sizeof(uint32_t) * 16;
+    L.off_keys = o;  o += sizeof(unsigned long long) * L.cap;
+    L.off_hist = o;  o += sizeof(uint32_t) * kSelBins;
+    L.off_Ld = o;    o += sizeof(float) * P * R;
+    L.off_Lid = o;   o += sizeof(uint32_t) * P * R;
+    L.off_ps = o;    o += sizeof(float) * 2 * L.npair;        // summed distances of the two pair lists
+    L.off_pt = o;    o += sizeof(uint32_t) * 2 * L.npair;     // their rank pairs (r << 16 | r')
+    L.off_len = o;   o += sizeof(uint32_t) * L.Tcap;
+    L.off_o0 = o;    o += sizeof(uint32_t) * L.Tcap;
+    L.off_slot = o;  o += sizeof(uint32_t) * L.Tcap;
+    if (P == 4 && 2 * L.npair >= L.Tcap) {
+        L.off_flag = L.off_ps;         // the pair sums are dead once every tuple has its slot
+    } else {
+        L.off_flag = o;
+        o += sizeof(uint32_t) * L.Tcap;
+    }
+    L.off_part = o;  o += sizeof(uint32_t) * (kRankThreads + 1);
+    L.off_misc = o;  o += sizeof(uint32_t) * 16;
     L.total = o;
     return L;
 }
@@ -65,9 +88,9 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
 size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed).total; }
 
 struct RankOffsets {   // layout handed to the kernel (computed once on the host)
-    int Tcap, cap, nreg;
+    int Tcap, cap, npair, nreg, nreg_pair;
     int force;             // 1: rank every query (taps wanted, or no head pass ran)
-    uint32_t keys, dkeys, hist, Ld, Lid, rowbase, len, o0, flag, part, misc;
+    uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, flag, part, misc;
 };
 
 constexpr int kHeadT = 64;                     // tuples the head pass ranks
@@ -193,23 +216,139 @@ __global__ __launch_bounds__(kRankThreads) void rank_head_kernel(RankArgs g, int
 // ------------------------------------------------------------------------------------------------
 // Full pass: workgroups take the queries the head pass listed (or every query when forced).
 // ------------------------------------------------------------------------------------------------
+
+// Calls f(ordered sum bits, a, b) for every pair of the region {a < nA, b < nB, (a+1)(b+1) <= Tn},
+// each pair once, spread over the workgroup.  Rows a < kRegionSplit are walked along b (they are
+// long); the remaining pairs have b < Tn / (kRegionSplit + 1) and are walked along a, so lanes stay
+// busy in the thin tail of the hyperbola as well.
+template <typename F>
+__device__ __forceinline__ void for_region(const float* A, int nA, const float* B, int nB, int Tn, int wave,
+                                           int lane, F&& f) {
+    constexpr int nwaves = kRankThreads / kWave;
+    const int rows = min(min(nA, Tn), kRegionSplit);
+    for (int a = wave; a < rows; a += nwaves) {
+        const int cnt = region_row_count(a, nB, Tn);
+        const float da = A[a];
+        for (int b = lane; b < cnt; b += kWave) f(mono_key(da + B[b]), (uint32_t)a, (uint32_t)b);
+    }
+    if (nA > kRegionSplit) {
+        const int cols = min(nB, Tn / (kRegionSplit + 1));
+        for (int b = wave; b < cols; b += nwaves) {
+            const int hi = min(nA, Tn / (b + 1));
+            const float db = B[b];
+            for (int a = kRegionSplit + lane; a < hi; a += kWave) f(mono_key(A[a] + db), (uint32_t)a, (uint32_t)b);
+        }
+    }
+}
+
+// Appends `key` to keys[] for every lane with take set; one LDS atomic per wavefront instruction.
+__device__ __forceinline__ void wave_append(bool take, unsigned long long key, unsigned long long* keys,
+                                            uint32_t* counter, int lane) {
+    const unsigned long long m = __ballot(take);
+    if (!take) return;
+    const int leader = __ffsll((long long)m) - 1;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+    base = (uint32_t)__shfl((int)base, leader, kWave);
+    keys[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = key;
+}
+
+// Leaves in keys[0..Tn) the first Tn pairs (a, b) of two ascending lists A[0..nA), B[0..nB) in the
+// order (fl32(A[a] + B[b]), a, b), as sorted keys (ordered sum bits << 32 | a << 16 | b).
+// Tn <= nA * nB; nreg = size of the region (a+1)(b+1) <= Tn; cap = entries of keys[] (a power of two
+// >= Tn).  If the region fits it is sorted directly; otherwise the Tn-th smallest key is found by a
+// radix select over the region (sums recomputed in every pass, never stored), ties at that key are cut
+// by (a, b), and only the Tn smallest are collected and sorted.  All threads call it; ends with a barrier.
+__device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* B, int nB, int Tn, int nreg,
+                                           int cap, unsigned long long* keys, uint32_t* hist, uint32_t* misc) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    uint32_t tau = 0xffffffffu, a_cut = 0xffffffffu, b_cut = 0xffffffffu;
+    const bool all = nreg <= cap;
+    if (!all) {
+        uint32_t prefix = 0, mask = 0, need = (uint32_t)Tn, less = 0, neq = 0;
+        const int shifts[4] = {22, 12, 2, 0};
+        const int nbits[4] = {10, 10, 10, 2};
+        for (int pass = 0; pass < 4; ++pass) {
+            for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
+            __syncthreads();
+            const int sh = shifts[pass];
+            const uint32_t dm = (1u << nbits[pass]) - 1u;
+            for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+                if ((k32 & mask) == prefix) atomicAdd(&hist[(k32 >> sh) & dm], 1u);
+            });
+            __syncthreads();
+            uint32_t digit, before, cnt;
+            hist_locate(hist, need, lane, digit, before, cnt);
+            less += before;
+            need -= before;
+            neq = cnt;
+            prefix |= digit << sh;
+            mask |= dm << sh;
+            __syncthreads();
+        }
+        tau = prefix;                                    // Tn-th smallest sum key; `need` of the neq ties count
+        if (less + neq > (uint32_t)cap) {                // too many ties to sort: cut them by (a, b)
+            // a and b can exceed the histogram's 1024 bins: select on the high then the low digit
+            uint32_t before, cnt, hi_d, lo_d;
+            auto pass = [&](auto&& digit_of) {           // digit_of(k32, a, b) -> bin or 0xffffffff (skip)
+                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
+                __syncthreads();
+                for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+                    const uint32_t d = digit_of(k32, a, b);
+                    if (d != 0xffffffffu) atomicAdd(&hist[d], 1u);
+                });
+                __syncthreads();
+                uint32_t digit;
+                hist_locate(hist, need, lane, digit, before, cnt);
+                need -= before;
+                __syncthreads();
+                return digit;
+            };
+            hi_d = pass([&](uint32_t k32, uint32_t a, uint32_t) { return k32 == tau ? (a >> 6) : 0xffffffffu; });
+            lo_d = pass([&](uint32_t k32, uint32_t a, uint32_t) {
+                return (k32 == tau && (a >> 6) == hi_d) ? (a & 63u) : 0xffffffffu;
+            });
+            a_cut = (hi_d << 6) | lo_d;
+            hi_d = pass([&](uint32_t k32, uint32_t a, uint32_t b) {
+                return (k32 == tau && a == a_cut) ? (b >> 6) : 0xffffffffu;
+            });
+            lo_d = pass([&](uint32_t k32, uint32_t a, uint32_t b) {
+                return (k32 == tau && a == a_cut && (b >> 6) == hi_d) ? (b & 63u) : 0xffffffffu;
+            });
+            b_cut = (hi_d << 6) | lo_d;
+        }
+    }
+    if (tid == 0) misc[0] = 0;
+    __syncthreads();
+    for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+        bool take = all || k32 < tau;
+        if (!all && k32 == tau) take = a_cut == 0xffffffffu || a < a_cut || (a == a_cut && b <= b_cut);
+        wave_append(take, ((unsigned long long)k32 << 32) | (a << 16) | b, keys, &misc[0], lane);
+    });
+    __syncthreads();
+    const int n = (int)misc[0];
+    const int npad = next_pow2(n);
+    for (int e = n + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
+    bitonic_sort_lds(keys, npad, tid, kRankThreads);
+}
+
 __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + L.keys);
-    unsigned long long* dkeys = reinterpret_cast<unsigned long long*>(smem + L.dkeys);
+    unsigned long long* dkeys = keys;                       // (slot, position) keys reuse the sort buffer
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
     float* sLd = reinterpret_cast<float*>(smem + L.Ld);
     uint32_t* sLid = reinterpret_cast<uint32_t*>(smem + L.Lid);
-    uint32_t* rowbase = reinterpret_cast<uint32_t*>(smem + L.rowbase);
+    float* ps = reinterpret_cast<float*>(smem + L.ps);
+    uint32_t* pt = reinterpret_cast<uint32_t*>(smem + L.pt);
     uint32_t* slen = reinterpret_cast<uint32_t*>(smem + L.len);
     uint32_t* so0 = reinterpret_cast<uint32_t*>(smem + L.o0);
+    uint32_t* sslot = reinterpret_cast<uint32_t*>(smem + L.slot);
     uint32_t* sflag = reinterpret_cast<uint32_t*>(smem + L.flag);
     uint32_t* part = reinterpret_cast<uint32_t*>(smem + L.part);
     uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);
 
     const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1), wave = tid / kWave;
-    constexpr int nwaves = kRankThreads / kWave;
     const int P = g.P, R = g.R, T = g.T;
     const int Tn = L.Tcap;                                  // min(T, R^P)
     const uint32_t C = (uint32_t)g.C;
@@ -223,115 +362,59 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
         }
         __syncthreads();
 
-        // ---- the first Tn tuples, sorted, as keys (ordered sum bits, r1, r2) -----------------------
+        // ---- the first Tn tuples, sorted, as keys (ordered sum bits, position, position) -------------
         if (P == 1) {
             for (int e = tid; e < Tn; e += kRankThreads)
                 keys[e] = ((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e;
             __syncthreads();                     // the list is already sorted by (distance, id)
-        } else if (L.nreg <= L.cap) {            // the whole region fits: sort it
-            for (int a = tid; a < R; a += kRankThreads) rowbase[a] = (uint32_t)region_row_count(a, R, Tn);
-            __syncthreads();
-            const uint32_t nreg = block_exclusive_scan(rowbase, R, part);
-            const int npad = next_pow2((int)nreg);
-            for (int a = wave; a < R; a += nwaves) {
-                const int cnt = region_row_count(a, R, Tn);
-                const uint32_t base = rowbase[a];
-                const float da = sLd[a];
-                for (int b = lane; b < cnt; b += kWave)
-                    keys[base + b] = ((unsigned long long)mono_key(da + sLd[R + b]) << 32) | ((unsigned)a << 16) | (unsigned)b;
-            }
-            for (int e = (int)nreg + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
-            bitonic_sort_lds(keys, npad, tid, kRankThreads);
+        } else if (P == 2) {
+            rank_pairs(sLd, R, sLd + R, R, Tn, L.nreg, L.cap, keys, hist, misc);
         } else {
-            // radix select of the Tn-th smallest sum over the region, keys recomputed in every pass
-            const int rows = R < Tn ? R : Tn;
-            auto for_region = [&](auto&& f) {
-                for (int a = wave; a < rows; a += nwaves) {
-                    const int cnt = region_row_count(a, R, Tn);
-                    const float da = sLd[a];
-                    for (int b = lane; b < cnt; b += kWave) f(mono_key(da + sLd[R + b]), (uint32_t)a, (uint32_t)b);
+            // parts (1,2) and (3,4) first; then pairs of positions in those two lists
+            const int np = L.npair;
+            for (int half = 0; half < 2; ++half) {
+                rank_pairs(sLd + 2 * half * R, R, sLd + (2 * half + 1) * R, R, np, L.nreg_pair, L.cap, keys, hist, misc);
+                for (int e = tid; e < np; e += kRankThreads) {
+                    const unsigned long long key = keys[e];
+                    ps[half * np + e] = mono_inv((uint32_t)(key >> 32));
+                    pt[half * np + e] = (uint32_t)key;
                 }
-            };
-            uint32_t prefix = 0, mask = 0, need = (uint32_t)Tn, less = 0, neq = 0;
-            const int shifts[4] = {22, 12, 2, 0};
-            const int nbits[4] = {10, 10, 10, 2};
-            for (int pass = 0; pass < 4; ++pass) {
-                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
-                __syncthreads();
-                const int sh = shifts[pass];
-                const uint32_t dm = (1u << nbits[pass]) - 1u;
-                for_region([&](uint32_t k32, uint32_t, uint32_t) {
-                    if ((k32 & mask) == prefix) atomicAdd(&hist[(k32 >> sh) & dm], 1u);
-                });
-                __syncthreads();
-                uint32_t digit, before, cnt;
-                hist_locate(hist, need, lane, digit, before, cnt);
-                less += before;
-                need -= before;
-                neq = cnt;
-                prefix |= digit << sh;
-                mask |= dm << sh;
                 __syncthreads();
             }
-            const uint32_t tau = prefix;                     // Tn-th smallest sum key; `need` of the neq ties count
-            uint32_t a_cut = 0xffffffffu, b_cut = 0xffffffffu;
-            if (less + neq > (uint32_t)L.cap) {              // too many ties: cut them by (r1, r2)
-                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
-                __syncthreads();
-                for_region([&](uint32_t k32, uint32_t a, uint32_t) {
-                    if (k32 == tau) atomicAdd(&hist[a], 1u);
-                });
-                __syncthreads();
-                uint32_t before, cnt;
-                hist_locate(hist, need, lane, a_cut, before, cnt);
-                need -= before;
-                __syncthreads();
-                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
-                __syncthreads();
-                for_region([&](uint32_t k32, uint32_t a, uint32_t b) {
-                    if (k32 == tau && a == a_cut) atomicAdd(&hist[b], 1u);
-                });
-                __syncthreads();
-                hist_locate(hist, need, lane, b_cut, before, cnt);
-                __syncthreads();
-            }
-            if (tid == 0) misc[0] = 0;
-            __syncthreads();
-            for_region([&](uint32_t k32, uint32_t a, uint32_t b) {
-                bool take = k32 < tau;
-                if (k32 == tau) take = a_cut == 0xffffffffu || a < a_cut || (a == a_cut && b <= b_cut);
-                if (take) keys[atomicAdd(&misc[0], 1u)] = ((unsigned long long)k32 << 32) | (a << 16) | b;
-            });
-            __syncthreads();
-            const int n = (int)misc[0];
-            const int npad = next_pow2(n);
-            for (int e = n + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
-            bitonic_sort_lds(keys, npad, tid, kRankThreads);
+            rank_pairs(ps, np, ps + np, np, Tn, L.nreg, L.cap, keys, hist, misc);
         }
 
         // ---- tuple -> bin number -> slot -> run of the inverted list -------------------------------
         for (int t = tid; t < Tn; t += kRankThreads) {
             const unsigned long long key = keys[t];
             unsigned long long lin;
-            unsigned r1, r2 = 0;
+            unsigned r[4] = {0, 0, 0, 0};
             if (P == 1) {
-                r1 = (unsigned)key & 0xffffu;
-                lin = sLid[r1];
+                r[0] = (unsigned)key & 0xffffu;
+                lin = sLid[r[0]];
+            } else if (P == 2) {
+                r[0] = ((unsigned)key >> 16) & 0xffffu;
+                r[1] = (unsigned)key & 0xffffu;
+                lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
             } else {
-                r1 = ((unsigned)key >> 16) & 0xffffu;
-                r2 = (unsigned)key & 0xffffu;
-                lin = (unsigned long long)sLid[r1] * g.k1k2 + sLid[R + r2];
+                const uint32_t t12 = pt[((unsigned)key >> 16) & 0xffffu];
+                const uint32_t t34 = pt[L.npair + ((unsigned)key & 0xffffu)];
+                r[0] = t12 >> 16; r[1] = t12 & 0xffffu; r[2] = t34 >> 16; r[3] = t34 & 0xffffu;
+                lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
+                lin = lin * g.k1k2 + sLid[2 * R + r[2]];
+                lin = lin * g.k1k2 + sLid[3 * R + r[3]];
             }
             const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
             const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
             so0[t] = o0;
             slen[t] = o1 - o0;
-            if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;
+            sslot[t] = (uint32_t)slot;
             if (g.tuples) {
                 uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
-                tp[0] = (uint16_t)r1; tp[1] = (uint16_t)r2; tp[2] = 0; tp[3] = 0;
+                tp[0] = (uint16_t)r[0]; tp[1] = (uint16_t)r[1]; tp[2] = (uint16_t)r[2]; tp[3] = (uint16_t)r[3];
             }
             if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
+            if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;          // keys[t] is not needed again
         }
         if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
         __syncthreads();
@@ -364,13 +447,7 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
             const bool emit = (t + 1 < Tn ? slen[t + 1] : nruns) != idx; // its flag was 1
             if (emit) {
                 g.runs[(size_t)q * T + idx] = make_uint2(so0[t], start);
-                if (g.slots) {
-                    const unsigned long long key = keys[t];
-                    unsigned long long lin;
-                    if (P == 1) lin = sLid[(unsigned)key & 0xffffu];
-                    else lin = (unsigned long long)sLid[((unsigned)key >> 16) & 0xffffu] * g.k1k2 + sLid[R + ((unsigned)key & 0xffffu)];
-                    g.slots[(size_t)q * T + idx] = g.hashed ? (lin % g.H) : lin;
-                }
+                if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t];
             }
         }
         if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
@@ -382,11 +459,11 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
     const RankLds L = rank_layout(a.P, a.R, a.T, a.hashed);
     RankOffsets o;
-    o.Tcap = L.Tcap; o.cap = L.cap; o.nreg = L.nreg;
-    o.keys = (uint32_t)L.off_keys; o.dkeys = (uint32_t)L.off_dkeys; o.hist = (uint32_t)L.off_hist;
-    o.Ld = (uint32_t)L.off_Ld; o.Lid = (uint32_t)L.off_Lid; o.rowbase = (uint32_t)L.off_rowbase;
-    o.len = (uint32_t)L.off_len; o.o0 = (uint32_t)L.off_o0; o.flag = (uint32_t)L.off_flag;
-    o.part = (uint32_t)L.off_part; o.misc = (uint32_t)L.off_misc;
+    o.Tcap = L.Tcap; o.cap = L.cap; o.npair = L.npair; o.nreg = L.nreg; o.nreg_pair = L.nreg_pair;
+    o.keys = (uint32_t)L.off_keys; o.hist = (uint32_t)L.off_hist;
+    o.Ld = (uint32_t)L.off_Ld; o.Lid = (uint32_t)L.off_Lid; o.ps = (uint32_t)L.off_ps; o.pt = (uint32_t)L.off_pt;
+    o.len = (uint32_t)L.off_len; o.o0 = (uint32_t)L.off_o0; o.slot = (uint32_t)L.off_slot;
+    o.flag = (uint32_t)L.off_flag; o.part = (uint32_t)L.off_part; o.misc = (uint32_t)L.off_misc;
     const bool taps = a.n_tuples || a.tuples || a.tuple_keys || a.slots;
     const bool head = (a.P == 2) && !taps;
     o.force = head ? 0 : 1;

@@ -113,12 +113,12 @@ def test_tiny_exhaustive_visits_everything(pqt, tiny, tmp_path):
         PU.check_query_stages(ix, Ys[q], taps, q, 10, cfg.k1, ix.K, cfg.N, ids, dists)
 
 
-def _exact_arithmetic_index(N=3000, seed=5, k1=4, k2=2):
+def _exact_arithmetic_index(N=3000, seed=5, k1=4, k2=2, P=2):
     """Integer codebooks, integer data and dyadic lambdas: every fp32 operation of the path is
     exact, so the GPU must equal the float64 oracle bit for bit, distances included."""
     from workloads import small_integer_vectors
     rng = np.random.default_rng(seed)
-    D, P, M = 16, 2, 4
+    D, M = 16, 4
     dp = D // P
     C1 = rng.integers(0, 8, size=(P, k1, dp)).astype(np.float32)
     C2 = np.clip(C1[:, :, None, :] + rng.integers(-1, 2, size=(P, k1, k2, dp)), 0, 7).astype(np.float32)
@@ -220,6 +220,37 @@ def test_wide_selection_two_elements_per_lane(pqt, tmp_path, rng):
     path = str(tmp_path / "wide.pqt")
     IO.write_index(path, ixw)
     _stagewise(pqt, ixw, path, Y, 20, 8, 300, 700)
+
+
+def test_four_part_index(pqt, tmp_path):
+    """P = 4: parts (1,2) and (3,4) are ranked first, then pairs of positions in those two lists."""
+    from workloads import tiny_mixture
+    X = tiny_mixture(4000, d=32, seed=3)
+    Y = tiny_mixture(24, d=32, seed=4)
+    ix4 = B.build_index(X, P=4, k1=4, k2=4, M=8, T=512, C=1024, iters=5)
+    path = str(tmp_path / "p4.pqt")
+    IO.write_index(path, ix4)
+    # (k, w, T, C): R = 8 -> pair lists of 64, final region larger than the sort buffer;
+    # R = 16 -> pair lists cut at T; R = 4 -> every combination, T not a power of two; a long T
+    for (k, w, T, C) in ((10, 2, 256, 1024), (10, 4, 512, 600), (5, 1, 100, 200), (10, 3, 4096, 4000)):
+        _stagewise(pqt, ix4, path, Y, k, w, T, C)
+    # hashed slots: bins collide, a slot is proposed once
+    ixh = B.build_index(X, P=4, k1=4, k2=4, M=8, H=997, T=512, C=1024, codebooks=(ix4.C1, ix4.C2),
+                        line_table=(ix4.tbl_i, ix4.tbl_j, ix4.tbl_lam))
+    path = str(tmp_path / "p4h.pqt")
+    IO.write_index(path, ixh)
+    _stagewise(pqt, ixh, path, Y[:12], 10, 2, 300, 1024)
+
+
+def test_four_part_exact_arithmetic_heavily_tied(pqt, tmp_path):
+    """P = 4 on the exact-arithmetic index: integer sums tie by the hundreds in the pair lists and in the
+    final ranking, so every tie cut by (position, position) is exercised; results must be bit-exact."""
+    ix, X, Y = _exact_arithmetic_index(N=6000, seed=21, k1=8, k2=2, P=4)
+    path = str(tmp_path / "exact_p4.pqt")
+    IO.write_index(path, ix)
+    for (k, w, T, C) in ((10, 8, 600, 2000), (10, 4, 256, 512), (20, 8, 2048, 4096), (10, 2, 30, 300)):
+        same, _ = _stagewise(pqt, ix, path, Y[:16], k, w, T, C, exact=True)
+        assert same == 16
 
 
 def test_error_codes(pqt, tiny, tmp_path):
@@ -340,3 +371,62 @@ def test_sift_full_size_parity(pqt, sift_full, w):
         decided += d
     print(f"sift w={w}: {same}/{len(sample)} sampled queries identical to the float64 oracle, {decided} decided")
     assert same >= 0.8 * len(sample)
+
+
+@pytest.fixture(scope="module")
+def gist_full(pqt, tmp_path_factory):
+    """GIST-shaped 1M x 960 database, 1,000 queries, P = 4 with H = K = 2^28 bin slots (the pointer
+    array alone is 1 GiB, so its probes are real HBM accesses); index built by the package's builder."""
+    import torch
+    from workloads import CONFIGS, gist_like_torch
+    from paper_1702_05911_amd import builder
+    cfg = CONFIGS["gist"]
+    dev = torch.device("cuda", 0)
+    X = gist_like_torch(0, cfg.N, d=cfg.D, seed=cfg.data_seed, device=dev)
+    Y = gist_like_torch(0, cfg.nq, d=cfg.D, seed=cfg.query_seed + 100, device=dev)
+    path = str(tmp_path_factory.mktemp("gist") / "gist.pqt")
+    builder.build_index(path, X, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M, H=cfg.H, T=cfg.T, C=cfg.C,
+                        train_n=cfg.train_n, device=dev)
+    Xh, Yh = X.cpu().numpy(), Y.cpu().numpy()
+    del X, Y
+    torch.cuda.empty_cache()
+    return cfg, Xh, Yh, path, IO.read_index(path)
+
+
+def test_gist_full_size_parity(pqt, gist_full):
+    cfg, X, Y, path, ix = gist_full
+    off = ix.offsets.astype(np.int64)
+    assert off[0] == 0 and off[-1] == cfg.N and ix.H == cfg.K
+    rng = np.random.default_rng(0)
+    mism = 0
+    for t in rng.integers(0, cfg.N, size=40):
+        slot = int(np.searchsorted(off, t, side="right")) - 1
+        mism += slot != B.bin_slot(X[ix.ids[t]], ix.C1, ix.C2, ix.H)
+    assert mism <= 2          # the fp32 builder may settle a near-tie differently from float64
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        ids, dists, taps = _run_debug(pqt, gix, Y, cfg.k, cfg.w)
+    finally:
+        pqt.pqt_index_free(gix)
+    nc = taps["n_cand"].astype(np.int64)
+    assert np.all(nc <= cfg.C)
+    print(f"gist: candidates per query mean {nc.mean():.1f} min {nc.min()} max {nc.max()}", flush=True)
+    for q in range(cfg.nq):
+        n = int(nc[q])
+        sc, cid = taps["scores"][q][:n], taps["cand_ids"][q][:n]
+        o = np.lexsort((cid, sc))[:cfg.k]
+        assert np.array_equal(ids[q][:len(o)], cid[o]), f"query {q}: top-k is not the k smallest (score, id)"
+        assert np.all(ids[q][len(o):] == -1)
+    same = decided = 0
+    sample = list(range(0, cfg.nq, 97))
+    for q in sample:
+        print(f"gist query {q}", flush=True)
+        tr = PU.check_query_stages(ix, Y[q], taps, q, cfg.k, cfg.w, cfg.T, cfg.C, ids, dists)
+        y64 = Y[q].astype(np.float64)
+        scale = float(np.dot(y64, y64) + np.max(np.sum(ix.C1.astype(np.float64) ** 2, axis=2)) * ix.P)
+        s, d = PU.end_to_end_agreement(tr, ids[q], dists[q], scale)
+        assert s or not d, f"query {q}: margins above threshold but ids differ"
+        same += s
+        decided += d
+    print(f"gist: {same}/{len(sample)} sampled queries identical to the float64 oracle, {decided} decided")
+    assert same >= 0.7 * len(sample)

@@ -12,5 +12,6 @@ from .synth import (  # noqa: F401
     sift_like_tables,
     sift_like_torch,
     gist_like,
+    gist_like_torch,
     small_integer_vectors,
 )

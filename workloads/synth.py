@@ -201,3 +201,35 @@ def sift_like_torch(start, count, d=128, seed=0, tables=None, device="cpu", chun
         x += ((h & 15) - ((h >> 4) & 15)) >> 1
         out[c0:c0 + n] = x.clamp_(0, 255).to(torch.float32)
     return out
+
+
+def gist_like_torch(start, count, d=960, seed=0, table_seed=0, device="cpu", chunk=65536):
+    """The GIST-shaped recipe of gist_like() drawn with torch's generator on `device` (same
+    cluster centres, latent basis and weights; the per-chunk random streams are torch's, so the
+    values differ from the NumPy version and are reproducible per device type).  Any range is
+    assembled from fixed chunks of `chunk` ids, each with its own seed."""
+    import torch
+    dev = torch.device(device)
+    trng = np.random.default_rng([table_seed, 0x6157, d])
+    centres = trng.random((N_CLUSTERS, d)) * (trng.random((N_CLUSTERS, d)) < 0.7)
+    basis = trng.standard_normal((N_LATENT, d)) * 0.08
+    wts = 1.0 / (np.arange(N_CLUSTERS) + 10.0) ** 0.9
+    cdf = torch.from_numpy(np.cumsum(wts / wts.sum())).to(dev)
+    centres = torch.from_numpy(centres.astype(np.float32)).to(dev)
+    basis = torch.from_numpy(basis.astype(np.float32)).to(dev)
+    out = torch.empty((count, d), dtype=torch.float32, device=dev)
+    first = start // chunk
+    last = (start + count - 1) // chunk if count > 0 else first - 1
+    gen = torch.Generator(device=dev)
+    for ci in range(first, last + 1):
+        gen.manual_seed((int(seed) * 0x9E3779B1 + ci * 0x85EBCA6B + 0x6157DA7A) & 0x7FFFFFFFFFFFFFFF)
+        u = torch.rand(chunk, generator=gen, device=dev, dtype=torch.float64)
+        cl = torch.searchsorted(cdf, u).clamp_(max=N_CLUSTERS - 1)
+        z = torch.randn((chunk, N_LATENT), generator=gen, device=dev)
+        x = centres[cl] + z @ basis + 0.02 * torch.randn((chunk, d), generator=gen, device=dev)
+        x.clamp_(0.0, 1.0)
+        x /= x.norm(dim=1, keepdim=True).clamp_min(1e-12)
+        lo = max(start, ci * chunk)
+        hi = min(start + count, (ci + 1) * chunk)
+        out[lo - start:hi - start] = x[lo - ci * chunk:hi - ci * chunk]
+    return out
