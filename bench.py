@@ -7,7 +7,8 @@ against exact brute force, per-stage times from HIP events recorded by the libra
 launch stream, the roofline of the dominant kernel, and the CPU oracle timed on a bounded
 sample of the same queries.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload sift|tiny|large] [--w 8]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload tiny|sift|gist|large|billion] [--w 8]
+                    [--batch B]
 """
 import argparse
 import json
@@ -41,7 +42,8 @@ def make_data(cfg, device):
         Y = synth.sift_like_torch(0, cfg.nq, d=cfg.D, seed=cfg.query_seed, tables=tables, device=device)
 
         def chunks(s, n):
-            return synth.sift_like_torch(s, n, d=cfg.D, seed=cfg.data_seed, tables=tables, device=device)
+            return synth.sift_like_torch(s, n, d=cfg.D, seed=cfg.data_seed, tables=tables, device=device,
+                                         chunk=1 << 19)
         X = chunks(0, cfg.N) if cfg.N <= 4_000_000 else None
         return X, Y, (chunks if X is None else (lambda s, n: X[s:s + n]))
     if cfg.kind == "gist":
@@ -51,23 +53,29 @@ def make_data(cfg, device):
     raise ValueError(cfg.kind)
 
 
-def exact_nn(chunks, N, Y, chunk=1 << 18):
-    """Exact nearest neighbour (Eq. 1) of every query by brute force on the GPU: running
-    minimum over database chunks, ties to the smaller id.  Measurement infrastructure, untimed."""
-    import torch
-    best_d = torch.full((Y.shape[0],), float("inf"), device=Y.device)
-    best_i = torch.full((Y.shape[0],), -1, dtype=torch.int64, device=Y.device)
-    yn = (Y * Y).sum(1)
-    for s in range(0, N, chunk):
-        Xc = chunks(s, min(chunk, N - s))
-        for q0 in range(0, Y.shape[0], 2048):
-            Yq = Y[q0:q0 + 2048]
-            d = yn[q0:q0 + 2048, None] - 2.0 * (Yq @ Xc.t()) + (Xc * Xc).sum(1)[None, :]
+class ExactNN:
+    """Exact nearest neighbour (Eq. 1) of every query by brute force on the GPU: a running minimum
+    over database chunks (fed one by one while the index is built), ties to the smaller id.
+    Measurement infrastructure, untimed."""
+
+    def __init__(self, Y):
+        import torch
+        self.Y = Y
+        self.yn = (Y * Y).sum(1)
+        self.best_d = torch.full((Y.shape[0],), float("inf"), device=Y.device)
+        self.best_i = torch.full((Y.shape[0],), -1, dtype=torch.int64, device=Y.device)
+
+    def update(self, start, Xc):
+        import torch
+        xn = (Xc * Xc).sum(1)
+        step = max(1, (1 << 31) // max(Xc.shape[0], 1))           # at most 8 GiB of distances at a time
+        for q0 in range(0, self.Y.shape[0], step):
+            sl = slice(q0, q0 + step)
+            d = self.yn[sl, None] - 2.0 * (self.Y[sl] @ Xc.t()) + xn[None, :]
             dmin, imin = d.min(1)
-            better = dmin < best_d[q0:q0 + 2048]
-            best_d[q0:q0 + 2048] = torch.where(better, dmin, best_d[q0:q0 + 2048])
-            best_i[q0:q0 + 2048] = torch.where(better, imin + s, best_i[q0:q0 + 2048])
-    return best_i
+            better = dmin < self.best_d[sl]
+            self.best_d[sl] = torch.where(better, dmin, self.best_d[sl])
+            self.best_i[sl] = torch.where(better, imin + start, self.best_i[sl])
 
 
 def recall_at(ids, gt, xs=(1, 10, 100)):
@@ -104,12 +112,12 @@ def _oracle_worker(args):
     return time.perf_counter() - t0, res
 
 
-def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0):
+def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16):
     """The CPU oracle, as it stands, on a bounded sample of the same queries and the same index
     file, one process per host core.  Also cross-checks the GPU ids on that sample."""
     import multiprocessing as mp
     import numpy as np
-    cores = min(len(os.sched_getaffinity(0)), 16)
+    cores = min(len(os.sched_getaffinity(0)), max_procs)
     # size the sample from one timed query
     t0 = time.perf_counter()
     _oracle_worker((path, Y_host, k, w, 0, 1))
@@ -141,7 +149,11 @@ def main():
     ap.add_argument("--workload", default="sift")
     ap.add_argument("--w", type=int, default=None)
     ap.add_argument("--nq", type=int, default=None, help="queries per step (default: the workload's)")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="queries per library call (default: all of them in one call); 1 gives a latency figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline", action="store_true",
+                    help="also for the 100M / 1B workloads (writes the index to a file for the oracle's processes)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 256 MiB out-of-place elementwise square roots (a streaming kernel of known traffic, "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -164,13 +176,37 @@ def main():
     dev = torch.device("cuda", 0)
     t_setup = time.perf_counter()
     X, Y, chunks = make_data(cfg, dev)
+    in_hbm_only = cfg.N > 4_000_000            # the database never exists as raw vectors: built chunk by chunk
+    n_gt = min(cfg.nq, 1000) if in_hbm_only else cfg.nq     # queries with exact ground truth
+    gt = ExactNN(Y[:n_gt])
+
+    def observe(start, Xc):
+        gt.update(start, Xc)
+        if in_hbm_only and (start >> 20) % 16 == 0:
+            print(f"[bench] built {start + Xc.shape[0]:,} of {cfg.N:,} vectors "
+                  f"({time.perf_counter() - t_setup:.0f} s)", file=sys.stderr, flush=True)
+
+    arrays = builder.build_arrays(chunks=chunks, N=cfg.N, D=cfg.D, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M,
+                                  H=cfg.H, T=cfg.T, C=cfg.C, train_n=cfg.train_n, device=dev,
+                                  chunk_rows=(1 << 20) if in_hbm_only else (1 << 18), observer=observe)
+    runs = torch.diff(arrays["offsets"])
+    occupancy = {"nonempty_slots": int((runs > 0).sum()), "max_run": int(runs.max()),
+                 "mean_run_nonempty": float(runs[runs > 0].float().mean())}
     tmp = tempfile.mkdtemp(prefix="pqt_bench_")
     path = os.path.join(tmp, f"{cfg.name}.pqt")
-    arrays = builder.build_index(path, chunks=chunks, N=cfg.N, D=cfg.D, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M,
-                                 H=cfg.H, T=cfg.T, C=cfg.C, train_n=cfg.train_n, device=dev)
-    runs = np.diff(arrays["offsets"].astype(np.int64))
-    gt = exact_nn(chunks, cfg.N, Y)
-    index = pqt.pqt_index_load(path, 0)
+    if in_hbm_only and not args.cpu_baseline:
+        index = pqt.pqt_index_from_arrays(arrays, 0)           # straight from the builder's device arrays
+        path = None
+    else:
+        host = dict(arrays)
+        for name, dt in (("offsets", np.uint32), ("ids", np.uint32), ("codes", np.uint8)):
+            host[name] = arrays[name].cpu().numpy().astype(dt)
+        builder.write_index_file(path, host, host)
+        del host
+        index = pqt.pqt_index_load(path, 0)
+    del arrays, X
+    torch.cuda.empty_cache()
+    gt = gt.best_i
     setup_s = time.perf_counter() - t_setup
 
     if args.calibrate_copy:
@@ -183,17 +219,30 @@ def main():
 
     out_ids = torch.empty((cfg.nq, cfg.k), dtype=torch.int64, device=dev)
     out_d = torch.empty((cfg.nq, cfg.k), dtype=torch.float32, device=dev)
+    B = args.batch or cfg.nq                   # queries per library call; one step still answers all nq
+
+    def step():
+        for o in range(0, cfg.nq, B):
+            pqt.pqt_query_batch(index, Y[o:o + B], cfg.k, w, out_ids[o:o + B], out_d[o:o + B])
+
     for _ in range(args.warmup):
-        pqt.pqt_query_batch(index, Y, cfg.k, w, out_ids, out_d)
+        step()
     torch.cuda.synchronize()
-    pqt.pqt_set_profiling(index, True)
+    pqt.pqt_set_profiling(index, B == cfg.nq)  # stage events only when a step is one call
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        pqt.pqt_query_batch(index, Y, cfg.k, w, out_ids, out_d)
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     stage_ms, calls = pqt.pqt_stage_times(index)
     pqt.pqt_set_profiling(index, False)
+    if calls == 0:                             # batched run: time one full-size call per stage for the accounting
+        pqt.pqt_set_profiling(index, True)
+        pqt.pqt_query_batch(index, Y, cfg.k, w, out_ids, out_d)
+        stage_ms, calls = pqt.pqt_stage_times(index)
+        pqt.pqt_set_profiling(index, False)
+        step()
+        torch.cuda.synchronize()
     stage_ms = [m / max(calls, 1) for m in stage_ms]
 
     # candidates actually gathered (for the byte accounting) via the debug taps, untimed
@@ -201,7 +250,8 @@ def main():
     torch.cuda.synchronize()
     mean_cand = float(taps["n_cand"].float().mean())
     mean_runs = float(taps["n_slots"].float().mean())
-    rec = recall_at(out_ids, gt)
+    rec = recall_at(out_ids[:n_gt], gt)
+    rec["queries_with_ground_truth"] = n_gt
 
     # ---- algorithmic work per launch (one launch = all nq queries) -----------------------------------
     nq, R = cfg.nq, w * cfg.k2
@@ -237,12 +287,14 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} D={cfg.D} nq={cfg.nq} P={cfg.P} k1={cfg.k1} k2={cfg.k2} "
                                f"M={cfg.M} H={cfg.H} w={w} T={cfg.T} C={cfg.C} k={cfg.k}",
-                   "mean_candidates": mean_cand, "mean_runs": mean_runs,
-                   "nonempty_slots": int((runs > 0).sum()), "max_run": int(runs.max())},
+                   "queries_per_call": B, "mean_candidates": mean_cand, "mean_runs": mean_runs, **occupancy},
         "recall": rec, "stage_ms": stage_ms, "stages": stages, "roofline": roofline, "setup_s": setup_s,
     }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(path, Y.cpu().numpy(), cfg.k, w, out_ids.cpu().numpy())
+    if B != cfg.nq:
+        result["us_per_call"] = elapsed / args.steps / (-(-cfg.nq // B)) * 1e6
+    if path is not None and not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(path, Y.cpu().numpy(), cfg.k, w, out_ids.cpu().numpy(),
+                                              max_procs=4 if cfg.N > 200_000_000 else 16)
     else:
         result["cpu_baseline"] = None
     pqt.pqt_index_free(index)

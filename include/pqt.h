@@ -72,6 +72,33 @@ typedef struct pqt_info {
  */
 int pqt_index_load(const char* path, int device, pqt_index** out);
 
+/*
+ * pqt_index_from_arrays -- the same index from arrays already in memory (what the offline
+ * phase of Sec. 3.1 / 3.3 / 4 produces, with the shapes listed for the file above).
+ * C1, C2, tbl_i, tbl_j, tbl_lambda and cc are always host pointers (they are small and the
+ * library derives its own tables from them).  offsets (H+1), ids (N) and codes (N x M) are
+ * host pointers when location == PQT_HOST and device pointers on GPU `device` when
+ * location == PQT_DEVICE (an index built on the GPU never has to leave it).  Everything is
+ * copied: the caller keeps ownership of all arrays and may release them after the call.
+ * T and C are the default budgets.  Errors as for pqt_index_load (no PQT_EIO).
+ */
+#define PQT_HOST   0
+#define PQT_DEVICE 1
+typedef struct pqt_index_arrays {
+    uint64_t N, H;
+    uint32_t D, P, k1, k2, M, T, C;
+    const float*    C1;          /* [P][k1][D/P]        host */
+    const float*    C2;          /* [P][k1][k2][D/P]    host */
+    const uint8_t*  tbl_i;       /* [M][256]            host */
+    const uint8_t*  tbl_j;       /* [M][256]            host */
+    const float*    tbl_lambda;  /* [M][256]            host */
+    const float*    cc;          /* [M][k1][k1]         host */
+    const uint32_t* offsets;     /* [H+1]               host or device */
+    const uint32_t* ids;         /* [N]                 host or device */
+    const uint8_t*  codes;       /* [N][M]              host or device */
+} pqt_index_arrays;
+int pqt_index_from_arrays(const pqt_index_arrays* arrays, int location, int device, pqt_index** out);
+
 /* Releases the index, its device arrays and its workspace.  NULL is allowed. */
 void pqt_index_free(pqt_index* index);
 

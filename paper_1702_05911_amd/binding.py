@@ -16,7 +16,7 @@ PQT_OK = 0
 PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -2, -3, -4, -5, -6
 
 EXPORTS = (
-    "pqt_index_load", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
+    "pqt_index_load", "pqt_index_from_arrays", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
     "pqt_query_batch_debug", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
 )
 
@@ -39,6 +39,16 @@ _TAP_FIELDS = ("a", "sel", "L_d", "L_id", "n_tuples", "tuples", "tuple_keys", "n
                "n_cand", "cand_ids", "scores", "lut")
 
 
+class _Arrays(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_uint64), ("H", ctypes.c_uint64)] + \
+               [(n, ctypes.c_uint32) for n in ("D", "P", "k1", "k2", "M", "T", "C")] + \
+               [(n, ctypes.c_void_p) for n in ("C1", "C2", "tbl_i", "tbl_j", "tbl_lambda", "cc",
+                                               "offsets", "ids", "codes")]
+
+
+PQT_HOST, PQT_DEVICE = 0, 1
+
+
 class _Taps(ctypes.Structure):
     _fields_ = [(name, ctypes.c_void_p) for name in _TAP_FIELDS]
 
@@ -50,6 +60,8 @@ def load_library(path=LIB_PATH):
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     lib.pqt_index_load.argtypes = [ctypes.c_char_p, ci, ctypes.POINTER(vp)]
     lib.pqt_index_load.restype = ci
+    lib.pqt_index_from_arrays.argtypes = [ctypes.POINTER(_Arrays), ci, ci, ctypes.POINTER(vp)]
+    lib.pqt_index_from_arrays.restype = ci
     lib.pqt_index_free.argtypes = [vp]
     lib.pqt_index_free.restype = None
     lib.pqt_index_info.argtypes = [vp, ctypes.POINTER(_Info)]
@@ -86,10 +98,45 @@ def _stream_handle(stream):
 class Index:
     """Handle of an index resident on one GPU (pqt_index_load / pqt_index_free)."""
 
-    def __init__(self, path, device=0):
+    def __init__(self, path=None, device=0, arrays=None):
         self._h = ctypes.c_void_p()
-        _check(_lib.pqt_index_load(os.fsencode(path), int(device), ctypes.byref(self._h)))
+        if arrays is None:
+            _check(_lib.pqt_index_load(os.fsencode(path), int(device), ctypes.byref(self._h)))
+        else:
+            self._from_arrays(arrays, int(device))
         self.device = torch.device("cuda", int(device))
+
+    def _from_arrays(self, a, device):
+        """pqt_index_from_arrays.  `a`: mapping with the header fields, the small arrays as NumPy
+        arrays, and offsets / ids / codes either all NumPy arrays (host) or all CUDA tensors on
+        `device` (int32 or int64 values below 2**32 are narrowed to the ABI's uint32 here)."""
+        import numpy as np
+        small = {"C1": np.float32, "C2": np.float32, "tbl_i": np.uint8, "tbl_j": np.uint8,
+                 "tbl_lam": np.float32, "cc": np.float32}
+        keep = [np.ascontiguousarray(a[n], dtype=dt) for n, dt in small.items()]
+        on_device = torch.is_tensor(a["offsets"])
+        big = []
+        for n, width in (("offsets", 4), ("ids", 4), ("codes", 1)):
+            t = a[n]
+            if on_device:
+                if not (torch.is_tensor(t) and t.is_cuda and t.device.index == device):
+                    raise ValueError(f"{n}: offsets, ids and codes must all be tensors on cuda:{device}")
+                if width == 4 and t.dtype != torch.int32:
+                    t = t.to(torch.int32)          # wraps: the low 32 bits are the uint32 the ABI reads
+                t = t.contiguous()
+                big.append((t, t.data_ptr()))
+            else:
+                t = np.ascontiguousarray(t, dtype=np.uint32 if width == 4 else np.uint8)
+                big.append((t, t.ctypes.data))
+        if on_device:
+            torch.cuda.synchronize(device)
+        ca = _Arrays(N=int(a["N"]), H=int(a["H"]), D=int(a["D"]), P=int(a["P"]), k1=int(a["k1"]), k2=int(a["k2"]),
+                     M=int(a["M"]), T=int(a["T"]), C=int(a["C"]),
+                     C1=keep[0].ctypes.data, C2=keep[1].ctypes.data, tbl_i=keep[2].ctypes.data,
+                     tbl_j=keep[3].ctypes.data, tbl_lambda=keep[4].ctypes.data, cc=keep[5].ctypes.data,
+                     offsets=big[0][1], ids=big[1][1], codes=big[2][1])
+        _check(_lib.pqt_index_from_arrays(ctypes.byref(ca), PQT_DEVICE if on_device else PQT_HOST, device,
+                                          ctypes.byref(self._h)))
 
     def close(self):
         if getattr(self, "_h", None) is not None and self._h.value:
@@ -173,6 +220,10 @@ def last_error():
 # ---- the C ABI's names, one to one ---------------------------------------------------------------
 def pqt_index_load(path, device=0):
     return Index(path, device)
+
+
+def pqt_index_from_arrays(arrays, device=0):
+    return Index(device=device, arrays=arrays)
 
 
 def pqt_index_free(index):

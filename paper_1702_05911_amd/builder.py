@@ -190,10 +190,14 @@ def write_index_file(path, hdr, arrays):
             np.ascontiguousarray(arrays[name], dtype=dt).tofile(f)
 
 
-def build_index(path, X=None, *, chunks=None, N=None, D=None, P, k1, k2, M, H=None, T=1024, C=4096,
-                train_n=None, iters=20, device=None, chunk_rows=1 << 18, table_train_n=100_000):
+def build_arrays(X=None, *, chunks=None, N=None, D=None, P, k1, k2, M, H=None, T=1024, C=4096,
+                 train_n=None, iters=20, device=None, chunk_rows=1 << 18, table_train_n=100_000,
+                 observer=None):
     """Builds the index of X (array, N x D) or of chunks(start, count) -> (count x D) fp32
-    tensor/array, writes it to `path`, and returns the arrays as a dict of NumPy arrays."""
+    tensor/array.  Returns a dict: the header fields, the small arrays (C1, C2, tbl_i, tbl_j,
+    tbl_lam, cc) as NumPy arrays, and offsets (int64, H+1), ids (int64, N) and codes (uint8,
+    N x M) as tensors on `device`.  observer(start, chunk) is called once per database chunk
+    (e.g. to accumulate exact nearest neighbours while the vectors exist)."""
     if device is None:
         device = torch.device("cuda") if torch.cuda.is_available() else torch.device("cpu")
     if X is not None:
@@ -210,23 +214,34 @@ def build_index(path, X=None, *, chunks=None, N=None, D=None, P, k1, k2, M, H=No
     C1, C2 = train_tree(Xt, P, k1, k2, iters)
     ti, tj, tl = line_table(Xt[:table_train_n], C1, M)
     del Xt
-    slots = torch.empty(N, dtype=torch.int64, device=device)
+    slots = torch.empty(N, dtype=torch.int32 if H < 2 ** 31 else torch.int64, device=device)
     codes = torch.empty((N, M), dtype=torch.uint8, device=device)
     for s in range(0, N, chunk_rows):
         n = min(chunk_rows, N - s)
         Xc = torch.as_tensor(chunks(s, n)).to(device=device, dtype=torch.float32)
-        slots[s:s + n] = assign_slots(Xc, C1, C2, H)
-        codes[s:s + n] = encode(Xc, C1, M, ti, tj, tl)
+        for s2 in range(0, n, 1 << 18):                            # bounds the n x k2 x dp gather below
+            sl = slice(s2, min(s2 + (1 << 18), n))
+            slots[s + sl.start:s + sl.stop] = assign_slots(Xc[sl], C1, C2, H).to(slots.dtype)
+            codes[s + sl.start:s + sl.stop] = encode(Xc[sl], C1, M, ti, tj, tl)
+        if observer is not None:
+            observer(s, Xc)
+        del Xc
     order = torch.sort(slots, stable=True).indices                # ids by (slot, id)
     hist = torch.bincount(slots, minlength=H)
+    del slots
     offsets = torch.zeros(H + 1, dtype=torch.int64, device=device)
     offsets[1:] = torch.cumsum(hist, 0)
-    arrays = {
-        "C1": C1.cpu().numpy(), "C2": C2.cpu().numpy(), "tbl_i": ti, "tbl_j": tj, "tbl_lam": tl,
-        "cc": pair_table(C1, M), "offsets": offsets.cpu().numpy().astype(np.uint32),
-        "ids": order.cpu().numpy().astype(np.uint32), "codes": codes[order].cpu().numpy(),
-    }
-    hdr = dict(D=D, P=P, k1=k1, k2=k2, M=M, N=N, H=H, T=T, C=C)
-    write_index_file(path, hdr, arrays)
-    arrays.update(hdr)
+    del hist
+    codes = codes[order]
+    return dict(D=D, P=P, k1=k1, k2=k2, M=M, N=N, H=H, T=T, C=C,
+                C1=C1.cpu().numpy(), C2=C2.cpu().numpy(), tbl_i=ti, tbl_j=tj, tbl_lam=tl, cc=pair_table(C1, M),
+                offsets=offsets, ids=order, codes=codes)
+
+
+def build_index(path, X=None, **kw):
+    """build_arrays(...) written to the index file `path`; returns the arrays as NumPy arrays."""
+    arrays = build_arrays(X, **kw)
+    for name, dt in (("offsets", np.uint32), ("ids", np.uint32), ("codes", np.uint8)):
+        arrays[name] = arrays[name].cpu().numpy().astype(dt)
+    write_index_file(path, arrays, arrays)
     return arrays

@@ -119,9 +119,9 @@ bool read_section(FILE* f, void* dst, size_t bytes) {
 }
 
 template <typename Tp>
-int upload(Tp** dev, const void* host, size_t bytes, uint64_t* account) {
+int upload(Tp** dev, const void* src, size_t bytes, hipMemcpyKind kind, uint64_t* account) {
     HIP_TRY(hipMalloc(reinterpret_cast<void**>(dev), bytes ? bytes : 1));
-    if (bytes) HIP_TRY(hipMemcpy(*dev, host, bytes, hipMemcpyHostToDevice));
+    if (bytes) HIP_TRY(hipMemcpy(*dev, src, bytes, kind));
     *account += bytes;
     return PQT_OK;
 }
@@ -180,6 +180,114 @@ extern "C" {
 
 const char* pqt_last_error(void) { return g_err; }
 
+int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, pqt_index** out) {
+    if (!a || !out) return fail(PQT_EINVAL, "pqt_index_from_arrays: null argument");
+    *out = nullptr;
+    if (location != PQT_HOST && location != PQT_DEVICE)
+        return fail(PQT_EINVAL, "pqt_index_from_arrays: location must be PQT_HOST or PQT_DEVICE");
+    if (!a->C1 || !a->C2 || !a->tbl_i || !a->tbl_j || !a->tbl_lambda || !a->cc || !a->offsets ||
+        (a->N > 0 && (!a->ids || !a->codes)))
+        return fail(PQT_EINVAL, "pqt_index_from_arrays: null array");
+    const pqt_index_arrays& h = *a;
+    if (h.D == 0 || h.P == 0 || h.k1 == 0 || h.k2 == 0 || h.M == 0 || h.H == 0 || h.D % h.P || h.D % h.M ||
+        h.M % h.P)
+        return fail(PQT_EFORMAT, "inconsistent sizes D=%u P=%u k1=%u k2=%u M=%u", h.D, h.P, h.k1, h.k2, h.M);
+    if (!(h.P == 1 || h.P == 2 || h.P == 4)) return fail(PQT_EUNSUPPORTED, "P=%u: only 1, 2 or 4 tree parts", h.P);
+    if (h.k1 > PQT_MAX_K1 || h.k2 > PQT_MAX_R || h.M > 64 || h.D > 8192)
+        return fail(PQT_EUNSUPPORTED, "k1=%u k2=%u M=%u D=%u beyond the kernel limits", h.k1, h.k2, h.M, h.D);
+    if (h.N >= 0xffffffffull || h.H >= 0xffffffffull)
+        return fail(PQT_EUNSUPPORTED, "N=%llu H=%llu: 32-bit ids and slots only", (unsigned long long)h.N,
+                    (unsigned long long)h.H);
+    long double K = 1;
+    for (uint32_t p = 0; p < h.P; ++p) K *= (long double)h.k1 * h.k2;
+    if (K >= 18446744073709551616.0L)
+        return fail(PQT_EUNSUPPORTED, "(k1*k2)^P = %Lg bins do not fit 64-bit bin numbers", K);
+    if ((long double)h.H > K) return fail(PQT_EFORMAT, "H exceeds the number of bins");
+    if (h.T < 1 || h.T > PQT_MAX_T || h.C < 1 || h.C > PQT_MAX_C)
+        return fail(PQT_EFORMAT, "default budgets T=%u C=%u out of range", h.T, h.C);
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev)
+        return fail(PQT_EHIP, "GPU %d is not available (%d visible)", device, ndev);
+    DeviceGuard guard(device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", device);
+
+    // the pointer array must be a prefix sum that spans the ids (checked on the host)
+    const size_t dp = h.D / h.P, ds = h.D / h.M;
+    std::vector<uint32_t> off_copy;
+    const uint32_t* off = h.offsets;
+    if (location == PQT_DEVICE) {
+        try {
+            off_copy.resize((size_t)h.H + 1);
+        } catch (const std::bad_alloc&) {
+            return fail(PQT_ENOMEM, "host allocation failed");
+        }
+        HIP_TRY(hipMemcpy(off_copy.data(), h.offsets, off_copy.size() * 4, hipMemcpyDeviceToHost));
+        off = off_copy.data();
+    }
+    if (off[0] != 0 || off[h.H] != h.N) return fail(PQT_EFORMAT, "offsets do not span the ids");
+    for (size_t s = 0; s < h.H; ++s)
+        if (off[s + 1] < off[s]) return fail(PQT_EFORMAT, "offsets not monotone at slot %zu", s);
+    const size_t ntab = (size_t)h.M * 256;
+    for (size_t e = 0; e < ntab; ++e)
+        if (h.tbl_i[e] >= h.k1 || h.tbl_j[e] >= h.k1) return fail(PQT_EFORMAT, "code table names centroid >= k1");
+
+    // squared norms of the centroid sub-parts, and the code table with its pair distance folded in
+    std::vector<float> c1n((size_t)h.M * h.k1);
+    const size_t per = h.M / h.P;
+    for (size_t m = 0; m < h.M; ++m) {
+        const size_t p = m / per, lo = m * ds - p * dp;
+        for (size_t i = 0; i < h.k1; ++i) {
+            double s = 0;
+            for (size_t d = 0; d < ds; ++d) {
+                const double v = h.C1[(p * h.k1 + i) * dp + lo + d];
+                s += v * v;
+            }
+            c1n[m * h.k1 + i] = (float)s;
+        }
+    }
+    std::vector<pqt::CodeEntry> table(ntab);
+    for (size_t m = 0; m < h.M; ++m)
+        for (size_t c = 0; c < 256; ++c) {
+            const size_t e = m * 256 + c;
+            table[e].ij = (uint32_t)h.tbl_i[e] | ((uint32_t)h.tbl_j[e] << 8);
+            table[e].lam = h.tbl_lambda[e];
+            table[e].cc = h.cc[(m * h.k1 + h.tbl_i[e]) * h.k1 + h.tbl_j[e]];
+        }
+
+    if (pqt::configure_traverse(pqt::kMaxLds) == hipSuccess && pqt::configure_rank(pqt::kMaxLds) == hipSuccess &&
+        pqt::configure_rerank(pqt::kMaxLds) == hipSuccess) {
+        g_lds_limit = pqt::kMaxLds;
+    } else {
+        (void)hipGetLastError();
+        g_lds_limit = 64 * 1024;
+        HIP_TRY(pqt::configure_traverse(g_lds_limit));
+        HIP_TRY(pqt::configure_rank(g_lds_limit));
+        HIP_TRY(pqt::configure_rerank(g_lds_limit));
+    }
+
+    pqt_index* ix = new (std::nothrow) pqt_index();
+    if (!ix) return fail(PQT_ENOMEM, "host allocation failed");
+    ix->D = h.D; ix->P = h.P; ix->k1 = h.k1; ix->k2 = h.k2; ix->M = h.M; ix->T = h.T; ix->C = h.C;
+    ix->N = h.N; ix->H = h.H; ix->device = device;
+    ix->hashed = (long double)h.H != K;
+    const hipMemcpyKind big = location == PQT_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    int rc = PQT_OK;
+    if ((rc = upload(&ix->C1, h.C1, (size_t)h.P * h.k1 * dp * 4, hipMemcpyHostToDevice, &ix->bytes_index)) ||
+        (rc = upload(&ix->c1n, c1n.data(), c1n.size() * 4, hipMemcpyHostToDevice, &ix->bytes_index)) ||
+        (rc = upload(&ix->C2, h.C2, (size_t)h.P * h.k1 * h.k2 * dp * 4, hipMemcpyHostToDevice, &ix->bytes_index)) ||
+        (rc = upload(&ix->table, table.data(), table.size() * sizeof(pqt::CodeEntry), hipMemcpyHostToDevice,
+                     &ix->bytes_index)) ||
+        (rc = upload(&ix->offsets, h.offsets, ((size_t)h.H + 1) * 4, big, &ix->bytes_index)) ||
+        (rc = upload(&ix->ids, h.ids, (size_t)h.N * 4, big, &ix->bytes_index)) ||
+        (rc = upload(&ix->codes, h.codes, (size_t)h.N * h.M, big, &ix->bytes_index))) {
+        pqt_index_free(ix);
+        return rc;
+    }
+    *out = ix;
+    return PQT_OK;
+}
+
 int pqt_index_load(const char* path, int device, pqt_index** out) {
     if (!path || !out) return fail(PQT_EINVAL, "pqt_index_load: null argument");
     *out = nullptr;
@@ -191,25 +299,18 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
     memcpy(&h, hdr, sizeof(h));
     if (memcmp(h.magic, "PQTIDX1\0", 8) != 0) return fail(PQT_EFORMAT, "'%s': bad magic", path);
     if (h.version != 1 || h.offset_bits != 32) return fail(PQT_EFORMAT, "'%s': unsupported version", path);
+    // the sizes the arrays are read with must be sane before anything is allocated
+    // (pqt_index_from_arrays repeats these checks for callers that bring their own arrays)
     if (h.D == 0 || h.P == 0 || h.k1 == 0 || h.k2 == 0 || h.M == 0 || h.H == 0 || h.D % h.P || h.D % h.M ||
         h.M % h.P)
         return fail(PQT_EFORMAT, "'%s': inconsistent sizes D=%u P=%u k1=%u k2=%u M=%u", path, h.D, h.P, h.k1,
                     h.k2, h.M);
-    if (!(h.P == 1 || h.P == 2 || h.P == 4)) return fail(PQT_EUNSUPPORTED, "P=%u: only 1, 2 or 4 tree parts", h.P);
-    if (h.k1 > PQT_MAX_K1 || h.k2 > PQT_MAX_R || h.M > 64 || h.D > 8192)
-        return fail(PQT_EUNSUPPORTED, "k1=%u k2=%u M=%u D=%u beyond the kernel limits", h.k1, h.k2, h.M, h.D);
-    if (h.N >= 0xffffffffull || h.H >= 0xffffffffull)
-        return fail(PQT_EUNSUPPORTED, "N=%llu H=%llu: 32-bit ids and slots only", (unsigned long long)h.N,
-                    (unsigned long long)h.H);
-    long double K = 1;
-    for (uint32_t p = 0; p < h.P; ++p) K *= (long double)h.k1 * h.k2;
-    if (K >= 18446744073709551616.0L)
-        return fail(PQT_EUNSUPPORTED, "(k1*k2)^P = %Lg bins do not fit 64-bit bin numbers", K);
-    if ((long double)h.H > K) return fail(PQT_EFORMAT, "'%s': H exceeds the number of bins", path);
-    if (h.T < 1 || h.T > PQT_MAX_T || h.C < 1 || h.C > PQT_MAX_C)
-        return fail(PQT_EFORMAT, "'%s': default budgets T=%u C=%u out of range", path, h.T, h.C);
+    if (h.k1 > PQT_MAX_K1 || h.k2 > PQT_MAX_R || h.M > 64 || h.D > 8192 || h.N >= 0xffffffffull ||
+        h.H >= 0xffffffffull)
+        return fail(PQT_EUNSUPPORTED, "'%s': k1=%u k2=%u M=%u D=%u N=%llu H=%llu beyond the kernel limits", path,
+                    h.k1, h.k2, h.M, h.D, (unsigned long long)h.N, (unsigned long long)h.H);
 
-    const size_t dp = h.D / h.P, ds = h.D / h.M;
+    const size_t dp = h.D / h.P;
     std::vector<float> C1, C2, lam, cc;
     std::vector<uint8_t> ti, tj, codes;
     std::vector<uint32_t> offsets, ids;
@@ -231,68 +332,16 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
         !read_section(f.get(), codes.data(), codes.size()))
         return fail(PQT_EFORMAT, "'%s': truncated", path);
 
-    if (offsets[0] != 0 || offsets[h.H] != h.N) return fail(PQT_EFORMAT, "'%s': offsets do not span the ids", path);
-    for (size_t s = 0; s < h.H; ++s)
-        if (offsets[s + 1] < offsets[s]) return fail(PQT_EFORMAT, "'%s': offsets not monotone at slot %zu", path, s);
-    for (size_t e = 0; e < ti.size(); ++e)
-        if (ti[e] >= h.k1 || tj[e] >= h.k1) return fail(PQT_EFORMAT, "'%s': code table names centroid >= k1", path);
-
-    // squared norms of the centroid sub-parts, and the code table with its pair distance folded in
-    std::vector<float> c1n((size_t)h.M * h.k1);
-    const size_t per = h.M / h.P;
-    for (size_t m = 0; m < h.M; ++m) {
-        const size_t p = m / per, lo = m * ds - p * dp;
-        for (size_t i = 0; i < h.k1; ++i) {
-            double s = 0;
-            for (size_t d = 0; d < ds; ++d) {
-                const double v = C1[(p * h.k1 + i) * dp + lo + d];
-                s += v * v;
-            }
-            c1n[m * h.k1 + i] = (float)s;
-        }
+    pqt_index_arrays a = {};
+    a.N = h.N; a.H = h.H; a.D = h.D; a.P = h.P; a.k1 = h.k1; a.k2 = h.k2; a.M = h.M; a.T = h.T; a.C = h.C;
+    a.C1 = C1.data(); a.C2 = C2.data(); a.tbl_i = ti.data(); a.tbl_j = tj.data(); a.tbl_lambda = lam.data();
+    a.cc = cc.data(); a.offsets = offsets.data(); a.ids = ids.data(); a.codes = codes.data();
+    const int rc = pqt_index_from_arrays(&a, PQT_HOST, device, out);
+    if (rc != PQT_OK) {
+        char msg[sizeof(g_err)];
+        snprintf(msg, sizeof(msg), "%s", g_err);
+        return fail(rc, "'%s': %.400s", path, msg);
     }
-    std::vector<pqt::CodeEntry> table((size_t)h.M * 256);
-    for (size_t m = 0; m < h.M; ++m)
-        for (size_t c = 0; c < 256; ++c) {
-            const size_t e = m * 256 + c;
-            table[e].ij = (uint32_t)ti[e] | ((uint32_t)tj[e] << 8);
-            table[e].lam = lam[e];
-            table[e].cc = cc[(m * h.k1 + ti[e]) * h.k1 + tj[e]];
-        }
-
-    int ndev = 0;
-    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev)
-        return fail(PQT_EHIP, "GPU %d is not available (%d visible)", device, ndev);
-    DeviceGuard guard(device);
-    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", device);
-    if (pqt::configure_traverse(pqt::kMaxLds) == hipSuccess && pqt::configure_rank(pqt::kMaxLds) == hipSuccess &&
-        pqt::configure_rerank(pqt::kMaxLds) == hipSuccess) {
-        g_lds_limit = pqt::kMaxLds;
-    } else {
-        (void)hipGetLastError();
-        g_lds_limit = 64 * 1024;
-        HIP_TRY(pqt::configure_traverse(g_lds_limit));
-        HIP_TRY(pqt::configure_rank(g_lds_limit));
-        HIP_TRY(pqt::configure_rerank(g_lds_limit));
-    }
-
-    pqt_index* ix = new (std::nothrow) pqt_index();
-    if (!ix) return fail(PQT_ENOMEM, "host allocation failed");
-    ix->D = h.D; ix->P = h.P; ix->k1 = h.k1; ix->k2 = h.k2; ix->M = h.M; ix->T = h.T; ix->C = h.C;
-    ix->N = h.N; ix->H = h.H; ix->device = device;
-    ix->hashed = (long double)h.H != K;
-    int rc = PQT_OK;
-    if ((rc = upload(&ix->C1, C1.data(), C1.size() * 4, &ix->bytes_index)) ||
-        (rc = upload(&ix->c1n, c1n.data(), c1n.size() * 4, &ix->bytes_index)) ||
-        (rc = upload(&ix->C2, C2.data(), C2.size() * 4, &ix->bytes_index)) ||
-        (rc = upload(&ix->table, table.data(), table.size() * sizeof(pqt::CodeEntry), &ix->bytes_index)) ||
-        (rc = upload(&ix->offsets, offsets.data(), offsets.size() * 4, &ix->bytes_index)) ||
-        (rc = upload(&ix->ids, ids.data(), ids.size() * 4, &ix->bytes_index)) ||
-        (rc = upload(&ix->codes, codes.data(), codes.size(), &ix->bytes_index))) {
-        pqt_index_free(ix);
-        return rc;
-    }
-    *out = ix;
     return PQT_OK;
 }
 
