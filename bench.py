@@ -149,6 +149,8 @@ def main():
     ap.add_argument("--workload", default="sift")
     ap.add_argument("--w", type=int, default=None)
     ap.add_argument("--nq", type=int, default=None, help="queries per step (default: the workload's)")
+    ap.add_argument("--T", type=int, default=None, help="bin tuples examined per query (default: the workload's)")
+    ap.add_argument("--C", type=int, default=None, help="candidate budget per query (default: the workload's)")
     ap.add_argument("--batch", type=int, default=None,
                     help="queries per library call (default: all of them in one call); 1 gives a latency figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -172,6 +174,10 @@ def main():
     cfg = CONFIGS[args.workload]
     if args.nq:
         cfg = cfg.with_(nq=args.nq)
+    if args.T:
+        cfg = cfg.with_(T=args.T)
+    if args.C:
+        cfg = cfg.with_(C=args.C)
     w = args.w or cfg.w
     dev = torch.device("cuda", 0)
     t_setup = time.perf_counter()

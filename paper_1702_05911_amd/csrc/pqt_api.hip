@@ -252,7 +252,8 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
             const size_t e = m * 256 + c;
             table[e].ij = (uint32_t)h.tbl_i[e] | ((uint32_t)h.tbl_j[e] << 8);
             table[e].lam = h.tbl_lambda[e];
-            table[e].cc = h.cc[(m * h.k1 + h.tbl_i[e]) * h.k1 + h.tbl_j[e]];
+            const double lam = h.tbl_lambda[e];
+            table[e].kc = (float)((lam * lam - lam) * (double)h.cc[(m * h.k1 + h.tbl_i[e]) * h.k1 + h.tbl_j[e]]);
         }
 
     if (pqt::configure_traverse(pqt::kMaxLds) == hipSuccess && pqt::configure_rank(pqt::kMaxLds) == hipSuccess &&

@@ -8,15 +8,17 @@ namespace pqt {
 
 constexpr int kQueryTile = 16;          // queries per workgroup of the traversal kernel (MFMA rows)
 constexpr int kTraverseThreads = 256;
-constexpr int kRankThreads = 256;
+constexpr int kRankThreads = 1024;        // full ranking pass: one workgroup per query
+constexpr int kRankHeadThreads = 256;     // head pass: one wavefront per query
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per workgroup on gfx950
 
 // One entry of the folded line-code table: centroid numbers i | j<<8, lambda, and
-// ||c_i - c_j||^2 of the sub-part (the pair table of Sec. 3.3 gathered per code value).
+// (lambda^2 - lambda) ||c_i - c_j||^2 of the sub-part (the pair table of Sec. 3.3 gathered per
+// code value; Eq. 9 reads b^2 + lambda (a^2 - b^2) + that constant).
 struct CodeEntry {
     uint32_t ij;
     float lam;
-    float cc;
+    float kc;
 };
 
 struct TraverseArgs {

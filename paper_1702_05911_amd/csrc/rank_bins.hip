@@ -33,6 +33,7 @@ int rank_region_size(int R, int T) { return (int)region_size(R, R, T); }
 
 constexpr int kSelBits = 10;
 constexpr int kSelBins = 1 << kSelBits;
+constexpr int kMidT = 256;         // tuples ranked first by the full pass; all T only if they do not fill C
 constexpr int kRegionSplit = 64;   // rows below it are walked along b, the rest of the region along a
 
 struct RankLds {
@@ -41,6 +42,8 @@ struct RankLds {
     int npair;   // P = 4: length of each of the two pair lists, min(T, R^2)
     int nreg;    // size of the hyperbolic region of the final ranking (P = 2, 4)
     int nreg_pair;   // P = 4: region size of each pair ranking
+    int Tmid;    // P = 2: tuples ranked in the first attempt (most queries need far fewer than Tcap)
+    int nreg_mid;    // region size for Tmid
     size_t off_keys, off_hist, off_Ld, off_Lid, off_ps, off_pt, off_len, off_o0, off_slot, off_flag, off_part,
         off_misc, total;
 };
@@ -54,10 +57,14 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     L.cap = next_pow2(L.Tcap) < 64 ? 64 : next_pow2(L.Tcap);
     L.npair = 0;
     L.nreg_pair = 0;
+    L.Tmid = L.Tcap;
+    L.nreg_mid = 0;
     if (P == 1) {
         L.nreg = L.Tcap;
     } else if (P == 2) {
         L.nreg = (int)region_size(R, R, L.Tcap);
+        L.Tmid = L.Tcap < kMidT ? L.Tcap : kMidT;
+        L.nreg_mid = (int)region_size(R, R, L.Tmid);
     } else {
         L.npair = (int)((long)T < (long)R * R ? (long)T : (long)R * R);
         L.nreg_pair = (int)region_size(R, R, L.npair);
@@ -88,7 +95,7 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
 size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed).total; }
 
 struct RankOffsets {   // layout handed to the kernel (computed once on the host)
-    int Tcap, cap, npair, nreg, nreg_pair;
+    int Tcap, cap, npair, nreg, nreg_pair, Tmid, nreg_mid;
     int force;             // 1: rank every query (taps wanted, or no head pass ran)
     uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, flag, part, misc;
 };
@@ -120,10 +127,10 @@ __device__ __forceinline__ void wave_compare_exchange(unsigned long long* keys, 
     }
 }
 
-__global__ __launch_bounds__(kRankThreads) void rank_head_kernel(RankArgs g, int Tn) {
-    __shared__ HeadLds lds[kRankThreads / kWave];
+__global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g, int Tn) {
+    __shared__ HeadLds lds[kRankHeadThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int64_t q = (int64_t)blockIdx.x * (kRankThreads / kWave) + wave;
+    const int64_t q = (int64_t)blockIdx.x * (kRankHeadThreads / kWave) + wave;
     if (q >= g.nq) return;
     HeadLds& S = lds[wave];
     const int R = g.R, T = g.T;
@@ -350,7 +357,6 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
 
     const int tid = threadIdx.x;
     const int P = g.P, R = g.R, T = g.T;
-    const int Tn = L.Tcap;                                  // min(T, R^P)
     const uint32_t C = (uint32_t)g.C;
     const uint32_t count = L.force ? (uint32_t)g.nq : g.todo[0];
     for (uint32_t item = blockIdx.x; item < count; item += gridDim.x) {
@@ -362,96 +368,107 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
         }
         __syncthreads();
 
-        // ---- the first Tn tuples, sorted, as keys (ordered sum bits, position, position) -------------
-        if (P == 1) {
-            for (int e = tid; e < Tn; e += kRankThreads)
-                keys[e] = ((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e;
-            __syncthreads();                     // the list is already sorted by (distance, id)
-        } else if (P == 2) {
-            rank_pairs(sLd, R, sLd + R, R, Tn, L.nreg, L.cap, keys, hist, misc);
-        } else {
-            // parts (1,2) and (3,4) first; then pairs of positions in those two lists
-            const int np = L.npair;
-            for (int half = 0; half < 2; ++half) {
-                rank_pairs(sLd + 2 * half * R, R, sLd + (2 * half + 1) * R, R, np, L.nreg_pair, L.cap, keys, hist, misc);
-                for (int e = tid; e < np; e += kRankThreads) {
-                    const unsigned long long key = keys[e];
-                    ps[half * np + e] = mono_inv((uint32_t)(key >> 32));
-                    pt[half * np + e] = (uint32_t)key;
+        // Two attempts for two parts: the first Tmid tuples fill the candidate budget for almost every
+        // query (tuples after the one that reaches C cannot change the result); all Tcap otherwise.
+        // With taps every tuple is wanted, so only the full attempt runs.
+        const bool staged = P == 2 && !L.force && L.Tmid < L.Tcap;
+        for (int attempt = staged ? 0 : 1; attempt < 2; ++attempt) {
+            const int Tn = attempt == 0 ? L.Tmid : L.Tcap;        // tuples ranked in this attempt
+
+            // ---- the first Tn tuples, sorted, as keys (ordered sum bits, position, position) ---------
+            if (P == 1) {
+                for (int e = tid; e < Tn; e += kRankThreads)
+                    keys[e] = ((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e;
+                __syncthreads();                 // the list is already sorted by (distance, id)
+            } else if (P == 2) {
+                rank_pairs(sLd, R, sLd + R, R, Tn, attempt == 0 ? L.nreg_mid : L.nreg, L.cap, keys, hist, misc);
+            } else {
+                // parts (1,2) and (3,4) first; then pairs of positions in those two lists
+                const int np = L.npair;
+                for (int half = 0; half < 2; ++half) {
+                    rank_pairs(sLd + 2 * half * R, R, sLd + (2 * half + 1) * R, R, np, L.nreg_pair, L.cap, keys, hist,
+                               misc);
+                    for (int e = tid; e < np; e += kRankThreads) {
+                        const unsigned long long key = keys[e];
+                        ps[half * np + e] = mono_inv((uint32_t)(key >> 32));
+                        pt[half * np + e] = (uint32_t)key;
+                    }
+                    __syncthreads();
+                }
+                rank_pairs(ps, np, ps + np, np, Tn, L.nreg, L.cap, keys, hist, misc);
+            }
+
+            // ---- tuple -> bin number -> slot -> run of the inverted list ---------------------------
+            for (int t = tid; t < Tn; t += kRankThreads) {
+                const unsigned long long key = keys[t];
+                unsigned long long lin;
+                unsigned r[4] = {0, 0, 0, 0};
+                if (P == 1) {
+                    r[0] = (unsigned)key & 0xffffu;
+                    lin = sLid[r[0]];
+                } else if (P == 2) {
+                    r[0] = ((unsigned)key >> 16) & 0xffffu;
+                    r[1] = (unsigned)key & 0xffffu;
+                    lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
+                } else {
+                    const uint32_t t12 = pt[((unsigned)key >> 16) & 0xffffu];
+                    const uint32_t t34 = pt[L.npair + ((unsigned)key & 0xffffu)];
+                    r[0] = t12 >> 16; r[1] = t12 & 0xffffu; r[2] = t34 >> 16; r[3] = t34 & 0xffffu;
+                    lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
+                    lin = lin * g.k1k2 + sLid[2 * R + r[2]];
+                    lin = lin * g.k1k2 + sLid[3 * R + r[3]];
+                }
+                const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+                const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
+                so0[t] = o0;
+                slen[t] = o1 - o0;
+                sslot[t] = (uint32_t)slot;
+                if (g.tuples) {
+                    uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
+                    tp[0] = (uint16_t)r[0]; tp[1] = (uint16_t)r[1]; tp[2] = (uint16_t)r[2]; tp[3] = (uint16_t)r[3];
+                }
+                if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
+                if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;      // keys[t] is not needed again
+            }
+            if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
+            __syncthreads();
+
+            // ---- a slot proposed earlier in the order is skipped (hashed indexes only) --------------
+            if (g.hashed) {
+                const int Tpad = next_pow2(Tn);
+                for (int e = Tn + tid; e < Tpad; e += kRankThreads) dkeys[e] = ~0ull;
+                bitonic_sort_lds(dkeys, Tpad, tid, kRankThreads);
+                for (int e = tid + 1; e < Tn; e += kRankThreads) {
+                    const unsigned long long cur = dkeys[e], prev = dkeys[e - 1];
+                    if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
                 }
                 __syncthreads();
             }
-            rank_pairs(ps, np, ps + np, np, Tn, L.nreg, L.cap, keys, hist, misc);
-        }
 
-        // ---- tuple -> bin number -> slot -> run of the inverted list -------------------------------
-        for (int t = tid; t < Tn; t += kRankThreads) {
-            const unsigned long long key = keys[t];
-            unsigned long long lin;
-            unsigned r[4] = {0, 0, 0, 0};
-            if (P == 1) {
-                r[0] = (unsigned)key & 0xffffu;
-                lin = sLid[r[0]];
-            } else if (P == 2) {
-                r[0] = ((unsigned)key >> 16) & 0xffffu;
-                r[1] = (unsigned)key & 0xffffu;
-                lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
-            } else {
-                const uint32_t t12 = pt[((unsigned)key >> 16) & 0xffffu];
-                const uint32_t t34 = pt[L.npair + ((unsigned)key & 0xffffu)];
-                r[0] = t12 >> 16; r[1] = t12 & 0xffffu; r[2] = t34 >> 16; r[3] = t34 & 0xffffu;
-                lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
-                lin = lin * g.k1k2 + sLid[2 * R + r[2]];
-                lin = lin * g.k1k2 + sLid[3 * R + r[3]];
-            }
-            const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
-            const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
-            so0[t] = o0;
-            slen[t] = o1 - o0;
-            sslot[t] = (uint32_t)slot;
-            if (g.tuples) {
-                uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
-                tp[0] = (uint16_t)r[0]; tp[1] = (uint16_t)r[1]; tp[2] = (uint16_t)r[2]; tp[3] = (uint16_t)r[3];
-            }
-            if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
-            if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;          // keys[t] is not needed again
-        }
-        if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
-        __syncthreads();
-
-        // ---- a slot proposed earlier in the order is skipped (hashed indexes only) ------------------
-        if (g.hashed) {
-            const int Tpad = next_pow2(Tn);
-            for (int e = Tn + tid; e < Tpad; e += kRankThreads) dkeys[e] = ~0ull;
-            bitonic_sort_lds(dkeys, Tpad, tid, kRankThreads);
-            for (int e = tid + 1; e < Tn; e += kRankThreads) {
-                const unsigned long long cur = dkeys[e], prev = dkeys[e - 1];
-                if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
+            // ---- lay the runs end to end, cut at C, compact --------------------------------------------
+            for (int t = tid; t < Tn; t += kRankThreads) sflag[t] = slen[t];
+            __syncthreads();
+            const uint32_t total = block_exclusive_scan(sflag, Tn, part);    // sflag[t] = start position
+            if (attempt == 0 && total < C) continue;                        // not enough: rank all Tcap tuples
+            for (int t = tid; t < Tn; t += kRankThreads) {
+                const uint32_t start = sflag[t];
+                slen[t] = (slen[t] > 0 && start < C) ? 1u : 0u;              // run is proposed
             }
             __syncthreads();
-        }
-
-        // ---- lay the runs end to end, cut at C, compact ------------------------------------------------
-        for (int t = tid; t < Tn; t += kRankThreads) sflag[t] = slen[t];
-        __syncthreads();
-        const uint32_t total = block_exclusive_scan(sflag, Tn, part);    // sflag[t] = start position
-        for (int t = tid; t < Tn; t += kRankThreads) {
-            const uint32_t start = sflag[t];
-            slen[t] = (slen[t] > 0 && start < C) ? 1u : 0u;              // run is proposed
-        }
-        __syncthreads();
-        const uint32_t nruns = block_exclusive_scan(slen, Tn, part);    // slen[t] = run index
-        for (int t = tid; t < Tn; t += kRankThreads) {
-            const uint32_t start = sflag[t];
-            const uint32_t idx = slen[t];
-            const bool emit = (t + 1 < Tn ? slen[t + 1] : nruns) != idx; // its flag was 1
-            if (emit) {
-                g.runs[(size_t)q * T + idx] = make_uint2(so0[t], start);
-                if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t];
+            const uint32_t nruns = block_exclusive_scan(slen, Tn, part);    // slen[t] = run index
+            for (int t = tid; t < Tn; t += kRankThreads) {
+                const uint32_t start = sflag[t];
+                const uint32_t idx = slen[t];
+                const bool emit = (t + 1 < Tn ? slen[t + 1] : nruns) != idx; // its flag was 1
+                if (emit) {
+                    g.runs[(size_t)q * T + idx] = make_uint2(so0[t], start);
+                    if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t];
+                }
             }
+            if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
+            __syncthreads();
+            break;
         }
-        if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
-        __syncthreads();
     }   // next query of the list
 }
 
@@ -460,6 +477,7 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
     const RankLds L = rank_layout(a.P, a.R, a.T, a.hashed);
     RankOffsets o;
     o.Tcap = L.Tcap; o.cap = L.cap; o.npair = L.npair; o.nreg = L.nreg; o.nreg_pair = L.nreg_pair;
+    o.Tmid = L.Tmid; o.nreg_mid = L.nreg_mid;
     o.keys = (uint32_t)L.off_keys; o.hist = (uint32_t)L.off_hist;
     o.Ld = (uint32_t)L.off_Ld; o.Lid = (uint32_t)L.off_Lid; o.ps = (uint32_t)L.off_ps; o.pt = (uint32_t)L.off_pt;
     o.len = (uint32_t)L.off_len; o.o0 = (uint32_t)L.off_o0; o.slot = (uint32_t)L.off_slot;
@@ -468,8 +486,8 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
     const bool head = (a.P == 2) && !taps;
     o.force = head ? 0 : 1;
     if (head) {
-        constexpr int per = kRankThreads / kWave;
-        hipLaunchKernelGGL(rank_head_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kRankThreads), 0, s, a,
+        constexpr int per = kRankHeadThreads / kWave;
+        hipLaunchKernelGGL(rank_head_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kRankHeadThreads), 0, s, a,
                            L.Tcap);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -36,9 +36,10 @@ static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads) 
     L.kpad = next_pow2(k);
     L.scap = 2 * L.kpad < 256 ? 256 : 2 * L.kpad;
     size_t o = 0;
+    L.lut = (uint32_t)o;       o += sizeof(float) * M * 256;   // at offset 0: lookups need no base register;
+                                                               // also the scan scratch of the exact fallback
+    L.skey = (uint32_t)o;      o += sizeof(uint32_t) * ((C + 3) & ~3);
     L.surv = (uint32_t)o;      o += sizeof(unsigned long long) * L.scap;
-    L.lut = (uint32_t)o;       o += sizeof(float) * M * 256;   // also the scan scratch of the exact fallback
-    L.skey = (uint32_t)o;      o += sizeof(uint32_t) * C;
     L.hist = (uint32_t)o;      o += sizeof(uint32_t) * kHistSize;
     L.a = (uint32_t)o;         o += sizeof(float) * M * k1;
     L.run_src = (uint32_t)o;   o += sizeof(uint32_t) * T;
@@ -112,22 +113,44 @@ __device__ __forceinline__ void radix_select_pass(int n, uint32_t prefix, uint32
 }
 
 // misc words
-enum { kMin = 0, kMax = 1, kNumSurv = 4, kRadix = 8 };
+enum { kMin = 0, kMax = 1, kSel = 2, kSelCount = 3, kNumSurv = 4, kRadix = 8 };
+
+// LUT[m][c] read through an LDS address formed from the code byte alone: the table sits at LDS
+// address 0 (the kernels here have no static LDS; the launcher checks that), so the address is
+// c * 4 plus the compile-time offset m * 1024 -- one sub-dword shift per lookup.
+typedef __attribute__((address_space(3))) const float lds_cfloat;
+__device__ __forceinline__ float lut_at(int m, uint32_t c) {
+    return *reinterpret_cast<lds_cfloat*>((uintptr_t)((c << 2) + (uint32_t)m * 1024u));
+}
+
+// The run a thread's current candidate position lies in, kept in registers: positions of a thread
+// only grow, so the run only moves forwards and LDS is read only when a position crosses into the
+// next run.
+struct RunCursor {
+    int run;
+    uint32_t next_start;   // run_start[run + 1]
+    uint32_t delta;        // run_src[run] - run_start[run]: position in ids/codes = candidate position + delta
+};
 
 // Scores U candidate positions per thread (base + u*nt + tid).  CHECK: positions may pass nc.
 template <int MW, int U, bool CHECK, bool TAPS>
 __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int base, int nc, int tid, int nt,
                                             const float* lut, uint32_t* skey, const uint32_t* run_src,
-                                            const uint32_t* run_start, int& run, uint32_t& kmin, uint32_t& kmax) {
-    const int M = g.M;
+                                            const uint32_t* run_start, RunCursor& cur, uint32_t& kmin,
+                                            uint32_t& kmax) {
+    const int M = MW > 0 ? 4 * MW : g.M;
     uint32_t src[U];
     uint32_t cw[U][MW > 0 ? MW : 1];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t p = (uint32_t)(base + u * nt + tid);
         if (!CHECK || p < (uint32_t)nc) {
-            while (run_start[run + 1] <= p) ++run;                 // run_start[nr] = nc > p ends the walk
-            src[u] = run_src[run] + (p - run_start[run]);
+            while (p >= cur.next_start) {                          // run_start[nr] = nc > p ends the walk
+                ++cur.run;
+                cur.next_start = run_start[cur.run + 1];
+                cur.delta = run_src[cur.run] - run_start[cur.run];
+            }
+            src[u] = p + cur.delta;
         } else {
             src[u] = run_src[0];
         }
@@ -158,14 +181,17 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
         if (CHECK && p >= nc) continue;
         float s;
         if (MW > 0) {
-            s = 0.0f;
+            s = lut_at(0, cw[u][0] & 0xffu);               // sum in ascending m
+            s += lut_at(1, (cw[u][0] >> 8) & 0xffu);
+            s += lut_at(2, (cw[u][0] >> 16) & 0xffu);
+            s += lut_at(3, cw[u][0] >> 24);
 #pragma unroll
-            for (int j = 0; j < MW; ++j) {
+            for (int j = 1; j < MW; ++j) {
                 const uint32_t wv = cw[u][j];
-                s += lut[(j * 4 + 0) * 256 + (wv & 0xffu)];
-                s += lut[(j * 4 + 1) * 256 + ((wv >> 8) & 0xffu)];
-                s += lut[(j * 4 + 2) * 256 + ((wv >> 16) & 0xffu)];
-                s += lut[(j * 4 + 3) * 256 + (wv >> 24)];
+                s += lut_at(j * 4 + 0, wv & 0xffu);
+                s += lut_at(j * 4 + 1, (wv >> 8) & 0xffu);
+                s += lut_at(j * 4 + 2, (wv >> 16) & 0xffu);
+                s += lut_at(j * 4 + 3, wv >> 24);
             }
         } else {
             const uint8_t* code = g.codes + (size_t)src[u] * M;
@@ -189,7 +215,7 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* surv = reinterpret_cast<unsigned long long*>(smem + L.surv);
     uint16_t* spos = reinterpret_cast<uint16_t*>(smem + L.spos);
-    float* lut = reinterpret_cast<float*>(smem + L.lut);
+    float* lut = reinterpret_cast<float*>(smem);                 // L.lut == 0
     float* sa = reinterpret_cast<float*>(smem + L.a);
     uint32_t* run_src = reinterpret_cast<uint32_t*>(smem + L.run_src);
     uint32_t* run_start = reinterpret_cast<uint32_t*>(smem + L.run_start);
@@ -236,7 +262,7 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
     }
     __syncthreads();
 
-    // ---- LUT of Eq. 9 summands: b^2 + lam^2 c^2 + lam (a^2 - b^2 - c^2) ----------------------------
+    // ---- LUT of Eq. 9 summands ------------------------------------------------------------------------
     for (int base = 0; base < nlut; base += nt * 4) {
         if (base > 0) {
 #pragma unroll
@@ -252,7 +278,8 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
             const int m = e >> 8;
             const float b2 = sa[m * k1 + (ent[u].ij & 0xffu)];
             const float a2 = sa[m * k1 + ((ent[u].ij >> 8) & 0xffu)];
-            const float v = (b2 + (ent[u].lam * ent[u].lam) * ent[u].cc) + ent[u].lam * ((a2 - b2) - ent[u].cc);
+            // Eq. 9 rearranged: b^2 + lam (a^2 - b^2) + (lam^2 - lam) c^2, the last term folded per code value
+            const float v = fmaf(ent[u].lam, a2 - b2, b2) + ent[u].kc;
             lut[e] = v;
             if (TAPS && g.lut) g.lut[(size_t)q * nlut + e] = v;
         }
@@ -261,15 +288,18 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
 
     // ---- scores ---------------------------------------------------------------------------------------
     uint32_t kmin = 0xffffffffu, kmax = 0u;
-    {
-        int run = 0;                           // run of this thread's current position (positions only grow)
+    if (nc > 0) {
+        RunCursor cur;                         // positions of a thread only grow
+        cur.run = 0;
+        cur.next_start = run_start[1];
+        cur.delta = run_src[0] - run_start[0];
         int base = 0;
         for (; base + 8 * nt <= nc; base += 8 * nt)
-            score_batch<MW, 8, false, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, run, kmin, kmax);
+            score_batch<MW, 8, false, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, cur, kmin, kmax);
         for (; base + 4 * nt <= nc; base += 4 * nt)
-            score_batch<MW, 4, false, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, run, kmin, kmax);
+            score_batch<MW, 4, false, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, cur, kmin, kmax);
         for (; base < nc; base += 4 * nt)
-            score_batch<MW, 4, true, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, run, kmin, kmax);
+            score_batch<MW, 4, true, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, cur, kmin, kmax);
     }
     if (TAPS && g.n_cand && tid == 0) g.n_cand[q] = (uint32_t)nc;
     kmin = wave_min_u32(kmin);
@@ -291,23 +321,43 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
         const uint32_t lo_key = misc[kMin];
         const uint32_t range = misc[kMax] - lo_key;
         const int width = 32 - __clz((int)(range | 1u));           // bits needed for range
-        const int shift = width > kHistBits ? width - kHistBits : 0;
-        for (int p = tid; p < nc; p += nt) {
-            const uint32_t key = skey[p];
-            const uint32_t b = key > lo_key ? min((key - lo_key) >> shift, (uint32_t)(kHistSize - 1)) : 0u;
-            atomicAdd(&hist[b], 1u);
+        const int shift = width > kHistBits ? width - kHistBits : 0;   // (key - lo_key) >> shift < 1024
+        const uint4* skey4 = reinterpret_cast<const uint4*>(skey);
+        const int nc4 = nc >> 2;
+        for (int p4 = tid; p4 < nc4; p4 += nt) {                   // four keys per LDS read
+            const uint4 kq = skey4[p4];
+            atomicAdd(&hist[(kq.x - lo_key) >> shift], 1u);
+            atomicAdd(&hist[(kq.y - lo_key) >> shift], 1u);
+            atomicAdd(&hist[(kq.z - lo_key) >> shift], 1u);
+            atomicAdd(&hist[(kq.w - lo_key) >> shift], 1u);
+        }
+        for (int p = 4 * nc4 + tid; p < nc; p += nt) atomicAdd(&hist[(skey[p] - lo_key) >> shift], 1u);
+        __syncthreads();
+        // the first wavefront finds the bin bsel with count(< bsel) < kk <= count(<= bsel)
+        if (tid < kWave) {
+            uint32_t bsel, below, inbin;
+            hist_locate(hist, (uint32_t)kk, lane, bsel, below, inbin);
+            if (tid == 0) {
+                misc[kSel] = bsel;
+                misc[kSelCount] = below + inbin;
+            }
         }
         __syncthreads();
-        // every wavefront: bin bsel with count(< bsel) < kk <= count(<= bsel)
-        uint32_t bsel, below, inbin;
-        hist_locate(hist, (uint32_t)kk, lane, bsel, below, inbin);
-        const uint32_t count_le = below + inbin;
+        const uint32_t bsel = misc[kSel];
+        const uint32_t count_le = misc[kSelCount];
         if (count_le <= (uint32_t)L.scap) {
-            for (int p = tid; p < nc; p += nt) {
-                const uint32_t key = skey[p];
-                const uint32_t b = key > lo_key ? min((key - lo_key) >> shift, (uint32_t)(kHistSize - 1)) : 0u;
-                if (b <= bsel) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)p;
+            // keys of the bins <= bsel are the keys <= thr
+            const unsigned long long thr64 = (unsigned long long)lo_key + (((unsigned long long)bsel + 1ull) << shift) - 1ull;
+            const uint32_t thr = thr64 > 0xffffffffull ? 0xffffffffu : (uint32_t)thr64;
+            for (int p4 = tid; p4 < nc4; p4 += nt) {
+                const uint4 kq = skey4[p4];
+                if (kq.x <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4);
+                if (kq.y <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4 + 1);
+                if (kq.z <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4 + 2);
+                if (kq.w <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4 + 3);
             }
+            for (int p = 4 * nc4 + tid; p < nc; p += nt)
+                if (skey[p] <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)p;
             nsurv = (int)count_le;
         } else {
             // exact selection: k-th smallest score key, then (only if that score is tied) the ids
@@ -425,7 +475,11 @@ hipError_t configure_rerank(size_t max_dynamic_lds) {
         reinterpret_cast<const void*>(rerank_kernel<1, true>),  reinterpret_cast<const void*>(rerank_kernel<2, true>),
         reinterpret_cast<const void*>(rerank_kernel<4, true>),  reinterpret_cast<const void*>(rerank_kernel<8, true>)};
     for (const void* kfn : kernels) {
-        hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+        hipFuncAttributes attr;
+        hipError_t e = hipFuncGetAttributes(&attr, kfn);
+        if (e != hipSuccess) return e;
+        if (attr.sharedSizeBytes != 0) return hipErrorInvalidValue;   // the LUT must start at LDS address 0
+        e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
