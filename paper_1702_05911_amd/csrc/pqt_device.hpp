@@ -159,6 +159,165 @@ __device__ __forceinline__ void wave_bitonic_sort_lds(K* keys, int n, int lane) 
     }
 }
 
+// ---- bitonic sorting of 64-bit keys held in registers ---------------------------------------------
+// A wavefront holds a chunk of 64*E keys, E per lane: element r*64 + lane of the chunk is k[r] of
+// that lane.  The chunk is elements gbase .. gbase + 64*E - 1 of a longer sequence (gbase a
+// multiple of 64*E, wave-uniform), whose bitonic network decides every direction: at merge level
+// `size` the block containing element g ascends iff (g & size) == 0.  Compare-exchange steps with a
+// stride below 64 exchange keys between lanes (DPP for strides 1 and 2, ds_swizzle for 4..16,
+// ds_bpermute for 32: no LDS memory is touched); larger strides exchange registers of one lane.
+// Equal keys are only ever padding, for which either choice is the same.
+
+// lanes l of a wavefront with (l & bit) == 0, as a mask
+__host__ __device__ constexpr unsigned long long lanes_with_bit_clear(int bit) {
+    unsigned long long m = 0;
+    for (int l = 0; l < 64; ++l)
+        if ((l & bit) == 0) m |= 1ull << l;
+    return m;
+}
+
+template <int STRIDE>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v, int lane) {
+    if constexpr (STRIDE == 1) return dpp_take<0xB1, 0xf>(v, v);
+    else if constexpr (STRIDE == 2) return dpp_take<0x4E, 0xf>(v, v);
+    else if constexpr (STRIDE < 32) return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, (STRIDE << 10) | 0x1f);
+    else return (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)v);
+}
+
+// One compare-exchange step with partner lane ^ STRIDE; keep_min[r]: lanes that keep the smaller key.
+template <int E, int STRIDE>
+__device__ __forceinline__ void xlane_step(unsigned long long (&k)[E], int lane, const unsigned long long (&keep_min)[E]) {
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const uint32_t ohi = lane_xor<STRIDE>((uint32_t)(k[r] >> 32), lane);
+        const uint32_t olo = lane_xor<STRIDE>((uint32_t)k[r], lane);
+        const unsigned long long o = ((unsigned long long)ohi << 32) | olo;
+        const bool km = __builtin_amdgcn_inverse_ballot_w64(keep_min[r]);
+        k[r] = ((o < k[r]) == km) ? o : k[r];
+    }
+}
+
+// Strides STRIDE, STRIDE/2, .., 1 of the merge level SIZE <= 32 (directions depend on lane bits only).
+template <int E, int SIZE, int STRIDE>
+__device__ __forceinline__ void merge_small(unsigned long long (&k)[E], int lane) {
+    constexpr unsigned long long km = ~(lanes_with_bit_clear(STRIDE) ^ lanes_with_bit_clear(SIZE));
+    unsigned long long keep[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) keep[r] = km;
+    xlane_step<E, STRIDE>(k, lane, keep);
+    if constexpr (STRIDE > 1) merge_small<E, SIZE, STRIDE / 2>(k, lane);
+}
+
+// Strides STRIDE, .., 1 (STRIDE < 64*E) of a merge level size >= 64: the direction is uniform per register.
+template <int E, int STRIDE>
+__device__ __forceinline__ void merge_large(unsigned long long (&k)[E], int lane, uint32_t gbase, uint32_t size) {
+    if constexpr (STRIDE >= 64) {
+        constexpr int dr = STRIDE / 64;
+#pragma unroll
+        for (int r = 0; r < E; ++r) {
+            if ((r & dr) != 0) continue;
+            const bool asc = ((gbase + (uint32_t)r * 64u) & size) == 0;
+            const unsigned long long x = k[r], y = k[r + dr];
+            const bool swap = (x > y) == asc;
+            k[r] = swap ? y : x;
+            k[r + dr] = swap ? x : y;
+        }
+    } else {
+        constexpr unsigned long long lower = lanes_with_bit_clear(STRIDE);
+        unsigned long long keep[E];
+#pragma unroll
+        for (int r = 0; r < E; ++r) keep[r] = (((gbase + (uint32_t)r * 64u) & size) == 0) ? lower : ~lower;
+        xlane_step<E, STRIDE>(k, lane, keep);
+    }
+    if constexpr (STRIDE > 1) merge_large<E, STRIDE / 2>(k, lane, gbase, size);
+}
+
+template <int E, int SIZE>
+__device__ __forceinline__ void sort_levels_large(unsigned long long (&k)[E], int lane, uint32_t gbase) {
+    if constexpr (SIZE <= 64 * E) {
+        merge_large<E, SIZE / 2>(k, lane, gbase, (uint32_t)SIZE);
+        sort_levels_large<E, SIZE * 2>(k, lane, gbase);
+    }
+}
+
+// Sorts the chunk (all merge levels 2 .. 64*E); gbase must be wave-uniform.
+template <int E>
+__device__ __forceinline__ void wave_sort_chunk(unsigned long long (&k)[E], int lane, uint32_t gbase) {
+    merge_small<E, 2, 1>(k, lane);
+    merge_small<E, 4, 2>(k, lane);
+    merge_small<E, 8, 4>(k, lane);
+    merge_small<E, 16, 8>(k, lane);
+    merge_small<E, 32, 16>(k, lane);
+    sort_levels_large<E, 64>(k, lane, gbase);
+}
+
+// The strides below 64*E of merge level `size` (>= 128*E): finishes a merge whose longer strides
+// were done through LDS.
+template <int E>
+__device__ __forceinline__ void wave_merge_chunk(unsigned long long (&k)[E], int lane, uint32_t gbase, uint32_t size) {
+    merge_large<E, 32 * E>(k, lane, gbase, size);
+}
+
+// Ascending sort of n keys in LDS (n a power of two, 64 <= n <= 64 * E * number of wavefronts) by the
+// whole workgroup: every wavefront sorts a chunk of 64*E keys in registers; merge levels beyond a
+// chunk do their long strides in LDS (one barrier each) and their short strides in registers again.
+template <int E>
+__device__ __forceinline__ void block_sort_chunks(unsigned long long* keys, int n, int tid, int nthreads) {
+    constexpr int chunk = 64 * E;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const bool active = wave * chunk < n;
+    const uint32_t gbase = (uint32_t)(wave * chunk);
+    unsigned long long k[E];
+    __syncthreads();
+    if (active) {
+#pragma unroll
+        for (int r = 0; r < E; ++r) k[r] = keys[gbase + r * 64 + lane];
+        wave_sort_chunk<E>(k, lane, gbase);
+#pragma unroll
+        for (int r = 0; r < E; ++r) keys[gbase + r * 64 + lane] = k[r];
+    }
+    __syncthreads();
+    for (int size = 2 * chunk; size <= n; size <<= 1) {
+        for (int stride = size >> 1; stride >= chunk; stride >>= 1) {
+            for (int e = tid; e < (n >> 1); e += nthreads) {
+                const int i = 2 * e - (e & (stride - 1));
+                const int j = i + stride;
+                const bool asc = (i & size) == 0;
+                const unsigned long long x = keys[i], y = keys[j];
+                if ((x > y) == asc) {
+                    keys[i] = y;
+                    keys[j] = x;
+                }
+            }
+            __syncthreads();
+        }
+        if (active) {
+#pragma unroll
+            for (int r = 0; r < E; ++r) k[r] = keys[gbase + r * 64 + lane];
+            wave_merge_chunk<E>(k, lane, gbase, (uint32_t)size);
+#pragma unroll
+            for (int r = 0; r < E; ++r) keys[gbase + r * 64 + lane] = k[r];
+        }
+        __syncthreads();
+    }
+}
+
+// Ascending sort of n (a power of two) keys in LDS by the workgroup; every thread calls it with the
+// same arguments; nthreads a power-of-two multiple of 64 with n <= 8 * nthreads.  Ends with a barrier.
+__device__ __forceinline__ void block_sort_lds(unsigned long long* keys, int n, int tid, int nthreads) {
+    if (n < 64) {
+        __syncthreads();
+        bitonic_sort_lds(keys, n, tid, nthreads);
+        return;
+    }
+    const int per = n / nthreads;
+    if (per <= 1) block_sort_chunks<1>(keys, n, tid, nthreads);
+    else if (per == 2) block_sort_chunks<2>(keys, n, tid, nthreads);
+    else if (per == 4) block_sort_chunks<4>(keys, n, tid, nthreads);
+    else block_sort_chunks<8>(keys, n, tid, nthreads);
+}
+
 // Exclusive prefix sum over data[0..n) in LDS, in place, by the whole workgroup.
 // part needs blockDim.x + 1 entries.  Returns the total.  Ends with a barrier.
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t* data, int n, uint32_t* part) {

@@ -336,7 +336,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
     const int n = (int)misc[0];
     const int npad = next_pow2(n);
     for (int e = n + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
-    bitonic_sort_lds(keys, npad, tid, kRankThreads);
+    block_sort_lds(keys, npad, tid, kRankThreads);
 }
 
 __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
             if (g.hashed) {
                 const int Tpad = next_pow2(Tn);
                 for (int e = Tn + tid; e < Tpad; e += kRankThreads) dkeys[e] = ~0ull;
-                bitonic_sort_lds(dkeys, Tpad, tid, kRankThreads);
+                block_sort_lds(dkeys, Tpad, tid, kRankThreads);
                 for (int e = tid + 1; e < Tn; e += kRankThreads) {
                     const unsigned long long cur = dkeys[e], prev = dkeys[e - 1];
                     if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
