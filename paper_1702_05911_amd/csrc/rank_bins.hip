@@ -100,34 +100,55 @@ struct RankOffsets {   // layout handed to the kernel (computed once on the host
     uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, flag, part, misc;
 };
 
-constexpr int kHeadT = 64;                     // tuples the head pass ranks
-constexpr int kHeadKeys = 320;                 // >= region size for R = T = 64 (280), in blocks of 64
+constexpr int kHeadT = 64;                     // tuples the head pass can rank
+constexpr int kHeadPairs = 320;                // pairs (a, b) with (a+1)(b+1) <= 64: 280, in blocks of 64
 
 // ------------------------------------------------------------------------------------------------
 // Head pass.  Most queries reach the candidate budget C within the first few dozen tuples of the
 // order (the later ones cannot change the result: their runs would start beyond C).  One wavefront
-// per query ranks only the first min(T, 64) tuples exactly and, if their runs already fill C (or
-// there are no more tuples), writes the final run list; otherwise it marks the query for the full
-// pass.  Wave-synchronous: no workgroup barrier, LDS accesses of one wave execute in program order.
+// per query ranks the first 32 tuples exactly, then -- only if their runs do not fill C -- the first
+// 64; if that is still not enough it marks the query for the full pass.  Keys live in registers: the
+// pairs of the region (a+1)(b+1) <= T1 are taken from a table ordered by that product (so the pairs
+// for a smaller T1 are a prefix), sorted in blocks of 64 across the lanes, and folded into the 64
+// smallest.  No workgroup barrier; LDS only holds the two lists.
 // ------------------------------------------------------------------------------------------------
+struct HeadPairTable {
+    uint8_t a[kHeadPairs], b[kHeadPairs];
+};
+constexpr HeadPairTable make_head_pair_table() {
+    HeadPairTable t{};
+    int n = 0;
+    for (int p = 1; p <= kHeadT; ++p)
+        for (int a = 0; a < kHeadT; ++a)
+            if (p % (a + 1) == 0 && p / (a + 1) <= kHeadT) {
+                t.a[n] = (uint8_t)a;
+                t.b[n] = (uint8_t)(p / (a + 1) - 1);
+                ++n;
+            }
+    for (; n < kHeadPairs; ++n) t.a[n] = t.b[n] = 255;
+    return t;
+}
+__device__ const HeadPairTable kHeadPairTable = make_head_pair_table();
+
+// number of pairs (a, b), a, b >= 0, with (a+1)(b+1) <= t
+static int head_pair_count(int t) {
+    int n = 0;
+    for (int a = 0; a < t; ++a) n += t / (a + 1);
+    return n;
+}
+
 struct HeadLds {
     float A[kHeadT], B[kHeadT];
     uint32_t Aid[kHeadT], Bid[kHeadT];
-    unsigned long long keys[kHeadKeys];
     uint32_t slot[kHeadT];
 };
 
-#define PQT_WAVE_LDS_ORDER() wave_lds_order()
+struct HeadLevels {
+    int T1[2];      // tuples ranked at each level: min(Tn, 32), min(Tn, 64)
+    int npairs[2];  // pairs of the region for that many tuples (a prefix of the table)
+};
 
-__device__ __forceinline__ void wave_compare_exchange(unsigned long long* keys, int i, int j, bool asc) {
-    const unsigned long long x = keys[i], y = keys[j];
-    if ((x > y) == asc) {
-        keys[i] = y;
-        keys[j] = x;
-    }
-}
-
-__global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g, int Tn) {
+__global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g, int Tn, HeadLevels lv) {
     __shared__ HeadLds lds[kRankHeadThreads / kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t q = (int64_t)blockIdx.x * (kRankHeadThreads / kWave) + wave;
@@ -135,7 +156,7 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
     HeadLds& S = lds[wave];
     const int R = g.R, T = g.T;
     const int R1 = R < kHeadT ? R : kHeadT;
-    const int T1 = Tn < kHeadT ? Tn : kHeadT;
+    const uint32_t C = (uint32_t)g.C;
 
     if (lane < R1) {
         S.A[lane] = g.L_d[q * 2 * R + lane];
@@ -143,81 +164,70 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
         S.B[lane] = g.L_d[q * 2 * R + R + lane];
         S.Bid[lane] = g.L_id[q * 2 * R + R + lane];
     }
-    PQT_WAVE_LDS_ORDER();
+    wave_lds_order();
 
-    // keys of the pairs with (r1+1)(r2+1) <= T1: lane = row r1
-    const int cnt = (lane < R1) ? region_row_count(lane, R1, T1) : 0;
-    const uint32_t incl = wave_inclusive_sum((uint32_t)cnt, lane);
-    const int base = (int)incl - cnt;
-    const int nreg = (int)__shfl(incl, kWave - 1, kWave);
-    const int nblk = (nreg + kWave - 1) / kWave;
-    {
-        const float da = (lane < R1) ? S.A[lane] : 0.0f;
-        for (int b = 0; b < cnt; ++b)
-            S.keys[base + b] = ((unsigned long long)mono_key(da + S.B[b]) << 32) | ((unsigned)lane << 16) | (unsigned)b;
-        for (int e = nreg + lane; e < nblk * kWave; e += kWave) S.keys[e] = ~0ull;
-    }
-    PQT_WAVE_LDS_ORDER();
-
-    // sort every block of 64 keys ascending
-    for (int size = 2; size <= kWave; size <<= 1)
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int c = lane; c < nblk * (kWave / 2); c += kWave) {
-                const int blk = c / (kWave / 2), e = c % (kWave / 2);
-                const int il = 2 * e - (e & (stride - 1));
-                wave_compare_exchange(S.keys + blk * kWave, il, il + stride, (il & size) == 0);
+    for (int level = 0; level < 2; ++level) {
+        const int T1 = lv.T1[level];
+        const int npairs = lv.npairs[level];
+        // ---- the T1 smallest keys (ordered sum bits, a, b) of the region, ascending over the lanes ----
+        unsigned long long best[1] = {~0ull};
+        for (int blk = 0; blk * kWave < npairs; ++blk) {
+            const int e = blk * kWave + lane;
+            unsigned long long cur[1] = {~0ull};
+            if (e < npairs) {
+                const unsigned a = kHeadPairTable.a[e], b = kHeadPairTable.b[e];
+                if (a < (unsigned)R1 && b < (unsigned)R1)
+                    cur[0] = ((unsigned long long)mono_key(S.A[a] + S.B[b]) << 32) | (a << 16) | b;
             }
-            PQT_WAVE_LDS_ORDER();
-        }
-    // fold the other blocks into block 0, keeping the 64 smallest each time: the lower half of the
-    // union of two ascending runs is min(x[i], y[63-i]) (a bitonic sequence), then a bitonic merge
-    for (int blk = 1; blk < nblk; ++blk) {
-        const unsigned long long x = S.keys[lane], y = S.keys[blk * kWave + (kWave - 1 - lane)];
-        S.keys[lane] = x < y ? x : y;
-        PQT_WAVE_LDS_ORDER();
-        for (int stride = kWave / 2; stride > 0; stride >>= 1) {
-            if (lane < kWave / 2) {
-                const int il = 2 * lane - (lane & (stride - 1));
-                wave_compare_exchange(S.keys, il, il + stride, true);
+            wave_sort_chunk<1>(cur, lane, 0u);
+            if (blk == 0) {
+                best[0] = cur[0];
+            } else {
+                // the 64 smallest of two ascending runs x, y: min(x[i], y[63-i]) is bitonic; merge it
+                const uint32_t rhi = (uint32_t)__builtin_amdgcn_ds_bpermute((63 - lane) << 2, (int)(uint32_t)(cur[0] >> 32));
+                const uint32_t rlo = (uint32_t)__builtin_amdgcn_ds_bpermute((63 - lane) << 2, (int)(uint32_t)cur[0]);
+                const unsigned long long y = ((unsigned long long)rhi << 32) | rlo;
+                best[0] = y < best[0] ? y : best[0];
+                wave_merge_chunk<1>(best, lane, 0u, 64u);
             }
-            PQT_WAVE_LDS_ORDER();
         }
-    }
 
-    // probe the first T1 tuples
-    uint32_t o0 = 0, len = 0;
-    if (lane < T1) {
-        const unsigned long long key = S.keys[lane];
-        const unsigned r1 = ((unsigned)key >> 16) & 0xffffu, r2 = (unsigned)key & 0xffffu;
-        const unsigned long long lin = (unsigned long long)S.Aid[r1] * g.k1k2 + S.Bid[r2];
-        const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
-        o0 = g.offsets[slot];
-        len = g.offsets[slot + 1] - o0;
-        S.slot[lane] = (uint32_t)slot;
-    }
-    if (g.hashed) {
-        PQT_WAVE_LDS_ORDER();
+        // ---- probe the first T1 tuples ---------------------------------------------------------------
+        uint32_t o0 = 0, len = 0;
         if (lane < T1) {
-            const uint32_t mine = S.slot[lane];
-            for (int t = 0; t < lane; ++t)
-                if (S.slot[t] == mine) len = 0;          // proposed earlier in the order
+            const unsigned r1 = ((unsigned)best[0] >> 16) & 0xffffu, r2 = (unsigned)best[0] & 0xffffu;
+            const unsigned long long lin = (unsigned long long)S.Aid[r1] * g.k1k2 + S.Bid[r2];
+            const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+            o0 = g.offsets[slot];
+            len = g.offsets[slot + 1] - o0;
+            S.slot[lane] = (uint32_t)slot;
         }
-    }
-    const uint32_t incl_len = wave_inclusive_sum(len, lane);
-    const uint32_t start = incl_len - len;
-    const uint32_t total = __shfl(incl_len, kWave - 1, kWave);
-    const uint32_t C = (uint32_t)g.C;
-    if (total < C && T1 < Tn) {                          // not enough yet and more tuples exist
-        if (lane == 0) g.todo[1 + atomicAdd(&g.todo[0], 1u)] = (uint32_t)q;
+        if (g.hashed) {
+            wave_lds_order();
+            if (lane < T1) {
+                const uint32_t mine = S.slot[lane];
+                for (int t = 0; t < lane; ++t)
+                    if (S.slot[t] == mine) len = 0;      // proposed earlier in the order
+            }
+            wave_lds_order();
+        }
+        const uint32_t incl_len = wave_inclusive_sum(len, lane);
+        const uint32_t start = incl_len - len;
+        const uint32_t total = __shfl(incl_len, kWave - 1, kWave);
+        if (total < C && T1 < Tn) {                      // not enough yet and more tuples exist
+            if (level == 0 && lv.T1[1] > T1) continue;   // rank twice as many
+            if (lane == 0) g.todo[1 + atomicAdd(&g.todo[0], 1u)] = (uint32_t)q;
+            return;
+        }
+        const bool emit = len > 0 && start < C;
+        const unsigned long long mask = __ballot(emit);
+        if (emit) {
+            const int idx = __popcll(mask & ((1ull << lane) - 1ull));
+            g.runs[(size_t)q * T + idx] = make_uint2(o0, start);
+        }
+        if (lane == 0) g.meta[q] = make_uint2((uint32_t)__popcll(mask), total < C ? total : C);
         return;
     }
-    const bool emit = len > 0 && start < C;
-    const unsigned long long mask = __ballot(emit);
-    if (emit) {
-        const int idx = __popcll(mask & ((1ull << lane) - 1ull));
-        g.runs[(size_t)q * T + idx] = make_uint2(o0, start);
-    }
-    if (lane == 0) g.meta[q] = make_uint2((uint32_t)__popcll(mask), total < C ? total : C);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -272,6 +282,67 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
     uint32_t tau = 0xffffffffu, a_cut = 0xffffffffu, b_cut = 0xffffffffu;
     const bool all = nreg <= cap;
     if (!all) {
+        // ---- usual case: one histogram over the range of the region's keys ----------------------------
+        // The region's smallest key is A[0]+B[0]; its largest is the last key of some row (both lists
+        // ascend).  1024 bins over that range: the bin holding the Tn-th key is found, the
+        // keys of lower bins go straight to keys[], the keys of that bin (a handful) to a side buffer
+        // that reuses the histogram, is sorted, and gives its first Tn - (lower count).
+        constexpr int kTailCap = kSelBins / 2;           // 64-bit entries the histogram's memory holds
+        const uint32_t lo_key = mono_key(A[0] + B[0]);
+        if (tid < 2) misc[tid] = 0;                      // [0] range maximum, [1] unused here
+        for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
+        __syncthreads();
+        {
+            const int rows = min(nA, Tn);               // every key of row a is <= the row's last key
+            uint32_t kmax = lo_key;
+            for (int a = tid; a < rows; a += kRankThreads)
+                kmax = max(kmax, mono_key(A[a] + B[region_row_count(a, nB, Tn) - 1]));
+            kmax = wave_max_u32(kmax);
+            if (lane == 0 && kmax > lo_key) atomicMax(&misc[0], kmax);
+        }
+        __syncthreads();
+        const uint32_t hi_key = max(misc[0], lo_key);
+        const uint32_t range = hi_key - lo_key;
+        const int width = 32 - __clz((int)(range | 1u));
+        const int shift = width > kSelBits ? width - kSelBits : 0;
+        for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+            atomicAdd(&hist[(k32 - lo_key) >> shift], 1u);
+        });
+        __syncthreads();
+        if (tid < kWave) {
+            uint32_t bsel, below, inbin;
+            hist_locate(hist, (uint32_t)Tn, lane, bsel, below, inbin);
+            if (tid == 0) {
+                misc[2] = bsel;
+                misc[3] = below;
+                misc[4] = inbin;
+                misc[0] = 0;                             // entries of keys[]
+                misc[1] = 0;                             // entries of the side buffer
+            }
+        }
+        __syncthreads();
+        const uint32_t bsel = misc[2], below = misc[3], inbin = misc[4];
+        if (inbin <= (uint32_t)kTailCap) {
+            unsigned long long* tail = reinterpret_cast<unsigned long long*>(hist);
+            for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+                const uint32_t bin = (k32 - lo_key) >> shift;
+                const unsigned long long key = ((unsigned long long)k32 << 32) | (a << 16) | b;
+                wave_append(bin < bsel, key, keys, &misc[0], lane);
+                wave_append(bin == bsel, key, tail, &misc[1], lane);
+            });
+            __syncthreads();
+            const int ntail = (int)inbin;
+            const int tpad = next_pow2(ntail) < 64 ? 64 : next_pow2(ntail);
+            for (int e = ntail + tid; e < tpad; e += kRankThreads) tail[e] = ~0ull;
+            block_sort_lds(tail, tpad, tid, kRankThreads);
+            for (int e = tid; e < Tn - (int)below; e += kRankThreads) keys[below + e] = tail[e];
+            const int npad = next_pow2(Tn);
+            for (int e = Tn + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
+            block_sort_lds(keys, npad, tid, kRankThreads);
+            return;
+        }
+        // ---- heavily tied keys: exact radix select ----------------------------------------------------
+        __syncthreads();
         uint32_t prefix = 0, mask = 0, need = (uint32_t)Tn, less = 0, neq = 0;
         const int shifts[4] = {22, 12, 2, 0};
         const int nbits[4] = {10, 10, 10, 2};
@@ -487,8 +558,13 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
     o.force = head ? 0 : 1;
     if (head) {
         constexpr int per = kRankHeadThreads / kWave;
+        HeadLevels lv;
+        lv.T1[0] = L.Tcap < kHeadT / 2 ? L.Tcap : kHeadT / 2;
+        lv.T1[1] = L.Tcap < kHeadT ? L.Tcap : kHeadT;
+        lv.npairs[0] = head_pair_count(lv.T1[0]);
+        lv.npairs[1] = head_pair_count(lv.T1[1]);
         hipLaunchKernelGGL(rank_head_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kRankHeadThreads), 0, s, a,
-                           L.Tcap);
+                           L.Tcap, lv);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
