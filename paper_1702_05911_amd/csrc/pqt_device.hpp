@@ -100,13 +100,37 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// Inclusive prefix sum across the 64 lanes of a wavefront.
+// Inclusive prefix sum across the 64 lanes of a wavefront (all lanes must be active): shifts inside
+// each row of 16 lanes, then the totals of rows 0 and 2 into rows 1 and 3, then the total of the
+// first 32 lanes into the last 32.  dpp_ctrl row_shr:n = 0x110 + n; lanes without a source add 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
 __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v, int lane) {
-    for (int off = 1; off < kWave; off <<= 1) {
-        const uint32_t n = __shfl_up(v, off, kWave);
-        if (lane >= off) v += n;
-    }
+    (void)lane;
+    v += dpp_or_zero<0x111, 0xf>(v);
+    v += dpp_or_zero<0x112, 0xf>(v);
+    v += dpp_or_zero<0x114, 0xf>(v);
+    v += dpp_or_zero<0x118, 0xf>(v);
+    v += dpp_or_zero<0x142, 0xa>(v);
+    v += dpp_or_zero<0x143, 0xc>(v);
     return v;
+}
+
+// Exclusive prefix of v over the threads of the workgroup in thread order; total = sum over all
+// threads.  part: one word of LDS per wavefront.  One barrier inside; every thread must call it.
+// part may be written again only after a later barrier.
+__device__ __forceinline__ uint32_t block_exclusive_sum(uint32_t v, uint32_t* part, uint32_t& total) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, nw = blockDim.x / kWave;
+    const uint32_t incl = wave_inclusive_sum(v, lane);
+    if (lane == kWave - 1) part[wave] = incl;
+    __syncthreads();
+    const uint32_t p = lane < nw ? part[lane] : 0u;
+    const uint32_t pin = wave_inclusive_sum(p, lane);
+    const uint32_t base = (uint32_t)__shfl((int)(pin - p), wave, kWave);
+    total = (uint32_t)__shfl((int)pin, nw - 1, kWave);
+    return base + incl - v;
 }
 
 // In a 1024-bin histogram held in LDS, find the bin that holds the item of 1-based rank `need`

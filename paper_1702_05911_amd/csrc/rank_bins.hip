@@ -44,7 +44,7 @@ struct RankLds {
     int nreg_pair;   // P = 4: region size of each pair ranking
     int Tmid;    // P = 2: tuples ranked in the first attempt (most queries need far fewer than Tcap)
     int nreg_mid;    // region size for Tmid
-    size_t off_keys, off_hist, off_Ld, off_Lid, off_ps, off_pt, off_len, off_o0, off_slot, off_flag, off_part,
+    size_t off_keys, off_hist, off_Ld, off_Lid, off_ps, off_pt, off_len, off_o0, off_slot, off_part,
         off_misc, total;
 };
 
@@ -80,12 +80,6 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     L.off_len = o;   o += sizeof(uint32_t) * L.Tcap;
     L.off_o0 = o;    o += sizeof(uint32_t) * L.Tcap;
     L.off_slot = o;  o += sizeof(uint32_t) * L.Tcap;
-    if (P == 4 && 2 * L.npair >= L.Tcap) {
-        L.off_flag = L.off_ps;         // the pair sums are dead once every tuple has its slot
-    } else {
-        L.off_flag = o;
-        o += sizeof(uint32_t) * L.Tcap;
-    }
     L.off_part = o;  o += sizeof(uint32_t) * (kRankThreads + 1);
     L.off_misc = o;  o += sizeof(uint32_t) * 16;
     L.total = o;
@@ -97,7 +91,7 @@ size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R
 struct RankOffsets {   // layout handed to the kernel (computed once on the host)
     int Tcap, cap, npair, nreg, nreg_pair, Tmid, nreg_mid;
     int force;             // 1: rank every query (taps wanted, or no head pass ran)
-    uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, flag, part, misc;
+    uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, part, misc;
 };
 
 constexpr int kHeadT = 64;                     // tuples the head pass can rank
@@ -422,7 +416,6 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
     uint32_t* slen = reinterpret_cast<uint32_t*>(smem + L.len);
     uint32_t* so0 = reinterpret_cast<uint32_t*>(smem + L.o0);
     uint32_t* sslot = reinterpret_cast<uint32_t*>(smem + L.slot);
-    uint32_t* sflag = reinterpret_cast<uint32_t*>(smem + L.flag);
     uint32_t* part = reinterpret_cast<uint32_t*>(smem + L.part);
     uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);
 
@@ -517,24 +510,37 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
             }
 
             // ---- lay the runs end to end, cut at C, compact --------------------------------------------
-            for (int t = tid; t < Tn; t += kRankThreads) sflag[t] = slen[t];
-            __syncthreads();
-            const uint32_t total = block_exclusive_scan(sflag, Tn, part);    // sflag[t] = start position
-            if (attempt == 0 && total < C) continue;                        // not enough: rank all Tcap tuples
-            for (int t = tid; t < Tn; t += kRankThreads) {
-                const uint32_t start = sflag[t];
-                slen[t] = (slen[t] > 0 && start < C) ? 1u : 0u;              // run is proposed
+            // every thread takes `per` consecutive tuples; both prefix sums run in registers
+            constexpr int kMaxPer = 8;                                      // Tn <= 8192 = kMaxPer * blockDim.x
+            const int per = (Tn + kRankThreads - 1) / kRankThreads;
+            const int t0 = tid * per;
+            uint32_t len[kMaxPer], sum = 0;
+#pragma unroll
+            for (int i = 0; i < kMaxPer; ++i) {
+                len[i] = (i < per && t0 + i < Tn) ? slen[t0 + i] : 0u;
+                sum += len[i];
             }
-            __syncthreads();
-            const uint32_t nruns = block_exclusive_scan(slen, Tn, part);    // slen[t] = run index
-            for (int t = tid; t < Tn; t += kRankThreads) {
-                const uint32_t start = sflag[t];
-                const uint32_t idx = slen[t];
-                const bool emit = (t + 1 < Tn ? slen[t + 1] : nruns) != idx; // its flag was 1
-                if (emit) {
-                    g.runs[(size_t)q * T + idx] = make_uint2(so0[t], start);
-                    if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t];
+            uint32_t total;
+            uint32_t start = block_exclusive_sum(sum, part, total);
+            if (attempt == 0 && total < C) continue;                        // not enough: rank all Tcap tuples
+            uint32_t first[kMaxPer], flags = 0, nflag = 0;
+#pragma unroll
+            for (int i = 0; i < kMaxPer; ++i) {
+                first[i] = start;
+                if (len[i] > 0 && start < C) {                              // run is proposed
+                    flags |= 1u << i;
+                    ++nflag;
                 }
+                start += len[i];
+            }
+            uint32_t nruns;
+            uint32_t idx = block_exclusive_sum(nflag, part + kRankThreads / kWave, nruns);
+#pragma unroll
+            for (int i = 0; i < kMaxPer; ++i) {
+                if (((flags >> i) & 1u) == 0) continue;
+                g.runs[(size_t)q * T + idx] = make_uint2(so0[t0 + i], first[i]);
+                if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t0 + i];
+                ++idx;
             }
             if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
             __syncthreads();
@@ -552,7 +558,7 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
     o.keys = (uint32_t)L.off_keys; o.hist = (uint32_t)L.off_hist;
     o.Ld = (uint32_t)L.off_Ld; o.Lid = (uint32_t)L.off_Lid; o.ps = (uint32_t)L.off_ps; o.pt = (uint32_t)L.off_pt;
     o.len = (uint32_t)L.off_len; o.o0 = (uint32_t)L.off_o0; o.slot = (uint32_t)L.off_slot;
-    o.flag = (uint32_t)L.off_flag; o.part = (uint32_t)L.off_part; o.misc = (uint32_t)L.off_misc;
+    o.part = (uint32_t)L.off_part; o.misc = (uint32_t)L.off_misc;
     const bool taps = a.n_tuples || a.tuples || a.tuple_keys || a.slots;
     const bool head = (a.P == 2) && !taps;
     o.force = head ? 0 : 1;
