@@ -76,7 +76,8 @@ struct pqt_index {
     uint32_t* ws_Lid = nullptr;
     uint2* ws_runs = nullptr;
     uint2* ws_meta = nullptr;
-    uint32_t* ws_todo = nullptr;
+    uint32_t* ws_counters = nullptr;   // 2 words
+    uint32_t* ws_order = nullptr;      // nq words
     uint64_t bytes_workspace = 0;
     // stage timing
     bool profiling = false;
@@ -85,8 +86,8 @@ struct pqt_index {
 
     void free_workspace() {
         (void)hipFree(ws_a); (void)hipFree(ws_Ld); (void)hipFree(ws_Lid);
-        (void)hipFree(ws_runs); (void)hipFree(ws_meta); (void)hipFree(ws_todo);
-        ws_a = ws_Ld = nullptr; ws_Lid = nullptr; ws_runs = ws_meta = nullptr; ws_todo = nullptr;
+        (void)hipFree(ws_runs); (void)hipFree(ws_meta); (void)hipFree(ws_counters); (void)hipFree(ws_order);
+        ws_a = ws_Ld = nullptr; ws_Lid = nullptr; ws_runs = ws_meta = nullptr; ws_counters = ws_order = nullptr;
         ws_nq = 0; bytes_workspace = 0;
     }
 };
@@ -139,12 +140,23 @@ int rerank_threads(const pqt_index* ix) {
     return t < cap ? t : cap;
 }
 
+// Can the re-rank kernel also run the full bin ranking of the queries the head pass leaves over?
+// (two tree parts; few enough tuples per thread of the re-rank workgroup; the LDS of both fits)
+bool can_fuse_ranking(const pqt_index* ix, int k, int w) {
+    if (ix->P != 2) return false;
+    const int R = w * (int)ix->k2;
+    const int threads = rerank_threads(ix);
+    const pqt::RankOffsets ro = pqt::rank_offsets(ix->P, R, ix->T, ix->hashed);
+    if (ro.Tcap > pqt::rerank_fused_tuples_per_thread() * threads) return false;
+    return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total) <= g_lds_limit;
+}
+
 int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
     const int R = w * (int)ix->k2;
     const size_t l1 = pqt::traverse_lds_bytes(ix->D, ix->P, ix->k1, ix->k2, ix->M, w);
     const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed);
     const int threads = rerank_threads(ix);
-    const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads);
+    const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0);
     if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)
         return fail(PQT_EUNSUPPORTED,
                     "LDS budget exceeded (traverse %zu, rank %zu, rerank %zu bytes of %zu) for D=%u M=%u k1=%u R=%d T=%u C=%u",
@@ -168,9 +180,10 @@ int ensure_workspace(pqt_index* ix, int64_t nq, int R) {
     HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_Lid), bl));
     HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_runs), br));
     HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_meta), bm));
-    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_todo), sizeof(uint32_t) * ((size_t)n + 1)));
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_counters), sizeof(uint32_t) * 2));
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_order), sizeof(uint32_t) * (size_t)n));
     ix->ws_nq = n; ix->ws_R = r; ix->ws_T = t;
-    ix->bytes_workspace = ba + 2 * bl + br + bm + sizeof(uint32_t) * ((size_t)n + 1);
+    ix->bytes_workspace = ba + 2 * bl + br + bm + sizeof(uint32_t) * ((size_t)n + 2);
     return PQT_OK;
 }
 
@@ -411,7 +424,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ta.queries = queries; ta.nq = nq;
     ta.D = ix->D; ta.P = ix->P; ta.k1 = ix->k1; ta.k2 = ix->k2; ta.M = ix->M; ta.w = w;
     ta.C1 = ix->C1; ta.c1n = ix->c1n; ta.C2 = ix->C2;
-    ta.a = ix->ws_a; ta.L_d = ix->ws_Ld; ta.L_id = ix->ws_Lid; ta.sel_tap = tp.sel; ta.todo = ix->ws_todo;
+    ta.a = ix->ws_a; ta.L_d = ix->ws_Ld; ta.L_id = ix->ws_Lid; ta.sel_tap = tp.sel; ta.counters = ix->ws_counters;
     if (ev) HIP_TRY(hipEventRecord(ev[0], stream));
     HIP_TRY(pqt::launch_traverse(ta, stream));
     if (ev) HIP_TRY(hipEventRecord(ev[1], stream));
@@ -420,9 +433,13 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ra.nq = nq; ra.P = ix->P; ra.R = R; ra.T = ix->T; ra.C = ix->C;
     ra.k1k2 = ix->k1 * ix->k2; ra.H = ix->H; ra.hashed = ix->hashed ? 1 : 0;
     ra.offsets = ix->offsets; ra.L_d = ix->ws_Ld; ra.L_id = ix->ws_Lid;
-    ra.runs = ix->ws_runs; ra.meta = ix->ws_meta; ra.todo = ix->ws_todo;
+    ra.runs = ix->ws_runs; ra.meta = ix->ws_meta; ra.counters = ix->ws_counters; ra.order = ix->ws_order;
     ra.n_tuples = tp.n_tuples; ra.tuples = tp.tuples; ra.tuple_keys = tp.tuple_keys; ra.slots = tp.slots;
-    HIP_TRY(pqt::launch_rank(ra, stream));
+    const bool rerank_taps = tp.n_cand || tp.cand_ids || tp.scores || tp.lut || tp.n_slots;
+    const bool head = pqt::rank_has_head(ra);
+    // the few queries the head pass cannot finish are ranked in full by their re-rank workgroup
+    const bool fuse = head && !rerank_taps && can_fuse_ranking(ix, k, w);
+    HIP_TRY(pqt::launch_rank(ra, stream, fuse));
     if (ev) HIP_TRY(hipEventRecord(ev[2], stream));
 
     pqt::RerankArgs ca;
@@ -430,8 +447,10 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ca.threads = rerank_threads(ix);
     ca.a = ix->ws_a; ca.table = ix->table; ca.runs = ix->ws_runs; ca.meta = ix->ws_meta;
     ca.ids = ix->ids; ca.codes = ix->codes; ca.out_ids = out_ids; ca.out_dists = out_dists;
+    ca.todo = ix->ws_order; ca.todo_count = ix->ws_counters;
+    ca.early = fuse ? (int)(nq < 1024 ? nq : 1024) : 0;   // unfinished queries first: they take longest
     ca.n_cand = tp.n_cand; ca.cand_ids = tp.cand_ids; ca.scores = tp.scores; ca.lut = tp.lut;
-    HIP_TRY(pqt::launch_rerank(ca, stream));
+    HIP_TRY(pqt::launch_rerank(ca, fuse ? &ra : nullptr, stream));
     if (ev) HIP_TRY(hipEventRecord(ev[3], stream));
 
     // taps that are plain copies of workspace arrays

@@ -328,7 +328,9 @@ __device__ __forceinline__ void block_sort_chunks(unsigned long long* keys, int 
 }
 
 // Ascending sort of n (a power of two) keys in LDS by the workgroup; every thread calls it with the
-// same arguments; nthreads a power-of-two multiple of 64 with n <= 8 * nthreads.  Ends with a barrier.
+// same arguments; nthreads a power-of-two multiple of 64 with n <= MAXE * nthreads (MAXE = 2, 4 or 8
+// keys per thread at most: fewer keeps the register count of the calling kernel down).  Ends with a barrier.
+template <int MAXE = 8>
 __device__ __forceinline__ void block_sort_lds(unsigned long long* keys, int n, int tid, int nthreads) {
     if (n < 64) {
         __syncthreads();
@@ -337,8 +339,8 @@ __device__ __forceinline__ void block_sort_lds(unsigned long long* keys, int n, 
     }
     const int per = n / nthreads;
     if (per <= 1) block_sort_chunks<1>(keys, n, tid, nthreads);
-    else if (per == 2) block_sort_chunks<2>(keys, n, tid, nthreads);
-    else if (per == 4) block_sort_chunks<4>(keys, n, tid, nthreads);
+    else if (per == 2 || MAXE == 2) block_sort_chunks<2>(keys, n, tid, nthreads);
+    else if (per == 4 || MAXE == 4) block_sort_chunks<4>(keys, n, tid, nthreads);
     else block_sort_chunks<8>(keys, n, tid, nthreads);
 }
 

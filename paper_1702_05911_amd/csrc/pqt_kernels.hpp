@@ -32,7 +32,7 @@ struct TraverseArgs {
     float* L_d;             // nq x P x R
     uint32_t* L_id;         // nq x P x R
     int32_t* sel_tap;       // nq x P x w or null
-    uint32_t* todo;         // [0] = number of queries left to the full ranking pass (reset here), or null
+    uint32_t* counters;     // [0], [1]: the bin ranking's query counters, reset here (null: nothing to reset)
 };
 size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w);
 hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s);
@@ -47,18 +47,33 @@ struct RankArgs {
     const float* L_d;
     const uint32_t* L_id;
     uint2* runs;              // nq x T   (.x = first position in ids/codes, .y = start in candidate list)
-    uint2* meta;              // nq       (.x = number of runs, .y = number of candidates)
-    uint32_t* todo;           // [0] = count, [1..] = queries the head pass left to the full pass
+    uint2* meta;              // nq       (.x = number of runs, .y = number of candidates; or .x = kMetaTodo:
+                              //           the head pass left the query to the full pass, .y = its place in order[])
+    uint32_t* counters;       // [0] = number of queries the head pass left to the full pass
+    uint32_t* order;          // nq: those queries
     // taps (nullable)
     uint32_t* n_tuples;
     uint16_t* tuples;         // nq x T x 4
     float* tuple_keys;        // nq x T
     uint64_t* slots;          // nq x T
 };
+constexpr uint32_t kMetaTodo = 0xffffffffu;
+
+struct RankOffsets {   // LDS layout of the full ranking pass (computed once on the host)
+    int Tcap, cap, npair, nreg, nreg_pair, Tmid, nreg_mid;
+    int force;             // 1: rank every query (taps wanted, or no head pass ran)
+    uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, part, misc;
+    uint32_t total;        // bytes
+};
 // number of (r1, r2) pairs that can be among the first T of an R x R sum table
 int rank_region_size(int R, int T);
 size_t rank_lds_bytes(int P, int R, int T, int hashed);
-hipError_t launch_rank(const RankArgs& a, hipStream_t s);
+RankOffsets rank_offsets(int P, int R, int T, int hashed);
+// does a head pass exist for these arguments (two tree parts, no taps of the ranking)?
+bool rank_has_head(const RankArgs& a);
+// defer_full: only the head pass is launched; the caller runs the full pass of the unfinished
+// queries elsewhere (inside the re-rank kernel).  Needs rank_has_head(a).
+hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full);
 
 struct RerankArgs {
     int64_t nq;
@@ -70,6 +85,12 @@ struct RerankArgs {
     const uint2* meta;
     const uint32_t* ids;
     const uint8_t* codes;     // N x M
+    // Queries the ranking head pass left unfinished take longest, so they go first: the first
+    // `early` workgroups take entries of todo[0 .. *todo_count) (the rest of them exit at once), then
+    // workgroup early + q takes query q unless one of the first did.  early = 0: workgroup q, query q.
+    const uint32_t* todo;
+    const uint32_t* todo_count;
+    int early;
     int64_t* out_ids;         // nq x k
     float* out_dists;         // nq x k
     // taps (nullable)
@@ -78,8 +99,12 @@ struct RerankArgs {
     float* scores;            // nq x C
     float* lut;               // nq x M x 256
 };
-size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads);
-hipError_t launch_rerank(const RerankArgs& a, hipStream_t s);
+// rank_lds: LDS bytes of the full ranking pass when the kernel also runs it (0: it does not)
+size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds);
+// tuples per thread the in-kernel ranking can hold: fusing needs min(T, R^2) <= that * threads
+int rerank_fused_tuples_per_thread();
+// fused: the full ranking pass of the queries whose meta.x is kMetaTodo runs inside the kernel
+hipError_t launch_rerank(const RerankArgs& a, const RankArgs* fused, hipStream_t s);
 
 // raise the dynamic-LDS ceiling of each kernel (once per device)
 hipError_t configure_traverse(size_t max_dynamic_lds);

@@ -12,15 +12,9 @@
 // fits the sort buffer it is sorted directly, otherwise the T-th smallest key is found by a
 // radix select over the region (keys recomputed on the fly, never stored) and only the T
 // smallest are collected and sorted.
-#include "pqt_device.hpp"
-#include "pqt_kernels.hpp"
+#include "rank_device.hpp"
 
 namespace pqt {
-
-__host__ __device__ inline int region_row_count(int a, int R, int T) {
-    const int c = T / (a + 1);
-    return c < R ? c : R;
-}
 
 // Number of pairs (a, b), a < nA, b < nB, with (a+1)(b+1) <= Tn.
 static long region_size(int nA, int nB, int Tn) {
@@ -31,10 +25,6 @@ static long region_size(int nA, int nB, int Tn) {
 
 int rank_region_size(int R, int T) { return (int)region_size(R, R, T); }
 
-constexpr int kSelBits = 10;
-constexpr int kSelBins = 1 << kSelBits;
-constexpr int kMidT = 256;         // tuples ranked first by the full pass; all T only if they do not fill C
-constexpr int kRegionSplit = 64;   // rows below it are walked along b, the rest of the region along a
 
 struct RankLds {
     int Tcap;    // tuples examined: min(T, R^P)
@@ -80,7 +70,7 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     L.off_len = o;   o += sizeof(uint32_t) * L.Tcap;
     L.off_o0 = o;    o += sizeof(uint32_t) * L.Tcap;
     L.off_slot = o;  o += sizeof(uint32_t) * L.Tcap;
-    L.off_part = o;  o += sizeof(uint32_t) * (kRankThreads + 1);
+    L.off_part = o;  o += sizeof(uint32_t) * 32;               // two prefix sums x up to 16 wavefronts
     L.off_misc = o;  o += sizeof(uint32_t) * 16;
     L.total = o;
     return L;
@@ -88,11 +78,6 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
 
 size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed).total; }
 
-struct RankOffsets {   // layout handed to the kernel (computed once on the host)
-    int Tcap, cap, npair, nreg, nreg_pair, Tmid, nreg_mid;
-    int force;             // 1: rank every query (taps wanted, or no head pass ran)
-    uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, part, misc;
-};
 
 constexpr int kHeadT = 64;                     // tuples the head pass can rank
 constexpr int kHeadPairs = 320;                // pairs (a, b) with (a+1)(b+1) <= 64: 280, in blocks of 64
@@ -210,7 +195,11 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
         const uint32_t total = __shfl(incl_len, kWave - 1, kWave);
         if (total < C && T1 < Tn) {                      // not enough yet and more tuples exist
             if (level == 0 && lv.T1[1] > T1) continue;   // rank twice as many
-            if (lane == 0) g.todo[1 + atomicAdd(&g.todo[0], 1u)] = (uint32_t)q;
+            if (lane == 0) {
+                const uint32_t pos = atomicAdd(&g.counters[0], 1u);
+                g.order[pos] = (uint32_t)q;
+                g.meta[q] = make_uint2(kMetaTodo, pos);      // .y: its place in the list
+            }
             return;
         }
         const bool emit = len > 0 && start < C;
@@ -228,354 +217,54 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
 // Full pass: workgroups take the queries the head pass listed (or every query when forced).
 // ------------------------------------------------------------------------------------------------
 
-// Calls f(ordered sum bits, a, b) for every pair of the region {a < nA, b < nB, (a+1)(b+1) <= Tn},
-// each pair once, spread over the workgroup.  Rows a < kRegionSplit are walked along b (they are
-// long); the remaining pairs have b < Tn / (kRegionSplit + 1) and are walked along a, so lanes stay
-// busy in the thin tail of the hyperbola as well.
-template <typename F>
-__device__ __forceinline__ void for_region(const float* A, int nA, const float* B, int nB, int Tn, int wave,
-                                           int lane, F&& f) {
-    constexpr int nwaves = kRankThreads / kWave;
-    const int rows = min(min(nA, Tn), kRegionSplit);
-    for (int a = wave; a < rows; a += nwaves) {
-        const int cnt = region_row_count(a, nB, Tn);
-        const float da = A[a];
-        for (int b = lane; b < cnt; b += kWave) f(mono_key(da + B[b]), (uint32_t)a, (uint32_t)b);
-    }
-    if (nA > kRegionSplit) {
-        const int cols = min(nB, Tn / (kRegionSplit + 1));
-        for (int b = wave; b < cols; b += nwaves) {
-            const int hi = min(nA, Tn / (b + 1));
-            const float db = B[b];
-            for (int a = kRegionSplit + lane; a < hi; a += kWave) f(mono_key(A[a] + db), (uint32_t)a, (uint32_t)b);
-        }
-    }
-}
-
-// Appends `key` to keys[] for every lane with take set; one LDS atomic per wavefront instruction.
-__device__ __forceinline__ void wave_append(bool take, unsigned long long key, unsigned long long* keys,
-                                            uint32_t* counter, int lane) {
-    const unsigned long long m = __ballot(take);
-    if (!take) return;
-    const int leader = __ffsll((long long)m) - 1;
-    uint32_t base = 0;
-    if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
-    base = (uint32_t)__shfl((int)base, leader, kWave);
-    keys[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = key;
-}
-
-// Leaves in keys[0..Tn) the first Tn pairs (a, b) of two ascending lists A[0..nA), B[0..nB) in the
-// order (fl32(A[a] + B[b]), a, b), as sorted keys (ordered sum bits << 32 | a << 16 | b).
-// Tn <= nA * nB; nreg = size of the region (a+1)(b+1) <= Tn; cap = entries of keys[] (a power of two
-// >= Tn).  If the region fits it is sorted directly; otherwise the Tn-th smallest key is found by a
-// radix select over the region (sums recomputed in every pass, never stored), ties at that key are cut
-// by (a, b), and only the Tn smallest are collected and sorted.  All threads call it; ends with a barrier.
-__device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* B, int nB, int Tn, int nreg,
-                                           int cap, unsigned long long* keys, uint32_t* hist, uint32_t* misc) {
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    uint32_t tau = 0xffffffffu, a_cut = 0xffffffffu, b_cut = 0xffffffffu;
-    const bool all = nreg <= cap;
-    if (!all) {
-        // ---- usual case: one histogram over the range of the region's keys ----------------------------
-        // The region's smallest key is A[0]+B[0]; its largest is the last key of some row (both lists
-        // ascend).  1024 bins over that range: the bin holding the Tn-th key is found, the
-        // keys of lower bins go straight to keys[], the keys of that bin (a handful) to a side buffer
-        // that reuses the histogram, is sorted, and gives its first Tn - (lower count).
-        constexpr int kTailCap = kSelBins / 2;           // 64-bit entries the histogram's memory holds
-        const uint32_t lo_key = mono_key(A[0] + B[0]);
-        if (tid < 2) misc[tid] = 0;                      // [0] range maximum, [1] unused here
-        for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
-        __syncthreads();
-        {
-            const int rows = min(nA, Tn);               // every key of row a is <= the row's last key
-            uint32_t kmax = lo_key;
-            for (int a = tid; a < rows; a += kRankThreads)
-                kmax = max(kmax, mono_key(A[a] + B[region_row_count(a, nB, Tn) - 1]));
-            kmax = wave_max_u32(kmax);
-            if (lane == 0 && kmax > lo_key) atomicMax(&misc[0], kmax);
-        }
-        __syncthreads();
-        const uint32_t hi_key = max(misc[0], lo_key);
-        const uint32_t range = hi_key - lo_key;
-        const int width = 32 - __clz((int)(range | 1u));
-        const int shift = width > kSelBits ? width - kSelBits : 0;
-        for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
-            atomicAdd(&hist[(k32 - lo_key) >> shift], 1u);
-        });
-        __syncthreads();
-        if (tid < kWave) {
-            uint32_t bsel, below, inbin;
-            hist_locate(hist, (uint32_t)Tn, lane, bsel, below, inbin);
-            if (tid == 0) {
-                misc[2] = bsel;
-                misc[3] = below;
-                misc[4] = inbin;
-                misc[0] = 0;                             // entries of keys[]
-                misc[1] = 0;                             // entries of the side buffer
-            }
-        }
-        __syncthreads();
-        const uint32_t bsel = misc[2], below = misc[3], inbin = misc[4];
-        if (inbin <= (uint32_t)kTailCap) {
-            unsigned long long* tail = reinterpret_cast<unsigned long long*>(hist);
-            for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
-                const uint32_t bin = (k32 - lo_key) >> shift;
-                const unsigned long long key = ((unsigned long long)k32 << 32) | (a << 16) | b;
-                wave_append(bin < bsel, key, keys, &misc[0], lane);
-                wave_append(bin == bsel, key, tail, &misc[1], lane);
-            });
-            __syncthreads();
-            const int ntail = (int)inbin;
-            const int tpad = next_pow2(ntail) < 64 ? 64 : next_pow2(ntail);
-            for (int e = ntail + tid; e < tpad; e += kRankThreads) tail[e] = ~0ull;
-            block_sort_lds(tail, tpad, tid, kRankThreads);
-            for (int e = tid; e < Tn - (int)below; e += kRankThreads) keys[below + e] = tail[e];
-            const int npad = next_pow2(Tn);
-            for (int e = Tn + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
-            block_sort_lds(keys, npad, tid, kRankThreads);
-            return;
-        }
-        // ---- heavily tied keys: exact radix select ----------------------------------------------------
-        __syncthreads();
-        uint32_t prefix = 0, mask = 0, need = (uint32_t)Tn, less = 0, neq = 0;
-        const int shifts[4] = {22, 12, 2, 0};
-        const int nbits[4] = {10, 10, 10, 2};
-        for (int pass = 0; pass < 4; ++pass) {
-            for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
-            __syncthreads();
-            const int sh = shifts[pass];
-            const uint32_t dm = (1u << nbits[pass]) - 1u;
-            for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
-                if ((k32 & mask) == prefix) atomicAdd(&hist[(k32 >> sh) & dm], 1u);
-            });
-            __syncthreads();
-            uint32_t digit, before, cnt;
-            hist_locate(hist, need, lane, digit, before, cnt);
-            less += before;
-            need -= before;
-            neq = cnt;
-            prefix |= digit << sh;
-            mask |= dm << sh;
-            __syncthreads();
-        }
-        tau = prefix;                                    // Tn-th smallest sum key; `need` of the neq ties count
-        if (less + neq > (uint32_t)cap) {                // too many ties to sort: cut them by (a, b)
-            // a and b can exceed the histogram's 1024 bins: select on the high then the low digit
-            uint32_t before, cnt, hi_d, lo_d;
-            auto pass = [&](auto&& digit_of) {           // digit_of(k32, a, b) -> bin or 0xffffffff (skip)
-                for (int e = tid; e < kSelBins; e += kRankThreads) hist[e] = 0;
-                __syncthreads();
-                for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
-                    const uint32_t d = digit_of(k32, a, b);
-                    if (d != 0xffffffffu) atomicAdd(&hist[d], 1u);
-                });
-                __syncthreads();
-                uint32_t digit;
-                hist_locate(hist, need, lane, digit, before, cnt);
-                need -= before;
-                __syncthreads();
-                return digit;
-            };
-            hi_d = pass([&](uint32_t k32, uint32_t a, uint32_t) { return k32 == tau ? (a >> 6) : 0xffffffffu; });
-            lo_d = pass([&](uint32_t k32, uint32_t a, uint32_t) {
-                return (k32 == tau && (a >> 6) == hi_d) ? (a & 63u) : 0xffffffffu;
-            });
-            a_cut = (hi_d << 6) | lo_d;
-            hi_d = pass([&](uint32_t k32, uint32_t a, uint32_t b) {
-                return (k32 == tau && a == a_cut) ? (b >> 6) : 0xffffffffu;
-            });
-            lo_d = pass([&](uint32_t k32, uint32_t a, uint32_t b) {
-                return (k32 == tau && a == a_cut && (b >> 6) == hi_d) ? (b & 63u) : 0xffffffffu;
-            });
-            b_cut = (hi_d << 6) | lo_d;
-        }
-    }
-    if (tid == 0) misc[0] = 0;
-    __syncthreads();
-    for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
-        bool take = all || k32 < tau;
-        if (!all && k32 == tau) take = a_cut == 0xffffffffu || a < a_cut || (a == a_cut && b <= b_cut);
-        wave_append(take, ((unsigned long long)k32 << 32) | (a << 16) | b, keys, &misc[0], lane);
-    });
-    __syncthreads();
-    const int n = (int)misc[0];
-    const int npad = next_pow2(n);
-    for (int e = n + tid; e < npad; e += kRankThreads) keys[e] = ~0ull;
-    block_sort_lds(keys, npad, tid, kRankThreads);
-}
-
 __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + L.keys);
-    unsigned long long* dkeys = keys;                       // (slot, position) keys reuse the sort buffer
-    uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
-    float* sLd = reinterpret_cast<float*>(smem + L.Ld);
-    uint32_t* sLid = reinterpret_cast<uint32_t*>(smem + L.Lid);
-    float* ps = reinterpret_cast<float*>(smem + L.ps);
-    uint32_t* pt = reinterpret_cast<uint32_t*>(smem + L.pt);
-    uint32_t* slen = reinterpret_cast<uint32_t*>(smem + L.len);
-    uint32_t* so0 = reinterpret_cast<uint32_t*>(smem + L.o0);
-    uint32_t* sslot = reinterpret_cast<uint32_t*>(smem + L.slot);
-    uint32_t* part = reinterpret_cast<uint32_t*>(smem + L.part);
-    uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);
-
-    const int tid = threadIdx.x;
-    const int P = g.P, R = g.R, T = g.T;
-    const uint32_t C = (uint32_t)g.C;
-    const uint32_t count = L.force ? (uint32_t)g.nq : g.todo[0];
+    const uint32_t count = L.force ? (uint32_t)g.nq : g.counters[0];
     for (uint32_t item = blockIdx.x; item < count; item += gridDim.x) {
-        const int64_t q = L.force ? (int64_t)item : (int64_t)g.todo[1 + item];
-
-        for (int e = tid; e < P * R; e += kRankThreads) {
-            sLd[e] = g.L_d[q * P * R + e];
-            sLid[e] = g.L_id[q * P * R + e];
-        }
-        __syncthreads();
-
-        // Two attempts for two parts: the first Tmid tuples fill the candidate budget for almost every
-        // query (tuples after the one that reaches C cannot change the result); all Tcap otherwise.
-        // With taps every tuple is wanted, so only the full attempt runs.
-        const bool staged = P == 2 && !L.force && L.Tmid < L.Tcap;
-        for (int attempt = staged ? 0 : 1; attempt < 2; ++attempt) {
-            const int Tn = attempt == 0 ? L.Tmid : L.Tcap;        // tuples ranked in this attempt
-
-            // ---- the first Tn tuples, sorted, as keys (ordered sum bits, position, position) ---------
-            if (P == 1) {
-                for (int e = tid; e < Tn; e += kRankThreads)
-                    keys[e] = ((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e;
-                __syncthreads();                 // the list is already sorted by (distance, id)
-            } else if (P == 2) {
-                rank_pairs(sLd, R, sLd + R, R, Tn, attempt == 0 ? L.nreg_mid : L.nreg, L.cap, keys, hist, misc);
-            } else {
-                // parts (1,2) and (3,4) first; then pairs of positions in those two lists
-                const int np = L.npair;
-                for (int half = 0; half < 2; ++half) {
-                    rank_pairs(sLd + 2 * half * R, R, sLd + (2 * half + 1) * R, R, np, L.nreg_pair, L.cap, keys, hist,
-                               misc);
-                    for (int e = tid; e < np; e += kRankThreads) {
-                        const unsigned long long key = keys[e];
-                        ps[half * np + e] = mono_inv((uint32_t)(key >> 32));
-                        pt[half * np + e] = (uint32_t)key;
-                    }
-                    __syncthreads();
-                }
-                rank_pairs(ps, np, ps + np, np, Tn, L.nreg, L.cap, keys, hist, misc);
-            }
-
-            // ---- tuple -> bin number -> slot -> run of the inverted list ---------------------------
-            for (int t = tid; t < Tn; t += kRankThreads) {
-                const unsigned long long key = keys[t];
-                unsigned long long lin;
-                unsigned r[4] = {0, 0, 0, 0};
-                if (P == 1) {
-                    r[0] = (unsigned)key & 0xffffu;
-                    lin = sLid[r[0]];
-                } else if (P == 2) {
-                    r[0] = ((unsigned)key >> 16) & 0xffffu;
-                    r[1] = (unsigned)key & 0xffffu;
-                    lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
-                } else {
-                    const uint32_t t12 = pt[((unsigned)key >> 16) & 0xffffu];
-                    const uint32_t t34 = pt[L.npair + ((unsigned)key & 0xffffu)];
-                    r[0] = t12 >> 16; r[1] = t12 & 0xffffu; r[2] = t34 >> 16; r[3] = t34 & 0xffffu;
-                    lin = (unsigned long long)sLid[r[0]] * g.k1k2 + sLid[R + r[1]];
-                    lin = lin * g.k1k2 + sLid[2 * R + r[2]];
-                    lin = lin * g.k1k2 + sLid[3 * R + r[3]];
-                }
-                const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
-                const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
-                so0[t] = o0;
-                slen[t] = o1 - o0;
-                sslot[t] = (uint32_t)slot;
-                if (g.tuples) {
-                    uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
-                    tp[0] = (uint16_t)r[0]; tp[1] = (uint16_t)r[1]; tp[2] = (uint16_t)r[2]; tp[3] = (uint16_t)r[3];
-                }
-                if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
-                if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;      // keys[t] is not needed again
-            }
-            if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
-            __syncthreads();
-
-            // ---- a slot proposed earlier in the order is skipped (hashed indexes only) --------------
-            if (g.hashed) {
-                const int Tpad = next_pow2(Tn);
-                for (int e = Tn + tid; e < Tpad; e += kRankThreads) dkeys[e] = ~0ull;
-                block_sort_lds(dkeys, Tpad, tid, kRankThreads);
-                for (int e = tid + 1; e < Tn; e += kRankThreads) {
-                    const unsigned long long cur = dkeys[e], prev = dkeys[e - 1];
-                    if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
-                }
-                __syncthreads();
-            }
-
-            // ---- lay the runs end to end, cut at C, compact --------------------------------------------
-            // every thread takes `per` consecutive tuples; both prefix sums run in registers
-            constexpr int kMaxPer = 8;                                      // Tn <= 8192 = kMaxPer * blockDim.x
-            const int per = (Tn + kRankThreads - 1) / kRankThreads;
-            const int t0 = tid * per;
-            uint32_t len[kMaxPer], sum = 0;
-#pragma unroll
-            for (int i = 0; i < kMaxPer; ++i) {
-                len[i] = (i < per && t0 + i < Tn) ? slen[t0 + i] : 0u;
-                sum += len[i];
-            }
-            uint32_t total;
-            uint32_t start = block_exclusive_sum(sum, part, total);
-            if (attempt == 0 && total < C) continue;                        // not enough: rank all Tcap tuples
-            uint32_t first[kMaxPer], flags = 0, nflag = 0;
-#pragma unroll
-            for (int i = 0; i < kMaxPer; ++i) {
-                first[i] = start;
-                if (len[i] > 0 && start < C) {                              // run is proposed
-                    flags |= 1u << i;
-                    ++nflag;
-                }
-                start += len[i];
-            }
-            uint32_t nruns;
-            uint32_t idx = block_exclusive_sum(nflag, part + kRankThreads / kWave, nruns);
-#pragma unroll
-            for (int i = 0; i < kMaxPer; ++i) {
-                if (((flags >> i) & 1u) == 0) continue;
-                g.runs[(size_t)q * T + idx] = make_uint2(so0[t0 + i], first[i]);
-                if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t0 + i];
-                ++idx;
-            }
-            if (tid == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
-            __syncthreads();
-            break;
-        }
-    }   // next query of the list
+        const int64_t q = L.force ? (int64_t)item : (int64_t)g.order[item];
+        rank_query<0, false, 8>(g, L, q, smem, nullptr, nullptr, nullptr);
+    }
 }
 
-hipError_t launch_rank(const RankArgs& a, hipStream_t s) {
-    if (a.nq <= 0) return hipSuccess;
-    const RankLds L = rank_layout(a.P, a.R, a.T, a.hashed);
+RankOffsets rank_offsets(int P, int R, int T, int hashed) {
+    const RankLds L = rank_layout(P, R, T, hashed);
     RankOffsets o;
     o.Tcap = L.Tcap; o.cap = L.cap; o.npair = L.npair; o.nreg = L.nreg; o.nreg_pair = L.nreg_pair;
     o.Tmid = L.Tmid; o.nreg_mid = L.nreg_mid;
+    o.force = 0;
     o.keys = (uint32_t)L.off_keys; o.hist = (uint32_t)L.off_hist;
     o.Ld = (uint32_t)L.off_Ld; o.Lid = (uint32_t)L.off_Lid; o.ps = (uint32_t)L.off_ps; o.pt = (uint32_t)L.off_pt;
     o.len = (uint32_t)L.off_len; o.o0 = (uint32_t)L.off_o0; o.slot = (uint32_t)L.off_slot;
     o.part = (uint32_t)L.off_part; o.misc = (uint32_t)L.off_misc;
+    o.total = (uint32_t)L.total;
+    return o;
+}
+
+bool rank_has_head(const RankArgs& a) {
     const bool taps = a.n_tuples || a.tuples || a.tuple_keys || a.slots;
-    const bool head = (a.P == 2) && !taps;
+    return a.P == 2 && !taps && a.order && a.counters;
+}
+
+hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
+    if (a.nq <= 0) return hipSuccess;
+    RankOffsets o = rank_offsets(a.P, a.R, a.T, a.hashed);
+    const bool head = rank_has_head(a);
+    if (defer_full && !head) return hipErrorInvalidValue;
     o.force = head ? 0 : 1;
     if (head) {
         constexpr int per = kRankHeadThreads / kWave;
         HeadLevels lv;
-        lv.T1[0] = L.Tcap < kHeadT / 2 ? L.Tcap : kHeadT / 2;
-        lv.T1[1] = L.Tcap < kHeadT ? L.Tcap : kHeadT;
+        lv.T1[0] = o.Tcap < kHeadT / 2 ? o.Tcap : kHeadT / 2;
+        lv.T1[1] = o.Tcap < kHeadT ? o.Tcap : kHeadT;
         lv.npairs[0] = head_pair_count(lv.T1[0]);
         lv.npairs[1] = head_pair_count(lv.T1[1]);
         hipLaunchKernelGGL(rank_head_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kRankHeadThreads), 0, s, a,
-                           L.Tcap, lv);
+                           o.Tcap, lv);
         hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
+        if (e != hipSuccess || defer_full) return e;
     }
     const unsigned grid = head ? (unsigned)(a.nq < 1024 ? a.nq : 1024) : (unsigned)a.nq;
-    hipLaunchKernelGGL(rank_kernel, dim3(grid), dim3(kRankThreads), L.total, s, a, o);
+    hipLaunchKernelGGL(rank_kernel, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     return hipGetLastError();
 }
 

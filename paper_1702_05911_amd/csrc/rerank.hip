@@ -15,8 +15,7 @@
 //     than k) are compacted, their ids fetched, and the (score bits, id) keys ordered by counting
 //     ranks, four lanes per survivor.  If the superset does not fit (heavily tied scores) an
 //     exact radix select on score bits, then on ids, picks exactly k.
-#include "pqt_device.hpp"
-#include "pqt_kernels.hpp"
+#include "rank_device.hpp"
 
 namespace pqt {
 
@@ -24,13 +23,14 @@ constexpr int kHistBits = 10;
 constexpr int kHistSize = 1 << kHistBits;
 constexpr int kCountRankMax = 512;   // survivors ordered by counting ranks up to this many, else bitonic
 constexpr int kRunPrefetch = 64;     // runs fetched before the run count is known
+constexpr int kFusedPer = 2;         // tuples per thread the in-kernel bin ranking may hold (keeps registers low)
 
 struct RerankLds {
     int kpad, scap;
     uint32_t surv, spos, lut, a, run_src, run_start, skey, hist, misc, total;
 };
 
-static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads) {
+static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, size_t rank_lds) {
     RerankLds L;
     (void)threads;
     L.kpad = next_pow2(k);
@@ -41,6 +41,9 @@ static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads) 
     L.skey = (uint32_t)o;      o += sizeof(uint32_t) * ((C + 3) & ~3);
     L.surv = (uint32_t)o;      o += sizeof(unsigned long long) * L.scap;
     L.hist = (uint32_t)o;      o += sizeof(uint32_t) * kHistSize;
+    // everything above is free while a workgroup runs the full bin ranking of its query, which uses
+    // the first rank_lds bytes; the arrays below receive its result
+    if (o < rank_lds) o = (rank_lds + 15) & ~size_t(15);
     L.a = (uint32_t)o;         o += sizeof(float) * M * k1;
     L.run_src = (uint32_t)o;   o += sizeof(uint32_t) * T;
     L.run_start = (uint32_t)o; o += sizeof(uint32_t) * (T + 1);
@@ -51,8 +54,8 @@ static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads) 
     return L;
 }
 
-size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads) {
-    return rerank_layout(M, k1, T, C, k, threads).total;
+size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds) {
+    return rerank_layout(M, k1, T, C, k, threads, rank_lds).total;
 }
 
 // Position p of the candidate list -> position in ids/codes: the run r with
@@ -113,7 +116,7 @@ __device__ __forceinline__ void radix_select_pass(int n, uint32_t prefix, uint32
 }
 
 // misc words
-enum { kMin = 0, kMax = 1, kSel = 2, kSelCount = 3, kNumSurv = 4, kRadix = 8 };
+enum { kMin = 0, kMax = 1, kSel = 2, kSelCount = 3, kNumSurv = 4, kRadix = 8, kRanked = 12 };
 
 // LUT[m][c] read through an LDS address formed from the code byte alone: the table sits at LDS
 // address 0 (the kernels here have no static LDS; the launcher checks that), so the address is
@@ -210,8 +213,10 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
 }
 
 // MW = 32-bit words per code (M/4) for M in {4, 8, 16, 32}; 0 = any other M (byte loads).
-template <int MW, bool TAPS>
-__global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L) {
+// FUSED: a query whose meta.x is kMetaTodo (the ranking head pass could not finish it) is first
+// ranked in full by this workgroup, which leaves the run list directly in LDS.
+template <int MW, bool TAPS, bool FUSED>
+__global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs g, RerankLds L, RankArgs rk, RankOffsets RL) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* surv = reinterpret_cast<unsigned long long*>(smem + L.surv);
     uint16_t* spos = reinterpret_cast<uint16_t*>(smem + L.spos);
@@ -225,14 +230,30 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
 
     const int tid = threadIdx.x, nt = blockDim.x;
     const int lane = tid & (kWave - 1);
-    const int64_t q = blockIdx.x;
     const int M = g.M, k1 = g.k1, T = g.T, k = g.k;
     const int nlut = M * 256;
 
+    int64_t q;
+    uint2 meta;
+    if ((int)blockIdx.x < g.early) {           // one of the queries the head pass left unfinished, if any
+        if (blockIdx.x >= *g.todo_count) return;
+        q = (int64_t)g.todo[blockIdx.x];
+        meta = g.meta[q];
+    } else {
+        q = (int64_t)blockIdx.x - g.early;
+        meta = g.meta[q];
+        if (g.early > 0 && meta.x == kMetaTodo && meta.y < (uint32_t)g.early) return;   // an early workgroup has it
+    }
+    bool ranked_here = false;
+    if (FUSED && meta.x == kMetaTodo) {        // same for the whole workgroup
+        rank_query<2, true, kFusedPer>(rk, RL, q, smem, run_src, run_start, misc + kRanked);
+        meta = make_uint2(misc[kRanked], misc[kRanked + 1]);
+        ranked_here = true;
+    }
+
     // ---- issue every load that needs no other result first ------------------------------------------
-    const uint2 meta = g.meta[q];
     uint2 run0 = make_uint2(0u, 0u);
-    if (tid < kRunPrefetch && tid < T) run0 = g.runs[(size_t)q * T + tid];
+    if (!ranked_here && tid < kRunPrefetch && tid < T) run0 = g.runs[(size_t)q * T + tid];
     CodeEntry ent[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -245,14 +266,16 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
     const int nc = (int)meta.y;
     int steps = 0;
     while ((1 << steps) < nr) ++steps;
-    if (tid < kRunPrefetch && tid < nr) {
-        run_src[tid] = run0.x;
-        run_start[tid] = run0.y;
-    }
-    for (int r = kRunPrefetch + tid; r < nr; r += nt) {
-        const uint2 run = g.runs[(size_t)q * T + r];
-        run_src[r] = run.x;
-        run_start[r] = run.y;
+    if (!ranked_here) {
+        if (tid < kRunPrefetch && tid < nr) {
+            run_src[tid] = run0.x;
+            run_start[tid] = run0.y;
+        }
+        for (int r = kRunPrefetch + tid; r < nr; r += nt) {
+            const uint2 run = g.runs[(size_t)q * T + r];
+            run_src[r] = run.x;
+            run_start[r] = run.y;
+        }
     }
     if (tid == 0) {
         run_start[nr] = (uint32_t)nc;
@@ -447,33 +470,49 @@ __global__ __launch_bounds__(1024) void rerank_kernel(RerankArgs g, RerankLds L)
     }
 }
 
-template <bool TAPS>
-static void launch_rerank_t(const RerankArgs& a, const RerankLds& L, hipStream_t s) {
-    const dim3 grid((unsigned)a.nq), block(a.threads);
+template <bool TAPS, bool FUSED>
+static void launch_rerank_t(const RerankArgs& a, const RerankLds& L, const RankArgs& rk, const RankOffsets& RL,
+                            hipStream_t s) {
+    const dim3 grid((unsigned)(a.nq + a.early)), block(a.threads);
     switch ((a.M % 4 == 0) ? a.M / 4 : 0) {
-        case 1: hipLaunchKernelGGL((rerank_kernel<1, TAPS>), grid, block, L.total, s, a, L); break;
-        case 2: hipLaunchKernelGGL((rerank_kernel<2, TAPS>), grid, block, L.total, s, a, L); break;
-        case 4: hipLaunchKernelGGL((rerank_kernel<4, TAPS>), grid, block, L.total, s, a, L); break;
-        case 8: hipLaunchKernelGGL((rerank_kernel<8, TAPS>), grid, block, L.total, s, a, L); break;
-        default: hipLaunchKernelGGL((rerank_kernel<0, TAPS>), grid, block, L.total, s, a, L); break;
+        case 1: hipLaunchKernelGGL((rerank_kernel<1, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+        case 2: hipLaunchKernelGGL((rerank_kernel<2, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+        case 4: hipLaunchKernelGGL((rerank_kernel<4, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+        case 8: hipLaunchKernelGGL((rerank_kernel<8, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+        default: hipLaunchKernelGGL((rerank_kernel<0, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
     }
 }
 
-hipError_t launch_rerank(const RerankArgs& a, hipStream_t s) {
+int rerank_fused_tuples_per_thread() { return kFusedPer; }
+
+hipError_t launch_rerank(const RerankArgs& a, const RankArgs* fused, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
-    const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads);
-    if (a.n_cand || a.cand_ids || a.scores || a.lut) launch_rerank_t<true>(a, L, s);
-    else launch_rerank_t<false>(a, L, s);
+    const bool taps = a.n_cand || a.cand_ids || a.scores || a.lut;
+    RankArgs rk = {};
+    RankOffsets RL = {};
+    if (fused) {
+        if (taps || fused->P != 2) return hipErrorInvalidValue;
+        rk = *fused;
+        RL = rank_offsets(rk.P, rk.R, rk.T, rk.hashed);
+        if (RL.Tcap > rerank_fused_tuples_per_thread() * a.threads) return hipErrorInvalidValue;
+    }
+    const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads, fused ? RL.total : 0);
+    if (fused) launch_rerank_t<false, true>(a, L, rk, RL, s);
+    else if (taps) launch_rerank_t<true, false>(a, L, rk, RL, s);
+    else launch_rerank_t<false, false>(a, L, rk, RL, s);
     return hipGetLastError();
 }
 
 hipError_t configure_rerank(size_t max_dynamic_lds) {
     const void* kernels[] = {
-        reinterpret_cast<const void*>(rerank_kernel<0, false>), reinterpret_cast<const void*>(rerank_kernel<1, false>),
-        reinterpret_cast<const void*>(rerank_kernel<2, false>), reinterpret_cast<const void*>(rerank_kernel<4, false>),
-        reinterpret_cast<const void*>(rerank_kernel<8, false>), reinterpret_cast<const void*>(rerank_kernel<0, true>),
-        reinterpret_cast<const void*>(rerank_kernel<1, true>),  reinterpret_cast<const void*>(rerank_kernel<2, true>),
-        reinterpret_cast<const void*>(rerank_kernel<4, true>),  reinterpret_cast<const void*>(rerank_kernel<8, true>)};
+        reinterpret_cast<const void*>(rerank_kernel<0, false, false>), reinterpret_cast<const void*>(rerank_kernel<1, false, false>),
+        reinterpret_cast<const void*>(rerank_kernel<2, false, false>), reinterpret_cast<const void*>(rerank_kernel<4, false, false>),
+        reinterpret_cast<const void*>(rerank_kernel<8, false, false>), reinterpret_cast<const void*>(rerank_kernel<0, true, false>),
+        reinterpret_cast<const void*>(rerank_kernel<1, true, false>),  reinterpret_cast<const void*>(rerank_kernel<2, true, false>),
+        reinterpret_cast<const void*>(rerank_kernel<4, true, false>),  reinterpret_cast<const void*>(rerank_kernel<8, true, false>),
+        reinterpret_cast<const void*>(rerank_kernel<0, false, true>),  reinterpret_cast<const void*>(rerank_kernel<1, false, true>),
+        reinterpret_cast<const void*>(rerank_kernel<2, false, true>),  reinterpret_cast<const void*>(rerank_kernel<4, false, true>),
+        reinterpret_cast<const void*>(rerank_kernel<8, false, true>)};
     for (const void* kfn : kernels) {
         hipFuncAttributes attr;
         hipError_t e = hipFuncGetAttributes(&attr, kfn);

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
     const int D = g.D, P = g.P, k1 = g.k1, k2 = g.k2, M = g.M, w = g.w;
     const int dp = D / P, ds = D / M, per = M / P, R = w * k2;
     const int64_t q0 = (int64_t)blockIdx.x * kQueryTile;
-    if (g.todo && blockIdx.x == 0 && tid == 0) g.todo[0] = 0u;   // list filled by the ranking head pass
+    if (g.counters && blockIdx.x == 0 && tid == 0) g.counters[0] = g.counters[1] = 0u;   // used by the bin ranking
 
     // ---- stage the query tile in LDS (rows past nq are zero) -------------------------------
     for (int e = tid; e < kQueryTile * D; e += kTraverseThreads) {
