@@ -63,6 +63,7 @@ struct pqt_index {
     float* C1 = nullptr;
     float* c1n = nullptr;
     float* C2 = nullptr;
+    float* C2t = nullptr;   // children of a cluster interleaved four dimensions at a time (dp % 4 == 0)
     pqt::CodeEntry* table = nullptr;
     uint32_t* offsets = nullptr;
     uint32_t* ids = nullptr;
@@ -259,6 +260,14 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
             c1n[m * h.k1 + i] = (float)s;
         }
     }
+    std::vector<float> c2t;
+    if (dp % 4 == 0) {
+        c2t.resize((size_t)h.P * h.k1 * h.k2 * dp);
+        for (size_t pi = 0; pi < (size_t)h.P * h.k1; ++pi)
+            for (size_t j = 0; j < h.k2; ++j)
+                for (size_t d = 0; d < dp; ++d)
+                    c2t[((pi * (dp / 4) + d / 4) * h.k2 + j) * 4 + d % 4] = h.C2[(pi * h.k2 + j) * dp + d];
+    }
     std::vector<pqt::CodeEntry> table(ntab);
     for (size_t m = 0; m < h.M; ++m)
         for (size_t c = 0; c < 256; ++c) {
@@ -290,6 +299,7 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     if ((rc = upload(&ix->C1, h.C1, (size_t)h.P * h.k1 * dp * 4, hipMemcpyHostToDevice, &ix->bytes_index)) ||
         (rc = upload(&ix->c1n, c1n.data(), c1n.size() * 4, hipMemcpyHostToDevice, &ix->bytes_index)) ||
         (rc = upload(&ix->C2, h.C2, (size_t)h.P * h.k1 * h.k2 * dp * 4, hipMemcpyHostToDevice, &ix->bytes_index)) ||
+        (c2t.size() && (rc = upload(&ix->C2t, c2t.data(), c2t.size() * 4, hipMemcpyHostToDevice, &ix->bytes_index))) ||
         (rc = upload(&ix->table, table.data(), table.size() * sizeof(pqt::CodeEntry), hipMemcpyHostToDevice,
                      &ix->bytes_index)) ||
         (rc = upload(&ix->offsets, h.offsets, ((size_t)h.H + 1) * 4, big, &ix->bytes_index)) ||
@@ -362,7 +372,7 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
 void pqt_index_free(pqt_index* ix) {
     if (!ix) return;
     DeviceGuard guard(ix->device);
-    (void)hipFree(ix->C1); (void)hipFree(ix->c1n); (void)hipFree(ix->C2); (void)hipFree(ix->table);
+    (void)hipFree(ix->C1); (void)hipFree(ix->c1n); (void)hipFree(ix->C2); (void)hipFree(ix->C2t); (void)hipFree(ix->table);
     (void)hipFree(ix->offsets); (void)hipFree(ix->ids); (void)hipFree(ix->codes);
     ix->free_workspace();
     for (hipEvent_t e : ix->events) (void)hipEventDestroy(e);
@@ -423,7 +433,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     pqt::TraverseArgs ta;
     ta.queries = queries; ta.nq = nq;
     ta.D = ix->D; ta.P = ix->P; ta.k1 = ix->k1; ta.k2 = ix->k2; ta.M = ix->M; ta.w = w;
-    ta.C1 = ix->C1; ta.c1n = ix->c1n; ta.C2 = ix->C2;
+    ta.C1 = ix->C1; ta.c1n = ix->c1n; ta.C2 = ix->C2; ta.C2t = ix->C2t;
     ta.a = ix->ws_a; ta.L_d = ix->ws_Ld; ta.L_id = ix->ws_Lid; ta.sel_tap = tp.sel; ta.counters = ix->ws_counters;
     if (ev) HIP_TRY(hipEventRecord(ev[0], stream));
     HIP_TRY(pqt::launch_traverse(ta, stream));

@@ -28,6 +28,7 @@ struct TraverseArgs {
     const float* C1;        // P x k1 x dp
     const float* c1n;       // M x k1   squared norms of the centroid sub-parts
     const float* C2;        // P x k1 x k2 x dp
+    const float* C2t;       // the same, children interleaved: P x k1 x dp/4 x k2 x 4 (null unless dp % 4 == 0)
     float* a;               // nq x M x k1
     float* L_d;             // nq x P x R
     uint32_t* L_id;         // nq x P x R

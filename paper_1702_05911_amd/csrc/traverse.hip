@@ -29,7 +29,7 @@ struct TraverseLds {
 
 __host__ __device__ inline TraverseLds traverse_layout(int D, int P, int k1, int k2, int M, int w) {
     TraverseLds L;
-    L.qs = D + 1;
+    L.qs = (D + 4) & ~3;       // rows 16-byte aligned, stride not a multiple of 32 words when D is
     L.k1p = (k1 + 15) & ~15;
     L.Rpad = next_pow2(w * k2);
     size_t o = 0;
@@ -46,6 +46,64 @@ __host__ __device__ inline TraverseLds traverse_layout(int D, int P, int k1, int
 
 size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w) {
     return traverse_layout(D, P, k1, k2, M, w).total;
+}
+
+// Level-2 lists of the tile's queries, E list entries per lane (R <= 64 * E), from the interleaved
+// codebook.  The distance is the plain sum of squared differences, dimensions in ascending order.
+template <int E>
+__device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, const float* sq, int qs, const int* ssel) {
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    constexpr int nwaves = kTraverseThreads / kWave;
+    const int P = g.P, k1 = g.k1, k2 = g.k2, w = g.w;
+    const int dp = g.D / P, R = w * k2, nd4 = dp / 4;
+    const float4* C2t = reinterpret_cast<const float4*>(g.C2t);
+    for (int job = wave; job < kQueryTile * P; job += nwaves) {
+        const int q = job / P, p = job - q * P;
+        if (q0 + q >= g.nq) continue;                              // uniform per wavefront
+        const float4* yp = reinterpret_cast<const float4*>(sq + q * qs + p * dp);   // 16-byte aligned rows
+        unsigned long long key[E];
+        const float4* row[E];
+        uint32_t leaf[E];
+        float acc[E];
+#pragma unroll
+        for (int r = 0; r < E; ++r) {
+            const int e = lane + r * kWave;
+            const int ee = e < R ? e : 0;
+            const int s = ee / k2, j = ee - s * k2;
+            const int i = ssel[(q * P + p) * w + s];
+            leaf[r] = (uint32_t)(i * k2 + j);
+            row[r] = C2t + ((size_t)p * k1 + i) * nd4 * k2 + j;
+            acc[r] = 0.0f;
+        }
+        for (int d4 = 0; d4 < nd4; ++d4) {
+            const float4 y = yp[d4];
+#pragma unroll
+            for (int r = 0; r < E; ++r) {
+                const float4 c = row[r][(size_t)d4 * k2];
+                float diff = y.x - c.x;
+                acc[r] = fmaf(diff, diff, acc[r]);
+                diff = y.y - c.y;
+                acc[r] = fmaf(diff, diff, acc[r]);
+                diff = y.z - c.z;
+                acc[r] = fmaf(diff, diff, acc[r]);
+                diff = y.w - c.w;
+                acc[r] = fmaf(diff, diff, acc[r]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < E; ++r)
+            key[r] = (lane + r * kWave < R) ? (((unsigned long long)mono_key(acc[r]) << 32) | leaf[r]) : ~0ull;
+        wave_sort_chunk<E>(key, lane, 0u);
+        const int64_t gq = q0 + q;
+#pragma unroll
+        for (int r = 0; r < E; ++r) {
+            const int e = lane + r * kWave;
+            if (e < R) {
+                g.L_d[(gq * P + p) * R + e] = mono_inv((uint32_t)(key[r] >> 32));
+                g.L_id[(gq * P + p) * R + e] = (uint32_t)key[r];
+            }
+        }
+    }
 }
 
 __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs g) {
@@ -142,6 +200,14 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
     __syncthreads();
 
     // ---- level 2: one wavefront per (query, part), one lane per child ---------------------------
+    if (g.C2t != nullptr && R <= 4 * kWave) {
+        // children of one cluster interleaved four dimensions at a time (C2t[p][i][d/4][j][4]): the
+        // lanes of one cluster read consecutive 16-byte pieces; lists sorted in registers
+        if (R <= kWave) level2_lists<1>(g, q0, sq, L.qs, ssel);
+        else if (R <= 2 * kWave) level2_lists<2>(g, q0, sq, L.qs, ssel);
+        else level2_lists<4>(g, q0, sq, L.qs, ssel);
+        return;
+    }
     unsigned long long* mykeys = skey + (size_t)wave * L.Rpad;
     for (int job = wave; job < kQueryTile * P; job += nwaves) {   // same trip count for every wave
         const int q = job / P, p = job - q * P;
@@ -153,31 +219,7 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
                 const int i = ssel[(q * P + p) * w + s];
                 const float* c = g.C2 + (((size_t)p * k1 + i) * k2 + j) * dp;
                 float acc = 0.0f;
-                int d = 0;
-                if ((dp & 3) == 0) {
-                    // 16 dimensions per step: four 16-byte loads in flight, then 16 dependent FMAs
-                    const float4* c4 = reinterpret_cast<const float4*>(c);
-                    for (; d + 16 <= dp; d += 16) {
-                        const float4 v0 = c4[d / 4], v1 = c4[d / 4 + 1], v2 = c4[d / 4 + 2], v3 = c4[d / 4 + 3];
-                        const float cv[16] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w,
-                                              v2.x, v2.y, v2.z, v2.w, v3.x, v3.y, v3.z, v3.w};
-#pragma unroll
-                        for (int u = 0; u < 16; ++u) {
-                            const float diff = yp[d + u] - cv[u];
-                            acc = fmaf(diff, diff, acc);
-                        }
-                    }
-                    for (; d + 4 <= dp; d += 4) {
-                        const float4 v = c4[d / 4];
-                        const float cv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            const float diff = yp[d + u] - cv[u];
-                            acc = fmaf(diff, diff, acc);
-                        }
-                    }
-                }
-                for (; d < dp; ++d) {
+                for (int d = 0; d < dp; ++d) {
                     const float diff = yp[d] - c[d];
                     acc = fmaf(diff, diff, acc);
                 }
