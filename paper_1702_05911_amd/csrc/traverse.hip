@@ -39,7 +39,7 @@ __host__ __device__ inline TraverseLds traverse_layout(int D, int P, int k1, int
     L.off_qn = o;  o += sizeof(float) * kQueryTile * M;
     L.off_sel = o; o += sizeof(int) * kQueryTile * P * w;
     o = (o + 7) & ~size_t(7);
-    L.off_key = o; o += sizeof(unsigned long long) * (kTraverseThreads / kWave) * L.Rpad;
+    L.off_key = o; o += sizeof(unsigned long long) * (kTraverseMaxThreads / kWave) * L.Rpad;
     L.total = o;
     return L;
 }
@@ -53,7 +53,7 @@ size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w) {
 template <int E>
 __device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, const float* sq, int qs, const int* ssel) {
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    constexpr int nwaves = kTraverseThreads / kWave;
+    const int nwaves = (int)blockDim.x / kWave;
     const int P = g.P, k1 = g.k1, k2 = g.k2, w = g.w;
     const int dp = g.D / P, R = w * k2, nd4 = dp / 4;
     const float4* C2t = reinterpret_cast<const float4*>(g.C2t);
@@ -106,7 +106,7 @@ __device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, 
     }
 }
 
-__global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs g) {
+__global__ __launch_bounds__(kTraverseMaxThreads) void traverse_kernel(TraverseArgs g) {
     extern __shared__ __align__(16) unsigned char smem[];
     const TraverseLds L = traverse_layout(g.D, g.P, g.k1, g.k2, g.M, g.w);
     float* sq = reinterpret_cast<float*>(smem + L.off_q);
@@ -119,20 +119,20 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    constexpr int nwaves = kTraverseThreads / kWave;
+    const int nthreads = blockDim.x, nwaves = nthreads / kWave;
     const int D = g.D, P = g.P, k1 = g.k1, k2 = g.k2, M = g.M, w = g.w;
     const int dp = D / P, ds = D / M, per = M / P, R = w * k2;
     const int64_t q0 = (int64_t)blockIdx.x * kQueryTile;
     if (g.counters && blockIdx.x == 0 && tid == 0) g.counters[0] = g.counters[1] = 0u;   // used by the bin ranking
 
     // ---- stage the query tile in LDS (rows past nq are zero) -------------------------------
-    for (int e = tid; e < kQueryTile * D; e += kTraverseThreads) {
+    for (int e = tid; e < kQueryTile * D; e += nthreads) {
         int q = e / D, d = e - q * D;
         int64_t gq = q0 + q;
         sq[q * L.qs + d] = (gq < g.nq) ? g.queries[gq * D + d] : 0.0f;
     }
     __syncthreads();
-    for (int e = tid; e < kQueryTile * M; e += kTraverseThreads) {
+    for (int e = tid; e < kQueryTile * M; e += nthreads) {
         int q = e / M, m = e - q * M;
         const float* row = sq + q * L.qs + m * ds;
         float s = 0.0f;
@@ -175,14 +175,14 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
     __syncthreads();
 
     // ---- per-part distances and the w closest clusters ------------------------------------------
-    for (int e = tid; e < kQueryTile * P * k1; e += kTraverseThreads) {
+    for (int e = tid; e < kQueryTile * P * k1; e += nthreads) {
         const int i = e % k1, qp = e / k1, p = qp % P, q = qp / P;
         float s = sa[(q * M + p * per) * k1 + i];
         for (int m = p * per + 1; m < (p + 1) * per; ++m) s += sa[(q * M + m) * k1 + i];
         sd1[e] = s;
     }
     __syncthreads();
-    for (int e = tid; e < kQueryTile * P * k1; e += kTraverseThreads) {
+    for (int e = tid; e < kQueryTile * P * k1; e += nthreads) {
         const int i = e % k1, qp = e / k1;
         const float* row = sd1 + qp * k1;
         const unsigned long long me = ((unsigned long long)mono_key(row[i]) << 32) | (unsigned)i;
@@ -240,11 +240,14 @@ __global__ __launch_bounds__(kTraverseThreads) void traverse_kernel(TraverseArgs
     }
 }
 
+// one wavefront per four (query, part) lists of the tile
+static int traverse_threads(int P) { return P >= 4 ? 1024 : (P == 2 ? 512 : 256); }
+
 hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
     const size_t lds = traverse_lds_bytes(a.D, a.P, a.k1, a.k2, a.M, a.w);
     const unsigned blocks = (unsigned)((a.nq + kQueryTile - 1) / kQueryTile);
-    hipLaunchKernelGGL(traverse_kernel, dim3(blocks), dim3(kTraverseThreads), lds, s, a);
+    hipLaunchKernelGGL(traverse_kernel, dim3(blocks), dim3(traverse_threads(a.P)), lds, s, a);
     return hipGetLastError();
 }
 
