@@ -220,6 +220,56 @@ def test_wide_selection_two_elements_per_lane(pqt, tmp_path, rng):
     path = str(tmp_path / "wide.pqt")
     IO.write_index(path, ixw)
     _stagewise(pqt, ixw, path, Y, 20, 8, 300, 700)
+    # R = 256: four list entries per lane; R = 512: lists sorted in LDS
+    _stagewise(pqt, ixw, path, Y[:8], 20, 16, 300, 700)
+    _stagewise(pqt, ixw, path, Y[:4], 20, 32, 300, 700)
+
+
+def test_part_dimension_not_a_multiple_of_four(pqt, tmp_path, rng):
+    """D/P = 6: the level-2 codebook keeps its plain layout (no 16-byte pieces)."""
+    X = rng.random(size=(3000, 12)).astype(np.float32)
+    Y = rng.random(size=(21, 12)).astype(np.float32)
+    ix6 = B.build_index(X, P=2, k1=8, k2=4, M=4, T=200, C=500, iters=4)
+    path = str(tmp_path / "dp6.pqt")
+    IO.write_index(path, ix6)
+    _stagewise(pqt, ix6, path, Y, 10, 3, 200, 500)
+
+
+def test_index_from_arrays_matches_index_from_file(pqt, tiny, tmp_path):
+    """pqt_index_from_arrays with host arrays and with device arrays answers exactly like the index
+    loaded from the file that holds the same arrays."""
+    import torch
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    arrays = dict(N=ix.N, H=ix.H, D=ix.D, P=ix.P, k1=ix.k1, k2=ix.k2, M=ix.M, T=ix.T, C=ix.C,
+                  C1=ix.C1, C2=ix.C2, tbl_i=ix.tbl_i, tbl_j=ix.tbl_j, tbl_lam=ix.tbl_lam, cc=ix.cc,
+                  offsets=ix.offsets, ids=ix.ids, codes=ix.codes)
+    on_dev = dict(arrays)
+    on_dev["offsets"] = torch.from_numpy(ix.offsets.astype(np.int64)).cuda()
+    on_dev["ids"] = torch.from_numpy(ix.ids.astype(np.int32)).cuda()
+    on_dev["codes"] = torch.from_numpy(ix.codes).cuda()
+    yq = torch.from_numpy(Y).cuda()
+    results = []
+    for make in (lambda: pqt.pqt_index_load(path, 0), lambda: pqt.pqt_index_from_arrays(arrays, 0),
+                 lambda: pqt.pqt_index_from_arrays(on_dev, 0)):
+        gix = make()
+        try:
+            ids, d = pqt.pqt_query_batch(gix, yq, cfg.k, cfg.w)
+            torch.cuda.synchronize()
+            results.append((ids.cpu(), d.cpu()))
+            info = pqt.pqt_index_info(gix)
+            assert (info["N"], info["H"], info["T"], info["C"]) == (ix.N, ix.H, ix.T, ix.C)
+        finally:
+            pqt.pqt_index_free(gix)
+    for ids, d in results[1:]:
+        assert torch.equal(ids, results[0][0]) and torch.equal(d.view(torch.int32), results[0][1].view(torch.int32))
+    bad = dict(arrays)
+    bad["offsets"] = ix.offsets.copy()
+    bad["offsets"][3] = bad["offsets"][-1] + 1
+    with pytest.raises(pqt.PqtError) as e:
+        pqt.pqt_index_from_arrays(bad, 0)
+    assert e.value.code == pqt.PQT_EFORMAT
 
 
 def test_four_part_index(pqt, tmp_path):
