@@ -14,7 +14,7 @@ __host__ __device__ inline int region_row_count(int a, int R, int T) {
 
 constexpr int kSelBits = 10;
 constexpr int kSelBins = 1 << kSelBits;
-constexpr int kMidT = 256;         // tuples ranked first by the full pass; all T only if they do not fill C
+constexpr int kMidT = 128;         // tuples ranked first by the full pass; all T only if they do not fill C
 constexpr int kRegionSplit = 64;   // rows below it are walked along b, the rest of the region along a
 
 // Calls f(ordered sum bits, a, b) for every pair of the region {a < nA, b < nB, (a+1)(b+1) <= Tn},
@@ -64,7 +64,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
                                            int cap, unsigned long long* keys, uint32_t* hist, uint32_t* misc) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, nt = blockDim.x;
     uint32_t tau = 0xffffffffu, a_cut = 0xffffffffu, b_cut = 0xffffffffu;
-    const bool all = nreg <= cap;
+    const bool all = nreg <= (next_pow2(Tn) < 64 ? 64 : next_pow2(Tn));   // sorting the region costs no more than sorting Tn keys
     if (!all) {
         // ---- usual case: one histogram over the range of the region's keys ----------------------------
         // The region's smallest key is A[0]+B[0]; its largest is the last key of some row (both lists
