@@ -151,6 +151,9 @@ def main():
     ap.add_argument("--nq", type=int, default=None, help="queries per step (default: the workload's)")
     ap.add_argument("--T", type=int, default=None, help="bin tuples examined per query (default: the workload's)")
     ap.add_argument("--C", type=int, default=None, help="candidate budget per query (default: the workload's)")
+    ap.add_argument("--exact", type=int, default=0, metavar="K_SHORT",
+                    help="also time pqt_query_batch_exact: exact re-ranking of the first K_SHORT results (the raw "
+                         "vectors stay in HBM, one byte per element for the integer-valued workloads)")
     ap.add_argument("--batch", type=int, default=None,
                     help="queries per library call (default: all of them in one call); 1 gives a latency figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -186,8 +189,13 @@ def main():
     n_gt = min(cfg.nq, 1000) if in_hbm_only else cfg.nq     # queries with exact ground truth
     gt = ExactNN(Y[:n_gt])
 
+    raw_dtype = torch.uint8 if cfg.kind == "sift" else torch.float32
+    raw = torch.empty((cfg.N, cfg.D), dtype=raw_dtype, device=dev) if args.exact else None
+
     def observe(start, Xc):
         gt.update(start, Xc)
+        if raw is not None:
+            raw[start:start + Xc.shape[0]] = Xc.to(raw_dtype)
         if in_hbm_only and (start >> 20) % 16 == 0:
             print(f"[bench] built {start + Xc.shape[0]:,} of {cfg.N:,} vectors "
                   f"({time.perf_counter() - t_setup:.0f} s)", file=sys.stderr, flush=True)
@@ -249,7 +257,7 @@ def main():
         pqt.pqt_set_profiling(index, False)
         step()
         torch.cuda.synchronize()
-    stage_ms = [m / max(calls, 1) for m in stage_ms]
+    stage_ms = [m / max(calls, 1) for m in stage_ms][:3]
 
     # candidates actually gathered (for the byte accounting) via the debug taps, untimed
     _, _, taps = pqt.pqt_query_batch_debug(index, Y, cfg.k, w, taps=("n_cand", "n_slots"))
@@ -310,12 +318,45 @@ def main():
         "recall": rec, "stage_ms": stage_ms, "stages": stages, "roofline": roofline, "setup_s": setup_s,
     }
     if B != cfg.nq:
-        result["us_per_call"] = elapsed / args.steps / (-(-cfg.nq // B)) * 1e6
+        result["us_per_call"] = elapsed / args.steps / (-(-cfg.nq // B)) * 1e6     # calls queued back to back
+        # latency of one call: submit, then wait for its results, one call at a time
+        ncalls = min(-(-cfg.nq // B), 200)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for c in range(ncalls):
+            o = c * B
+            pqt.pqt_query_batch(index, Y[o:o + B], cfg.k, w, out_ids[o:o + B], out_d[o:o + B])
+            torch.cuda.synchronize()
+        result["latency_us_per_call"] = (time.perf_counter() - t0) / ncalls * 1e6
     if path is not None and not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(path, Y.cpu().numpy(), cfg.k, w, out_ids.cpu().numpy(),
                                               max_procs=4 if cfg.N > 200_000_000 else 16)
     else:
         result["cpu_baseline"] = None
+    if args.exact:
+        # exact re-ranking of the first K_SHORT results (the paper's PQT_2): HBM-bound gather of raw rows
+        ks = args.exact
+        pqt.pqt_index_set_vectors(index, raw)
+        for _ in range(args.warmup):
+            pqt.pqt_query_batch_exact(index, Y, ks, cfg.k, w, out_ids, out_d)
+        torch.cuda.synchronize()
+        pqt.pqt_set_profiling(index, True)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            pqt.pqt_query_batch_exact(index, Y, ks, cfg.k, w, out_ids, out_d)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        ems, ecalls = pqt.pqt_stage_times(index)
+        pqt.pqt_set_profiling(index, False)
+        ems = [m / max(ecalls, 1) for m in ems]
+        row_bytes = cfg.D * raw.element_size()
+        ebytes = nq * (min(ks, mean_cand) * (row_bytes + 8) + cfg.D * 4 + cfg.k * 12)
+        result["exact"] = {"k_short": ks, "value": cfg.nq * args.steps / el, "unit": "queries/s",
+                           "ms_per_step": el / args.steps * 1e3, "stage_ms": ems,
+                           "recall": recall_at(out_ids[:n_gt], gt), "vector_bytes": row_bytes,
+                           "roofline": {"kernel": "exact_rerank_kernel", "bound": "hbm",
+                                        "achieved": ebytes / (ems[3] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                                        "unit": "GB/s", "frac": ebytes / (ems[3] * 1e-3) / 1e9 / HBM_PEAK_GBS}}
     pqt.pqt_index_free(index)
     print(json.dumps(result))
 

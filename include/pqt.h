@@ -135,6 +135,30 @@ int pqt_query_batch(pqt_index* index, const float* queries, int64_t nq, int k, i
                     int64_t* out_ids, float* out_dists, void* hip_stream);
 
 /*
+ * Exact re-ranking of a short list -- step (3) of the pipelines named in Sec. 1 of the paper
+ * ("re-ranking the vectors on a short-list by their exact distance"), the variant PQT_2 of
+ * Table 1.
+ *
+ * pqt_index_set_vectors attaches the raw database vectors, N x D row-major in id order, as
+ * 4-byte floats (elem_bytes = 4) or 1-byte unsigned integers (elem_bytes = 1, for integer-valued
+ * data such as SIFT descriptors; 10^9 x 128 bytes fit one GPU).  location == PQT_HOST: the
+ * array is copied to the GPU and the library owns the copy.  location == PQT_DEVICE: the
+ * array is used in place, NOT copied: the caller keeps it alive and unchanged until the index
+ * is freed or other vectors are attached.  vectors == NULL detaches.  Synchronises the
+ * device.  Errors: PQT_EINVAL, PQT_EUNSUPPORTED (a row is not a whole number of 16-byte pieces:
+ * D not a multiple of 4 for floats, of 16 for bytes), PQT_ENOMEM, PQT_EHIP.
+ *
+ * pqt_query_batch_exact runs pqt_query_batch with k_short results per query (held in the
+ * library's workspace), computes ||y - x||^2 exactly (fp32) for each of them and returns
+ * the k best by (distance, id): out_ids / out_dists as for pqt_query_batch, but out_dists
+ * are exact squared distances.  1 <= k <= k_short <= min(C, PQT_MAX_K).  Errors as for
+ * pqt_query_batch; PQT_EINVAL also when no vectors are attached.
+ */
+int pqt_index_set_vectors(pqt_index* index, const void* vectors, int elem_bytes, int location);
+int pqt_query_batch_exact(pqt_index* index, const float* queries, int64_t nq, int k_short, int k, int w,
+                          int64_t* out_ids, float* out_dists, void* hip_stream);
+
+/*
  * Optional device buffers that receive every intermediate of the path, for checking it
  * stage by stage.  Any pointer may be NULL (that tap is skipped).  Shapes are per batch:
  *   a          nq x M x k1   fp32   level-1 sub-part distances (Eq. 6 per sub-part)
@@ -174,13 +198,15 @@ int pqt_query_batch_debug(pqt_index* index, const float* queries, int64_t nq, in
 /*
  * Per-stage device timing.  With profiling enabled every pqt_query_batch records HIP events
  * on its stream around its three kernels: [0] traversal (level-1 + level-2 distances and
- * sorts), [1] bin ranking and run list, [2] gather + re-rank + top-k.
+ * sorts), [1] bin ranking head pass (all of the bin ranking for four tree parts), [2] gather +
+ * re-rank + top-k (with the full bin ranking of the queries the head pass left over), [3] exact
+ * re-ranking of the short list (pqt_query_batch_exact only, else 0).
  * pqt_stage_times synchronises on the recorded events, adds up the elapsed milliseconds of
- * all calls since the last pqt_stage_times (at most 256 are kept) into ms[3], stores the
+ * all calls since the last pqt_stage_times (at most 256 are kept) into ms[4], stores the
  * number of calls in *calls, and resets.  PQT_EINVAL on null arguments.
  */
 int pqt_set_profiling(pqt_index* index, int enabled);
-int pqt_stage_times(pqt_index* index, float ms[3], int* calls);
+int pqt_stage_times(pqt_index* index, float ms[4], int* calls);
 
 /* Message of the last failing call on this thread ("" if none).  Static storage. */
 const char* pqt_last_error(void);

@@ -305,6 +305,14 @@ def brute_force(y, X, k):
     return top_k(d, np.arange(X.shape[0]), k)
 
 
+def exact_rerank_short_list(y, X, short_ids, k):
+    """Step (3) of the pipelines in Sec. 1 (PQT_2 of Table 1): the entries of a short list (ids, -1 =
+    no entry) are re-ranked by their exact squared distance to y; the k best by (distance, id)."""
+    ids = np.asarray([i for i in short_ids if i >= 0], dtype=np.int64)
+    diff = X[ids].astype(np.float64) - np.asarray(y, dtype=np.float64)[None, :]
+    return top_k(np.sum(diff * diff, axis=1), ids, k)
+
+
 def reconstruct(index, code):
     """The point a code stands for: per sub-part (1-lam)*[c_i]_m + lam*[c_j]_m  (Sec. 3.3)."""
     x = np.zeros(index.D, dtype=np.float64)

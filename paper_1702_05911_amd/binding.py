@@ -17,7 +17,7 @@ PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -
 
 EXPORTS = (
     "pqt_index_load", "pqt_index_from_arrays", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
-    "pqt_query_batch_debug", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
+    "pqt_query_batch_debug", "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
 )
 
 
@@ -72,9 +72,13 @@ def load_library(path=LIB_PATH):
     lib.pqt_query_batch.restype = ci
     lib.pqt_query_batch_debug.argtypes = [vp, vp, i64, ci, ci, vp, vp, vp, ctypes.POINTER(_Taps)]
     lib.pqt_query_batch_debug.restype = ci
+    lib.pqt_index_set_vectors.argtypes = [vp, vp, ci, ci]
+    lib.pqt_index_set_vectors.restype = ci
+    lib.pqt_query_batch_exact.argtypes = [vp, vp, i64, ci, ci, ci, vp, vp, vp]
+    lib.pqt_query_batch_exact.restype = ci
     lib.pqt_set_profiling.argtypes = [vp, ci]
     lib.pqt_set_profiling.restype = ci
-    lib.pqt_stage_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 3), ctypes.POINTER(ci)]
+    lib.pqt_stage_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4), ctypes.POINTER(ci)]
     lib.pqt_stage_times.restype = ci
     lib.pqt_last_error.argtypes = []
     lib.pqt_last_error.restype = ctypes.c_char_p
@@ -202,12 +206,46 @@ class Index:
                                           out_dists.data_ptr(), _stream_handle(stream), ctypes.byref(ct)))
         return out_ids, out_dists, bufs
 
+    def set_vectors(self, vectors):
+        """pqt_index_set_vectors.  vectors: (N, D) float32 or uint8; a NumPy array is copied to the GPU,
+        a CUDA tensor is used in place (this object keeps a reference to it); None detaches."""
+        import numpy as np
+        if vectors is None:
+            _check(_lib.pqt_index_set_vectors(self._h, None, 0, PQT_HOST))
+            self._vectors = None
+            return
+        on_device = torch.is_tensor(vectors)
+        if on_device:
+            if not (vectors.is_cuda and vectors.is_contiguous() and vectors.dtype in (torch.float32, torch.uint8)):
+                raise ValueError("vectors must be a contiguous float32 or uint8 CUDA tensor")
+            elem, ptr = vectors.element_size(), vectors.data_ptr()
+            torch.cuda.synchronize(vectors.device)
+        else:
+            if vectors.dtype not in (np.float32, np.uint8):
+                raise ValueError("vectors must be float32 or uint8")
+            vectors = np.ascontiguousarray(vectors)
+            elem, ptr = vectors.dtype.itemsize, vectors.ctypes.data
+        inf = self.info()
+        if tuple(vectors.shape) != (inf["N"], inf["D"]):
+            raise ValueError(f"vectors have shape {tuple(vectors.shape)}, index has N={inf['N']} D={inf['D']}")
+        _check(_lib.pqt_index_set_vectors(self._h, ptr, elem, PQT_DEVICE if on_device else PQT_HOST))
+        self._vectors = vectors if on_device else None
+
+    def query_batch_exact(self, queries, k_short, k, w, out_ids=None, out_dists=None, stream=None):
+        """pqt_query_batch_exact.  Returns (ids int64, exact squared distances float32)."""
+        nq, ids_, dists_ = self._buffers(queries, k)
+        out_ids = ids_ if out_ids is None else out_ids
+        out_dists = dists_ if out_dists is None else out_dists
+        _check(_lib.pqt_query_batch_exact(self._h, queries.data_ptr(), nq, int(k_short), int(k), int(w),
+                                          out_ids.data_ptr(), out_dists.data_ptr(), _stream_handle(stream)))
+        return out_ids, out_dists
+
     def set_profiling(self, enabled):
         _check(_lib.pqt_set_profiling(self._h, 1 if enabled else 0))
 
     def stage_times(self):
         """(ms per stage summed over the calls since the last read, number of calls)."""
-        ms = (ctypes.c_float * 3)()
+        ms = (ctypes.c_float * 4)()
         calls = ctypes.c_int()
         _check(_lib.pqt_stage_times(self._h, ctypes.byref(ms), ctypes.byref(calls)))
         return [float(v) for v in ms], int(calls.value)
@@ -244,6 +282,14 @@ def pqt_query_batch(index, queries, k, w, out_ids=None, out_dists=None, stream=N
 
 def pqt_query_batch_debug(index, queries, k, w, taps=_TAP_FIELDS, stream=None):
     return index.query_batch_debug(queries, k, w, taps, stream)
+
+
+def pqt_index_set_vectors(index, vectors):
+    index.set_vectors(vectors)
+
+
+def pqt_query_batch_exact(index, queries, k_short, k, w, out_ids=None, out_dists=None, stream=None):
+    return index.query_batch_exact(queries, k_short, k, w, out_ids, out_dists, stream)
 
 
 def pqt_set_profiling(index, enabled):

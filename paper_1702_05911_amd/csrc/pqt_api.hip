@@ -69,6 +69,13 @@ struct pqt_index {
     uint32_t* ids = nullptr;
     uint8_t* codes = nullptr;
     uint64_t bytes_index = 0;
+    // raw database vectors for exact re-ranking (optional)
+    const void* vectors = nullptr;
+    void* vectors_owned = nullptr;      // set when the library holds its own copy
+    int vector_elem_bytes = 0;
+    int64_t* ws_short_ids = nullptr;    // nq x k_short results of the line-quantisation re-ranking
+    float* ws_short_dists = nullptr;
+    size_t ws_short_entries = 0;
     // workspace (device), sized for ws_nq queries at ws_R list entries and ws_T tuples
     int64_t ws_nq = 0;
     int ws_R = 0, ws_T = 0;
@@ -83,7 +90,8 @@ struct pqt_index {
     // stage timing
     bool profiling = false;
     int prof_calls = 0;
-    std::vector<hipEvent_t> events;   // 4 per profiled call
+    std::vector<hipEvent_t> events;   // 5 per profiled call
+    hipEvent_t* last_events = nullptr;  // events of the most recent profiled call (for the exact re-rank stage)
 
     void free_workspace() {
         (void)hipFree(ws_a); (void)hipFree(ws_Ld); (void)hipFree(ws_Lid);
@@ -372,6 +380,7 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
 void pqt_index_free(pqt_index* ix) {
     if (!ix) return;
     DeviceGuard guard(ix->device);
+    (void)hipFree(ix->vectors_owned); (void)hipFree(ix->ws_short_ids); (void)hipFree(ix->ws_short_dists);
     (void)hipFree(ix->C1); (void)hipFree(ix->c1n); (void)hipFree(ix->C2); (void)hipFree(ix->C2t); (void)hipFree(ix->table);
     (void)hipFree(ix->offsets); (void)hipFree(ix->ids); (void)hipFree(ix->codes);
     ix->free_workspace();
@@ -420,13 +429,14 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     const pqt_debug_taps& tp = taps ? *taps : no_taps;
 
     hipEvent_t* ev = nullptr;
+    ix->last_events = nullptr;
     if (ix->profiling && ix->prof_calls < kMaxProfiledCalls) {
-        while ((int)ix->events.size() < 4 * (ix->prof_calls + 1)) {
+        while ((int)ix->events.size() < 5 * (ix->prof_calls + 1)) {
             hipEvent_t e;
             HIP_TRY(hipEventCreate(&e));
             ix->events.push_back(e);
         }
-        ev = &ix->events[4 * ix->prof_calls];
+        ev = &ix->events[5 * ix->prof_calls];
         ix->prof_calls++;
     }
 
@@ -461,7 +471,11 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ca.early = fuse ? (int)(nq < 1024 ? nq : 1024) : 0;   // unfinished queries first: they take longest
     ca.n_cand = tp.n_cand; ca.cand_ids = tp.cand_ids; ca.scores = tp.scores; ca.lut = tp.lut;
     HIP_TRY(pqt::launch_rerank(ca, fuse ? &ra : nullptr, stream));
-    if (ev) HIP_TRY(hipEventRecord(ev[3], stream));
+    if (ev) {
+        HIP_TRY(hipEventRecord(ev[3], stream));
+        HIP_TRY(hipEventRecord(ev[4], stream));     // moved behind the exact re-rank when that runs
+        ix->last_events = ev;
+    }
 
     // taps that are plain copies of workspace arrays
     if (tp.a)
@@ -483,6 +497,68 @@ int pqt_query_batch(pqt_index* ix, const float* queries, int64_t nq, int k, int 
     return pqt_query_batch_debug(ix, queries, nq, k, w, out_ids, out_dists, hip_stream, nullptr);
 }
 
+int pqt_index_set_vectors(pqt_index* ix, const void* vectors, int elem_bytes, int location) {
+    if (!ix) return fail(PQT_EINVAL, "pqt_index_set_vectors: null index");
+    if (vectors && elem_bytes != 4 && elem_bytes != 1)
+        return fail(PQT_EINVAL, "pqt_index_set_vectors: elements are 4-byte floats or 1-byte unsigned integers");
+    if (vectors && location != PQT_HOST && location != PQT_DEVICE)
+        return fail(PQT_EINVAL, "pqt_index_set_vectors: location must be PQT_HOST or PQT_DEVICE");
+    if (vectors && ix->D % (16 / elem_bytes))
+        return fail(PQT_EUNSUPPORTED, "exact re-ranking reads rows in 16-byte pieces: D=%u must be a multiple of %d",
+                    ix->D, 16 / elem_bytes);
+    DeviceGuard guard(ix->device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
+    HIP_TRY(hipDeviceSynchronize());               // no query may still be reading the old vectors
+    (void)hipFree(ix->vectors_owned);
+    ix->vectors_owned = nullptr;
+    ix->vectors = nullptr;
+    ix->vector_elem_bytes = 0;
+    if (!vectors) return PQT_OK;
+    if (location == PQT_HOST) {
+        const size_t bytes = (size_t)ix->N * ix->D * (size_t)elem_bytes;
+        HIP_TRY(hipMalloc(&ix->vectors_owned, bytes ? bytes : 1));
+        if (bytes) HIP_TRY(hipMemcpy(ix->vectors_owned, vectors, bytes, hipMemcpyHostToDevice));
+        ix->vectors = ix->vectors_owned;
+    } else {
+        ix->vectors = vectors;                     // borrowed: the caller keeps it alive
+    }
+    ix->vector_elem_bytes = elem_bytes;
+    return PQT_OK;
+}
+
+int pqt_query_batch_exact(pqt_index* ix, const float* queries, int64_t nq, int k_short, int k, int w,
+                          int64_t* out_ids, float* out_dists, void* hip_stream) {
+    if (!ix) return fail(PQT_EINVAL, "pqt_query_batch_exact: null index");
+    if (!ix->vectors) return fail(PQT_EINVAL, "pqt_query_batch_exact: no database vectors (pqt_index_set_vectors)");
+    if (k < 1 || k > k_short) return fail(PQT_EINVAL, "pqt_query_batch_exact: k=%d outside 1..k_short=%d", k, k_short);
+    if (nq < 0) return fail(PQT_EINVAL, "pqt_query_batch_exact: nq=%lld < 0", (long long)nq);
+    if (nq == 0) return PQT_OK;
+    if (!queries || !out_ids || !out_dists) return fail(PQT_EINVAL, "pqt_query_batch_exact: null buffer");
+    if (k_short > PQT_MAX_K || (uint32_t)k_short > ix->C)
+        return fail(PQT_EINVAL, "pqt_query_batch_exact: k_short=%d outside 1..min(C=%u, %d)", k_short, ix->C, PQT_MAX_K);
+    if (pqt::exact_lds_bytes(ix->D, k_short) > 64 * 1024)
+        return fail(PQT_EUNSUPPORTED, "pqt_query_batch_exact: D=%u with k_short=%d exceeds the LDS budget", ix->D, k_short);
+    DeviceGuard guard(ix->device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
+    const size_t entries = (size_t)nq * (size_t)k_short;
+    if (entries > ix->ws_short_entries) {
+        (void)hipFree(ix->ws_short_ids); (void)hipFree(ix->ws_short_dists);
+        ix->ws_short_ids = nullptr; ix->ws_short_dists = nullptr; ix->ws_short_entries = 0;
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_short_ids), entries * sizeof(int64_t)));
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->ws_short_dists), entries * sizeof(float)));
+        ix->ws_short_entries = entries;
+    }
+    const int rc = pqt_query_batch(ix, queries, nq, k_short, w, ix->ws_short_ids, ix->ws_short_dists, hip_stream);
+    if (rc) return rc;
+    pqt::ExactArgs ea;
+    ea.nq = nq; ea.D = ix->D; ea.k_short = k_short; ea.k = k; ea.elem_bytes = ix->vector_elem_bytes;
+    ea.queries = queries; ea.vectors = ix->vectors; ea.short_ids = ix->ws_short_ids;
+    ea.out_ids = out_ids; ea.out_dists = out_dists;
+    HIP_TRY(pqt::launch_exact_rerank(ea, reinterpret_cast<hipStream_t>(hip_stream)));
+    if (ix->last_events) HIP_TRY(hipEventRecord(ix->last_events[4], reinterpret_cast<hipStream_t>(hip_stream)));
+    return PQT_OK;
+}
+
 int pqt_set_profiling(pqt_index* ix, int enabled) {
     if (!ix) return fail(PQT_EINVAL, "pqt_set_profiling: null index");
     ix->profiling = enabled != 0;
@@ -490,14 +566,14 @@ int pqt_set_profiling(pqt_index* ix, int enabled) {
     return PQT_OK;
 }
 
-int pqt_stage_times(pqt_index* ix, float ms[3], int* calls) {
+int pqt_stage_times(pqt_index* ix, float ms[4], int* calls) {
     if (!ix || !ms || !calls) return fail(PQT_EINVAL, "pqt_stage_times: null argument");
     DeviceGuard guard(ix->device);
-    ms[0] = ms[1] = ms[2] = 0.0f;
+    ms[0] = ms[1] = ms[2] = ms[3] = 0.0f;
     for (int c = 0; c < ix->prof_calls; ++c) {
-        hipEvent_t* ev = &ix->events[4 * c];
-        HIP_TRY(hipEventSynchronize(ev[3]));
-        for (int s = 0; s < 3; ++s) {
+        hipEvent_t* ev = &ix->events[5 * c];
+        HIP_TRY(hipEventSynchronize(ev[4]));
+        for (int s = 0; s < 4; ++s) {
             float t = 0.0f;
             HIP_TRY(hipEventElapsedTime(&t, ev[s], ev[s + 1]));
             ms[s] += t;

@@ -107,6 +107,19 @@ int rerank_fused_tuples_per_thread();
 // fused: the full ranking pass of the queries whose meta.x is kMetaTodo runs inside the kernel
 hipError_t launch_rerank(const RerankArgs& a, const RankArgs* fused, hipStream_t s);
 
+struct ExactArgs {
+    int64_t nq;
+    int D, k_short, k;
+    int elem_bytes;            // 4: fp32 vectors, 1: uint8 vectors
+    const float* queries;      // nq x D
+    const void* vectors;       // N x D, row id = database id
+    const int64_t* short_ids;  // nq x k_short, -1 = no entry
+    int64_t* out_ids;          // nq x k
+    float* out_dists;          // nq x k
+};
+size_t exact_lds_bytes(int D, int k_short);
+hipError_t launch_exact_rerank(const ExactArgs& a, hipStream_t s);
+
 // raise the dynamic-LDS ceiling of each kernel (once per device)
 hipError_t configure_traverse(size_t max_dynamic_lds);
 hipError_t configure_rank(size_t max_dynamic_lds);

@@ -272,6 +272,69 @@ def test_index_from_arrays_matches_index_from_file(pqt, tiny, tmp_path):
     assert e.value.code == pqt.PQT_EFORMAT
 
 
+def _check_exact(pqt, gix, ix, X, Y, k_short, k, w, bit_exact):
+    """pqt_query_batch_exact against the oracle: the short list is the line-quantisation top-k_short
+    (already checked stage by stage elsewhere; taken from the GPU here), its exact re-ranking must be
+    the oracle's on the same list."""
+    import torch
+    yq = torch.from_numpy(np.ascontiguousarray(Y)).cuda()
+    short, _ = pqt.pqt_query_batch(gix, yq, k_short, w)
+    ids, d = pqt.pqt_query_batch_exact(gix, yq, k_short, k, w)
+    ids_all, d_all = pqt.pqt_query_batch_exact(gix, yq, k_short, k_short, w)
+    torch.cuda.synchronize()
+    short, ids, d, ids_all, d_all = (PU.to_np(t) for t in (short, ids, d, ids_all, d_all))
+    for q in range(Y.shape[0]):
+        o_ids, o_d = Q.exact_rerank_short_list(Y[q], X, short[q], k_short)
+        have = o_ids >= 0
+        # every exact distance within tolerance (compare through the id)
+        lookup = dict(zip(o_ids[have].tolist(), o_d[have].tolist()))
+        assert sorted(ids_all[q][ids_all[q] >= 0].tolist()) == sorted(o_ids[have].tolist()), "id set of the short list"
+        got = np.array([lookup[i] for i in ids_all[q][ids_all[q] >= 0].tolist()])
+        gd = d_all[q][ids_all[q] >= 0]
+        assert np.all(np.abs(gd - got) <= PU.RTOL * np.abs(got) + 1e-6), f"query {q}: exact distances"
+        # the order is the order of the GPU's own distances, ties by id; the first k are the k-result call
+        o = np.lexsort((ids_all[q][ids_all[q] >= 0], gd))
+        assert np.array_equal(o, np.arange(o.shape[0])), f"query {q}: not sorted by (distance, id)"
+        assert np.array_equal(ids[q], ids_all[q][:k]) and np.array_equal(d[q], d_all[q][:k])
+        assert np.all(ids_all[q][have.sum():] == -1) and np.all(np.isinf(d_all[q][have.sum():]))
+        if bit_exact:
+            assert np.array_equal(ids_all[q], o_ids) and np.array_equal(d_all[q].astype(np.float64)[have], o_d[have])
+
+
+def test_exact_rerank_of_short_list(pqt, tiny, tmp_path):
+    import torch
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_query_batch_exact(gix, torch.from_numpy(Y).cuda(), 50, 10, cfg.w)
+        assert e.value.code == pqt.PQT_EINVAL                      # no vectors attached yet
+        pqt.pqt_index_set_vectors(gix, X)                          # host array: copied
+        _check_exact(pqt, gix, ix, X, Y[:40], 50, 10, cfg.w, bit_exact=False)
+        _check_exact(pqt, gix, ix, X, Y[:10], 256, 100, cfg.k1, bit_exact=False)     # more than the candidates of some queries
+        Xd = torch.from_numpy(X).cuda()
+        pqt.pqt_index_set_vectors(gix, Xd)                         # device tensor: used in place
+        _check_exact(pqt, gix, ix, X, Y[:10], 64, 64, cfg.w, bit_exact=False)
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_query_batch_exact(gix, torch.from_numpy(Y).cuda(), 10, 20, cfg.w)   # k > k_short
+        assert e.value.code == pqt.PQT_EINVAL
+    finally:
+        pqt.pqt_index_free(gix)
+    # integer data: fp32 and uint8 storage, every operation exact -> equal to the float64 oracle bit for bit
+    ixe, Xe, Ye = _exact_arithmetic_index()
+    path = str(tmp_path / "exact.pqt")
+    IO.write_index(path, ixe)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        for stored in (Xe, Xe.astype(np.uint8)):
+            pqt.pqt_index_set_vectors(gix, stored)
+            _check_exact(pqt, gix, ixe, Xe, Ye[:32], 100, 20, 2, bit_exact=True)
+    finally:
+        pqt.pqt_index_free(gix)
+
+
 def test_four_part_index(pqt, tmp_path):
     """P = 4: parts (1,2) and (3,4) are ranked first, then pairs of positions in those two lists."""
     from workloads import tiny_mixture

@@ -310,3 +310,22 @@ def test_sift_like_numpy_and_torch_agree():
     assert np.array_equal(a, b)
     assert a.min() >= 0 and a.max() <= 255 and np.array_equal(a, np.round(a))
     assert np.array_equal(sift_like(987654 + 100, 50, seed=1), a[100:150])     # counter based: any chunk
+
+
+def test_exact_short_list_rerank_is_brute_force_on_the_list(tiny, rng):
+    """Re-ranking a short list by exact distance = brute force (cdist + sort) restricted to the list;
+    with the whole database as the list it is Eq. 1."""
+    from scipy.spatial.distance import cdist
+    cfg, X, Y, ix = tiny
+    y = Y[3]
+    short = rng.choice(cfg.N, size=200, replace=False)
+    short[10] = -1
+    ids, d = Q.exact_rerank_short_list(y, X, short, 20)
+    keep = short[short >= 0]
+    dd = cdist(y[None].astype(np.float64), X[keep].astype(np.float64), "sqeuclidean")[0]
+    want = sorted(zip(dd.tolist(), keep.tolist()))[:20]
+    assert ids.tolist() == [i for _, i in want]
+    assert np.allclose(d, [v for v, _ in want], rtol=1e-12)
+    ids_all, d_all = Q.exact_rerank_short_list(y, X, np.arange(cfg.N), 10)
+    bf_ids, bf_d = Q.brute_force(y, X, 10)
+    assert np.array_equal(ids_all, bf_ids) and np.array_equal(d_all, bf_d)
