@@ -79,17 +79,17 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
 size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed).total; }
 
 
-constexpr int kHeadT = 64;                     // tuples the head pass can rank
-constexpr int kHeadPairs = 320;                // pairs (a, b) with (a+1)(b+1) <= 64: 280, in blocks of 64
+constexpr int kHeadT = 128;                    // tuples the head pass can rank
+constexpr int kHeadPairs = 704;                // pairs (a, b) with (a+1)(b+1) <= 128: 668, in blocks of 64
 
 // ------------------------------------------------------------------------------------------------
 // Head pass.  Most queries reach the candidate budget C within the first few dozen tuples of the
 // order (the later ones cannot change the result: their runs would start beyond C).  One wavefront
 // per query ranks the first 32 tuples exactly, then -- only if their runs do not fill C -- the first
-// 64; if that is still not enough it marks the query for the full pass.  Keys live in registers: the
-// pairs of the region (a+1)(b+1) <= T1 are taken from a table ordered by that product (so the pairs
-// for a smaller T1 are a prefix), sorted in blocks of 64 across the lanes, and folded into the 64
-// smallest.  No workgroup barrier; LDS only holds the two lists.
+// 64, then the first 128; if that is still not enough it marks the query for the full pass.  Keys
+// live in registers: the pairs of the region (a+1)(b+1) <= T1 are taken from a table ordered by that
+// product (so the pairs for a smaller T1 are a prefix), sorted in blocks of 64 across the lanes, and
+// folded into the T1 smallest.  No workgroup barrier; LDS only holds the two lists.
 // ------------------------------------------------------------------------------------------------
 struct HeadPairTable {
     uint8_t a[kHeadPairs], b[kHeadPairs];
@@ -122,10 +122,102 @@ struct HeadLds {
     uint32_t slot[kHeadT];
 };
 
+constexpr int kHeadLevels = 3;
 struct HeadLevels {
-    int T1[2];      // tuples ranked at each level: min(Tn, 32), min(Tn, 64)
-    int npairs[2];  // pairs of the region for that many tuples (a prefix of the table)
+    int T1[kHeadLevels];      // tuples ranked at each level: min(Tn, 32), min(Tn, 64), min(Tn, 128)
+    int npairs[kHeadLevels];  // pairs of the region for that many tuples (a prefix of the table)
 };
+
+// One level: ranks the first T1 <= 64 * E tuples, probes their slots, and either writes the final run
+// list (returns 1), finds that more tuples are needed (returns 0), or -- on the last level -- lists the
+// query for the full pass (returns 1).
+template <int E>
+__device__ __forceinline__ int head_level(const RankArgs& g, HeadLds& S, int64_t q, int lane, int R1, int T1,
+                                          int npairs, int Tn, bool last_level) {
+    const int T = g.T;
+    const uint32_t C = (uint32_t)g.C;
+    // ---- the T1 smallest keys (ordered sum bits, a, b) of the region, ascending over (register, lane) ----
+    unsigned long long best[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) best[r] = ~0ull;
+    for (int blk = 0; blk * kWave < npairs; ++blk) {
+        const int e = blk * kWave + lane;
+        unsigned long long cur[1] = {~0ull};
+        if (e < npairs) {
+            const unsigned a = kHeadPairTable.a[e], b = kHeadPairTable.b[e];
+            if (a < (unsigned)R1 && b < (unsigned)R1)
+                cur[0] = ((unsigned long long)mono_key(S.A[a] + S.B[b]) << 32) | (a << 16) | b;
+        }
+        wave_sort_chunk<1>(cur, lane, 0u);
+        if (blk == 0) {
+            best[0] = cur[0];
+        } else {
+            // the 64*E smallest of the ascending runs `best` and `cur` (padded with +inf to 64*E keys):
+            // minimum against the reversed padded run gives a bitonic sequence; merge it
+            const uint32_t rhi = (uint32_t)__builtin_amdgcn_ds_bpermute((63 - lane) << 2, (int)(uint32_t)(cur[0] >> 32));
+            const uint32_t rlo = (uint32_t)__builtin_amdgcn_ds_bpermute((63 - lane) << 2, (int)(uint32_t)cur[0]);
+            const unsigned long long y = ((unsigned long long)rhi << 32) | rlo;
+            best[E - 1] = y < best[E - 1] ? y : best[E - 1];
+            wave_merge_chunk<E>(best, lane, 0u, 64u * E);
+        }
+    }
+
+    // ---- probe the first T1 tuples ---------------------------------------------------------------
+    uint32_t o0[E], len[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const int t = r * kWave + lane;
+        o0[r] = 0;
+        len[r] = 0;
+        if (t < T1) {
+            const unsigned r1 = ((unsigned)best[r] >> 16) & 0xffffu, r2 = (unsigned)best[r] & 0xffffu;
+            const unsigned long long lin = (unsigned long long)S.Aid[r1] * g.k1k2 + S.Bid[r2];
+            const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+            o0[r] = g.offsets[slot];
+            len[r] = g.offsets[slot + 1] - o0[r];
+            S.slot[t] = (uint32_t)slot;
+        }
+    }
+    if (g.hashed) {
+        wave_lds_order();
+#pragma unroll
+        for (int r = 0; r < E; ++r) {
+            const int t = r * kWave + lane;
+            if (t < T1) {
+                const uint32_t mine = S.slot[t];
+                for (int u = 0; u < t; ++u)
+                    if (S.slot[u] == mine) len[r] = 0;   // proposed earlier in the order
+            }
+        }
+        wave_lds_order();
+    }
+    uint32_t start[E], total = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const uint32_t incl = wave_inclusive_sum(len[r], lane);
+        start[r] = total + incl - len[r];
+        total += (uint32_t)__shfl((int)incl, kWave - 1, kWave);
+    }
+    if (total < C && T1 < Tn) {                          // not enough yet and more tuples exist
+        if (!last_level) return 0;
+        if (lane == 0) {
+            const uint32_t pos = atomicAdd(&g.counters[0], 1u);
+            g.order[pos] = (uint32_t)q;
+            g.meta[q] = make_uint2(kMetaTodo, pos);          // .y: its place in the list
+        }
+        return 1;
+    }
+    uint32_t nruns = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const bool emit = len[r] > 0 && start[r] < C;
+        const unsigned long long mask = __ballot(emit);
+        if (emit) g.runs[(size_t)q * T + nruns + __popcll(mask & ((1ull << lane) - 1ull))] = make_uint2(o0[r], start[r]);
+        nruns += (uint32_t)__popcll(mask);
+    }
+    if (lane == 0) g.meta[q] = make_uint2(nruns, total < C ? total : C);
+    return 1;
+}
 
 __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g, int Tn, HeadLevels lv) {
     __shared__ HeadLds lds[kRankHeadThreads / kWave];
@@ -133,84 +225,19 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
     const int64_t q = (int64_t)blockIdx.x * (kRankHeadThreads / kWave) + wave;
     if (q >= g.nq) return;
     HeadLds& S = lds[wave];
-    const int R = g.R, T = g.T;
+    const int R = g.R;
     const int R1 = R < kHeadT ? R : kHeadT;
-    const uint32_t C = (uint32_t)g.C;
-
-    if (lane < R1) {
-        S.A[lane] = g.L_d[q * 2 * R + lane];
-        S.Aid[lane] = g.L_id[q * 2 * R + lane];
-        S.B[lane] = g.L_d[q * 2 * R + R + lane];
-        S.Bid[lane] = g.L_id[q * 2 * R + R + lane];
+    for (int e = lane; e < R1; e += kWave) {
+        S.A[e] = g.L_d[q * 2 * R + e];
+        S.Aid[e] = g.L_id[q * 2 * R + e];
+        S.B[e] = g.L_d[q * 2 * R + R + e];
+        S.Bid[e] = g.L_id[q * 2 * R + R + e];
     }
     wave_lds_order();
-
-    for (int level = 0; level < 2; ++level) {
-        const int T1 = lv.T1[level];
-        const int npairs = lv.npairs[level];
-        // ---- the T1 smallest keys (ordered sum bits, a, b) of the region, ascending over the lanes ----
-        unsigned long long best[1] = {~0ull};
-        for (int blk = 0; blk * kWave < npairs; ++blk) {
-            const int e = blk * kWave + lane;
-            unsigned long long cur[1] = {~0ull};
-            if (e < npairs) {
-                const unsigned a = kHeadPairTable.a[e], b = kHeadPairTable.b[e];
-                if (a < (unsigned)R1 && b < (unsigned)R1)
-                    cur[0] = ((unsigned long long)mono_key(S.A[a] + S.B[b]) << 32) | (a << 16) | b;
-            }
-            wave_sort_chunk<1>(cur, lane, 0u);
-            if (blk == 0) {
-                best[0] = cur[0];
-            } else {
-                // the 64 smallest of two ascending runs x, y: min(x[i], y[63-i]) is bitonic; merge it
-                const uint32_t rhi = (uint32_t)__builtin_amdgcn_ds_bpermute((63 - lane) << 2, (int)(uint32_t)(cur[0] >> 32));
-                const uint32_t rlo = (uint32_t)__builtin_amdgcn_ds_bpermute((63 - lane) << 2, (int)(uint32_t)cur[0]);
-                const unsigned long long y = ((unsigned long long)rhi << 32) | rlo;
-                best[0] = y < best[0] ? y : best[0];
-                wave_merge_chunk<1>(best, lane, 0u, 64u);
-            }
-        }
-
-        // ---- probe the first T1 tuples ---------------------------------------------------------------
-        uint32_t o0 = 0, len = 0;
-        if (lane < T1) {
-            const unsigned r1 = ((unsigned)best[0] >> 16) & 0xffffu, r2 = (unsigned)best[0] & 0xffffu;
-            const unsigned long long lin = (unsigned long long)S.Aid[r1] * g.k1k2 + S.Bid[r2];
-            const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
-            o0 = g.offsets[slot];
-            len = g.offsets[slot + 1] - o0;
-            S.slot[lane] = (uint32_t)slot;
-        }
-        if (g.hashed) {
-            wave_lds_order();
-            if (lane < T1) {
-                const uint32_t mine = S.slot[lane];
-                for (int t = 0; t < lane; ++t)
-                    if (S.slot[t] == mine) len = 0;      // proposed earlier in the order
-            }
-            wave_lds_order();
-        }
-        const uint32_t incl_len = wave_inclusive_sum(len, lane);
-        const uint32_t start = incl_len - len;
-        const uint32_t total = __shfl(incl_len, kWave - 1, kWave);
-        if (total < C && T1 < Tn) {                      // not enough yet and more tuples exist
-            if (level == 0 && lv.T1[1] > T1) continue;   // rank twice as many
-            if (lane == 0) {
-                const uint32_t pos = atomicAdd(&g.counters[0], 1u);
-                g.order[pos] = (uint32_t)q;
-                g.meta[q] = make_uint2(kMetaTodo, pos);      // .y: its place in the list
-            }
-            return;
-        }
-        const bool emit = len > 0 && start < C;
-        const unsigned long long mask = __ballot(emit);
-        if (emit) {
-            const int idx = __popcll(mask & ((1ull << lane) - 1ull));
-            g.runs[(size_t)q * T + idx] = make_uint2(o0, start);
-        }
-        if (lane == 0) g.meta[q] = make_uint2((uint32_t)__popcll(mask), total < C ? total : C);
-        return;
-    }
+    // levels whose tuple count does not grow are skipped (T smaller than 64 or 128)
+    if (head_level<1>(g, S, q, lane, R1, lv.T1[0], lv.npairs[0], Tn, lv.T1[1] == lv.T1[0])) return;
+    if (head_level<1>(g, S, q, lane, R1, lv.T1[1], lv.npairs[1], Tn, lv.T1[2] == lv.T1[1])) return;
+    head_level<2>(g, S, q, lane, R1, lv.T1[2], lv.npairs[2], Tn, true);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -254,10 +281,11 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
     if (head) {
         constexpr int per = kRankHeadThreads / kWave;
         HeadLevels lv;
-        lv.T1[0] = o.Tcap < kHeadT / 2 ? o.Tcap : kHeadT / 2;
-        lv.T1[1] = o.Tcap < kHeadT ? o.Tcap : kHeadT;
-        lv.npairs[0] = head_pair_count(lv.T1[0]);
-        lv.npairs[1] = head_pair_count(lv.T1[1]);
+        for (int l = 0; l < kHeadLevels; ++l) {
+            const int t = kHeadT >> (kHeadLevels - 1 - l);          // 32, 64, 128
+            lv.T1[l] = o.Tcap < t ? o.Tcap : t;
+            lv.npairs[l] = head_pair_count(lv.T1[l]);
+        }
         hipLaunchKernelGGL(rank_head_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kRankHeadThreads), 0, s, a,
                            o.Tcap, lv);
         hipError_t e = hipGetLastError();
