@@ -156,6 +156,9 @@ def main():
                          "vectors stay in HBM, one byte per element for the integer-valued workloads)")
     ap.add_argument("--batch", type=int, default=None,
                     help="queries per library call (default: all of them in one call); 1 gives a latency figure")
+    ap.add_argument("--also-batches", default="", metavar="B1,B2,..",
+                    help="after the main measurement, answer the same queries B per call for each listed B "
+                         "(queued back to back, and one call at a time for the latency)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline", action="store_true",
                     help="also for the 100M / 1B workloads (writes the index to a file for the oracle's processes)")
@@ -333,6 +336,32 @@ def main():
                                               max_procs=4 if cfg.N > 200_000_000 else 16)
     else:
         result["cpu_baseline"] = None
+    extra = []
+    for Bx in [int(v) for v in args.also_batches.split(",") if v]:
+        ncall = -(-cfg.nq // Bx)
+        reps = max(1, min(args.steps, 20000 // ncall))
+
+        def run_all():
+            for o in range(0, cfg.nq, Bx):
+                pqt.pqt_query_batch(index, Y[o:o + Bx], cfg.k, w, out_ids[o:o + Bx], out_d[o:o + Bx])
+        run_all()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run_all()
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        nlat = min(ncall, 200)
+        t1 = time.perf_counter()
+        for c in range(nlat):
+            o = c * Bx
+            pqt.pqt_query_batch(index, Y[o:o + Bx], cfg.k, w, out_ids[o:o + Bx], out_d[o:o + Bx])
+            torch.cuda.synchronize()
+        lat = (time.perf_counter() - t1) / nlat
+        extra.append({"queries_per_call": Bx, "queries_per_s": cfg.nq * reps / el,
+                      "us_per_call_queued": el / reps / ncall * 1e6, "latency_us_per_call": lat * 1e6})
+    if extra:
+        result["batches"] = extra
     if args.exact:
         # exact re-ranking of the first K_SHORT results (the paper's PQT_2): HBM-bound gather of raw rows
         ks = args.exact

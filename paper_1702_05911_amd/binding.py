@@ -109,6 +109,7 @@ class Index:
         else:
             self._from_arrays(arrays, int(device))
         self.device = torch.device("cuda", int(device))
+        self._D = self.info()["D"]
 
     def _from_arrays(self, a, device):
         """pqt_index_from_arrays.  `a`: mapping with the header fields, the small arrays as NumPy
@@ -173,9 +174,8 @@ class Index:
 
     def query_batch(self, queries, k, w, out_ids=None, out_dists=None, stream=None):
         """pqt_query_batch.  queries: (nq, D) float32 CUDA tensor.  Returns (ids int64, dists float32)."""
-        info_d = self.info()["D"]
-        if queries.dim() == 2 and queries.shape[1] != info_d:
-            raise ValueError(f"queries have dimension {queries.shape[1]}, index has D={info_d}")
+        if queries.dim() == 2 and queries.shape[1] != self._D:
+            raise ValueError(f"queries have dimension {queries.shape[1]}, index has D={self._D}")
         nq, ids_, dists_ = self._buffers(queries, k)
         out_ids = ids_ if out_ids is None else out_ids
         out_dists = dists_ if out_dists is None else out_dists

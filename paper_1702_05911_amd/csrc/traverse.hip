@@ -75,6 +75,7 @@ __device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, 
             row[r] = C2t + ((size_t)p * k1 + i) * nd4 * k2 + j;
             acc[r] = 0.0f;
         }
+#pragma unroll 4
         for (int d4 = 0; d4 < nd4; ++d4) {
             const float4 y = yp[d4];
 #pragma unroll
