@@ -203,25 +203,22 @@ def main():
             print(f"[bench] built {start + Xc.shape[0]:,} of {cfg.N:,} vectors "
                   f"({time.perf_counter() - t_setup:.0f} s)", file=sys.stderr, flush=True)
 
-    arrays = builder.build_arrays(chunks=chunks, N=cfg.N, D=cfg.D, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M,
-                                  H=cfg.H, T=cfg.T, C=cfg.C, train_n=cfg.train_n, device=dev,
-                                  chunk_rows=(1 << 20) if in_hbm_only else (1 << 18), observer=observe)
-    runs = torch.diff(arrays["offsets"])
+    # the library's own streaming builder (pqt_builder_*): codebooks trained here on a sample, every
+    # vector binned and encoded by HIP kernels, lists assembled on the GPU
+    index = builder.build_index_native(chunks=chunks, N=cfg.N, D=cfg.D, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M,
+                                       H=cfg.H, T=cfg.T, C=cfg.C, train_n=cfg.train_n, device=0,
+                                       chunk_rows=(1 << 20) if in_hbm_only else (1 << 18), observer=observe)
+    runs = torch.diff(pqt.pqt_index_export(index, ("offsets",))["offsets"])
     occupancy = {"nonempty_slots": int((runs > 0).sum()), "max_run": int(runs.max()),
                  "mean_run_nonempty": float(runs[runs > 0].float().mean())}
+    del runs
     tmp = tempfile.mkdtemp(prefix="pqt_bench_")
     path = os.path.join(tmp, f"{cfg.name}.pqt")
     if in_hbm_only and not args.cpu_baseline:
-        index = pqt.pqt_index_from_arrays(arrays, 0)           # straight from the builder's device arrays
         path = None
     else:
-        host = dict(arrays)
-        for name, dt in (("offsets", np.uint32), ("ids", np.uint32), ("codes", np.uint8)):
-            host[name] = arrays[name].cpu().numpy().astype(dt)
-        builder.write_index_file(path, host, host)
-        del host
-        index = pqt.pqt_index_load(path, 0)
-    del arrays, X
+        pqt.pqt_index_save(index, path)        # the oracle's processes read the same index from this file
+    del X
     torch.cuda.empty_cache()
     gt = gt.best_i
     setup_s = time.perf_counter() - t_setup

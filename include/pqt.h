@@ -99,6 +99,49 @@ typedef struct pqt_index_arrays {
 } pqt_index_arrays;
 int pqt_index_from_arrays(const pqt_index_arrays* arrays, int location, int device, pqt_index** out);
 
+/*
+ * Streaming index construction on the GPU -- the per-vector part of the offline phase
+ * (Sec. 3.1: every database vector is sorted into its bin by the tree; Sec. 3.3 "Offline
+ * computation": its line-quantisation code; Sec. 4: ids sorted by bin, pointer array from a
+ * histogram and a prefix sum).  The codebooks and the line-code table are trained by the
+ * caller (a few Lloyd iterations on a sample) and passed in `params`, whose N is the number
+ * of vectors that will be added and whose offsets / ids / codes are ignored.
+ *   pqt_builder_create  copies the codebooks to GPU `device`.
+ *   pqt_builder_add     takes n more vectors (device, n x D row-major fp32; they get the next
+ *                       n ids), sorts them into bins with the query path's own traversal
+ *                       kernel and encodes them; asynchronous on hip_stream.  Any number of
+ *                       calls; the total must be N.
+ *   pqt_builder_finish  orders the ids by (slot, id), builds the pointer array, permutes the
+ *                       codes, and returns the finished index (released with
+ *                       pqt_index_free); the builder is then empty and only needs
+ *                       pqt_builder_free.  Synchronises the device.
+ * A code byte is the nearest of the 256 code points of its sub-part, with distances from
+ * Eq. 9 on the vector's own level-1 distances (fp32); ties go to the smaller code value.
+ * Errors: PQT_EINVAL (null, N = 0, more or fewer than N vectors), PQT_EFORMAT /
+ * PQT_EUNSUPPORTED as for pqt_index_from_arrays, PQT_ENOMEM, PQT_EHIP.
+ */
+typedef struct pqt_builder pqt_builder;
+int  pqt_builder_create(const pqt_index_arrays* params, int device, pqt_builder** out);
+int  pqt_builder_add(pqt_builder* builder, const float* vectors, int64_t n, void* hip_stream);
+int  pqt_builder_finish(pqt_builder* builder, pqt_index** out);
+void pqt_builder_free(pqt_builder* builder);
+
+/*
+ * pqt_index_export -- copy the index arrays out.  dst names caller-owned buffers of the sizes
+ * pqt_index_info reports (shapes as for pqt_index_from_arrays; the scalar fields of dst are
+ * ignored); a NULL pointer skips that array.  C1 .. cc are host buffers; offsets, ids and
+ * codes are host buffers when location == PQT_HOST, device buffers on the index's GPU when
+ * location == PQT_DEVICE.  Synchronous.  Errors: PQT_EINVAL, PQT_EHIP.
+ */
+int pqt_index_export(const pqt_index* index, const pqt_index_arrays* dst, int location);
+
+/*
+ * pqt_index_save -- write the index to a file in the format pqt_index_load reads (the
+ * device arrays are copied back through host memory).  Errors: PQT_EINVAL, PQT_EIO,
+ * PQT_ENOMEM, PQT_EHIP.
+ */
+int pqt_index_save(const pqt_index* index, const char* path);
+
 /* Releases the index, its device arrays and its workspace.  NULL is allowed. */
 void pqt_index_free(pqt_index* index);
 

@@ -16,7 +16,8 @@ PQT_OK = 0
 PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -2, -3, -4, -5, -6
 
 EXPORTS = (
-    "pqt_index_load", "pqt_index_from_arrays", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
+    "pqt_index_load", "pqt_index_from_arrays", "pqt_index_save", "pqt_index_export", "pqt_builder_create", "pqt_builder_add",
+    "pqt_builder_finish", "pqt_builder_free", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
     "pqt_query_batch_debug", "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
 )
 
@@ -62,6 +63,18 @@ def load_library(path=LIB_PATH):
     lib.pqt_index_load.restype = ci
     lib.pqt_index_from_arrays.argtypes = [ctypes.POINTER(_Arrays), ci, ci, ctypes.POINTER(vp)]
     lib.pqt_index_from_arrays.restype = ci
+    lib.pqt_index_export.argtypes = [vp, ctypes.POINTER(_Arrays), ci]
+    lib.pqt_index_export.restype = ci
+    lib.pqt_index_save.argtypes = [vp, ctypes.c_char_p]
+    lib.pqt_index_save.restype = ci
+    lib.pqt_builder_create.argtypes = [ctypes.POINTER(_Arrays), ci, ctypes.POINTER(vp)]
+    lib.pqt_builder_create.restype = ci
+    lib.pqt_builder_add.argtypes = [vp, vp, i64, vp]
+    lib.pqt_builder_add.restype = ci
+    lib.pqt_builder_finish.argtypes = [vp, ctypes.POINTER(vp)]
+    lib.pqt_builder_finish.restype = ci
+    lib.pqt_builder_free.argtypes = [vp]
+    lib.pqt_builder_free.restype = None
     lib.pqt_index_free.argtypes = [vp]
     lib.pqt_index_free.restype = None
     lib.pqt_index_info.argtypes = [vp, ctypes.POINTER(_Info)]
@@ -102,9 +115,11 @@ def _stream_handle(stream):
 class Index:
     """Handle of an index resident on one GPU (pqt_index_load / pqt_index_free)."""
 
-    def __init__(self, path=None, device=0, arrays=None):
+    def __init__(self, path=None, device=0, arrays=None, handle=None):
         self._h = ctypes.c_void_p()
-        if arrays is None:
+        if handle is not None:
+            self._h = handle                       # an index the library already made (pqt_builder_finish)
+        elif arrays is None:
             _check(_lib.pqt_index_load(os.fsencode(path), int(device), ctypes.byref(self._h)))
         else:
             self._from_arrays(arrays, int(device))
@@ -116,9 +131,7 @@ class Index:
         arrays, and offsets / ids / codes either all NumPy arrays (host) or all CUDA tensors on
         `device` (int32 or int64 values below 2**32 are narrowed to the ABI's uint32 here)."""
         import numpy as np
-        small = {"C1": np.float32, "C2": np.float32, "tbl_i": np.uint8, "tbl_j": np.uint8,
-                 "tbl_lam": np.float32, "cc": np.float32}
-        keep = [np.ascontiguousarray(a[n], dtype=dt) for n, dt in small.items()]
+        keep = _small_arrays(a)
         on_device = torch.is_tensor(a["offsets"])
         big = []
         for n, width in (("offsets", 4), ("ids", 4), ("codes", 1)):
@@ -155,6 +168,20 @@ class Index:
 
     def __exit__(self, *exc):
         self.close()
+
+    def export(self, names=("offsets",)):
+        """pqt_index_export of the large arrays named (offsets, ids, codes) into new CUDA tensors
+        (int32 views of the uint32 data for offsets and ids)."""
+        inf = self.info()
+        shapes = {"offsets": ((inf["H"] + 1,), torch.int32), "ids": ((inf["N"],), torch.int32),
+                  "codes": ((inf["N"], inf["M"]), torch.uint8)}
+        bufs = {n: torch.empty(shapes[n][0], dtype=shapes[n][1], device=self.device) for n in names}
+        ca = _Arrays(**{n: bufs[n].data_ptr() for n in names})
+        _check(_lib.pqt_index_export(self._h, ctypes.byref(ca), PQT_DEVICE))
+        return bufs
+
+    def save(self, path):
+        _check(_lib.pqt_index_save(self._h, os.fsencode(path)))
 
     def info(self):
         out = _Info()
@@ -251,6 +278,47 @@ class Index:
         return [float(v) for v in ms], int(calls.value)
 
 
+def _small_arrays(a):
+    import numpy as np
+    small = {"C1": np.float32, "C2": np.float32, "tbl_i": np.uint8, "tbl_j": np.uint8,
+             "tbl_lam": np.float32, "cc": np.float32}
+    return [np.ascontiguousarray(a[n], dtype=dt) for n, dt in small.items()]
+
+
+class Builder:
+    """pqt_builder_create / add / finish / free: streams database vectors (CUDA tensors) into an index."""
+
+    def __init__(self, params, device=0):
+        keep = _small_arrays(params)
+        ca = _Arrays(N=int(params["N"]), H=int(params["H"]), D=int(params["D"]), P=int(params["P"]),
+                     k1=int(params["k1"]), k2=int(params["k2"]), M=int(params["M"]), T=int(params["T"]),
+                     C=int(params["C"]), C1=keep[0].ctypes.data, C2=keep[1].ctypes.data,
+                     tbl_i=keep[2].ctypes.data, tbl_j=keep[3].ctypes.data, tbl_lambda=keep[4].ctypes.data,
+                     cc=keep[5].ctypes.data, offsets=None, ids=None, codes=None)
+        self._h = ctypes.c_void_p()
+        self._device = int(device)
+        self._D = int(params["D"])
+        _check(_lib.pqt_builder_create(ctypes.byref(ca), self._device, ctypes.byref(self._h)))
+
+    def add(self, vectors, stream=None):
+        if vectors.dtype != torch.float32 or not vectors.is_cuda or not vectors.is_contiguous() or \
+                vectors.dim() != 2 or vectors.shape[1] != self._D:
+            raise ValueError(f"vectors must be a contiguous (n, {self._D}) float32 CUDA tensor")
+        _check(_lib.pqt_builder_add(self._h, vectors.data_ptr(), vectors.shape[0], _stream_handle(stream)))
+
+    def finish(self):
+        h = ctypes.c_void_p()
+        _check(_lib.pqt_builder_finish(self._h, ctypes.byref(h)))
+        return Index(device=self._device, handle=h)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            _lib.pqt_builder_free(self._h)
+            self._h = ctypes.c_void_p()
+
+    __del__ = close
+
+
 def last_error():
     return _lib.pqt_last_error().decode("utf-8", "replace")
 
@@ -262,6 +330,30 @@ def pqt_index_load(path, device=0):
 
 def pqt_index_from_arrays(arrays, device=0):
     return Index(device=device, arrays=arrays)
+
+
+def pqt_index_export(index, names=("offsets",)):
+    return index.export(names)
+
+
+def pqt_index_save(index, path):
+    index.save(path)
+
+
+def pqt_builder_create(params, device=0):
+    return Builder(params, device)
+
+
+def pqt_builder_add(builder, vectors, stream=None):
+    builder.add(vectors, stream)
+
+
+def pqt_builder_finish(builder):
+    return builder.finish()
+
+
+def pqt_builder_free(builder):
+    builder.close()
 
 
 def pqt_index_free(index):

@@ -238,6 +238,42 @@ def build_arrays(X=None, *, chunks=None, N=None, D=None, P, k1, k2, M, H=None, T
                 offsets=offsets, ids=order, codes=codes)
 
 
+def train(Xt, *, P, k1, k2, M, iters=20, table_train_n=100_000):
+    """Everything that is learned from a sample: the two-level codebooks, the line-code table and the
+    centroid-pair distances.  Returns NumPy arrays named as the index arrays."""
+    C1, C2 = train_tree(Xt, P, k1, k2, iters)
+    ti, tj, tl = line_table(Xt[:table_train_n], C1, M)
+    return dict(C1=C1.cpu().numpy(), C2=C2.cpu().numpy(), tbl_i=ti, tbl_j=tj, tbl_lam=tl, cc=pair_table(C1, M))
+
+
+def build_index_native(*, chunks, N, D, P, k1, k2, M, H=None, T=1024, C=4096, train_n=None, iters=20,
+                       device=0, chunk_rows=1 << 20, table_train_n=100_000, observer=None):
+    """The same index built by the library's own streaming builder (pqt_builder_*): codebooks and
+    table are trained here on the first train_n vectors, every vector is then binned and encoded by
+    HIP kernels and the lists are assembled on the GPU.  Returns the binding's Index."""
+    from . import binding
+    dev = torch.device("cuda", device)
+    H = (k1 * k2) ** P if H is None else H
+    train_n = min(train_n or N, N)
+    Xt = torch.as_tensor(chunks(0, train_n)).to(device=dev, dtype=torch.float32)
+    params = train(Xt, P=P, k1=k1, k2=k2, M=M, iters=iters, table_train_n=table_train_n)
+    del Xt
+    params.update(N=N, H=H, D=D, P=P, k1=k1, k2=k2, M=M, T=T, C=C)
+    b = binding.pqt_builder_create(params, device)
+    try:
+        for s in range(0, N, chunk_rows):
+            n = min(chunk_rows, N - s)
+            Xc = torch.as_tensor(chunks(s, n)).to(device=dev, dtype=torch.float32).contiguous()
+            binding.pqt_builder_add(b, Xc)
+            if observer is not None:
+                observer(s, Xc)
+            torch.cuda.synchronize(dev)                             # Xc must outlive the kernels that read it
+            del Xc
+        return binding.pqt_builder_finish(b)
+    finally:
+        binding.pqt_builder_free(b)
+
+
 def build_index(path, X=None, **kw):
     """build_arrays(...) written to the index file `path`; returns the arrays as NumPy arrays."""
     arrays = build_arrays(X, **kw)

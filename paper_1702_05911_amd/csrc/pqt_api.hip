@@ -12,39 +12,29 @@
 #include <string>
 #include <vector>
 
-#include "../../include/pqt.h"
-#include "pqt_kernels.hpp"
+#include "pqt_index.hpp"
 
-namespace {
+namespace pqt_host {
 
-thread_local char g_err[512] = "";
+char* error_buffer() {
+    static thread_local char buf[512] = "";
+    return buf;
+}
 
 int fail(int code, const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
-    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    vsnprintf(error_buffer(), 512, fmt, ap);
     va_end(ap);
     return code;
 }
 
-#define HIP_TRY(expr)                                                                          \
-    do {                                                                                       \
-        hipError_t e_ = (expr);                                                                \
-        if (e_ != hipSuccess)                                                                  \
-            return fail(e_ == hipErrorOutOfMemory ? PQT_ENOMEM : PQT_EHIP, "%s: %s", #expr,    \
-                        hipGetErrorString(e_));                                                \
-    } while (0)
+}  // namespace pqt_host
 
-struct DeviceGuard {   // make the index's GPU current for the duration of a call
-    int prev = -1;
-    bool ok = false;
-    explicit DeviceGuard(int dev) {
-        if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true;
-    }
-    ~DeviceGuard() {
-        if (prev >= 0) (void)hipSetDevice(prev);
-    }
-};
+using pqt_host::DeviceGuard;
+using pqt_host::fail;
+
+namespace {
 
 constexpr int kMaxProfiledCalls = 256;
 
@@ -54,52 +44,6 @@ size_t g_lds_limit = 64 * 1024;
 
 }  // namespace
 
-struct pqt_index {
-    uint32_t D = 0, P = 0, k1 = 0, k2 = 0, M = 0, T = 0, C = 0;
-    uint64_t N = 0, H = 0;
-    int device = 0;
-    bool hashed = false;
-    // index arrays (device)
-    float* C1 = nullptr;
-    float* c1n = nullptr;
-    float* C2 = nullptr;
-    float* C2t = nullptr;   // children of a cluster interleaved four dimensions at a time (dp % 4 == 0)
-    pqt::CodeEntry* table = nullptr;
-    uint32_t* offsets = nullptr;
-    uint32_t* ids = nullptr;
-    uint8_t* codes = nullptr;
-    uint64_t bytes_index = 0;
-    // raw database vectors for exact re-ranking (optional)
-    const void* vectors = nullptr;
-    void* vectors_owned = nullptr;      // set when the library holds its own copy
-    int vector_elem_bytes = 0;
-    int64_t* ws_short_ids = nullptr;    // nq x k_short results of the line-quantisation re-ranking
-    float* ws_short_dists = nullptr;
-    size_t ws_short_entries = 0;
-    // workspace (device), sized for ws_nq queries at ws_R list entries and ws_T tuples
-    int64_t ws_nq = 0;
-    int ws_R = 0, ws_T = 0;
-    float* ws_a = nullptr;
-    float* ws_Ld = nullptr;
-    uint32_t* ws_Lid = nullptr;
-    uint2* ws_runs = nullptr;
-    uint2* ws_meta = nullptr;
-    uint32_t* ws_counters = nullptr;   // 2 words
-    uint32_t* ws_order = nullptr;      // nq words
-    uint64_t bytes_workspace = 0;
-    // stage timing
-    bool profiling = false;
-    int prof_calls = 0;
-    std::vector<hipEvent_t> events;   // 5 per profiled call
-    hipEvent_t* last_events = nullptr;  // events of the most recent profiled call (for the exact re-rank stage)
-
-    void free_workspace() {
-        (void)hipFree(ws_a); (void)hipFree(ws_Ld); (void)hipFree(ws_Lid);
-        (void)hipFree(ws_runs); (void)hipFree(ws_meta); (void)hipFree(ws_counters); (void)hipFree(ws_order);
-        ws_a = ws_Ld = nullptr; ws_Lid = nullptr; ws_runs = ws_meta = nullptr; ws_counters = ws_order = nullptr;
-        ws_nq = 0; bytes_workspace = 0;
-    }
-};
 
 namespace {
 
@@ -174,7 +118,9 @@ int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
     return PQT_OK;
 }
 
-int ensure_workspace(pqt_index* ix, int64_t nq, int R) {
+}  // namespace
+
+int pqt_host::ensure_workspace(pqt_index* ix, int64_t nq, int R) {
     if (nq <= ix->ws_nq && R <= ix->ws_R && (int)ix->T <= ix->ws_T) return PQT_OK;
     ix->free_workspace();
     const int64_t n = nq > ix->ws_nq ? nq : ix->ws_nq;
@@ -196,11 +142,9 @@ int ensure_workspace(pqt_index* ix, int64_t nq, int R) {
     return PQT_OK;
 }
 
-}  // namespace
-
 extern "C" {
 
-const char* pqt_last_error(void) { return g_err; }
+const char* pqt_last_error(void) { return pqt_host::error_buffer(); }
 
 int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, pqt_index** out) {
     if (!a || !out) return fail(PQT_EINVAL, "pqt_index_from_arrays: null argument");
@@ -302,6 +246,17 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     ix->D = h.D; ix->P = h.P; ix->k1 = h.k1; ix->k2 = h.k2; ix->M = h.M; ix->T = h.T; ix->C = h.C;
     ix->N = h.N; ix->H = h.H; ix->device = device;
     ix->hashed = (long double)h.H != K;
+    try {
+        ix->h_C1.assign(h.C1, h.C1 + (size_t)h.P * h.k1 * dp);
+        ix->h_C2.assign(h.C2, h.C2 + (size_t)h.P * h.k1 * h.k2 * dp);
+        ix->h_ti.assign(h.tbl_i, h.tbl_i + ntab);
+        ix->h_tj.assign(h.tbl_j, h.tbl_j + ntab);
+        ix->h_lam.assign(h.tbl_lambda, h.tbl_lambda + ntab);
+        ix->h_cc.assign(h.cc, h.cc + (size_t)h.M * h.k1 * h.k1);
+    } catch (const std::bad_alloc&) {
+        delete ix;
+        return fail(PQT_ENOMEM, "host allocation failed");
+    }
     const hipMemcpyKind big = location == PQT_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
     int rc = PQT_OK;
     if ((rc = upload(&ix->C1, h.C1, (size_t)h.P * h.k1 * dp * 4, hipMemcpyHostToDevice, &ix->bytes_index)) ||
@@ -370,10 +325,80 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
     a.cc = cc.data(); a.offsets = offsets.data(); a.ids = ids.data(); a.codes = codes.data();
     const int rc = pqt_index_from_arrays(&a, PQT_HOST, device, out);
     if (rc != PQT_OK) {
-        char msg[sizeof(g_err)];
-        snprintf(msg, sizeof(msg), "%s", g_err);
+        char msg[512];
+        snprintf(msg, sizeof(msg), "%s", pqt_host::error_buffer());
         return fail(rc, "'%s': %.400s", path, msg);
     }
+    return PQT_OK;
+}
+
+int pqt_index_save(const pqt_index* ix, const char* path) {
+    if (!ix || !path) return fail(PQT_EINVAL, "pqt_index_save: null argument");
+    DeviceGuard guard(ix->device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
+    std::unique_ptr<FILE, FileCloser> f(fopen(path, "wb"));
+    if (!f) return fail(PQT_EIO, "cannot create '%s'", path);
+    unsigned char hdr[kAlign] = {0};
+    FileHeader h;
+    memset(&h, 0, sizeof(h));
+    memcpy(h.magic, "PQTIDX1\0", 8);
+    h.version = 1; h.D = ix->D; h.P = ix->P; h.k1 = ix->k1; h.k2 = ix->k2; h.M = ix->M;
+    h.N = ix->N; h.H = ix->H; h.T = ix->T; h.C = ix->C; h.offset_bits = 32;
+    memcpy(hdr, &h, sizeof(h));
+    bool ok = fwrite(hdr, 1, kAlign, f.get()) == kAlign;
+    auto put = [&](const void* src, size_t bytes) {
+        static const unsigned char zeros[kAlign] = {0};
+        const long pos = ftell(f.get());
+        const size_t pad = (kAlign - (size_t)pos % kAlign) % kAlign;
+        ok = ok && pos >= 0 && (pad == 0 || fwrite(zeros, 1, pad, f.get()) == pad) &&
+             (bytes == 0 || fwrite(src, 1, bytes, f.get()) == bytes);
+    };
+    put(ix->h_C1.data(), ix->h_C1.size() * 4);
+    put(ix->h_C2.data(), ix->h_C2.size() * 4);
+    put(ix->h_ti.data(), ix->h_ti.size());
+    put(ix->h_tj.data(), ix->h_tj.size());
+    put(ix->h_lam.data(), ix->h_lam.size() * 4);
+    put(ix->h_cc.data(), ix->h_cc.size() * 4);
+    // the large arrays come back from the GPU in pieces of at most 256 MiB
+    std::vector<unsigned char> stage;
+    try {
+        stage.resize(256u << 20);
+    } catch (const std::bad_alloc&) {
+        return fail(PQT_ENOMEM, "host allocation failed");
+    }
+    auto put_device = [&](const void* dev, size_t bytes) -> int {
+        put(nullptr, 0);
+        for (size_t o = 0; o < bytes && ok; o += stage.size()) {
+            const size_t n = bytes - o < stage.size() ? bytes - o : stage.size();
+            HIP_TRY(hipMemcpy(stage.data(), static_cast<const unsigned char*>(dev) + o, n, hipMemcpyDeviceToHost));
+            ok = fwrite(stage.data(), 1, n, f.get()) == n;
+        }
+        return PQT_OK;
+    };
+    int rc;
+    if ((rc = put_device(ix->offsets, ((size_t)ix->H + 1) * 4)) || (rc = put_device(ix->ids, (size_t)ix->N * 4)) ||
+        (rc = put_device(ix->codes, (size_t)ix->N * ix->M)))
+        return rc;
+    if (!ok || fflush(f.get()) != 0) return fail(PQT_EIO, "write to '%s' failed", path);
+    return PQT_OK;
+}
+
+int pqt_index_export(const pqt_index* ix, const pqt_index_arrays* dst, int location) {
+    if (!ix || !dst) return fail(PQT_EINVAL, "pqt_index_export: null argument");
+    if (location != PQT_HOST && location != PQT_DEVICE)
+        return fail(PQT_EINVAL, "pqt_index_export: location must be PQT_HOST or PQT_DEVICE");
+    DeviceGuard guard(ix->device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
+    if (dst->C1) memcpy(const_cast<float*>(dst->C1), ix->h_C1.data(), ix->h_C1.size() * 4);
+    if (dst->C2) memcpy(const_cast<float*>(dst->C2), ix->h_C2.data(), ix->h_C2.size() * 4);
+    if (dst->tbl_i) memcpy(const_cast<uint8_t*>(dst->tbl_i), ix->h_ti.data(), ix->h_ti.size());
+    if (dst->tbl_j) memcpy(const_cast<uint8_t*>(dst->tbl_j), ix->h_tj.data(), ix->h_tj.size());
+    if (dst->tbl_lambda) memcpy(const_cast<float*>(dst->tbl_lambda), ix->h_lam.data(), ix->h_lam.size() * 4);
+    if (dst->cc) memcpy(const_cast<float*>(dst->cc), ix->h_cc.data(), ix->h_cc.size() * 4);
+    const hipMemcpyKind kind = location == PQT_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+    if (dst->offsets) HIP_TRY(hipMemcpy(const_cast<uint32_t*>(dst->offsets), ix->offsets, ((size_t)ix->H + 1) * 4, kind));
+    if (dst->ids && ix->N) HIP_TRY(hipMemcpy(const_cast<uint32_t*>(dst->ids), ix->ids, (size_t)ix->N * 4, kind));
+    if (dst->codes && ix->N) HIP_TRY(hipMemcpy(const_cast<uint8_t*>(dst->codes), ix->codes, (size_t)ix->N * ix->M, kind));
     return PQT_OK;
 }
 
@@ -423,7 +448,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     DeviceGuard guard(ix->device);
     if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
     const int R = w * (int)ix->k2;
-    if ((rc = ensure_workspace(ix, nq, R))) return rc;
+    if ((rc = pqt_host::ensure_workspace(ix, nq, R))) return rc;
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
     static const pqt_debug_taps no_taps = {};
     const pqt_debug_taps& tp = taps ? *taps : no_taps;

@@ -335,6 +335,59 @@ def test_exact_rerank_of_short_list(pqt, tiny, tmp_path):
         pqt.pqt_index_free(gix)
 
 
+def test_native_builder(pqt, tiny, tmp_path):
+    """pqt_builder_*: vectors streamed in ragged chunks; the saved index satisfies the oracle's
+    definitions (bin of every vector, nearest code point, sorted lists) and answers queries exactly as
+    the oracle does on that index."""
+    import torch
+    cfg, X, Y, ix = tiny
+    params = dict(N=cfg.N, H=ix.H, D=ix.D, P=ix.P, k1=ix.k1, k2=ix.k2, M=ix.M, T=ix.T, C=ix.C,
+                  C1=ix.C1, C2=ix.C2, tbl_i=ix.tbl_i, tbl_j=ix.tbl_j, tbl_lam=ix.tbl_lam, cc=ix.cc)
+    Xd = torch.from_numpy(X).cuda()
+    b = pqt.pqt_builder_create(params, 0)
+    try:
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_builder_finish(b)                              # nothing added yet
+        assert e.value.code == pqt.PQT_EINVAL
+        for lo, hi in ((0, 1), (1, 4097), (4097, 4097), (4097, cfg.N)):
+            pqt.pqt_builder_add(b, Xd[lo:hi].contiguous())
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_builder_add(b, Xd[:1].contiguous())            # more than N
+        assert e.value.code == pqt.PQT_EINVAL
+        gix = pqt.pqt_builder_finish(b)
+    finally:
+        pqt.pqt_builder_free(b)
+    path = str(tmp_path / "native.pqt")
+    try:
+        pqt.pqt_index_save(gix, path)
+    finally:
+        pqt.pqt_index_free(gix)
+    nix = IO.read_index(path)
+    off = nix.offsets.astype(np.int64)
+    assert off[0] == 0 and off[-1] == cfg.N and np.all(np.diff(off) >= 0)
+    assert np.array_equal(np.sort(nix.ids), np.arange(cfg.N, dtype=np.uint32))
+    for name in ("C1", "C2", "tbl_i", "tbl_j", "tbl_lam", "cc"):
+        assert np.array_equal(getattr(nix, name), getattr(ix, name)), name
+    slot_of = np.repeat(np.arange(nix.H), np.diff(off))
+    want_slots = B.bin_slots_batch(X, nix.C1, nix.C2, nix.H)
+    assert np.mean(slot_of != want_slots[nix.ids]) <= 2e-3       # fp32 vs float64 near-ties only
+    for s in np.nonzero(np.diff(off) > 1)[0][:200]:
+        assert np.all(np.diff(nix.ids[off[s]:off[s + 1]].astype(np.int64)) > 0)   # ids ascend inside a slot
+    # codes: the chosen code point is (within fp32 rounding) as near as the nearest one
+    ds = nix.D // nix.M
+    worst = 0.0
+    for t in np.random.default_rng(3).integers(0, cfg.N, size=300):
+        x = X[nix.ids[t]].astype(np.float64)
+        for m in range(nix.M):
+            pts = B.code_points(B.subpart_centroids(nix.C1, nix.M, m), nix.tbl_i[m], nix.tbl_j[m], nix.tbl_lam[m])
+            d = np.sum((pts - x[m * ds:(m + 1) * ds][None]) ** 2, axis=1)
+            worst = max(worst, d[nix.codes[t, m]] - d.min())
+    assert worst <= 1e-4
+    # the index is input data: full stage-wise parity on it
+    same, _ = _stagewise(pqt, nix, path, Y[:30], cfg.k, cfg.w, cfg.T, cfg.C)
+    assert same >= 27
+
+
 def test_four_part_index(pqt, tmp_path):
     """P = 4: parts (1,2) and (3,4) are ranked first, then pairs of positions in those two lists."""
     from workloads import tiny_mixture

@@ -53,6 +53,12 @@ CONFIGS = {
     # SIFT1B-shaped (Sec. 5.1, Fig. 6)
     "billion": WorkloadConfig("billion", "sift", N=1_000_000_000, D=128, nq=10_000, P=2, k1=64, k2=16,
                               M=8, H=(64 * 16) ** 2, T=1024, C=10_000, k=100, w=8, train_n=1_000_000),
+    # the tree the paper itself uses at this scale (Sec. 5.1): four parts, bin numbers hashed by a plain
+    # modulus to a prime number of slots near N/10 (collisions share a list)
+    "large4": WorkloadConfig("large4", "sift", N=100_000_000, D=128, nq=10_000, P=4, k1=32, k2=16, M=8,
+                             H=10_000_019, T=1024, C=10_000, k=100, w=8, train_n=1_000_000),
+    "billion4": WorkloadConfig("billion4", "sift", N=1_000_000_000, D=128, nq=10_000, P=4, k1=32, k2=16,
+                               M=8, H=100_000_007, T=1024, C=10_000, k=100, w=8, train_n=1_000_000),
 }
 
 
