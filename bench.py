@@ -154,6 +154,9 @@ def main():
     ap.add_argument("--exact", type=int, default=0, metavar="K_SHORT",
                     help="also time pqt_query_batch_exact: exact re-ranking of the first K_SHORT results (the raw "
                          "vectors stay in HBM, one byte per element for the integer-valued workloads)")
+    ap.add_argument("--brute-force", action="store_true",
+                    help="also time pqt_brute_force (exact k nearest neighbours on the matrix cores, the paper's strong "
+                         "baseline) on the same queries")
     ap.add_argument("--batch", type=int, default=None,
                     help="queries per library call (default: all of them in one call); 1 gives a latency figure")
     ap.add_argument("--also-batches", default="", metavar="B1,B2,..",
@@ -193,7 +196,7 @@ def main():
     gt = ExactNN(Y[:n_gt])
 
     raw_dtype = torch.uint8 if cfg.kind == "sift" else torch.float32
-    raw = torch.empty((cfg.N, cfg.D), dtype=raw_dtype, device=dev) if args.exact else None
+    raw = torch.empty((cfg.N, cfg.D), dtype=raw_dtype, device=dev) if (args.exact or args.brute_force) else None
 
     def observe(start, Xc):
         gt.update(start, Xc)
@@ -383,6 +386,25 @@ def main():
                            "roofline": {"kernel": "exact_rerank_kernel", "bound": "hbm",
                                         "achieved": ebytes / (ems[3] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                                         "unit": "GB/s", "frac": ebytes / (ems[3] * 1e-3) / 1e9 / HBM_PEAK_GBS}}
+    if args.brute_force:
+        pqt.pqt_index_set_vectors(index, raw)
+        bf_ids, bf_d = pqt.pqt_brute_force(index, Y, cfg.k)          # warm-up: workspace and database norms
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(1, min(args.steps, 3))
+        e0.record()
+        for _ in range(reps):
+            pqt.pqt_brute_force(index, Y, cfg.k, bf_ids, bf_d)
+        e1.record()
+        torch.cuda.synchronize()
+        bf_ms = e0.elapsed_time(e1) / reps
+        flops = 2.0 * cfg.nq * cfg.N * cfg.D
+        result["brute_force"] = {"k": cfg.k, "value": cfg.nq / (bf_ms * 1e-3), "unit": "queries/s", "ms_per_step": bf_ms,
+                                 "agrees_with_ground_truth": float((bf_ids[:n_gt, 0] == gt).float().mean()),
+                                 "roofline": {"kernel": "bf_distance_kernel", "bound": "mfma",
+                                              "achieved": flops / (bf_ms * 1e-3) / 1e12, "peak": MFMA_FP32_PEAK_TFLOPS,
+                                              "unit": "TFLOP/s", "frac": flops / (bf_ms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS,
+                                              "note": "whole call (distance and selection kernels)"}}
     pqt.pqt_index_free(index)
     print(json.dumps(result))
 

@@ -202,6 +202,18 @@ int pqt_query_batch_exact(pqt_index* index, const float* queries, int64_t nq, in
                           int64_t* out_ids, float* out_dists, void* hip_stream);
 
 /*
+ * pqt_brute_force -- Eq. 1 itself: the k exact nearest database vectors of every query, by
+ * brute force over the attached vectors (pqt_index_set_vectors); the paper's "strong baseline"
+ * (Table 1) and the ground truth for recall.  Distances are ||q||^2 + ||x||^2 - 2 q.x in fp32
+ * (exact for integer-valued data with norms below 2^24); results ascend by (distance, id).
+ *   queries device nq x D fp32; out_ids device nq x k int64; out_dists device nq x k fp32;
+ *   1 <= k <= min(N, 256).  Asynchronous on hip_stream except for workspace growth.
+ * Errors: PQT_EINVAL (no vectors attached, k or nq out of range, null), PQT_ENOMEM, PQT_EHIP.
+ */
+int pqt_brute_force(pqt_index* index, const float* queries, int64_t nq, int k,
+                    int64_t* out_ids, float* out_dists, void* hip_stream);
+
+/*
  * Optional device buffers that receive every intermediate of the path, for checking it
  * stage by stage.  Any pointer may be NULL (that tap is skipped).  Shapes are per batch:
  *   a          nq x M x k1   fp32   level-1 sub-part distances (Eq. 6 per sub-part)

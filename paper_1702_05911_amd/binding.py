@@ -18,7 +18,7 @@ PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -
 EXPORTS = (
     "pqt_index_load", "pqt_index_from_arrays", "pqt_index_save", "pqt_index_export", "pqt_builder_create", "pqt_builder_add",
     "pqt_builder_finish", "pqt_builder_free", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
-    "pqt_query_batch_debug", "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
+    "pqt_query_batch_debug", "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_brute_force", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
 )
 
 
@@ -89,6 +89,8 @@ def load_library(path=LIB_PATH):
     lib.pqt_index_set_vectors.restype = ci
     lib.pqt_query_batch_exact.argtypes = [vp, vp, i64, ci, ci, ci, vp, vp, vp]
     lib.pqt_query_batch_exact.restype = ci
+    lib.pqt_brute_force.argtypes = [vp, vp, i64, ci, vp, vp, vp]
+    lib.pqt_brute_force.restype = ci
     lib.pqt_set_profiling.argtypes = [vp, ci]
     lib.pqt_set_profiling.restype = ci
     lib.pqt_stage_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4), ctypes.POINTER(ci)]
@@ -267,6 +269,15 @@ class Index:
                                           out_ids.data_ptr(), out_dists.data_ptr(), _stream_handle(stream)))
         return out_ids, out_dists
 
+    def brute_force(self, queries, k, out_ids=None, out_dists=None, stream=None):
+        """pqt_brute_force.  Returns (ids int64, exact squared distances float32)."""
+        nq, ids_, dists_ = self._buffers(queries, k)
+        out_ids = ids_ if out_ids is None else out_ids
+        out_dists = dists_ if out_dists is None else out_dists
+        _check(_lib.pqt_brute_force(self._h, queries.data_ptr(), nq, int(k), out_ids.data_ptr(),
+                                    out_dists.data_ptr(), _stream_handle(stream)))
+        return out_ids, out_dists
+
     def set_profiling(self, enabled):
         _check(_lib.pqt_set_profiling(self._h, 1 if enabled else 0))
 
@@ -382,6 +393,10 @@ def pqt_index_set_vectors(index, vectors):
 
 def pqt_query_batch_exact(index, queries, k_short, k, w, out_ids=None, out_dists=None, stream=None):
     return index.query_batch_exact(queries, k_short, k, w, out_ids, out_dists, stream)
+
+
+def pqt_brute_force(index, queries, k, out_ids=None, out_dists=None, stream=None):
+    return index.brute_force(queries, k, out_ids, out_dists, stream)
 
 
 def pqt_set_profiling(index, enabled):

@@ -406,6 +406,7 @@ void pqt_index_free(pqt_index* ix) {
     if (!ix) return;
     DeviceGuard guard(ix->device);
     (void)hipFree(ix->vectors_owned); (void)hipFree(ix->ws_short_ids); (void)hipFree(ix->ws_short_dists);
+    (void)hipFree(ix->vector_norms); (void)hipFree(ix->bf_qnorm); (void)hipFree(ix->bf_dist); (void)hipFree(ix->bf_best);
     (void)hipFree(ix->C1); (void)hipFree(ix->c1n); (void)hipFree(ix->C2); (void)hipFree(ix->C2t); (void)hipFree(ix->table);
     (void)hipFree(ix->offsets); (void)hipFree(ix->ids); (void)hipFree(ix->codes);
     ix->free_workspace();
@@ -535,6 +536,8 @@ int pqt_index_set_vectors(pqt_index* ix, const void* vectors, int elem_bytes, in
     if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
     HIP_TRY(hipDeviceSynchronize());               // no query may still be reading the old vectors
     (void)hipFree(ix->vectors_owned);
+    (void)hipFree(ix->vector_norms);
+    ix->vector_norms = nullptr;
     ix->vectors_owned = nullptr;
     ix->vectors = nullptr;
     ix->vector_elem_bytes = 0;
@@ -581,6 +584,47 @@ int pqt_query_batch_exact(pqt_index* ix, const float* queries, int64_t nq, int k
     ea.out_ids = out_ids; ea.out_dists = out_dists;
     HIP_TRY(pqt::launch_exact_rerank(ea, reinterpret_cast<hipStream_t>(hip_stream)));
     if (ix->last_events) HIP_TRY(hipEventRecord(ix->last_events[4], reinterpret_cast<hipStream_t>(hip_stream)));
+    return PQT_OK;
+}
+
+int pqt_brute_force(pqt_index* ix, const float* queries, int64_t nq, int k, int64_t* out_ids, float* out_dists,
+                    void* hip_stream) {
+    if (!ix) return fail(PQT_EINVAL, "pqt_brute_force: null index");
+    if (!ix->vectors) return fail(PQT_EINVAL, "pqt_brute_force: no database vectors (pqt_index_set_vectors)");
+    if (k < 1 || k > 256 || (uint64_t)k > ix->N) return fail(PQT_EINVAL, "pqt_brute_force: k=%d outside 1..min(N, 256)", k);
+    if (nq < 0) return fail(PQT_EINVAL, "pqt_brute_force: nq=%lld < 0", (long long)nq);
+    if (nq == 0) return PQT_OK;
+    if (!queries || !out_ids || !out_dists) return fail(PQT_EINVAL, "pqt_brute_force: null buffer");
+    DeviceGuard guard(ix->device);
+    if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
+    hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+    if (!ix->vector_norms) {
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->vector_norms), sizeof(float) * ix->N));
+        HIP_TRY(pqt::launch_row_norms(ix->vectors, ix->vector_elem_bytes, (int64_t)ix->N, (int)ix->D, ix->vector_norms, stream));
+    }
+    // distance block: at most 2^30 floats (4 GiB), at most 65536 database vectors per pass
+    int64_t chunk = (int64_t)(1ll << 30) / nq;
+    if (chunk > 65536) chunk = 65536;
+    if (chunk > (int64_t)ix->N) chunk = (int64_t)ix->N;
+    chunk = chunk / 128 * 128;
+    if (chunk < 128) chunk = 128;
+    if (nq > ix->bf_nq || chunk > ix->bf_chunk || k > ix->bf_k) {
+        (void)hipFree(ix->bf_qnorm); (void)hipFree(ix->bf_dist); (void)hipFree(ix->bf_best);
+        ix->bf_qnorm = nullptr; ix->bf_dist = nullptr; ix->bf_best = nullptr; ix->bf_nq = 0;
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->bf_qnorm), sizeof(float) * (size_t)nq));
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->bf_dist), sizeof(float) * (size_t)nq * (size_t)chunk));
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->bf_best), sizeof(unsigned long long) * (size_t)nq * (size_t)k));
+        ix->bf_nq = nq; ix->bf_chunk = chunk; ix->bf_k = k;
+    }
+    HIP_TRY(pqt::launch_row_norms(queries, 4, nq, (int)ix->D, ix->bf_qnorm, stream));
+    pqt::BruteArgs ba;
+    ba.nq = nq; ba.D = ix->D; ba.k = k; ba.elem_bytes = ix->vector_elem_bytes; ba.chunk = chunk;
+    ba.queries = queries; ba.vectors = ix->vectors; ba.qnorm = ix->bf_qnorm; ba.xnorm = ix->vector_norms;
+    ba.dist = ix->bf_dist; ba.best = ix->bf_best; ba.out_ids = out_ids; ba.out_dists = out_dists;
+    for (int64_t x0 = 0; x0 < (int64_t)ix->N; x0 += chunk) {
+        const int64_t nx = (int64_t)ix->N - x0 < chunk ? (int64_t)ix->N - x0 : chunk;
+        HIP_TRY(pqt::launch_brute_chunk(ba, x0, nx, x0 == 0, x0 + nx >= (int64_t)ix->N, stream));
+    }
     return PQT_OK;
 }
 

@@ -60,6 +60,12 @@ struct pqt_index {
     const void* vectors = nullptr;
     void* vectors_owned = nullptr;      // set when the library holds its own copy
     int vector_elem_bytes = 0;
+    float* vector_norms = nullptr;      // squared norms of the attached vectors (made on first brute-force call)
+    float* bf_qnorm = nullptr;          // brute-force workspace: query norms, distance block, running best
+    float* bf_dist = nullptr;
+    unsigned long long* bf_best = nullptr;
+    int64_t bf_nq = 0, bf_chunk = 0;
+    int bf_k = 0;
     int64_t* ws_short_ids = nullptr;    // nq x k_short results of the line-quantisation re-ranking
     float* ws_short_dists = nullptr;
     size_t ws_short_entries = 0;

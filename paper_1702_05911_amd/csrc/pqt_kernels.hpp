@@ -120,6 +120,25 @@ struct ExactArgs {
 size_t exact_lds_bytes(int D, int k_short);
 hipError_t launch_exact_rerank(const ExactArgs& a, hipStream_t s);
 
+struct BruteArgs {
+    int64_t nq;
+    int D, k;
+    int elem_bytes;               // 4: fp32 vectors, 1: uint8 vectors
+    int64_t chunk;                // database vectors per pass = row stride of dist
+    const float* queries;         // nq x D
+    const void* vectors;          // N x D
+    const float* qnorm;           // nq
+    const float* xnorm;           // N
+    float* dist;                  // nq x chunk
+    unsigned long long* best;     // nq x k running result between passes
+    int64_t* out_ids;             // nq x k
+    float* out_dists;             // nq x k
+};
+hipError_t launch_row_norms(const void* x, int elem_bytes, int64_t n, int D, float* out, hipStream_t s);
+size_t brute_select_lds_bytes(int k);
+// distances of all queries to database vectors x0 .. x0+nx-1, then the running k best
+hipError_t launch_brute_chunk(const BruteArgs& a, int64_t x0, int64_t nx, bool first, bool last, hipStream_t s);
+
 // raise the dynamic-LDS ceiling of each kernel (once per device)
 hipError_t configure_traverse(size_t max_dynamic_lds);
 hipError_t configure_rank(size_t max_dynamic_lds);

@@ -388,6 +388,61 @@ def test_native_builder(pqt, tiny, tmp_path):
     assert same >= 27
 
 
+def test_brute_force(pqt, tiny, tmp_path):
+    """pqt_brute_force against Eq. 1 written out (the oracle's brute_force): integer data bit for bit
+    (fp32 and byte storage, several passes over the database, ragged last pass and tile), real-valued
+    data within tolerance with the order replayed on the GPU's own distances."""
+    import torch
+    ixe, Xe, Ye = _exact_arithmetic_index(N=20000, seed=31)
+    path = str(tmp_path / "exact.pqt")
+    IO.write_index(path, ixe)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        yq = torch.from_numpy(Ye).cuda()
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_brute_force(gix, yq, 10)
+        assert e.value.code == pqt.PQT_EINVAL                      # no vectors attached
+        for stored in (Xe, Xe.astype(np.uint8)):
+            pqt.pqt_index_set_vectors(gix, stored)
+            for k in (1, 10, 100):
+                ids, d = pqt.pqt_brute_force(gix, yq, k)
+                torch.cuda.synchronize()
+                ids, d = PU.to_np(ids), PU.to_np(d)
+                for q in range(0, Ye.shape[0], 7):
+                    o_ids, o_d = Q.brute_force(Ye[q], Xe, k)
+                    assert np.array_equal(ids[q], o_ids), f"k={k} query {q}"
+                    assert np.array_equal(d[q].astype(np.float64), o_d)
+    finally:
+        pqt.pqt_index_free(gix)
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        pqt.pqt_index_set_vectors(gix, X)
+        yq = torch.from_numpy(Y).cuda()
+        ids, d = pqt.pqt_brute_force(gix, yq, 20)
+        ids1, d1 = pqt.pqt_brute_force(gix, yq[:3].contiguous(), 1)
+        torch.cuda.synchronize()
+        ids, d = PU.to_np(ids), PU.to_np(d)
+        assert np.array_equal(PU.to_np(ids1)[:, 0], ids[:3, 0])
+        same = 0
+        for q in range(cfg.nq):
+            o_ids, o_d = Q.brute_force(Y[q], X, 21)
+            y64 = Y[q].astype(np.float64)
+            xx = np.sum(X[ids[q]].astype(np.float64) ** 2, axis=1)
+            exact = np.sum((X[ids[q]].astype(np.float64) - y64[None]) ** 2, axis=1)
+            assert np.all(np.abs(d[q] - exact) <= PU.RTOL * exact + PU.ATOL_SCALE * (np.dot(y64, y64) + xx)), f"query {q}"
+            assert np.array_equal(np.lexsort((ids[q], d[q])), np.arange(20)), "not sorted by (distance, id)"
+            gaps = np.diff(o_d) / np.maximum(o_d[1:], 1e-30)
+            if np.all(gaps > 1e-4):                                 # no near-ties among the first 21: ids must agree
+                assert np.array_equal(ids[q], o_ids[:20]), f"query {q}"
+                same += 1
+        assert same >= 0.5 * cfg.nq
+    finally:
+        pqt.pqt_index_free(gix)
+
+
 def test_four_part_index(pqt, tmp_path):
     """P = 4: parts (1,2) and (3,4) are ranked first, then pairs of positions in those two lists."""
     from workloads import tiny_mixture
