@@ -159,6 +159,9 @@ def main():
                          "baseline) on the same queries")
     ap.add_argument("--batch", type=int, default=None,
                     help="queries per library call (default: all of them in one call); 1 gives a latency figure")
+    ap.add_argument("--sweep-w", default="", metavar="W1,W2,..",
+                    help="after the main measurement, queries/s and recall for each listed w")
+    ap.add_argument("--M", type=int, default=None, help="code bytes per vector (default: the workload's)")
     ap.add_argument("--also-batches", default="", metavar="B1,B2,..",
                     help="after the main measurement, answer the same queries B per call for each listed B "
                          "(queued back to back, and one call at a time for the latency)")
@@ -187,6 +190,8 @@ def main():
         cfg = cfg.with_(T=args.T)
     if args.C:
         cfg = cfg.with_(C=args.C)
+    if args.M:
+        cfg = cfg.with_(M=args.M)
     w = args.w or cfg.w
     dev = torch.device("cuda", 0)
     t_setup = time.perf_counter()
@@ -208,7 +213,8 @@ def main():
 
     # the library's own streaming builder (pqt_builder_*): codebooks trained here on a sample, every
     # vector binned and encoded by HIP kernels, lists assembled on the GPU
-    index = builder.build_index_native(chunks=chunks, N=cfg.N, D=cfg.D, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M,
+    result_tables = {}
+    index = builder.build_index_native(trained_out=result_tables, chunks=chunks, N=cfg.N, D=cfg.D, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M,
                                        H=cfg.H, T=cfg.T, C=cfg.C, train_n=cfg.train_n, device=0,
                                        chunk_rows=(1 << 20) if in_hbm_only else (1 << 18), observer=observe)
     runs = torch.diff(pqt.pqt_index_export(index, ("offsets",))["offsets"])
@@ -299,8 +305,12 @@ def main():
          "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "note": "includes the full bin ranking of the queries the head pass leaves over (two tree parts)"},
     ]
+    hbm_meas, mfma_meas = pqt.pqt_measure_peaks(0)       # streaming read of 4 GiB; loop of independent MFMAs
     for s in stages:
         s["frac"] = s["achieved"] / s["peak"]
+        meas = {"hbm": hbm_meas, "mfma": mfma_meas}.get(s["bound"])
+        if meas:
+            s["frac_of_measured_peak"] = s["achieved"] / meas
     # LDS look-ups of the re-rank scoring (M per candidate) against the LDS rate of the chip:
     # 256 CUs x 32 banks x 4 bytes x 2.4 GHz = 78.6 TB/s, i.e. 19.7 T look-ups/s without bank conflicts
     stages[2]["lds_lookups_per_s"] = nq * mean_cand * cfg.M / (stage_ms[2] * 1e-3)
@@ -319,6 +329,8 @@ def main():
                                f"M={cfg.M} H={cfg.H} w={w} T={cfg.T} C={cfg.C} k={cfg.k}",
                    "queries_per_call": B, "mean_candidates": mean_cand, "mean_runs": mean_runs, **occupancy},
         "recall": rec, "stage_ms": stage_ms, "stages": stages, "roofline": roofline, "setup_s": setup_s,
+        "measured_peaks": {"hbm_read_GBs": hbm_meas, "mfma_f32_TFLOPs": mfma_meas,
+                           "how": "pqt_measure_peaks: 4 GiB streaming read; loop of independent v_mfma_f32_16x16x4_f32"},
     }
     if B != cfg.nq:
         result["us_per_call"] = elapsed / args.steps / (-(-cfg.nq // B)) * 1e6     # calls queued back to back
@@ -336,6 +348,43 @@ def main():
                                               max_procs=4 if cfg.N > 200_000_000 else 16)
     else:
         result["cpu_baseline"] = None
+    sweep = []
+    for wx in [int(v) for v in args.sweep_w.split(",") if v]:
+        pqt.pqt_query_batch(index, Y, cfg.k, wx, out_ids, out_d)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            pqt.pqt_query_batch(index, Y, cfg.k, wx, out_ids, out_d)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        sweep.append({"w": wx, "queries_per_s": cfg.nq * args.steps / el, "ms_per_step": el / args.steps * 1e3,
+                      "recall": recall_at(out_ids[:n_gt], gt)})
+    if sweep:
+        result["w_sweep"] = sweep
+        pqt.pqt_query_batch(index, Y, cfg.k, w, out_ids, out_d)
+        torch.cuda.synchronize()
+    if args.M or args.sweep_w:
+        # mean squared error of the stored codes against the vectors they stand for (Table 3's distortion):
+        # reconstruction per Sec. 3.3 from the exported codes, on the first 100,000 database ids
+        ex = pqt.pqt_index_export(index, ("ids", "codes"))
+        ids_e = ex["ids"].to(torch.int64) & 0xFFFFFFFF
+        pick = torch.nonzero(ids_e < 100_000).flatten()
+        codes_e = ex["codes"][pick].to(torch.int64)
+        Xs = chunks(0, min(100_000, cfg.N))[ids_e[pick]]
+        tr = result_tables
+        ds_ = cfg.D // cfg.M
+        err = torch.zeros((), device=dev, dtype=torch.float64)
+        for m in range(cfg.M):
+            p_, lo_ = (m * ds_) // (cfg.D // cfg.P), (m * ds_) % (cfg.D // cfg.P)
+            cen = torch.from_numpy(tr["C1"][p_][:, lo_:lo_ + ds_]).to(dev)
+            ti_ = torch.from_numpy(tr["tbl_i"][m].astype(np.int64)).to(dev)
+            tj_ = torch.from_numpy(tr["tbl_j"][m].astype(np.int64)).to(dev)
+            lam_ = torch.from_numpy(tr["tbl_lam"][m]).to(dev)[:, None]
+            pts = (1.0 - lam_) * cen[ti_] + lam_ * cen[tj_]
+            diff = Xs[:, m * ds_:(m + 1) * ds_] - pts[codes_e[:, m]]
+            err += (diff.double() ** 2).sum()
+        result["distortion"] = {"mean_squared_error": float(err / pick.numel()), "vectors": int(pick.numel()), "M": cfg.M}
+        del ex
     extra = []
     for Bx in [int(v) for v in args.also_batches.split(",") if v]:
         ncall = -(-cfg.nq // Bx)

@@ -263,6 +263,15 @@ int pqt_query_batch_debug(pqt_index* index, const float* queries, int64_t nq, in
 int pqt_set_profiling(pqt_index* index, int enabled);
 int pqt_stage_times(pqt_index* index, float ms[4], int* calls);
 
+/*
+ * pqt_measure_peaks -- what GPU `device` delivers, measured: the read bandwidth of a 4 GiB
+ * streaming read (GB/s) and the rate of a loop of independent fp32 matrix-core instructions
+ * (TFLOP/s).  The benchmark prices the query kernels against these as well as against the
+ * published peaks.  Takes about a second; allocates and frees 4 GiB.  Errors: PQT_EINVAL,
+ * PQT_ENOMEM, PQT_EHIP.
+ */
+int pqt_measure_peaks(int device, double* hbm_read_gb_per_s, double* mfma_f32_tflop_per_s);
+
 /* Message of the last failing call on this thread ("" if none).  Static storage. */
 const char* pqt_last_error(void);
 

@@ -18,7 +18,7 @@ PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -
 EXPORTS = (
     "pqt_index_load", "pqt_index_from_arrays", "pqt_index_save", "pqt_index_export", "pqt_builder_create", "pqt_builder_add",
     "pqt_builder_finish", "pqt_builder_free", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
-    "pqt_query_batch_debug", "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_brute_force", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
+    "pqt_query_batch_debug", "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_brute_force", "pqt_measure_peaks", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
 )
 
 
@@ -91,6 +91,8 @@ def load_library(path=LIB_PATH):
     lib.pqt_query_batch_exact.restype = ci
     lib.pqt_brute_force.argtypes = [vp, vp, i64, ci, vp, vp, vp]
     lib.pqt_brute_force.restype = ci
+    lib.pqt_measure_peaks.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.pqt_measure_peaks.restype = ci
     lib.pqt_set_profiling.argtypes = [vp, ci]
     lib.pqt_set_profiling.restype = ci
     lib.pqt_stage_times.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 4), ctypes.POINTER(ci)]
@@ -328,6 +330,13 @@ class Builder:
             self._h = ctypes.c_void_p()
 
     __del__ = close
+
+
+def pqt_measure_peaks(device=0):
+    """(HBM read GB/s, fp32 MFMA TFLOP/s) measured on the device."""
+    bw, fl = ctypes.c_double(), ctypes.c_double()
+    _check(_lib.pqt_measure_peaks(int(device), ctypes.byref(bw), ctypes.byref(fl)))
+    return bw.value, fl.value
 
 
 def last_error():

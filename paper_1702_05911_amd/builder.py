@@ -247,7 +247,7 @@ def train(Xt, *, P, k1, k2, M, iters=20, table_train_n=100_000):
 
 
 def build_index_native(*, chunks, N, D, P, k1, k2, M, H=None, T=1024, C=4096, train_n=None, iters=20,
-                       device=0, chunk_rows=1 << 20, table_train_n=100_000, observer=None):
+                       device=0, chunk_rows=1 << 20, table_train_n=100_000, observer=None, trained_out=None):
     """The same index built by the library's own streaming builder (pqt_builder_*): codebooks and
     table are trained here on the first train_n vectors, every vector is then binned and encoded by
     HIP kernels and the lists are assembled on the GPU.  Returns the binding's Index."""
@@ -258,6 +258,8 @@ def build_index_native(*, chunks, N, D, P, k1, k2, M, H=None, T=1024, C=4096, tr
     Xt = torch.as_tensor(chunks(0, train_n)).to(device=dev, dtype=torch.float32)
     params = train(Xt, P=P, k1=k1, k2=k2, M=M, iters=iters, table_train_n=table_train_n)
     del Xt
+    if trained_out is not None:
+        trained_out.update(params)                                  # the caller wants the codebooks and table too
     params.update(N=N, H=H, D=D, P=P, k1=k1, k2=k2, M=M, T=T, C=C)
     b = binding.pqt_builder_create(params, device)
     try:

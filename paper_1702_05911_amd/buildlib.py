@@ -3,7 +3,7 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ("pqt_api.hip", "traverse.hip", "rank_bins.hip", "rerank.hip", "exact_rerank.hip", "builder.hip", "brute_force.hip")
+SOURCES = ("pqt_api.hip", "traverse.hip", "rank_bins.hip", "rerank.hip", "exact_rerank.hip", "builder.hip", "brute_force.hip", "peaks.hip")
 OUTPUT = os.path.join(HERE, "libpqt.so")
 
 
