@@ -107,7 +107,7 @@ bool can_fuse_ranking(const pqt_index* ix, int k, int w) {
 int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
     const int R = w * (int)ix->k2;
     const size_t l1 = pqt::traverse_lds_bytes(ix->D, ix->P, ix->k1, ix->k2, ix->M, w);
-    const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed);
+    const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed ? 1 : 2);   // 2: room for the slots tap
     const int threads = rerank_threads(ix);
     const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0);
     if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)

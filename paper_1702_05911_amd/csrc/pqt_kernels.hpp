@@ -63,7 +63,7 @@ constexpr uint32_t kMetaTodo = 0xffffffffu;
 struct RankOffsets {   // LDS layout of the full ranking pass (computed once on the host)
     int Tcap, cap, npair, nreg, nreg_pair, Tmid, nreg_mid;
     int force;             // 1: rank every query (taps wanted, or no head pass ran)
-    uint32_t keys, hist, Ld, Lid, ps, pt, len, o0, slot, part, misc;
+    uint32_t keys, hist, Ld, Lid, ps, pt, len, slot, part, misc;
     uint32_t total;        // bytes
 };
 // number of (r1, r2) pairs that can be among the first T of an R x R sum table

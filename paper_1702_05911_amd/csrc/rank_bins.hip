@@ -34,12 +34,12 @@ struct RankLds {
     int nreg_pair;   // P = 4: region size of each pair ranking
     int Tmid;    // P = 2: tuples ranked in the first attempt (most queries need far fewer than Tcap)
     int nreg_mid;    // region size for Tmid
-    size_t off_keys, off_hist, off_Ld, off_Lid, off_ps, off_pt, off_len, off_o0, off_slot, off_part,
+    size_t off_keys, off_hist, off_Ld, off_Lid, off_ps, off_pt, off_len, off_slot, off_part,
         off_misc, total;
 };
 
+// hashed: slots may repeat (their lengths and numbers go through LDS); 2: the slots tap also wants the numbers
 static RankLds rank_layout(int P, int R, int T, int hashed) {
-    (void)hashed;                      // the de-duplication keys reuse the sort buffer
     RankLds L;
     long total_tuples = 1;
     for (int p = 0; p < P; ++p) total_tuples = (total_tuples * R > (1L << 40)) ? (1L << 40) : total_tuples * R;
@@ -67,9 +67,8 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     L.off_Lid = o;   o += sizeof(uint32_t) * P * R;
     L.off_ps = o;    o += sizeof(float) * 2 * L.npair;        // summed distances of the two pair lists
     L.off_pt = o;    o += sizeof(uint32_t) * 2 * L.npair;     // their rank pairs (r << 16 | r')
-    L.off_len = o;   o += sizeof(uint32_t) * L.Tcap;
-    L.off_o0 = o;    o += sizeof(uint32_t) * L.Tcap;
-    L.off_slot = o;  o += sizeof(uint32_t) * L.Tcap;
+    L.off_len = o;   o += hashed == 1 ? sizeof(uint32_t) * L.Tcap : 0;
+    L.off_slot = o;  o += hashed ? sizeof(uint32_t) * L.Tcap : 0;
     L.off_part = o;  o += sizeof(uint32_t) * 32;               // two prefix sums x up to 16 wavefronts
     L.off_misc = o;  o += sizeof(uint32_t) * 16;
     L.total = o;
@@ -261,7 +260,7 @@ RankOffsets rank_offsets(int P, int R, int T, int hashed) {
     o.force = 0;
     o.keys = (uint32_t)L.off_keys; o.hist = (uint32_t)L.off_hist;
     o.Ld = (uint32_t)L.off_Ld; o.Lid = (uint32_t)L.off_Lid; o.ps = (uint32_t)L.off_ps; o.pt = (uint32_t)L.off_pt;
-    o.len = (uint32_t)L.off_len; o.o0 = (uint32_t)L.off_o0; o.slot = (uint32_t)L.off_slot;
+    o.len = (uint32_t)L.off_len; o.slot = (uint32_t)L.off_slot;
     o.part = (uint32_t)L.off_part; o.misc = (uint32_t)L.off_misc;
     o.total = (uint32_t)L.total;
     return o;
@@ -274,7 +273,7 @@ bool rank_has_head(const RankArgs& a) {
 
 hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
     if (a.nq <= 0) return hipSuccess;
-    RankOffsets o = rank_offsets(a.P, a.R, a.T, a.hashed);
+    RankOffsets o = rank_offsets(a.P, a.R, a.T, a.hashed ? 1 : (a.slots ? 2 : 0));
     const bool head = rank_has_head(a);
     if (defer_full && !head) return hipErrorInvalidValue;
     o.force = head ? 0 : 1;

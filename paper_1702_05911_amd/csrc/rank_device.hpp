@@ -210,7 +210,6 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
     float* ps = reinterpret_cast<float*>(smem + L.ps);
     uint32_t* pt = reinterpret_cast<uint32_t*>(smem + L.pt);
     uint32_t* slen = reinterpret_cast<uint32_t*>(smem + L.len);
-    uint32_t* so0 = reinterpret_cast<uint32_t*>(smem + L.o0);
     uint32_t* sslot = reinterpret_cast<uint32_t*>(smem + L.slot);
     uint32_t* part = reinterpret_cast<uint32_t*>(smem + L.part);
     uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);
@@ -256,7 +255,19 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
         }
 
         // ---- tuple -> bin number -> slot -> run of the inverted list ---------------------------
-        for (int t = tid; t < Tn; t += nt) {
+        // every thread takes `per` consecutive tuples and keeps their runs in registers; LDS copies of the
+        // run lengths and slots exist only where other threads need them (hashed slots, the slots tap)
+        constexpr int kMaxPer = MAXPER;
+        const int per = (Tn + nt - 1) / nt;
+        const int t0 = tid * per;
+        const bool keep_slots = g.hashed || g.slots;
+        uint32_t len[kMaxPer], o0[kMaxPer];
+#pragma unroll
+        for (int i = 0; i < kMaxPer; ++i) {
+            const int t = t0 + i;
+            len[i] = 0;
+            o0[i] = 0;
+            if (i >= per || t >= Tn) continue;
             const unsigned long long key = keys[t];
             unsigned long long lin;
             unsigned r[4] = {0, 0, 0, 0};
@@ -276,22 +287,26 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
                 lin = lin * g.k1k2 + sLid[3 * R + r[3]];
             }
             const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
-            const uint32_t o0 = g.offsets[slot], o1 = g.offsets[slot + 1];
-            so0[t] = o0;
-            slen[t] = o1 - o0;
-            sslot[t] = (uint32_t)slot;
+            o0[i] = g.offsets[slot];
+            len[i] = g.offsets[slot + 1] - o0[i];
+            if (keep_slots) sslot[t] = (uint32_t)slot;
+            if (g.hashed) slen[t] = len[i];
             if (g.tuples) {
                 uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
                 tp[0] = (uint16_t)r[0]; tp[1] = (uint16_t)r[1]; tp[2] = (uint16_t)r[2]; tp[3] = (uint16_t)r[3];
             }
             if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = mono_inv((uint32_t)(key >> 32));
-            if (g.hashed) dkeys[t] = (slot << 32) | (unsigned)t;      // keys[t] is not needed again
         }
         if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
-        __syncthreads();
 
         // ---- a slot proposed earlier in the order is skipped (hashed indexes only) --------------
         if (g.hashed) {
+            __syncthreads();                                  // every keys[t] has been read
+#pragma unroll
+            for (int i = 0; i < kMaxPer; ++i) {
+                const int t = t0 + i;
+                if (i < per && t < Tn) dkeys[t] = ((unsigned long long)sslot[t] << 32) | (unsigned)t;
+            }
             const int Tpad = next_pow2(Tn);
             for (int e = Tn + tid; e < Tpad; e += nt) dkeys[e] = ~0ull;
             block_sort_lds<MAXPER>(dkeys, Tpad, tid, nt);
@@ -300,19 +315,15 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
                 if ((cur >> 32) == (prev >> 32)) slen[(unsigned)cur] = 0;   // not the first of its slot
             }
             __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kMaxPer; ++i)
+                if (i < per && t0 + i < Tn) len[i] = slen[t0 + i];
         }
 
         // ---- lay the runs end to end, cut at C, compact --------------------------------------------
-        // every thread takes `per` consecutive tuples; both prefix sums run in registers
-        constexpr int kMaxPer = MAXPER;
-        const int per = (Tn + nt - 1) / nt;
-        const int t0 = tid * per;
-        uint32_t len[kMaxPer], sum = 0;
+        uint32_t sum = 0;
 #pragma unroll
-        for (int i = 0; i < kMaxPer; ++i) {
-            len[i] = (i < per && t0 + i < Tn) ? slen[t0 + i] : 0u;
-            sum += len[i];
-        }
+        for (int i = 0; i < kMaxPer; ++i) sum += len[i];
         uint32_t total;
         uint32_t start = block_exclusive_sum(sum, part, total);
         if (attempt == 0 && total < C) continue;                        // not enough: rank all Tcap tuples
@@ -332,10 +343,10 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
         for (int i = 0; i < kMaxPer; ++i) {
             if (((flags >> i) & 1u) == 0) continue;
             if (TO_LDS) {
-                out_src[idx] = so0[t0 + i];
+                out_src[idx] = o0[i];
                 out_start[idx] = first[i];
             } else {
-                g.runs[(size_t)q * T + idx] = make_uint2(so0[t0 + i], first[i]);
+                g.runs[(size_t)q * T + idx] = make_uint2(o0[i], first[i]);
                 if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t0 + i];
             }
             ++idx;
