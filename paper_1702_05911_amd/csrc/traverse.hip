@@ -155,11 +155,22 @@ __global__ __launch_bounds__(kTraverseMaxThreads) void traverse_kernel(TraverseA
             const float* arow = sq + row * L.qs + m * ds;
             const float* brow = g.C1 + ((size_t)p * k1 + (col < k1 ? col : 0)) * dp + lo;
             v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
-            for (int kk = 0; kk < ds; kk += 4) {
-                const int kd = kk + kq;
-                const float av = (kd < ds) ? arow[kd] : 0.0f;
-                const float bv = (kd < ds && col < k1) ? brow[kd] : 0.0f;
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc, 0, 0, 0);
+            // the centroid values of eight k-steps are fetched together, so that their latencies overlap
+            for (int k0 = 0; k0 < ds; k0 += 32) {
+                float bv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int kd = k0 + 4 * u + kq;
+                    bv[u] = (kd < ds && col < k1) ? brow[kd] : 0.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int kd = k0 + 4 * u + kq;
+                    if (k0 + 4 * u < ds) {                               // uniform
+                        const float av = (kd < ds) ? arow[kd] : 0.0f;
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv[u], acc, 0, 0, 0);
+                    }
+                }
             }
             if (col < k1) {
                 const float cn = g.c1n[m * k1 + col];
