@@ -282,6 +282,22 @@ def main():
     mean_runs = float(taps["n_slots"].float().mean())
     rec = recall_at(out_ids[:n_gt], gt)
     rec["queries_with_ground_truth"] = n_gt
+    # two tree parts, unhashed: how many tuples of the order a query needs before its runs fill C
+    # (the ranking head pass stops at 32, 64 or 128; beyond that the query gets the full ranking)
+    tuples_needed = None
+    if cfg.P == 2 and cfg.H == (cfg.k1 * cfg.k2) ** 2:
+        nsub = min(cfg.nq, 2000)
+        _, _, t2 = pqt.pqt_query_batch_debug(index, Y[:nsub], cfg.k, w, taps=("slots", "n_tuples"))
+        off = pqt.pqt_index_export(index, ("offsets",))["offsets"].to(torch.int64)
+        sl = t2["slots"].clamp_(0, cfg.H - 1)
+        lens = off[sl + 1] - off[sl]
+        valid = torch.arange(cfg.T, device=dev)[None, :] < t2["n_tuples"][:, None]
+        csum = torch.cumsum(lens * valid, dim=1)
+        need = (csum < cfg.C).sum(dim=1) + 1            # tuples until the budget is reached (T + 1: never)
+        tuples_needed = {"queries": nsub}
+        for t in (32, 64, 128):
+            tuples_needed[f"<={t}"] = float((need <= min(t, cfg.T)).float().mean())
+        del t2, off, sl, lens, valid, csum
 
     # ---- algorithmic work per launch (one launch = all nq queries) -----------------------------------
     nq, R = cfg.nq, w * cfg.k2
@@ -336,7 +352,7 @@ def main():
         "config": {"workload": f"{cfg.name}: N={cfg.N} D={cfg.D} nq={cfg.nq} P={cfg.P} k1={cfg.k1} k2={cfg.k2} "
                                f"M={cfg.M} H={cfg.H} w={w} T={cfg.T} C={cfg.C} k={cfg.k}",
                    "queries_per_call": B, "mean_candidates": mean_cand, "mean_runs": mean_runs, **occupancy},
-        "recall": rec, "stage_ms": stage_ms, "stages": stages, "roofline": roofline, "setup_s": setup_s,
+        "recall": rec, "tuples_needed": tuples_needed, "stage_ms": stage_ms, "stages": stages, "roofline": roofline, "setup_s": setup_s,
         "measured_peaks": {"hbm_read_GBs": hbm_meas, "mfma_f32_TFLOPs": mfma_meas,
                            "how": "pqt_measure_peaks: 4 GiB streaming read; loop of independent v_mfma_f32_16x16x4_f32"},
     }
