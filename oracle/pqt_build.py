@@ -248,14 +248,30 @@ def encode_batch(X, C1, M, tbl_i, tbl_j, tbl_lam):
     return codes
 
 
+def encode_pair_lambda(X, C1, M):
+    """Code format 1 (Eq. 7 stored directly, Sec. 3.3 "Offline computation"): per sub-part the
+    centroid pair whose line is nearest to the sub-vector (smallest projection error; ties: first
+    pair), then the grid level nearest to the projection's lambda.  Two bytes per sub-part."""
+    from .pqt_query import level_of_lambda
+    n, D = X.shape
+    ds = D // M
+    codes = np.zeros((n, 2 * M), dtype=np.uint8)
+    for m in range(M):
+        pair, lam, _ = best_lines(np.asarray(X[:, m * ds:(m + 1) * ds], dtype=np.float64), subpart_centroids(C1, M, m))
+        codes[:, 2 * m] = pair
+        codes[:, 2 * m + 1] = level_of_lambda(lam)
+    return codes
+
+
 # ---------------------------------------------------------------------------
 # the whole build
 # ---------------------------------------------------------------------------
 def build_index(X, P, k1, k2, M, H=None, T=1024, C=4096, train_n=None, iters=20,
-                codebooks=None, line_table=None):
+                codebooks=None, line_table=None, code_format=0):
     """Train (or take) the tree, sort X into bins, build the inverted lists, the line
     code table and the codes.  `codebooks=(C1, C2)` and `line_table=(tbl_i, tbl_j, tbl_lam)`
-    let a test supply hand-made ones."""
+    let a test supply hand-made ones.  code_format 1 stores (pair, lambda level) per sub-part
+    instead of an entry of the line table (which is then left at zeros)."""
     N, D = X.shape
     assert D % P == 0 and D % M == 0 and M % P == 0 and k1 <= 256
     K = (k1 * k2) ** P
@@ -265,7 +281,10 @@ def build_index(X, P, k1, k2, M, H=None, T=1024, C=4096, train_n=None, iters=20,
         C1, C2 = train_tree(Xt, P, k1, k2, iters)
     else:
         C1, C2 = (np.asarray(c, dtype=np.float32) for c in codebooks)
-    if line_table is None:
+    if code_format == 1:
+        assert 2 <= k1 and k1 * (k1 - 1) // 2 <= 256
+        ti, tj, tl = np.zeros((M, 256), np.uint8), np.zeros((M, 256), np.uint8), np.zeros((M, 256), np.float32)
+    elif line_table is None:
         ds = D // M
         ti = np.zeros((M, 256), np.uint8)
         tj = np.zeros((M, 256), np.uint8)
@@ -278,8 +297,8 @@ def build_index(X, P, k1, k2, M, H=None, T=1024, C=4096, train_n=None, iters=20,
         ti, tj, tl = np.asarray(ti, np.uint8), np.asarray(tj, np.uint8), np.asarray(tl, np.float32)
     slots = bin_slots_batch(X, C1, C2, H)
     offsets, order = inverted_lists(slots, H)
-    codes = encode_batch(X, C1, M, ti, tj, tl)[order]
+    codes = (encode_pair_lambda(X, C1, M) if code_format == 1 else encode_batch(X, C1, M, ti, tj, tl))[order]
     return PQTIndex(D=D, P=P, k1=k1, k2=k2, M=M, N=N, H=H, T=T, C=C, C1=C1, C2=C2,
                     tbl_i=ti, tbl_j=tj, tbl_lam=tl, cc=pair_table(C1, M).astype(np.float32),
                     offsets=offsets.astype(np.uint32), ids=order.astype(np.uint32),
-                    codes=np.ascontiguousarray(codes))
+                    codes=np.ascontiguousarray(codes), code_format=code_format)

@@ -8,7 +8,7 @@ Layout (little endian).  256-byte header:
    0  char[8]  "PQTIDX1\\0"
    8  u32 version (=1)   12 u32 D   16 u32 P   20 u32 k1   24 u32 k2   28 u32 M
   32  u64 N              40 u64 H   48 u32 T   52 u32 C    56 u32 offset_bits (=32)
-  60..255 zero
+  60  u32 code_format (0: one byte per sub-part, 1: two)   64..255 zero
 then nine sections, each starting at the next multiple of 256 bytes:
   C1      f32 [P][k1][D/P]
   C2      f32 [P][k1][k2][D/P]
@@ -18,7 +18,7 @@ then nine sections, each starting at the next multiple of 256 bytes:
   cc      f32 [M][k1][k1]
   offsets u32 [H+1]
   ids     u32 [N]
-  codes   u8  [N][M]
+  codes   u8  [N][M]   ([N][2M] for code_format 1)
 """
 import struct
 
@@ -30,7 +30,7 @@ MAGIC = b"PQTIDX1\0"
 ALIGN = 256
 
 
-def _sections(D, P, k1, k2, M, N, H):
+def _sections(D, P, k1, k2, M, N, H, code_format=0):
     dp = D // P
     return [
         ("C1", np.float32, (P, k1, dp)),
@@ -41,7 +41,7 @@ def _sections(D, P, k1, k2, M, N, H):
         ("cc", np.float32, (M, k1, k1)),
         ("offsets", np.uint32, (H + 1,)),
         ("ids", np.uint32, (N,)),
-        ("codes", np.uint8, (N, M)),
+        ("codes", np.uint8, (N, M * (2 if code_format == 1 else 1))),
     ]
 
 
@@ -50,10 +50,10 @@ def write_index(path, ix: PQTIndex):
     hdr[0:8] = MAGIC
     struct.pack_into("<6I", hdr, 8, 1, ix.D, ix.P, ix.k1, ix.k2, ix.M)
     struct.pack_into("<2Q", hdr, 32, ix.N, ix.H)
-    struct.pack_into("<3I", hdr, 48, ix.T, ix.C, 32)
+    struct.pack_into("<4I", hdr, 48, ix.T, ix.C, 32, ix.code_format)
     with open(path, "wb") as f:
         f.write(hdr)
-        for name, dt, shape in _sections(ix.D, ix.P, ix.k1, ix.k2, ix.M, ix.N, ix.H):
+        for name, dt, shape in _sections(ix.D, ix.P, ix.k1, ix.k2, ix.M, ix.N, ix.H, ix.code_format):
             arr = np.ascontiguousarray(getattr(ix, name), dtype=dt)
             assert arr.shape == shape, (name, arr.shape, shape)
             pad = (-f.tell()) % ALIGN
@@ -68,15 +68,15 @@ def read_index(path) -> PQTIndex:
             raise ValueError("not a PQT index file")
         ver, D, P, k1, k2, M = struct.unpack_from("<6I", hdr, 8)
         N, H = struct.unpack_from("<2Q", hdr, 32)
-        T, C, obits = struct.unpack_from("<3I", hdr, 48)
-        if ver != 1 or obits != 32:
+        T, C, obits, fmt = struct.unpack_from("<4I", hdr, 48)
+        if ver != 1 or obits != 32 or fmt > 1:
             raise ValueError("unsupported PQT index version")
         fields = {}
-        for name, dt, shape in _sections(D, P, k1, k2, M, N, H):
+        for name, dt, shape in _sections(D, P, k1, k2, M, N, H, fmt):
             f.seek((-f.tell()) % ALIGN, 1)
             cnt = int(np.prod(shape))
             arr = np.fromfile(f, dtype=dt, count=cnt)
             if arr.shape[0] != cnt:
                 raise ValueError("truncated PQT index file")
             fields[name] = arr.reshape(shape)
-    return PQTIndex(D=D, P=P, k1=k1, k2=k2, M=M, N=N, H=H, T=T, C=C, **fields)
+    return PQTIndex(D=D, P=P, k1=k1, k2=k2, M=M, N=N, H=H, T=T, C=C, code_format=fmt, **fields)

@@ -46,7 +46,9 @@ class PQTIndex:
     cc: np.ndarray             # (M, k1, k1) float32  ||[c_s]_m - [c_t]_m||^2   (Sec. 3.3)
     offsets: np.ndarray        # (H+1,)  start of every bin slot in ids/codes    (Sec. 4)
     ids: np.ndarray            # (N,) uint32, ascending inside a slot
-    codes: np.ndarray          # (N, M) uint8, row t belongs to ids[t]
+    codes: np.ndarray          # (N, M) uint8, row t belongs to ids[t]; (N, 2M) for code_format 1
+    code_format: int = 0       # 0: one byte per sub-part = entry of the (i, j, lambda) table
+                               # 1: two bytes per sub-part = (centroid pair, lambda level), Eq. 7 stored directly
 
     @property
     def dp(self):
@@ -273,6 +275,44 @@ def build_lut(a, tbl_i, tbl_j, tbl_lam, cc):
     return lut
 
 
+# Code format 1 stores the triple of Eq. 7 itself: one byte numbers the centroid pair i < j in
+# lexicographic order, one byte is the level of lambda on a fixed grid.  (The paper gives "1+1 bytes"
+# but neither the numbering nor the grid; the grid below has 0 and 1 on it and reaches half a
+# segment length beyond either end.)
+LAMBDA_ZERO_LEVEL = 64
+LAMBDA_LEVELS_PER_UNIT = 128
+
+
+def lambda_of_level(level):
+    return (np.asarray(level, dtype=np.float64) - LAMBDA_ZERO_LEVEL) / LAMBDA_LEVELS_PER_UNIT
+
+
+def level_of_lambda(lam):
+    """Nearest grid level (halves go up), clamped to a byte."""
+    return np.clip(np.floor(np.asarray(lam, dtype=np.float64) * LAMBDA_LEVELS_PER_UNIT + LAMBDA_ZERO_LEVEL + 0.5),
+                   0, 255).astype(np.uint8)
+
+
+def centroid_pairs(k1):
+    """(i, j) of pair number 0, 1, ...: all i < j in lexicographic order."""
+    return [(i, j) for i in range(k1) for j in range(i + 1, k1)]
+
+
+def score_pair_lambda(a, cc, codes):
+    """Eq. 8-9 on codes of format 1: for every sub-part m, in ascending order, the summand
+    b^2 + lam^2 c^2 + lam (a^2 - b^2 - c^2) with (i, j) = pair codes[:, 2m], lam = level codes[:, 2m+1],
+    b^2 = a[m][i], a^2 = a[m][j], c^2 = cc[m][i][j]."""
+    M, k1 = a.shape
+    pairs = np.asarray(centroid_pairs(k1), dtype=np.int64).reshape(-1, 2)
+    s = np.zeros(codes.shape[0], dtype=np.float64)
+    for m in range(M):
+        i, j = pairs[codes[:, 2 * m], 0], pairs[codes[:, 2 * m], 1]
+        lam = lambda_of_level(codes[:, 2 * m + 1])
+        b2, a2, c2 = a[m, i].astype(np.float64), a[m, j].astype(np.float64), cc[m, i, j].astype(np.float64)
+        s = s + (b2 + lam * lam * c2 + lam * (a2 - b2 - c2))
+    return s
+
+
 def score_codes(lut, codes):
     """score(x) = sum over m = 0..M-1, in that order, of LUT[m][code_x[m]]   (Eq. 8-9)."""
     n, M = codes.shape
@@ -317,13 +357,18 @@ def reconstruct(index, code):
     """The point a code stands for: per sub-part (1-lam)*[c_i]_m + lam*[c_j]_m  (Sec. 3.3)."""
     x = np.zeros(index.D, dtype=np.float64)
     ds, dp = index.ds, index.dp
+    pairs = centroid_pairs(index.k1)
     for m in range(index.M):
         p = (m * ds) // dp
         lo = m * ds - p * dp
-        c = int(code[m])
-        ci = index.C1[p, int(index.tbl_i[m, c]), lo:lo + ds].astype(np.float64)
-        cj = index.C1[p, int(index.tbl_j[m, c]), lo:lo + ds].astype(np.float64)
-        lam = float(index.tbl_lam[m, c])
+        if index.code_format == 1:
+            i, j = pairs[int(code[2 * m])]
+            lam = float(lambda_of_level(code[2 * m + 1]))
+        else:
+            c = int(code[m])
+            i, j, lam = int(index.tbl_i[m, c]), int(index.tbl_j[m, c]), float(index.tbl_lam[m, c])
+        ci = index.C1[p, i, lo:lo + ds].astype(np.float64)
+        cj = index.C1[p, j, lo:lo + ds].astype(np.float64)
         x[m * ds:(m + 1) * ds] = (1.0 - lam) * ci + lam * cj
     return x
 
@@ -375,6 +420,8 @@ def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_meth
     if exact_rerank:
         diff = X[tr.cand_ids].astype(np.float64) - np.asarray(y, dtype=np.float64)[None, :]
         tr.scores = np.sum(diff * diff, axis=1)
+    elif index.code_format == 1:
+        tr.scores = score_pair_lambda(tr.a, index.cc, index.codes[tr.cand_pos])
     else:
         tr.lut = build_lut(tr.a, index.tbl_i, index.tbl_j, index.tbl_lam, index.cc.astype(np.float64))
         tr.scores = score_codes(tr.lut, index.codes[tr.cand_pos])

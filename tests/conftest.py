@@ -26,5 +26,15 @@ def tiny():
 
 
 @pytest.fixture(scope="session")
+def tiny_pair(tiny):
+    """The tiny index with its codes stored as (centroid pair, lambda level) per sub-part."""
+    import dataclasses
+    from oracle import pqt_build
+    cfg, X, Y, ix = tiny
+    codes = pqt_build.encode_pair_lambda(X, ix.C1, ix.M)[ix.ids]
+    return cfg, X, Y, dataclasses.replace(ix, codes=np.ascontiguousarray(codes), code_format=1)
+
+
+@pytest.fixture(scope="session")
 def rng():
     return np.random.default_rng(12345)

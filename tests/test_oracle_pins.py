@@ -329,3 +329,85 @@ def test_exact_short_list_rerank_is_brute_force_on_the_list(tiny, rng):
     ids_all, d_all = Q.exact_rerank_short_list(y, X, np.arange(cfg.N), 10)
     bf_ids, bf_d = Q.brute_force(y, X, 10)
     assert np.array_equal(ids_all, bf_ids) and np.array_equal(d_all, bf_d)
+
+
+# ---- codes stored as (centroid pair, lambda level): Eq. 7 directly -----------------------------
+def test_pair_lambda_score_equals_distance_to_reconstruction(tiny_pair):
+    cfg, X, Y, ix = tiny_pair
+    cc64 = B.pair_table(ix.C1, ix.M)
+    assert ix.codes.shape == (cfg.N, 2 * cfg.M)
+    for q in range(5):
+        a = Q.level1_subpart_distances(Y[q], ix.C1, ix.M)
+        pos = np.arange(q, cfg.N, 211)
+        s = Q.score_pair_lambda(a, cc64, ix.codes[pos])
+        for t, ps in enumerate(pos):
+            xr = Q.reconstruct(ix, ix.codes[ps])
+            want = float(np.sum((Y[q].astype(np.float64) - xr) ** 2))
+            assert abs(s[t] - want) <= 1e-9 * max(want, 1e-30)
+
+
+def test_pair_lambda_codes_name_the_nearest_line(tiny_pair):
+    """Brute force over every centroid pair with the point-to-line distance from a least-squares
+    solve (not the projection formula the oracle uses)."""
+    cfg, X, Y, ix = tiny_pair
+    ds = cfg.D // cfg.M
+    pairs = Q.centroid_pairs(cfg.k1)
+    for t in range(0, cfg.N, 487):
+        x = X[ix.ids[t]].astype(np.float64)
+        for m in range(cfg.M):
+            cen = B.subpart_centroids(ix.C1, ix.M, m)
+            xs = x[m * ds:(m + 1) * ds]
+            best, best_pi, best_lam = np.inf, -1, 0.0
+            for pi, (i, j) in enumerate(pairs):
+                u = (cen[j] - cen[i])[:, None]
+                sol, res, rank, _ = np.linalg.lstsq(u, xs - cen[i], rcond=None)
+                err = float(np.sum((xs - cen[i] - u[:, 0] * sol[0]) ** 2))
+                if rank == 1 and err < best * (1 - 1e-12):
+                    best, best_pi, best_lam = err, pi, float(sol[0])
+            assert ix.codes[t, 2 * m] == best_pi
+            lam_q = float(Q.lambda_of_level(ix.codes[t, 2 * m + 1]))
+            if -0.5 <= best_lam <= 191.0 / 128:
+                assert abs(lam_q - best_lam) <= 0.5 / 128 + 1e-12
+            else:
+                assert ix.codes[t, 2 * m + 1] in (0, 255)
+
+
+def test_pair_lambda_grid_and_pair_numbering():
+    assert Q.lambda_of_level(64) == 0.0 and Q.lambda_of_level(192) == 1.0
+    assert Q.lambda_of_level(0) == -0.5 and Q.lambda_of_level(255) == 191.0 / 128
+    assert list(Q.level_of_lambda([-10.0, 10.0, 0.0, 1.0, 0.5 / 128, 0.49 / 128, -0.51 / 128])) == [0, 255, 64, 192, 65, 64, 63]
+    for k1 in (2, 5, 16, 23):
+        pairs = Q.centroid_pairs(k1)
+        assert len(pairs) == k1 * (k1 - 1) // 2
+        for pi, (i, j) in enumerate(pairs):
+            assert i < j and pi == i * (2 * k1 - i - 1) // 2 + (j - i - 1)
+
+
+def test_pair_lambda_point_on_a_segment_is_reproduced(rng):
+    """A vector whose sub-vectors sit on a centroid segment at a grid lambda costs nothing."""
+    P, k1, D, M = 2, 6, 8, 4
+    C1 = rng.normal(size=(P, k1, D // P)).astype(np.float32)
+    ds = D // M
+    x = np.zeros(D)
+    want = []
+    for m, (i, j, level) in enumerate([(0, 3, 96), (1, 2, 64 + 128), (4, 5, 70), (2, 5, 10)]):
+        cen = B.subpart_centroids(C1, M, m)
+        lam = (level - 64) / 128
+        x[m * ds:(m + 1) * ds] = (1 - lam) * cen[i] + lam * cen[j]
+        want += [Q.centroid_pairs(k1).index((i, j)), level]
+    code = B.encode_pair_lambda(x[None], C1, M)[0]
+    # lambda = 1 on (1, 2) is the point c_2 itself, which lies on every line through c_2: the first such pair wins
+    assert list(code[:2]) == want[:2] and list(code[4:]) == want[4:]
+    ix = Q.PQTIndex(D=D, P=P, k1=k1, k2=1, M=M, N=1, H=1, T=1, C=1, C1=C1, C2=None, tbl_i=None, tbl_j=None,
+                    tbl_lam=None, cc=None, offsets=None, ids=None, codes=code[None], code_format=1)
+    assert np.allclose(Q.reconstruct(ix, code), x, rtol=0, atol=1e-12)
+
+
+def test_pair_lambda_index_file_roundtrip(tiny_pair, tmp_path):
+    cfg, X, Y, ix = tiny_pair
+    path = str(tmp_path / "pair.pqt")
+    IO.write_index(path, ix)
+    back = IO.read_index(path)
+    assert back.code_format == 1 and np.array_equal(back.codes, ix.codes) and np.array_equal(back.ids, ix.ids)
+    tr0, tr1 = Q.query(ix, Y[0], cfg.k, cfg.w), Q.query(back, Y[0], cfg.k, cfg.w)
+    assert np.array_equal(tr0.out_ids, tr1.out_ids)
