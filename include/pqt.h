@@ -46,6 +46,19 @@ extern "C" {
 
 typedef struct pqt_index pqt_index;   /* opaque; owns all device and host memory of one index */
 
+/*
+ * Re-rank code formats (Sec. 3.3, Eq. 7: a vector is the tuple of (lambda, i, j) of its sub-parts).
+ *   PQT_CODES_TABLE        one byte per sub-part: the number of an (i, j, lambda) entry in a table of
+ *                          256 per sub-part (tbl_i, tbl_j, tbl_lambda); M bytes per vector.
+ *   PQT_CODES_PAIR_LAMBDA  the tuple stored directly in "1+1 bytes" per sub-part (Sec. 3.3): byte 2m is
+ *                          the number of the centroid pair i < j in lexicographic order
+ *                          (i (2 k1 - i - 1) / 2 + j - i - 1; needs k1 (k1 - 1) / 2 <= 256), byte 2m+1 the
+ *                          level of lambda = (level - 64) / 128; 2M bytes per vector.  The score is Eq. 9
+ *                          evaluated per candidate; the line table is not used and may be NULL.
+ */
+#define PQT_CODES_TABLE        0
+#define PQT_CODES_PAIR_LAMBDA  1
+
 typedef struct pqt_info {
     uint64_t N, H;
     uint32_t D, P, k1, k2, M;
@@ -53,6 +66,8 @@ typedef struct pqt_info {
     int32_t  device;
     uint64_t bytes_index;        /* device bytes held by the index arrays                    */
     uint64_t bytes_workspace;    /* device bytes held by the per-batch workspace             */
+    uint32_t code_format;        /* PQT_CODES_*                                              */
+    uint32_t code_bytes;         /* bytes per vector in the codes array                      */
 } pqt_info;
 
 /*
@@ -62,13 +77,15 @@ typedef struct pqt_info {
  * the centroid-pair distance table of Sec. 3.3, the pointer array over the H hashed bin
  * slots, the ids sorted by slot, and the codes stored in the same order as the ids.
  * Layout: 256-byte header  "PQTIDX1\0", u32 version=1, D, P, k1, k2, M, u64 N, u64 H,
- * u32 T, u32 C, u32 offset_bits=32; then, each at the next multiple of 256 bytes:
+ * u32 T, u32 C, u32 offset_bits=32, u32 code_format; then, each at the next multiple of 256 bytes:
  * C1 f32[P][k1][D/P], C2 f32[P][k1][k2][D/P], tbl_i u8[M][256], tbl_j u8[M][256],
- * tbl_lambda f32[M][256], cc f32[M][k1][k1], offsets u32[H+1], ids u32[N], codes u8[N][M].
+ * tbl_lambda f32[M][256], cc f32[M][k1][k1], offsets u32[H+1], ids u32[N], codes u8[N][M]
+ * (u8[N][2M] for PQT_CODES_PAIR_LAMBDA, whose table sections are present but unused).
  * On success *out is a handle the caller releases with pqt_index_free.
  * Errors: PQT_EINVAL (null), PQT_EIO, PQT_EFORMAT (also: offsets not monotone,
- * offsets[H] != N, table entries >= k1), PQT_EUNSUPPORTED (P not in {1,2,4}, sizes beyond
- * the limits above), PQT_ENOMEM, PQT_EHIP.
+ * offsets[H] != N, table entries >= k1, a pair byte >= k1 (k1 - 1) / 2), PQT_EUNSUPPORTED (P not in
+ * {1,2,4}, sizes beyond the limits above, more than 256 centroid pairs for PQT_CODES_PAIR_LAMBDA),
+ * PQT_ENOMEM, PQT_EHIP.
  */
 int pqt_index_load(const char* path, int device, pqt_index** out);
 
@@ -95,7 +112,9 @@ typedef struct pqt_index_arrays {
     const float*    cc;          /* [M][k1][k1]         host */
     const uint32_t* offsets;     /* [H+1]               host or device */
     const uint32_t* ids;         /* [N]                 host or device */
-    const uint8_t*  codes;       /* [N][M]              host or device */
+    const uint8_t*  codes;       /* [N][M] or [N][2M]   host or device */
+    uint32_t        code_format; /* PQT_CODES_TABLE (0) or PQT_CODES_PAIR_LAMBDA; with the latter
+                                    tbl_i, tbl_j, tbl_lambda may be NULL */
 } pqt_index_arrays;
 int pqt_index_from_arrays(const pqt_index_arrays* arrays, int location, int device, pqt_index** out);
 
@@ -117,6 +136,10 @@ int pqt_index_from_arrays(const pqt_index_arrays* arrays, int location, int devi
  *                       pqt_builder_free.  Synchronises the device.
  * A code byte is the nearest of the 256 code points of its sub-part, with distances from
  * Eq. 9 on the vector's own level-1 distances (fp32); ties go to the smaller code value.
+ * With params->code_format == PQT_CODES_PAIR_LAMBDA a sub-part's code is the centroid pair
+ * whose line is nearest to the sub-vector (projection error from the same level-1 distances
+ * and the pair distance table; ties: smaller pair number; pairs of coinciding centroids never
+ * win) and the level nearest to the projection's lambda, clamped to 0..255.
  * Errors: PQT_EINVAL (null, N = 0, more or fewer than N vectors), PQT_EFORMAT /
  * PQT_EUNSUPPORTED as for pqt_index_from_arrays, PQT_ENOMEM, PQT_EHIP.
  */
@@ -227,7 +250,7 @@ int pqt_brute_force(pqt_index* index, const float* queries, int64_t nq, int k,
  *   n_cand     nq            uint32 candidates gathered (<= C)
  *   cand_ids   nq x C        int64  candidate ids in visit order
  *   scores     nq x C        fp32   their Eq. 8-9 scores
- *   lut        nq x M x 256  fp32   per-query table of Eq. 9 summands
+ *   lut        nq x M x 256  fp32   per-query table of Eq. 9 summands (PQT_CODES_TABLE only: PQT_EINVAL otherwise)
  */
 typedef struct pqt_debug_taps {
     float*    a;

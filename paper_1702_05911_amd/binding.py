@@ -33,7 +33,8 @@ class _Info(ctypes.Structure):
                 ("D", ctypes.c_uint32), ("P", ctypes.c_uint32), ("k1", ctypes.c_uint32),
                 ("k2", ctypes.c_uint32), ("M", ctypes.c_uint32), ("T", ctypes.c_uint32),
                 ("C", ctypes.c_uint32), ("device", ctypes.c_int32),
-                ("bytes_index", ctypes.c_uint64), ("bytes_workspace", ctypes.c_uint64)]
+                ("bytes_index", ctypes.c_uint64), ("bytes_workspace", ctypes.c_uint64),
+                ("code_format", ctypes.c_uint32), ("code_bytes", ctypes.c_uint32)]
 
 
 _TAP_FIELDS = ("a", "sel", "L_d", "L_id", "n_tuples", "tuples", "tuple_keys", "n_slots", "slots",
@@ -44,10 +45,12 @@ class _Arrays(ctypes.Structure):
     _fields_ = [("N", ctypes.c_uint64), ("H", ctypes.c_uint64)] + \
                [(n, ctypes.c_uint32) for n in ("D", "P", "k1", "k2", "M", "T", "C")] + \
                [(n, ctypes.c_void_p) for n in ("C1", "C2", "tbl_i", "tbl_j", "tbl_lambda", "cc",
-                                               "offsets", "ids", "codes")]
+                                               "offsets", "ids", "codes")] + \
+               [("code_format", ctypes.c_uint32)]
 
 
 PQT_HOST, PQT_DEVICE = 0, 1
+PQT_CODES_TABLE, PQT_CODES_PAIR_LAMBDA = 0, 1
 
 
 class _Taps(ctypes.Structure):
@@ -156,7 +159,7 @@ class Index:
                      M=int(a["M"]), T=int(a["T"]), C=int(a["C"]),
                      C1=keep[0].ctypes.data, C2=keep[1].ctypes.data, tbl_i=keep[2].ctypes.data,
                      tbl_j=keep[3].ctypes.data, tbl_lambda=keep[4].ctypes.data, cc=keep[5].ctypes.data,
-                     offsets=big[0][1], ids=big[1][1], codes=big[2][1])
+                     offsets=big[0][1], ids=big[1][1], codes=big[2][1], code_format=int(a.get("code_format", 0)))
         _check(_lib.pqt_index_from_arrays(ctypes.byref(ca), PQT_DEVICE if on_device else PQT_HOST, device,
                                           ctypes.byref(self._h)))
 
@@ -178,7 +181,7 @@ class Index:
         (int32 views of the uint32 data for offsets and ids)."""
         inf = self.info()
         shapes = {"offsets": ((inf["H"] + 1,), torch.int32), "ids": ((inf["N"],), torch.int32),
-                  "codes": ((inf["N"], inf["M"]), torch.uint8)}
+                  "codes": ((inf["N"], inf["code_bytes"]), torch.uint8)}
         bufs = {n: torch.empty(shapes[n][0], dtype=shapes[n][1], device=self.device) for n in names}
         ca = _Arrays(**{n: bufs[n].data_ptr() for n in names})
         _check(_lib.pqt_index_export(self._h, ctypes.byref(ca), PQT_DEVICE))
@@ -292,10 +295,18 @@ class Index:
 
 
 def _small_arrays(a):
+    """The small host arrays in the ABI's order.  The line table may be missing for (pair, lambda)
+    codes, which do not use it; zeros stand in."""
     import numpy as np
     small = {"C1": np.float32, "C2": np.float32, "tbl_i": np.uint8, "tbl_j": np.uint8,
              "tbl_lam": np.float32, "cc": np.float32}
-    return [np.ascontiguousarray(a[n], dtype=dt) for n, dt in small.items()]
+    out = []
+    for n, dt in small.items():
+        v = a.get(n)
+        if v is None and n.startswith("tbl_") and int(a.get("code_format", 0)) == PQT_CODES_PAIR_LAMBDA:
+            v = np.zeros((int(a["M"]), 256), dtype=dt)
+        out.append(np.ascontiguousarray(v, dtype=dt))
+    return out
 
 
 class Builder:
@@ -307,7 +318,8 @@ class Builder:
                      k1=int(params["k1"]), k2=int(params["k2"]), M=int(params["M"]), T=int(params["T"]),
                      C=int(params["C"]), C1=keep[0].ctypes.data, C2=keep[1].ctypes.data,
                      tbl_i=keep[2].ctypes.data, tbl_j=keep[3].ctypes.data, tbl_lambda=keep[4].ctypes.data,
-                     cc=keep[5].ctypes.data, offsets=None, ids=None, codes=None)
+                     cc=keep[5].ctypes.data, offsets=None, ids=None, codes=None,
+                     code_format=int(params.get("code_format", 0)))
         self._h = ctypes.c_void_p()
         self._device = int(device)
         self._D = int(params["D"])

@@ -59,6 +59,67 @@ __global__ __launch_bounds__(kEncodeThreads) void encode_kernel(const float* a, 
     }
 }
 
+// (pair, lambda) codes (Sec. 3.3 "Offline computation": the line through two level-1 centroids that
+// is nearest to the sub-vector, and the projection's lambda; Eq. 7 stored directly).  One wavefront
+// per vector, up to four centroid pairs per lane.  With b^2, a^2 the sub-vector's distances to c_i,
+// c_j and c^2 = ||c_i - c_j||^2, the projection is at lambda = (b^2 - a^2 + c^2) / (2 c^2) and its
+// error is b^2 - lambda^2 c^2; the smallest (error, pair number) wins, pairs with c^2 = 0 never do.
+// `table` holds the pairs (entry = pair number, kc = c^2).
+__global__ __launch_bounds__(kEncodeThreads) void encode_pairs_kernel(const float* a, const uint32_t* leaf, int64_t n, int M,
+                                                                      int k1, int P, uint32_t k1k2, unsigned long long H,
+                                                                      const CodeEntry* table, uint8_t* codes,
+                                                                      uint32_t* slots) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t v = (int64_t)blockIdx.x * (kEncodeThreads / kWave) + threadIdx.x / kWave;
+    if (v >= n) return;
+    const float* av = a + (size_t)v * M * k1;
+    const int npairs = k1 * (k1 - 1) / 2;
+    for (int m = 0; m < M; ++m) {
+        unsigned long long best = ~0ull;
+        float best_lam = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = u * kWave + lane;
+            if (c >= npairs) continue;
+            const CodeEntry e = table[m * 256 + c];
+            if (!(e.kc > 0.0f)) continue;
+            const float b2 = av[m * k1 + (e.ij & 0xffu)], a2 = av[m * k1 + ((e.ij >> 8) & 0xffu)];
+            const float lam = ((b2 - a2) + e.kc) / (2.0f * e.kc);
+            const float err = fmaf(-lam * lam, e.kc, b2);
+            const unsigned long long key = ((unsigned long long)mono_key(err) << 32) | (unsigned)c;
+            if (key < best) {
+                best = key;
+                best_lam = lam;
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(best >> 32), off, kWave);
+            const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)best, off, kWave);
+            const float ol = __shfl_xor(best_lam, off, kWave);
+            const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+            if (o < best) {
+                best = o;
+                best_lam = ol;
+            }
+        }
+        if (lane == 0) {
+            uint32_t pair = 0, level = 64;                 // no usable pair: pair 0 at lambda = 0
+            if (best != ~0ull) {
+                pair = (uint32_t)best & 0xffu;
+                const float l = floorf(fmaf(best_lam, 128.0f, 64.5f));
+                level = (uint32_t)fminf(fmaxf(l, 0.0f), 255.0f);
+            }
+            codes[((size_t)v * M + m) * 2] = (uint8_t)pair;
+            codes[((size_t)v * M + m) * 2 + 1] = (uint8_t)level;
+        }
+    }
+    if (lane == 0) {
+        unsigned long long lin = 0;
+        for (int p = 0; p < P; ++p) lin = lin * k1k2 + leaf[(size_t)v * P + p];
+        slots[v] = (uint32_t)(lin % H);
+    }
+}
+
 __global__ void iota_kernel(uint32_t* out, uint64_t n) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) out[i] = (uint32_t)i;
@@ -69,7 +130,7 @@ __global__ void histogram_kernel(const uint32_t* slots, uint64_t n, uint32_t* co
     if (i < n) atomicAdd(&counts[slots[i]], 1u);
 }
 
-// codes_out[i] = codes_in[order[i]], one thread per byte-row piece
+// codes_out[i] = codes_in[order[i]], one thread per row of M bytes
 __global__ void permute_codes_kernel(const uint8_t* in, const uint32_t* order, uint64_t n, int M, uint8_t* out) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
@@ -138,7 +199,7 @@ int pqt_builder_create(const pqt_index_arrays* params, int device, pqt_builder**
     DeviceGuard guard(device);
     b->chunk = (int64_t)(b->N < (uint64_t)kChunk ? b->N : (uint64_t)kChunk);
     hipError_t e = hipMalloc(reinterpret_cast<void**>(&b->slots), sizeof(uint32_t) * b->N);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&b->codes), (size_t)b->N * ix->M);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&b->codes), (size_t)b->N * ix->code_bytes());
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&b->leaf), sizeof(uint32_t) * (size_t)b->chunk * ix->P);
     if (e != hipSuccess) {
         pqt_builder_free(b);
@@ -186,9 +247,10 @@ int pqt_builder_add(pqt_builder* b, const float* vectors, int64_t n, void* hip_s
         hipLaunchKernelGGL(pqt::first_leaf_kernel, dim3((unsigned)((m * ix->P + tb - 1) / tb)), dim3(tb), 0, stream,
                            ix->ws_Lid, m, (int)ix->P, R, b->leaf);
         constexpr int per = pqt::kEncodeThreads / pqt::kWave;
-        hipLaunchKernelGGL(pqt::encode_kernel, dim3((unsigned)((m + per - 1) / per)), dim3(pqt::kEncodeThreads), 0, stream,
+        hipLaunchKernelGGL(ix->code_format == PQT_CODES_PAIR_LAMBDA ? pqt::encode_pairs_kernel : pqt::encode_kernel,
+                           dim3((unsigned)((m + per - 1) / per)), dim3(pqt::kEncodeThreads), 0, stream,
                            ix->ws_a, b->leaf, m, (int)ix->M, (int)ix->k1, (int)ix->P, ix->k1 * ix->k2,
-                           (unsigned long long)ix->H, ix->table, b->codes + (size_t)(b->added + s) * ix->M,
+                           (unsigned long long)ix->H, ix->table, b->codes + (size_t)(b->added + s) * ix->code_bytes(),
                            b->slots + b->added + s);
         HIP_TRY(hipGetLastError());
     }
@@ -247,8 +309,9 @@ int pqt_builder_finish(pqt_builder* b, pqt_index** out) {
     BUILD_TRY(hipMalloc(&temp, temp_bytes ? temp_bytes : 1));
     BUILD_TRY(hipcub::DeviceScan::ExclusiveSum(temp, temp_bytes, counts, offsets, (size_t)ix->H + 1));
     // codes in the order of the ids
-    BUILD_TRY(hipMalloc(reinterpret_cast<void**>(&codes_out), (size_t)N * ix->M));
-    hipLaunchKernelGGL(pqt::permute_codes_kernel, dim3(nb), dim3(tb), 0, 0, b->codes, ids_out, N, (int)ix->M, codes_out);
+    BUILD_TRY(hipMalloc(reinterpret_cast<void**>(&codes_out), (size_t)N * ix->code_bytes()));
+    hipLaunchKernelGGL(pqt::permute_codes_kernel, dim3(nb), dim3(tb), 0, 0, b->codes, ids_out, N, (int)ix->code_bytes(),
+                       codes_out);
     BUILD_TRY(hipGetLastError());
     BUILD_TRY(hipDeviceSynchronize());
 #undef BUILD_TRY
@@ -257,7 +320,7 @@ int pqt_builder_finish(pqt_builder* b, pqt_index** out) {
     ix->offsets = offsets;
     ix->ids = ids_out;
     ix->codes = codes_out;
-    ix->bytes_index += (uint64_t)N * (4 + ix->M);
+    ix->bytes_index += (uint64_t)N * (4 + ix->code_bytes());
     ix->N = N;
     ix->free_workspace();                 // sized for the builder's chunks and w = 1
     (void)hipFree(b->slots); (void)hipFree(b->codes); (void)hipFree(b->leaf);

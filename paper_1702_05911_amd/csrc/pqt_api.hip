@@ -2,6 +2,7 @@
 // Host code only; the three kernels live in traverse.hip, rank_bins.hip and rerank.hip.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -49,11 +50,19 @@ namespace {
 
 constexpr size_t kAlign = 256;
 
+// largest byte at an even position (the pair bytes of (pair, lambda) codes); n = number of byte pairs
+__global__ void max_even_byte_kernel(const uint8_t* codes, uint64_t n, uint32_t* out) {
+    uint32_t worst = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+        worst = max(worst, (uint32_t)codes[2 * i]);
+    atomicMax(out, worst);
+}
+
 struct FileHeader {
     char magic[8];
     uint32_t version, D, P, k1, k2, M;
     uint64_t N, H;
-    uint32_t T, C, offset_bits, reserved;
+    uint32_t T, C, offset_bits, code_format;
 };
 static_assert(sizeof(FileHeader) == 64, "header prefix is 64 bytes");
 
@@ -101,7 +110,7 @@ bool can_fuse_ranking(const pqt_index* ix, int k, int w) {
     const int threads = rerank_threads(ix);
     const pqt::RankOffsets ro = pqt::rank_offsets(ix->P, R, ix->T, ix->hashed);
     if (ro.Tcap > pqt::rerank_fused_tuples_per_thread() * threads) return false;
-    return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total) <= g_lds_limit;
+    return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total, (int)ix->code_format) <= g_lds_limit;
 }
 
 int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
@@ -109,7 +118,7 @@ int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
     const size_t l1 = pqt::traverse_lds_bytes(ix->D, ix->P, ix->k1, ix->k2, ix->M, w);
     const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed ? 1 : 2);   // 2: room for the slots tap
     const int threads = rerank_threads(ix);
-    const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0);
+    const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0, (int)ix->code_format);
     if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)
         return fail(PQT_EUNSUPPORTED,
                     "LDS budget exceeded (traverse %zu, rank %zu, rerank %zu bytes of %zu) for D=%u M=%u k1=%u R=%d T=%u C=%u",
@@ -151,8 +160,11 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     *out = nullptr;
     if (location != PQT_HOST && location != PQT_DEVICE)
         return fail(PQT_EINVAL, "pqt_index_from_arrays: location must be PQT_HOST or PQT_DEVICE");
-    if (!a->C1 || !a->C2 || !a->tbl_i || !a->tbl_j || !a->tbl_lambda || !a->cc || !a->offsets ||
-        (a->N > 0 && (!a->ids || !a->codes)))
+    if (a->code_format != PQT_CODES_TABLE && a->code_format != PQT_CODES_PAIR_LAMBDA)
+        return fail(PQT_EINVAL, "pqt_index_from_arrays: code_format %u", a->code_format);
+    const bool pair_codes = a->code_format == PQT_CODES_PAIR_LAMBDA;   // the line table is not used then
+    if (!a->C1 || !a->C2 || !a->cc || !a->offsets || (a->N > 0 && (!a->ids || !a->codes)) ||
+        (!pair_codes && (!a->tbl_i || !a->tbl_j || !a->tbl_lambda)))
         return fail(PQT_EINVAL, "pqt_index_from_arrays: null array");
     const pqt_index_arrays& h = *a;
     if (h.D == 0 || h.P == 0 || h.k1 == 0 || h.k2 == 0 || h.M == 0 || h.H == 0 || h.D % h.P || h.D % h.M ||
@@ -171,6 +183,9 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     if ((long double)h.H > K) return fail(PQT_EFORMAT, "H exceeds the number of bins");
     if (h.T < 1 || h.T > PQT_MAX_T || h.C < 1 || h.C > PQT_MAX_C)
         return fail(PQT_EFORMAT, "default budgets T=%u C=%u out of range", h.T, h.C);
+    const uint32_t npairs = h.k1 * (h.k1 - 1) / 2;
+    if (pair_codes && (h.k1 < 2 || npairs > 256))
+        return fail(PQT_EUNSUPPORTED, "k1=%u: (pair, lambda) codes number the %u centroid pairs in one byte", h.k1, npairs);
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev)
@@ -195,8 +210,28 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     for (size_t s = 0; s < h.H; ++s)
         if (off[s + 1] < off[s]) return fail(PQT_EFORMAT, "offsets not monotone at slot %zu", s);
     const size_t ntab = (size_t)h.M * 256;
-    for (size_t e = 0; e < ntab; ++e)
+    for (size_t e = 0; e < ntab && !pair_codes; ++e)
         if (h.tbl_i[e] >= h.k1 || h.tbl_j[e] >= h.k1) return fail(PQT_EFORMAT, "code table names centroid >= k1");
+    const size_t code_bytes = (size_t)h.M * (pair_codes ? 2 : 1);
+    if (pair_codes && h.N > 0) {       // every pair byte must name a pair
+        uint32_t worst = 0;
+        if (location == PQT_HOST) {
+            for (size_t v = 0; v < (size_t)h.N; ++v)
+                for (size_t m = 0; m < h.M; ++m) worst = std::max<uint32_t>(worst, h.codes[v * code_bytes + 2 * m]);
+        } else {
+            uint32_t* dmax = nullptr;
+            HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dmax), sizeof(uint32_t)));
+            hipError_t e = hipMemset(dmax, 0, sizeof(uint32_t));
+            if (e == hipSuccess) {
+                hipLaunchKernelGGL(max_even_byte_kernel, dim3(1024), dim3(256), 0, 0, h.codes, (uint64_t)h.N * h.M, dmax);
+                e = hipGetLastError();
+            }
+            if (e == hipSuccess) e = hipMemcpy(&worst, dmax, sizeof(uint32_t), hipMemcpyDeviceToHost);
+            (void)hipFree(dmax);
+            if (e != hipSuccess) return fail(PQT_EHIP, "checking the codes: %s", hipGetErrorString(e));
+        }
+        if (worst >= npairs) return fail(PQT_EFORMAT, "a code names centroid pair %u of %u", worst, npairs);
+    }
 
     // squared norms of the centroid sub-parts, and the code table with its pair distance folded in
     std::vector<float> c1n((size_t)h.M * h.k1);
@@ -221,7 +256,20 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
                     c2t[((pi * (dp / 4) + d / 4) * h.k2 + j) * 4 + d % 4] = h.C2[(pi * h.k2 + j) * dp + d];
     }
     std::vector<pqt::CodeEntry> table(ntab);
-    for (size_t m = 0; m < h.M; ++m)
+    if (pair_codes) {
+        // entry = pair number of i < j in lexicographic order; kc holds ||c_i - c_j||^2 of the sub-part
+        for (size_t m = 0; m < h.M; ++m) {
+            size_t e = m * 256;
+            for (uint32_t i = 0; i < h.k1; ++i)
+                for (uint32_t j = i + 1; j < h.k1; ++j, ++e) {
+                    table[e].ij = i | (j << 8);
+                    table[e].lam = 0.0f;
+                    table[e].kc = h.cc[(m * h.k1 + i) * h.k1 + j];
+                }
+            for (; e < (m + 1) * 256; ++e) table[e] = pqt::CodeEntry{0u, 0.0f, 0.0f};
+        }
+    }
+    for (size_t m = 0; m < h.M && !pair_codes; ++m)
         for (size_t c = 0; c < 256; ++c) {
             const size_t e = m * 256 + c;
             table[e].ij = (uint32_t)h.tbl_i[e] | ((uint32_t)h.tbl_j[e] << 8);
@@ -246,12 +294,19 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     ix->D = h.D; ix->P = h.P; ix->k1 = h.k1; ix->k2 = h.k2; ix->M = h.M; ix->T = h.T; ix->C = h.C;
     ix->N = h.N; ix->H = h.H; ix->device = device;
     ix->hashed = (long double)h.H != K;
+    ix->code_format = h.code_format;
     try {
         ix->h_C1.assign(h.C1, h.C1 + (size_t)h.P * h.k1 * dp);
         ix->h_C2.assign(h.C2, h.C2 + (size_t)h.P * h.k1 * h.k2 * dp);
-        ix->h_ti.assign(h.tbl_i, h.tbl_i + ntab);
-        ix->h_tj.assign(h.tbl_j, h.tbl_j + ntab);
-        ix->h_lam.assign(h.tbl_lambda, h.tbl_lambda + ntab);
+        if (h.tbl_i && h.tbl_j && h.tbl_lambda) {
+            ix->h_ti.assign(h.tbl_i, h.tbl_i + ntab);
+            ix->h_tj.assign(h.tbl_j, h.tbl_j + ntab);
+            ix->h_lam.assign(h.tbl_lambda, h.tbl_lambda + ntab);
+        } else {                       // (pair, lambda) codes without a line table: kept as zeros
+            ix->h_ti.assign(ntab, 0);
+            ix->h_tj.assign(ntab, 0);
+            ix->h_lam.assign(ntab, 0.0f);
+        }
         ix->h_cc.assign(h.cc, h.cc + (size_t)h.M * h.k1 * h.k1);
     } catch (const std::bad_alloc&) {
         delete ix;
@@ -267,7 +322,7 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
                      &ix->bytes_index)) ||
         (rc = upload(&ix->offsets, h.offsets, ((size_t)h.H + 1) * 4, big, &ix->bytes_index)) ||
         (rc = upload(&ix->ids, h.ids, (size_t)h.N * 4, big, &ix->bytes_index)) ||
-        (rc = upload(&ix->codes, h.codes, (size_t)h.N * h.M, big, &ix->bytes_index))) {
+        (rc = upload(&ix->codes, h.codes, (size_t)h.N * code_bytes, big, &ix->bytes_index))) {
         pqt_index_free(ix);
         return rc;
     }
@@ -285,7 +340,8 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
     FileHeader h;
     memcpy(&h, hdr, sizeof(h));
     if (memcmp(h.magic, "PQTIDX1\0", 8) != 0) return fail(PQT_EFORMAT, "'%s': bad magic", path);
-    if (h.version != 1 || h.offset_bits != 32) return fail(PQT_EFORMAT, "'%s': unsupported version", path);
+    if (h.version != 1 || h.offset_bits != 32 || h.code_format > PQT_CODES_PAIR_LAMBDA)
+        return fail(PQT_EFORMAT, "'%s': unsupported version", path);
     // the sizes the arrays are read with must be sane before anything is allocated
     // (pqt_index_from_arrays repeats these checks for callers that bring their own arrays)
     if (h.D == 0 || h.P == 0 || h.k1 == 0 || h.k2 == 0 || h.M == 0 || h.H == 0 || h.D % h.P || h.D % h.M ||
@@ -308,7 +364,7 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
         cc.resize((size_t)h.M * h.k1 * h.k1);
         offsets.resize((size_t)h.H + 1);
         ids.resize((size_t)h.N);
-        codes.resize((size_t)h.N * h.M);
+        codes.resize((size_t)h.N * h.M * (h.code_format == PQT_CODES_PAIR_LAMBDA ? 2 : 1));
     } catch (const std::bad_alloc&) {
         return fail(PQT_ENOMEM, "host allocation failed while reading '%s'", path);
     }
@@ -323,6 +379,7 @@ int pqt_index_load(const char* path, int device, pqt_index** out) {
     a.N = h.N; a.H = h.H; a.D = h.D; a.P = h.P; a.k1 = h.k1; a.k2 = h.k2; a.M = h.M; a.T = h.T; a.C = h.C;
     a.C1 = C1.data(); a.C2 = C2.data(); a.tbl_i = ti.data(); a.tbl_j = tj.data(); a.tbl_lambda = lam.data();
     a.cc = cc.data(); a.offsets = offsets.data(); a.ids = ids.data(); a.codes = codes.data();
+    a.code_format = h.code_format;
     const int rc = pqt_index_from_arrays(&a, PQT_HOST, device, out);
     if (rc != PQT_OK) {
         char msg[512];
@@ -343,7 +400,7 @@ int pqt_index_save(const pqt_index* ix, const char* path) {
     memset(&h, 0, sizeof(h));
     memcpy(h.magic, "PQTIDX1\0", 8);
     h.version = 1; h.D = ix->D; h.P = ix->P; h.k1 = ix->k1; h.k2 = ix->k2; h.M = ix->M;
-    h.N = ix->N; h.H = ix->H; h.T = ix->T; h.C = ix->C; h.offset_bits = 32;
+    h.N = ix->N; h.H = ix->H; h.T = ix->T; h.C = ix->C; h.offset_bits = 32; h.code_format = ix->code_format;
     memcpy(hdr, &h, sizeof(h));
     bool ok = fwrite(hdr, 1, kAlign, f.get()) == kAlign;
     auto put = [&](const void* src, size_t bytes) {
@@ -377,7 +434,7 @@ int pqt_index_save(const pqt_index* ix, const char* path) {
     };
     int rc;
     if ((rc = put_device(ix->offsets, ((size_t)ix->H + 1) * 4)) || (rc = put_device(ix->ids, (size_t)ix->N * 4)) ||
-        (rc = put_device(ix->codes, (size_t)ix->N * ix->M)))
+        (rc = put_device(ix->codes, (size_t)ix->N * ix->code_bytes())))
         return rc;
     if (!ok || fflush(f.get()) != 0) return fail(PQT_EIO, "write to '%s' failed", path);
     return PQT_OK;
@@ -398,7 +455,7 @@ int pqt_index_export(const pqt_index* ix, const pqt_index_arrays* dst, int locat
     const hipMemcpyKind kind = location == PQT_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
     if (dst->offsets) HIP_TRY(hipMemcpy(const_cast<uint32_t*>(dst->offsets), ix->offsets, ((size_t)ix->H + 1) * 4, kind));
     if (dst->ids && ix->N) HIP_TRY(hipMemcpy(const_cast<uint32_t*>(dst->ids), ix->ids, (size_t)ix->N * 4, kind));
-    if (dst->codes && ix->N) HIP_TRY(hipMemcpy(const_cast<uint8_t*>(dst->codes), ix->codes, (size_t)ix->N * ix->M, kind));
+    if (dst->codes && ix->N) HIP_TRY(hipMemcpy(const_cast<uint8_t*>(dst->codes), ix->codes, (size_t)ix->N * ix->code_bytes(), kind));
     return PQT_OK;
 }
 
@@ -418,6 +475,7 @@ int pqt_index_info(const pqt_index* ix, pqt_info* out) {
     if (!ix || !out) return fail(PQT_EINVAL, "pqt_index_info: null argument");
     out->N = ix->N; out->H = ix->H; out->D = ix->D; out->P = ix->P; out->k1 = ix->k1; out->k2 = ix->k2;
     out->M = ix->M; out->T = ix->T; out->C = ix->C; out->device = ix->device;
+    out->code_format = ix->code_format; out->code_bytes = ix->code_bytes();
     out->bytes_index = ix->bytes_index; out->bytes_workspace = ix->bytes_workspace;
     return PQT_OK;
 }
@@ -481,6 +539,8 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ra.offsets = ix->offsets; ra.L_d = ix->ws_Ld; ra.L_id = ix->ws_Lid;
     ra.runs = ix->ws_runs; ra.meta = ix->ws_meta; ra.counters = ix->ws_counters; ra.order = ix->ws_order;
     ra.n_tuples = tp.n_tuples; ra.tuples = tp.tuples; ra.tuple_keys = tp.tuple_keys; ra.slots = tp.slots;
+    if (tp.lut && ix->code_format == PQT_CODES_PAIR_LAMBDA)
+        return fail(PQT_EINVAL, "pqt_query_batch_debug: the lut tap is the table of the one-byte code format");
     const bool rerank_taps = tp.n_cand || tp.cand_ids || tp.scores || tp.lut || tp.n_slots;
     const bool head = pqt::rank_has_head(ra);
     // the few queries the head pass cannot finish are ranked in full by their re-rank workgroup
@@ -491,6 +551,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     pqt::RerankArgs ca;
     ca.nq = nq; ca.M = ix->M; ca.k1 = ix->k1; ca.T = ix->T; ca.C = ix->C; ca.k = k;
     ca.threads = rerank_threads(ix);
+    ca.code_format = (int)ix->code_format;
     ca.a = ix->ws_a; ca.table = ix->table; ca.runs = ix->ws_runs; ca.meta = ix->ws_meta;
     ca.ids = ix->ids; ca.codes = ix->codes; ca.out_ids = out_ids; ca.out_dists = out_dists;
     ca.todo = ix->ws_order; ca.todo_count = ix->ws_counters;

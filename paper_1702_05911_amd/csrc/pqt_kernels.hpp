@@ -82,10 +82,13 @@ struct RerankArgs {
     int threads;              // workgroup size (multiple of 64)
     const float* a;           // nq x M x k1
     const CodeEntry* table;   // M x 256
+    int code_format;          // 0: codes are entries of the table, one byte per sub-part;
+                              // 1: two bytes per sub-part, (centroid pair, lambda level); the table is then
+                              //    indexed by pair number and its kc field holds ||c_i - c_j||^2
     const uint2* runs;
     const uint2* meta;
     const uint32_t* ids;
-    const uint8_t* codes;     // N x M
+    const uint8_t* codes;     // N x M (N x 2M for code format 1)
     // Queries the ranking head pass left unfinished take longest, so they go first: the first
     // `early` workgroups take entries of todo[0 .. *todo_count) (the rest of them exit at once), then
     // workgroup early + q takes query q unless one of the first did.  early = 0: workgroup q, query q.
@@ -101,7 +104,7 @@ struct RerankArgs {
     float* lut;               // nq x M x 256
 };
 // rank_lds: LDS bytes of the full ranking pass when the kernel also runs it (0: it does not)
-size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds);
+size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format);
 // tuples per thread the in-kernel ranking can hold: fusing needs min(T, R^2) <= that * threads
 int rerank_fused_tuples_per_thread();
 // fused: the full ranking pass of the queries whose meta.x is kMetaTodo runs inside the kernel

@@ -30,14 +30,15 @@ struct RerankLds {
     uint32_t surv, spos, lut, a, run_src, run_start, skey, hist, misc, total;
 };
 
-static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, size_t rank_lds) {
+static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format) {
     RerankLds L;
     (void)threads;
     L.kpad = next_pow2(k);
     L.scap = 2 * L.kpad < 256 ? 256 : 2 * L.kpad;
     size_t o = 0;
-    L.lut = (uint32_t)o;       o += sizeof(float) * M * 256;   // at offset 0: lookups need no base register;
-                                                               // also the scan scratch of the exact fallback
+    // at offset 0: lookups need no base register; also the scan scratch of the exact fallback.
+    // One float per table entry, or (b^2, a^2 - b^2, c^2, -) per centroid pair for (pair, lambda) codes.
+    L.lut = (uint32_t)o;       o += sizeof(float) * M * 256 * (code_format == 1 ? 4 : 1);
     L.skey = (uint32_t)o;      o += sizeof(uint32_t) * ((C + 3) & ~3);
     L.surv = (uint32_t)o;      o += sizeof(unsigned long long) * L.scap;
     L.hist = (uint32_t)o;      o += sizeof(uint32_t) * kHistSize;
@@ -54,8 +55,8 @@ static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, 
     return L;
 }
 
-size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds) {
-    return rerank_layout(M, k1, T, C, k, threads, rank_lds).total;
+size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format) {
+    return rerank_layout(M, k1, T, C, k, threads, rank_lds, code_format).total;
 }
 
 // Position p of the candidate list -> position in ids/codes: the run r with
@@ -135,6 +136,15 @@ struct RunCursor {
     uint32_t delta;        // run_src[run] - run_start[run]: position in ids/codes = candidate position + delta
 };
 
+// (pair, lambda level) codes: the summand of Eq. 9 for one sub-part from the pair's LDS entry
+// (b^2, a^2 - b^2, c^2) and the level; lambda = (level - 64) / 128 is exact in fp32.
+constexpr int kPairLambda = -1;      // value of MW that selects this code format
+__device__ __forceinline__ float pair_lambda_term(const float4* plut, int m, uint32_t pair, uint32_t level) {
+    const float4 e = plut[m * 256 + pair];
+    const float lam = fmaf((float)level, 0.0078125f, -0.5f);
+    return fmaf(fmaf(lam, lam, -lam), e.z, fmaf(lam, e.y, e.x));
+}
+
 // Scores U candidate positions per thread (base + u*nt + tid).  CHECK: positions may pass nc.
 template <int MW, int U, bool CHECK, bool TAPS>
 __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int base, int nc, int tid, int nt,
@@ -196,6 +206,21 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
                 s += lut_at(j * 4 + 2, (wv >> 16) & 0xffu);
                 s += lut_at(j * 4 + 3, wv >> 24);
             }
+        } else if (MW == kPairLambda) {
+            // two bytes per sub-part; M is even whenever there are two or four tree parts
+            const float4* plut = reinterpret_cast<const float4*>(lut);
+            s = 0.0f;
+            if ((M & 1) == 0) {
+                const uint32_t* cwp = reinterpret_cast<const uint32_t*>(g.codes + (size_t)src[u] * 2 * M);
+                for (int j = 0; j < M / 2; ++j) {
+                    const uint32_t wv = cwp[j];
+                    s += pair_lambda_term(plut, 2 * j, wv & 0xffu, (wv >> 8) & 0xffu);
+                    s += pair_lambda_term(plut, 2 * j + 1, (wv >> 16) & 0xffu, wv >> 24);
+                }
+            } else {
+                const uint8_t* code = g.codes + (size_t)src[u] * 2 * M;
+                for (int m = 0; m < M; ++m) s += pair_lambda_term(plut, m, code[2 * m], code[2 * m + 1]);
+            }
         } else {
             const uint8_t* code = g.codes + (size_t)src[u] * M;
             s = 0.0f;
@@ -212,7 +237,8 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
     }
 }
 
-// MW = 32-bit words per code (M/4) for M in {4, 8, 16, 32}; 0 = any other M (byte loads).
+// MW = 32-bit words per code (M/4) for M in {4, 8, 16, 32}; 0 = any other M (byte loads);
+// kPairLambda = codes hold (centroid pair, lambda level) per sub-part, scored by Eq. 9 directly.
 // FUSED: a query whose meta.x is kMetaTodo (the ranking head pass could not finish it) is first
 // ranked in full by this workgroup, which leaves the run list directly in LDS.
 template <int MW, bool TAPS, bool FUSED>
@@ -301,6 +327,11 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
             const int m = e >> 8;
             const float b2 = sa[m * k1 + (ent[u].ij & 0xffu)];
             const float a2 = sa[m * k1 + ((ent[u].ij >> 8) & 0xffu)];
+            if (MW == kPairLambda) {
+                // entry = centroid pair number; its kc field holds c^2
+                reinterpret_cast<float4*>(lut)[e] = make_float4(b2, a2 - b2, ent[u].kc, 0.0f);
+                continue;
+            }
             // Eq. 9 rearranged: b^2 + lam (a^2 - b^2) + (lam^2 - lam) c^2, the last term folded per code value
             const float v = fmaf(ent[u].lam, a2 - b2, b2) + ent[u].kc;
             lut[e] = v;
@@ -474,6 +505,10 @@ template <bool TAPS, bool FUSED>
 static void launch_rerank_t(const RerankArgs& a, const RerankLds& L, const RankArgs& rk, const RankOffsets& RL,
                             hipStream_t s) {
     const dim3 grid((unsigned)(a.nq + a.early)), block(a.threads);
+    if (a.code_format == 1) {
+        hipLaunchKernelGGL((rerank_kernel<kPairLambda, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL);
+        return;
+    }
     switch ((a.M % 4 == 0) ? a.M / 4 : 0) {
         case 1: hipLaunchKernelGGL((rerank_kernel<1, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
         case 2: hipLaunchKernelGGL((rerank_kernel<2, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
@@ -496,7 +531,8 @@ hipError_t launch_rerank(const RerankArgs& a, const RankArgs* fused, hipStream_t
         RL = rank_offsets(rk.P, rk.R, rk.T, rk.hashed);
         if (RL.Tcap > rerank_fused_tuples_per_thread() * a.threads) return hipErrorInvalidValue;
     }
-    const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads, fused ? RL.total : 0);
+    if (a.code_format == 1 && a.lut) return hipErrorInvalidValue;      // that tap is the one-byte format's table
+    const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads, fused ? RL.total : 0, a.code_format);
     if (fused) launch_rerank_t<false, true>(a, L, rk, RL, s);
     else if (taps) launch_rerank_t<true, false>(a, L, rk, RL, s);
     else launch_rerank_t<false, false>(a, L, rk, RL, s);
@@ -512,7 +548,10 @@ hipError_t configure_rerank(size_t max_dynamic_lds) {
         reinterpret_cast<const void*>(rerank_kernel<4, true, false>),  reinterpret_cast<const void*>(rerank_kernel<8, true, false>),
         reinterpret_cast<const void*>(rerank_kernel<0, false, true>),  reinterpret_cast<const void*>(rerank_kernel<1, false, true>),
         reinterpret_cast<const void*>(rerank_kernel<2, false, true>),  reinterpret_cast<const void*>(rerank_kernel<4, false, true>),
-        reinterpret_cast<const void*>(rerank_kernel<8, false, true>)};
+        reinterpret_cast<const void*>(rerank_kernel<8, false, true>),
+        reinterpret_cast<const void*>(rerank_kernel<kPairLambda, false, false>),
+        reinterpret_cast<const void*>(rerank_kernel<kPairLambda, true, false>),
+        reinterpret_cast<const void*>(rerank_kernel<kPairLambda, false, true>)};
     for (const void* kfn : kernels) {
         hipFuncAttributes attr;
         hipError_t e = hipFuncGetAttributes(&attr, kfn);

@@ -78,6 +78,18 @@ def check_query_stages(ix, y, taps, q, k, w, T, C, out_ids, out_dists, exact=Fal
     cand_r = ix.ids[pos_r].astype(np.int64)
     assert np.array_equal(taps["cand_ids"][q][:nc], cand_r), "S5 candidate ids"
 
+    if ix.code_format == 1:
+        # ---- S6-S7 (pair, lambda) codes: Eq. 9 per candidate, no table; float comparison -----------------
+        sc_g = taps["scores"][q][:nc]
+        sc_o = Q.score_pair_lambda(a_g.astype(np.float64), ix.cc, ix.codes[pos_r])
+        assert close(sc_g, sc_o, scale), "S7 scores vs oracle formula on the GPU's a"
+        if exact:
+            assert np.array_equal(sc_g.astype(np.float64), tr.scores), "S7 scores (exact)"
+        ids_r, d_r = Q.top_k(sc_g, cand_r, k)
+        assert np.array_equal(out_ids[q], ids_r), "S8 ids replay"
+        assert np.array_equal(out_dists[q], d_r.astype(np.float32)), "S8 distances replay"
+        return tr
+
     # ---- S6 LUT (float), S7 scores replayed on the GPU's LUT (fp32, ascending m) ------------------------
     lut_g = taps["lut"][q]
     lut_o = Q.build_lut(a_g.astype(np.float64), ix.tbl_i, ix.tbl_j, ix.tbl_lam, ix.cc.astype(np.float64))

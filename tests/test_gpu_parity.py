@@ -29,7 +29,8 @@ def pqt():
 def _run_debug(pqt, gix, Y, k, w):
     import torch
     yq = torch.from_numpy(np.ascontiguousarray(Y)).cuda()
-    ids, dists, taps = pqt.pqt_query_batch_debug(gix, yq, k, w)
+    names = tuple(n for n in pqt._TAP_FIELDS if n != "lut" or pqt.pqt_index_info(gix)["code_format"] == 0)
+    ids, dists, taps = pqt.pqt_query_batch_debug(gix, yq, k, w, taps=names)
     torch.cuda.synchronize()
     ids2, dists2 = pqt.pqt_query_batch(gix, yq, k, w)
     torch.cuda.synchronize()
@@ -384,6 +385,92 @@ def test_native_builder(pqt, tiny, tmp_path):
             worst = max(worst, d[nix.codes[t, m]] - d.min())
     assert worst <= 1e-4
     # the index is input data: full stage-wise parity on it
+    same, _ = _stagewise(pqt, nix, path, Y[:30], cfg.k, cfg.w, cfg.T, cfg.C)
+    assert same >= 27
+
+
+def test_pair_lambda_codes(pqt, tiny_pair, tmp_path):
+    """Codes stored as (centroid pair, lambda level): stage-wise parity of the query path on an
+    oracle-built index; the lut tap is refused; a pair byte beyond the last pair is a format error."""
+    import torch
+    cfg, X, Y, ix = tiny_pair
+    path = str(tmp_path / "pair.pqt")
+    IO.write_index(path, ix)
+    same, decided = _stagewise(pqt, ix, path, Y[:40], cfg.k, cfg.w, cfg.T, cfg.C)
+    assert same >= 36
+    # ragged budgets: few candidates, one tuple
+    _stagewise(pqt, ix, path, Y[:8], 5, 1, 1, 7)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        inf = pqt.pqt_index_info(gix)
+        assert inf["code_format"] == pqt.PQT_CODES_PAIR_LAMBDA and inf["code_bytes"] == 2 * cfg.M
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_query_batch_debug(gix, torch.from_numpy(Y[:2]).cuda(), cfg.k, cfg.w, taps=("lut",))
+        assert e.value.code == pqt.PQT_EINVAL
+        back = pqt.pqt_index_export(gix, ("codes",))["codes"]
+        assert np.array_equal(PU.to_np(back), ix.codes)
+    finally:
+        pqt.pqt_index_free(gix)
+    arrays = dict(N=ix.N, H=ix.H, D=ix.D, P=ix.P, k1=ix.k1, k2=ix.k2, M=ix.M, T=ix.T, C=ix.C, C1=ix.C1, C2=ix.C2,
+                  cc=ix.cc, offsets=ix.offsets, ids=ix.ids, codes=ix.codes.copy(), code_format=1)
+    arrays["codes"][17, 2] = ix.k1 * (ix.k1 - 1) // 2          # one past the last pair
+    for on_device in (False, True):
+        a = dict(arrays)
+        if on_device:
+            for n in ("offsets", "ids"):
+                a[n] = torch.from_numpy(arrays[n].astype(np.int64)).cuda()
+            a["codes"] = torch.from_numpy(arrays["codes"]).cuda()
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_index_from_arrays(a, 0)
+        assert e.value.code == pqt.PQT_EFORMAT
+
+
+def test_pair_lambda_native_builder(pqt, tiny_pair, tmp_path):
+    """pqt_builder_* with (pair, lambda) codes: every code names a line that is (within fp32 rounding of
+    the level-1 distances it is computed from) as near as the nearest one and the level nearest to the
+    projection on that line; the index answers queries as the oracle does on it."""
+    import torch
+    cfg, X, Y, ix = tiny_pair
+    params = dict(N=cfg.N, H=ix.H, D=ix.D, P=ix.P, k1=ix.k1, k2=ix.k2, M=ix.M, T=ix.T, C=ix.C,
+                  C1=ix.C1, C2=ix.C2, cc=ix.cc, code_format=1)
+    b = pqt.pqt_builder_create(params, 0)
+    try:
+        Xd = torch.from_numpy(X).cuda()
+        for lo, hi in ((0, 4097), (4097, cfg.N)):
+            pqt.pqt_builder_add(b, Xd[lo:hi].contiguous())
+        gix = pqt.pqt_builder_finish(b)
+    finally:
+        pqt.pqt_builder_free(b)
+    path = str(tmp_path / "native_pair.pqt")
+    try:
+        pqt.pqt_index_save(gix, path)
+    finally:
+        pqt.pqt_index_free(gix)
+    nix = IO.read_index(path)
+    assert nix.code_format == 1 and nix.codes.shape == (cfg.N, 2 * cfg.M)
+    assert np.array_equal(np.sort(nix.ids), np.arange(cfg.N, dtype=np.uint32))
+    ds = nix.D // nix.M
+    pairs = Q.centroid_pairs(nix.k1)
+    same_pair = total = 0
+    for t in np.random.default_rng(5).integers(0, cfg.N, size=300):
+        x = X[nix.ids[t]].astype(np.float64)
+        want = B.encode_pair_lambda(X[nix.ids[t]][None], nix.C1, nix.M)[0]
+        for m in range(nix.M):
+            cen = B.subpart_centroids(nix.C1, nix.M, m)
+            xs = x[m * ds:(m + 1) * ds]
+            errs = np.array([B.line_projection(xs, cen[i], cen[j])[1] for i, j in pairs])
+            i, j = pairs[nix.codes[t, 2 * m]]
+            lam, err = B.line_projection(xs, cen[i], cen[j])
+            scale = float(np.dot(xs, xs) + np.max(np.sum(cen * cen, axis=1)))
+            assert err - errs.min() <= 4e-6 * scale, (t, m, err, errs.min())
+            level = int(nix.codes[t, 2 * m + 1])
+            if 0 < level < 255:
+                assert abs(float(Q.lambda_of_level(level)) - lam) <= 0.5 / 128 + 1e-4
+            else:
+                assert lam < -0.49 or lam > 1.48
+            same_pair += int(nix.codes[t, 2 * m] == want[2 * m])
+            total += 1
+    assert same_pair >= 0.99 * total
     same, _ = _stagewise(pqt, nix, path, Y[:30], cfg.k, cfg.w, cfg.T, cfg.C)
     assert same >= 27
 
