@@ -165,6 +165,10 @@ def main():
     ap.add_argument("--also-batches", default="", metavar="B1,B2,..",
                     help="after the main measurement, answer the same queries B per call for each listed B "
                          "(queued back to back, and one call at a time for the latency)")
+    ap.add_argument("--codes", choices=("table", "pair"), default="table",
+                    help="re-rank code format: one byte per sub-part naming a table entry (default), or two bytes "
+                         "holding (centroid pair, lambda level) as in Sec. 3.3; with --M or --sweep-w also prints the "
+                         "codes' distortion")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline", action="store_true",
                     help="also for the 100M / 1B workloads (writes the index to a file for the oracle's processes)")
@@ -193,6 +197,8 @@ def main():
     if args.M:
         cfg = cfg.with_(M=args.M)
     w = args.w or cfg.w
+    code_format = 1 if args.codes == "pair" else 0
+    code_bytes = cfg.M * (2 if code_format else 1)
     dev = torch.device("cuda", 0)
     t_setup = time.perf_counter()
     X, Y, chunks = make_data(cfg, dev)
@@ -216,7 +222,8 @@ def main():
     result_tables = {}
     index = builder.build_index_native(trained_out=result_tables, chunks=chunks, N=cfg.N, D=cfg.D, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M,
                                        H=cfg.H, T=cfg.T, C=cfg.C, train_n=cfg.train_n, device=0,
-                                       chunk_rows=(1 << 20) if in_hbm_only else (1 << 18), observer=observe)
+                                       chunk_rows=(1 << 20) if in_hbm_only else (1 << 18), observer=observe,
+                                       code_format=code_format)
     runs = torch.diff(pqt.pqt_index_export(index, ("offsets",))["offsets"])
     occupancy = {"nonempty_slots": int((runs > 0).sum()), "max_run": int(runs.max()),
                  "mean_run_nonempty": float(runs[runs > 0].float().mean())}
@@ -317,7 +324,7 @@ def main():
         Tn = min(cfg.T, R ** cfg.P)
         lg = max(1, (Tn - 1).bit_length())
         rank_ops = nq * (Tn // 2) * lg * (lg + 1) // 2
-    rerank_bytes = nq * (mean_cand * cfg.M + cfg.k * (8 + 4 + 4) + cfg.M * cfg.k1 * 4 + mean_runs * 8)
+    rerank_bytes = nq * (mean_cand * code_bytes + cfg.k * (8 + 4 + 4) + cfg.M * cfg.k1 * 4 + mean_runs * 8)
     stages = [
         {"kernel": "traverse_kernel", "ms": stage_ms[0], "bound": "mfma", "achieved": trav_flops / (stage_ms[0] * 1e-3) / 1e12,
          "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "hbm_GBs": trav_bytes / (stage_ms[0] * 1e-3) / 1e9},
@@ -340,7 +347,7 @@ def main():
     stages[2]["lds_lookup_frac"] = stages[2]["lds_lookups_per_s"] / (256 * 32 * 2.4e9)
     dom = max(stages, key=lambda s: s["ms"])
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                "unit": dom["unit"], "frac": dom["frac"], "traffic": measured_traffic(dom["kernel"], cfg.name, w)}
+                "unit": dom["unit"], "frac": dom["frac"], "traffic": None if (code_format or args.M) else measured_traffic(dom["kernel"], cfg.name, w)}
 
     ms_per_step = elapsed / args.steps * 1e3
     result = {
@@ -350,7 +357,7 @@ def main():
         "ms_per_step_with_stage_events": elapsed_profiled / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} D={cfg.D} nq={cfg.nq} P={cfg.P} k1={cfg.k1} k2={cfg.k2} "
-                               f"M={cfg.M} H={cfg.H} w={w} T={cfg.T} C={cfg.C} k={cfg.k}",
+                               f"M={cfg.M} H={cfg.H} w={w} T={cfg.T} C={cfg.C} k={cfg.k}" + (" codes=(pair,lambda)" if code_format else ""),
                    "queries_per_call": B, "mean_candidates": mean_cand, "mean_runs": mean_runs, **occupancy},
         "recall": rec, "tuples_needed": tuples_needed, "stage_ms": stage_ms, "stages": stages, "roofline": roofline, "setup_s": setup_s,
         "measured_peaks": {"hbm_read_GBs": hbm_meas, "mfma_f32_TFLOPs": mfma_meas,
@@ -397,17 +404,25 @@ def main():
         Xs = chunks(0, min(100_000, cfg.N))[ids_e[pick]]
         tr = result_tables
         ds_ = cfg.D // cfg.M
-        err = torch.zeros((), device=dev, dtype=torch.float64)
+        err = torch.zeros(pick.numel(), device=dev, dtype=torch.float64)
+        pair_ij = torch.tensor([(i, j) for i in range(cfg.k1) for j in range(i + 1, cfg.k1)], device=dev).reshape(-1, 2)
         for m in range(cfg.M):
             p_, lo_ = (m * ds_) // (cfg.D // cfg.P), (m * ds_) % (cfg.D // cfg.P)
             cen = torch.from_numpy(tr["C1"][p_][:, lo_:lo_ + ds_]).to(dev)
-            ti_ = torch.from_numpy(tr["tbl_i"][m].astype(np.int64)).to(dev)
-            tj_ = torch.from_numpy(tr["tbl_j"][m].astype(np.int64)).to(dev)
-            lam_ = torch.from_numpy(tr["tbl_lam"][m]).to(dev)[:, None]
-            pts = (1.0 - lam_) * cen[ti_] + lam_ * cen[tj_]
-            diff = Xs[:, m * ds_:(m + 1) * ds_] - pts[codes_e[:, m]]
-            err += (diff.double() ** 2).sum()
-        result["distortion"] = {"mean_squared_error": float(err / pick.numel()), "vectors": int(pick.numel()), "M": cfg.M}
+            if code_format:
+                ij = pair_ij[codes_e[:, 2 * m]]
+                lam_ = ((codes_e[:, 2 * m + 1].float() - 96.0) / 32.0)[:, None]
+                rec = (1.0 - lam_) * cen[ij[:, 0]] + lam_ * cen[ij[:, 1]]
+            else:
+                ti_ = torch.from_numpy(tr["tbl_i"][m].astype(np.int64)).to(dev)
+                tj_ = torch.from_numpy(tr["tbl_j"][m].astype(np.int64)).to(dev)
+                lam_ = torch.from_numpy(tr["tbl_lam"][m]).to(dev)[:, None]
+                rec = ((1.0 - lam_) * cen[ti_] + lam_ * cen[tj_])[codes_e[:, m]]
+            diff = Xs[:, m * ds_:(m + 1) * ds_] - rec
+            err += (diff.double() ** 2).sum(dim=1)
+        # the columns of Table 3: smallest, largest and average squared error over the vectors
+        result["distortion"] = {"min": float(err.min()), "max": float(err.max()), "mean_squared_error": float(err.mean()),
+                                "vectors": int(pick.numel()), "M": cfg.M, "code_bytes": code_bytes}
         del ex
     extra = []
     for Bx in [int(v) for v in args.also_batches.split(",") if v]:

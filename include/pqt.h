@@ -53,7 +53,8 @@ typedef struct pqt_index pqt_index;   /* opaque; owns all device and host memory
  *   PQT_CODES_PAIR_LAMBDA  the tuple stored directly in "1+1 bytes" per sub-part (Sec. 3.3): byte 2m is
  *                          the number of the centroid pair i < j in lexicographic order
  *                          (i (2 k1 - i - 1) / 2 + j - i - 1; needs k1 (k1 - 1) / 2 <= 256), byte 2m+1 the
- *                          level of lambda = (level - 64) / 128; 2M bytes per vector.  The score is Eq. 9
+ *                          level of lambda = (level - 96) / 32, i.e. -3 .. 4.97 in steps of 1/32;
+ *                          2M bytes per vector.  The score is Eq. 9
  *                          evaluated per candidate; the line table is not used and may be NULL.
  */
 #define PQT_CODES_TABLE        0
@@ -136,10 +137,11 @@ int pqt_index_from_arrays(const pqt_index_arrays* arrays, int location, int devi
  *                       pqt_builder_free.  Synchronises the device.
  * A code byte is the nearest of the 256 code points of its sub-part, with distances from
  * Eq. 9 on the vector's own level-1 distances (fp32); ties go to the smaller code value.
- * With params->code_format == PQT_CODES_PAIR_LAMBDA a sub-part's code is the centroid pair
- * whose line is nearest to the sub-vector (projection error from the same level-1 distances
- * and the pair distance table; ties: smaller pair number; pairs of coinciding centroids never
- * win) and the level nearest to the projection's lambda, clamped to 0..255.
+ * With params->code_format == PQT_CODES_PAIR_LAMBDA a sub-part's code is the nearest of the
+ * points (pair, level) stand for: per centroid pair the level nearest to the projection's
+ * lambda (clamped to 0..255), then the pair whose point is nearest by Eq. 9 on the same
+ * level-1 distances and the pair distance table (ties: smaller pair number; pairs of
+ * coinciding centroids never win).
  * Errors: PQT_EINVAL (null, N = 0, more or fewer than N vectors), PQT_EFORMAT /
  * PQT_EUNSUPPORTED as for pqt_index_from_arrays, PQT_ENOMEM, PQT_EHIP.
  */

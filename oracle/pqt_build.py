@@ -249,17 +249,38 @@ def encode_batch(X, C1, M, tbl_i, tbl_j, tbl_lam):
 
 
 def encode_pair_lambda(X, C1, M):
-    """Code format 1 (Eq. 7 stored directly, Sec. 3.3 "Offline computation"): per sub-part the
-    centroid pair whose line is nearest to the sub-vector (smallest projection error; ties: first
-    pair), then the grid level nearest to the projection's lambda.  Two bytes per sub-part."""
-    from .pqt_query import level_of_lambda
+    """Code format 1 (Eq. 7 stored directly, Sec. 3.3 "Offline computation").  A (pair, level) code
+    stands for the point (1-lam) c_i + lam c_j with lam on the level grid, and a sub-vector gets the
+    code of the NEAREST such point (ties: smaller pair number).  On one line the
+    error is quadratic in lam, so its nearest grid point is the level nearest to the projection's
+    lambda (halves go up; clamped to a byte); the pairs are then compared by the error of that point.  (Choosing the
+    line by its unclamped projection error instead often picks a line whose projection lies far
+    outside what a byte of lambda can express.)  Two bytes per sub-part."""
+    from .pqt_query import lambda_of_level, level_of_lambda
     n, D = X.shape
     ds = D // M
+    k1 = C1.shape[1]
     codes = np.zeros((n, 2 * M), dtype=np.uint8)
     for m in range(M):
-        pair, lam, _ = best_lines(np.asarray(X[:, m * ds:(m + 1) * ds], dtype=np.float64), subpart_centroids(C1, M, m))
-        codes[:, 2 * m] = pair
-        codes[:, 2 * m + 1] = level_of_lambda(lam)
+        cen = subpart_centroids(C1, M, m)
+        Xs = np.asarray(X[:, m * ds:(m + 1) * ds], dtype=np.float64)
+        best_err = np.full(n, np.inf)
+        codes[:, 2 * m + 1] = level_of_lambda(0.0)        # no usable pair: pair 0 at lambda = 0
+        pid = 0
+        for i in range(k1):
+            for j in range(i + 1, k1):
+                u = cen[j] - cen[i]
+                uu = float(np.dot(u, u))
+                if uu > 0.0:
+                    level = level_of_lambda(((Xs - cen[i][None]) @ u) / uu)
+                    lam = lambda_of_level(level)
+                    r = Xs - ((1.0 - lam)[:, None] * cen[i][None] + lam[:, None] * cen[j][None])
+                    err = np.sum(r * r, axis=1)
+                    better = err < best_err
+                    best_err[better] = err[better]
+                    codes[better, 2 * m] = pid
+                    codes[better, 2 * m + 1] = level[better]
+                pid += 1
     return codes
 
 

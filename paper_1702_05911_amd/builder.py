@@ -247,10 +247,12 @@ def train(Xt, *, P, k1, k2, M, iters=20, table_train_n=100_000):
 
 
 def build_index_native(*, chunks, N, D, P, k1, k2, M, H=None, T=1024, C=4096, train_n=None, iters=20,
-                       device=0, chunk_rows=1 << 20, table_train_n=100_000, observer=None, trained_out=None):
+                       device=0, chunk_rows=1 << 20, table_train_n=100_000, observer=None, trained_out=None,
+                       code_format=0):
     """The same index built by the library's own streaming builder (pqt_builder_*): codebooks and
     table are trained here on the first train_n vectors, every vector is then binned and encoded by
-    HIP kernels and the lists are assembled on the GPU.  Returns the binding's Index."""
+    HIP kernels and the lists are assembled on the GPU.  code_format 1: codes are (centroid pair,
+    lambda level) per sub-part instead of table entries.  Returns the binding's Index."""
     from . import binding
     dev = torch.device("cuda", device)
     H = (k1 * k2) ** P if H is None else H
@@ -260,7 +262,7 @@ def build_index_native(*, chunks, N, D, P, k1, k2, M, H=None, T=1024, C=4096, tr
     del Xt
     if trained_out is not None:
         trained_out.update(params)                                  # the caller wants the codebooks and table too
-    params.update(N=N, H=H, D=D, P=P, k1=k1, k2=k2, M=M, T=T, C=C)
+    params.update(N=N, H=H, D=D, P=P, k1=k1, k2=k2, M=M, T=T, C=C, code_format=code_format)
     b = binding.pqt_builder_create(params, device)
     try:
         for s in range(0, N, chunk_rows):

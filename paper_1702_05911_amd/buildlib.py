@@ -1,23 +1,37 @@
 """Compiles the HIP sources in csrc/ into libpqt.so for gfx950 (cross-compiles without a GPU)."""
 import os
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = ("pqt_api.hip", "traverse.hip", "rank_bins.hip", "rerank.hip", "exact_rerank.hip", "builder.hip", "brute_force.hip", "peaks.hip")
 OUTPUT = os.path.join(HERE, "libpqt.so")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+         # packed fp32 instructions are kept off for all device code
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build_library(verbose=False):
+def build_library(verbose=False, jobs=None):
+    """One hipcc process per source file (they are independent translation units), then the link."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           # packed fp32 instructions are kept off for all device code
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-o", OUTPUT] + [os.path.join(HERE, "csrc", s) for s in SOURCES]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if verbose or res.returncode != 0:
-        print(res.stdout + res.stderr)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    jobs = jobs or min(len(SOURCES), os.cpu_count() or 1, 8)
+    log = []
+
+    def run(cmd):
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        log.append(res.stdout + res.stderr)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + res.stderr)
+
+    with tempfile.TemporaryDirectory(prefix="pqt_build_") as tmp:
+        objects = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
+        with ThreadPoolExecutor(max_workers=jobs) as pool:
+            list(pool.map(lambda so: run([hipcc] + FLAGS + ["-c", os.path.join(HERE, "csrc", so[0]), "-o", so[1]]),
+                          zip(SOURCES, objects)))
+        run([hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", OUTPUT] + objects)
+    if verbose:
+        print("".join(log))
     return OUTPUT
 
 

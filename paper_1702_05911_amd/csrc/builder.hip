@@ -59,12 +59,13 @@ __global__ __launch_bounds__(kEncodeThreads) void encode_kernel(const float* a, 
     }
 }
 
-// (pair, lambda) codes (Sec. 3.3 "Offline computation": the line through two level-1 centroids that
-// is nearest to the sub-vector, and the projection's lambda; Eq. 7 stored directly).  One wavefront
-// per vector, up to four centroid pairs per lane.  With b^2, a^2 the sub-vector's distances to c_i,
-// c_j and c^2 = ||c_i - c_j||^2, the projection is at lambda = (b^2 - a^2 + c^2) / (2 c^2) and its
-// error is b^2 - lambda^2 c^2; the smallest (error, pair number) wins, pairs with c^2 = 0 never do.
-// `table` holds the pairs (entry = pair number, kc = c^2).
+// (pair, lambda) codes (Sec. 3.3 "Offline computation"; Eq. 7 stored directly).  A code stands for the
+// point (1 - lambda) c_i + lambda c_j with lambda = (level - 96) / 32; a sub-vector gets the code of
+// the nearest such point.  One wavefront per vector, up to four centroid pairs per lane.  With b^2, a^2
+// the sub-vector's own distances to c_i, c_j and c^2 = ||c_i - c_j||^2, the projection on the line is
+// at (b^2 - a^2 + c^2) / (2 c^2); the level nearest to it (clamped to a byte) is the line's nearest
+// code point, whose distance is Eq. 9 on the same values.  The smallest (distance, pair number) wins;
+// pairs with c^2 = 0 never do.  `table` holds the pairs (entry = pair number, kc = c^2).
 __global__ __launch_bounds__(kEncodeThreads) void encode_pairs_kernel(const float* a, const uint32_t* leaf, int64_t n, int M,
                                                                       int k1, int P, uint32_t k1k2, unsigned long long H,
                                                                       const CodeEntry* table, uint8_t* codes,
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(kEncodeThreads) void encode_pairs_kernel(const floa
     const int npairs = k1 * (k1 - 1) / 2;
     for (int m = 0; m < M; ++m) {
         unsigned long long best = ~0ull;
-        float best_lam = 0.0f;
+        uint32_t best_level = 96;                          // no usable pair: pair 0 at lambda = 0
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int c = u * kWave + lane;
@@ -84,33 +85,29 @@ __global__ __launch_bounds__(kEncodeThreads) void encode_pairs_kernel(const floa
             const CodeEntry e = table[m * 256 + c];
             if (!(e.kc > 0.0f)) continue;
             const float b2 = av[m * k1 + (e.ij & 0xffu)], a2 = av[m * k1 + ((e.ij >> 8) & 0xffu)];
-            const float lam = ((b2 - a2) + e.kc) / (2.0f * e.kc);
-            const float err = fmaf(-lam * lam, e.kc, b2);
-            const unsigned long long key = ((unsigned long long)mono_key(err) << 32) | (unsigned)c;
+            const float proj = ((b2 - a2) + e.kc) / (2.0f * e.kc);
+            const float level = fminf(fmaxf(floorf(fmaf(proj, 32.0f, 96.5f)), 0.0f), 255.0f);
+            const float lam = fmaf(level, 0.03125f, -3.0f);
+            const float dist = fmaf(fmaf(lam, lam, -lam), e.kc, fmaf(lam, a2 - b2, b2));
+            const unsigned long long key = ((unsigned long long)mono_key(dist) << 32) | (unsigned)c;
             if (key < best) {
                 best = key;
-                best_lam = lam;
+                best_level = (uint32_t)level;
             }
         }
         for (int off = 32; off > 0; off >>= 1) {
             const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(best >> 32), off, kWave);
             const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)best, off, kWave);
-            const float ol = __shfl_xor(best_lam, off, kWave);
+            const uint32_t ol = (uint32_t)__shfl_xor((int)best_level, off, kWave);
             const unsigned long long o = ((unsigned long long)hi << 32) | lo;
             if (o < best) {
                 best = o;
-                best_lam = ol;
+                best_level = ol;
             }
         }
         if (lane == 0) {
-            uint32_t pair = 0, level = 64;                 // no usable pair: pair 0 at lambda = 0
-            if (best != ~0ull) {
-                pair = (uint32_t)best & 0xffu;
-                const float l = floorf(fmaf(best_lam, 128.0f, 64.5f));
-                level = (uint32_t)fminf(fmaxf(l, 0.0f), 255.0f);
-            }
-            codes[((size_t)v * M + m) * 2] = (uint8_t)pair;
-            codes[((size_t)v * M + m) * 2 + 1] = (uint8_t)level;
+            codes[((size_t)v * M + m) * 2] = best != ~0ull ? (uint8_t)(best & 0xffu) : (uint8_t)0;
+            codes[((size_t)v * M + m) * 2 + 1] = (uint8_t)best_level;
         }
     }
     if (lane == 0) {

@@ -85,6 +85,7 @@ struct RerankArgs {
     int code_format;          // 0: codes are entries of the table, one byte per sub-part;
                               // 1: two bytes per sub-part, (centroid pair, lambda level); the table is then
                               //    indexed by pair number and its kc field holds ||c_i - c_j||^2
+    int pair_shift;           // code format 1: log2 of the LDS table's entries per sub-part (set by launch_rerank)
     const uint2* runs;
     const uint2* meta;
     const uint32_t* ids;

@@ -30,6 +30,9 @@ struct RerankLds {
     uint32_t surv, spos, lut, a, run_src, run_start, skey, hist, misc, total;
 };
 
+// (pair, lambda) codes: entries per sub-part in the LDS table of centroid pairs (128 while the pairs fit)
+static int pair_table_shift(int k1) { return k1 * (k1 - 1) / 2 <= 128 ? 7 : 8; }
+
 static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format) {
     RerankLds L;
     (void)threads;
@@ -38,7 +41,7 @@ static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, 
     size_t o = 0;
     // at offset 0: lookups need no base register; also the scan scratch of the exact fallback.
     // One float per table entry, or (b^2, a^2 - b^2, c^2, -) per centroid pair for (pair, lambda) codes.
-    L.lut = (uint32_t)o;       o += sizeof(float) * M * 256 * (code_format == 1 ? 4 : 1);
+    L.lut = (uint32_t)o;       o += code_format == 1 ? sizeof(float4) * ((size_t)M << pair_table_shift(k1)) : sizeof(float) * M * 256;
     L.skey = (uint32_t)o;      o += sizeof(uint32_t) * ((C + 3) & ~3);
     L.surv = (uint32_t)o;      o += sizeof(unsigned long long) * L.scap;
     L.hist = (uint32_t)o;      o += sizeof(uint32_t) * kHistSize;
@@ -137,11 +140,11 @@ struct RunCursor {
 };
 
 // (pair, lambda level) codes: the summand of Eq. 9 for one sub-part from the pair's LDS entry
-// (b^2, a^2 - b^2, c^2) and the level; lambda = (level - 64) / 128 is exact in fp32.
-constexpr int kPairLambda = -1;      // value of MW that selects this code format
-__device__ __forceinline__ float pair_lambda_term(const float4* plut, int m, uint32_t pair, uint32_t level) {
-    const float4 e = plut[m * 256 + pair];
-    const float lam = fmaf((float)level, 0.0078125f, -0.5f);
+// (b^2, a^2 - b^2, c^2) and the level; lambda = (level - 96) / 32 is exact in fp32.
+constexpr int kPairLambda = -1;      // MW < 0 selects this code format: -1 any M (byte loads), else -(words per code)
+__device__ __forceinline__ float pair_lambda_term(const float4* plut, int shift, int m, uint32_t pair, uint32_t level) {
+    const float4 e = plut[(m << shift) + pair];
+    const float lam = fmaf((float)level, 0.03125f, -3.0f);
     return fmaf(fmaf(lam, lam, -lam), e.z, fmaf(lam, e.y, e.x));
 }
 
@@ -151,9 +154,10 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
                                             const float* lut, uint32_t* skey, const uint32_t* run_src,
                                             const uint32_t* run_start, RunCursor& cur, uint32_t& kmin,
                                             uint32_t& kmax) {
-    const int M = MW > 0 ? 4 * MW : g.M;
+    constexpr int NW = MW > 0 ? MW : (MW < -1 ? -MW : 0);      // code words fetched up front (0: byte loads)
+    const int M = MW > 0 ? 4 * MW : (MW < -1 ? -2 * MW : g.M);
     uint32_t src[U];
-    uint32_t cw[U][MW > 0 ? MW : 1];
+    uint32_t cw[U][NW > 0 ? NW : 1];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t p = (uint32_t)(base + u * nt + tid);
@@ -168,23 +172,23 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
             src[u] = run_src[0];
         }
     }
-    if (MW > 0) {
+    if (NW > 0) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t* c = reinterpret_cast<const uint32_t*>(g.codes + (size_t)src[u] * M);
-            if (MW == 2) {
+            const uint32_t* c = reinterpret_cast<const uint32_t*>(g.codes + (size_t)src[u] * (4 * NW));
+            if (NW == 2) {
                 const uint2 v = *reinterpret_cast<const uint2*>(c);
                 cw[u][0] = v.x;
-                cw[u][MW > 1 ? 1 : 0] = v.y;
-            } else if (MW == 4) {
+                cw[u][NW > 1 ? 1 : 0] = v.y;
+            } else if (NW == 4) {
                 const uint4 v = *reinterpret_cast<const uint4*>(c);
                 cw[u][0] = v.x;
-                cw[u][MW > 1 ? 1 : 0] = v.y;
-                cw[u][MW > 2 ? 2 : 0] = v.z;
-                cw[u][MW > 3 ? 3 : 0] = v.w;
+                cw[u][NW > 1 ? 1 : 0] = v.y;
+                cw[u][NW > 2 ? 2 : 0] = v.z;
+                cw[u][NW > 3 ? 3 : 0] = v.w;
             } else {
 #pragma unroll
-                for (int j = 0; j < MW; ++j) cw[u][j] = c[j];
+                for (int j = 0; j < NW; ++j) cw[u][j] = c[j];
             }
         }
     }
@@ -206,21 +210,21 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
                 s += lut_at(j * 4 + 2, (wv >> 16) & 0xffu);
                 s += lut_at(j * 4 + 3, wv >> 24);
             }
-        } else if (MW == kPairLambda) {
-            // two bytes per sub-part; M is even whenever there are two or four tree parts
+        } else if (MW < -1) {
+            // two bytes per sub-part, two sub-parts per word
             const float4* plut = reinterpret_cast<const float4*>(lut);
             s = 0.0f;
-            if ((M & 1) == 0) {
-                const uint32_t* cwp = reinterpret_cast<const uint32_t*>(g.codes + (size_t)src[u] * 2 * M);
-                for (int j = 0; j < M / 2; ++j) {
-                    const uint32_t wv = cwp[j];
-                    s += pair_lambda_term(plut, 2 * j, wv & 0xffu, (wv >> 8) & 0xffu);
-                    s += pair_lambda_term(plut, 2 * j + 1, (wv >> 16) & 0xffu, wv >> 24);
-                }
-            } else {
-                const uint8_t* code = g.codes + (size_t)src[u] * 2 * M;
-                for (int m = 0; m < M; ++m) s += pair_lambda_term(plut, m, code[2 * m], code[2 * m + 1]);
+#pragma unroll
+            for (int j = 0; j < NW; ++j) {
+                const uint32_t wv = cw[u][j];
+                s += pair_lambda_term(plut, g.pair_shift, 2 * j, wv & 0xffu, (wv >> 8) & 0xffu);
+                s += pair_lambda_term(plut, g.pair_shift, 2 * j + 1, (wv >> 16) & 0xffu, wv >> 24);
             }
+        } else if (MW == kPairLambda) {
+            const float4* plut = reinterpret_cast<const float4*>(lut);
+            const uint8_t* code = g.codes + (size_t)src[u] * 2 * M;
+            s = 0.0f;
+            for (int m = 0; m < M; ++m) s += pair_lambda_term(plut, g.pair_shift, m, code[2 * m], code[2 * m + 1]);
         } else {
             const uint8_t* code = g.codes + (size_t)src[u] * M;
             s = 0.0f;
@@ -327,9 +331,11 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
             const int m = e >> 8;
             const float b2 = sa[m * k1 + (ent[u].ij & 0xffu)];
             const float a2 = sa[m * k1 + ((ent[u].ij >> 8) & 0xffu)];
-            if (MW == kPairLambda) {
+            if (MW < 0) {
                 // entry = centroid pair number; its kc field holds c^2
-                reinterpret_cast<float4*>(lut)[e] = make_float4(b2, a2 - b2, ent[u].kc, 0.0f);
+                const int pair = e & 255;
+                if (pair < (1 << g.pair_shift))
+                    reinterpret_cast<float4*>(lut)[(m << g.pair_shift) + pair] = make_float4(b2, a2 - b2, ent[u].kc, 0.0f);
                 continue;
             }
             // Eq. 9 rearranged: b^2 + lam (a^2 - b^2) + (lam^2 - lam) c^2, the last term folded per code value
@@ -506,7 +512,13 @@ static void launch_rerank_t(const RerankArgs& a, const RerankLds& L, const RankA
                             hipStream_t s) {
     const dim3 grid((unsigned)(a.nq + a.early)), block(a.threads);
     if (a.code_format == 1) {
-        hipLaunchKernelGGL((rerank_kernel<kPairLambda, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL);
+        // word-wise variants for the plain entry point; the tapped one takes the byte-wise kernel
+        switch (TAPS || a.M % 2 ? 0 : a.M / 2) {
+            case 2: hipLaunchKernelGGL((rerank_kernel<TAPS ? kPairLambda : -2, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+            case 4: hipLaunchKernelGGL((rerank_kernel<TAPS ? kPairLambda : -4, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+            case 8: hipLaunchKernelGGL((rerank_kernel<TAPS ? kPairLambda : -8, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+            default: hipLaunchKernelGGL((rerank_kernel<kPairLambda, TAPS, FUSED>), grid, block, L.total, s, a, L, rk, RL); break;
+        }
         return;
     }
     switch ((a.M % 4 == 0) ? a.M / 4 : 0) {
@@ -520,8 +532,10 @@ static void launch_rerank_t(const RerankArgs& a, const RerankLds& L, const RankA
 
 int rerank_fused_tuples_per_thread() { return kFusedPer; }
 
-hipError_t launch_rerank(const RerankArgs& a, const RankArgs* fused, hipStream_t s) {
-    if (a.nq <= 0) return hipSuccess;
+hipError_t launch_rerank(const RerankArgs& a_in, const RankArgs* fused, hipStream_t s) {
+    if (a_in.nq <= 0) return hipSuccess;
+    RerankArgs a = a_in;
+    a.pair_shift = pair_table_shift(a.k1);
     const bool taps = a.n_cand || a.cand_ids || a.scores || a.lut;
     RankArgs rk = {};
     RankOffsets RL = {};
@@ -551,7 +565,10 @@ hipError_t configure_rerank(size_t max_dynamic_lds) {
         reinterpret_cast<const void*>(rerank_kernel<8, false, true>),
         reinterpret_cast<const void*>(rerank_kernel<kPairLambda, false, false>),
         reinterpret_cast<const void*>(rerank_kernel<kPairLambda, true, false>),
-        reinterpret_cast<const void*>(rerank_kernel<kPairLambda, false, true>)};
+        reinterpret_cast<const void*>(rerank_kernel<kPairLambda, false, true>),
+        reinterpret_cast<const void*>(rerank_kernel<-2, false, false>), reinterpret_cast<const void*>(rerank_kernel<-2, false, true>),
+        reinterpret_cast<const void*>(rerank_kernel<-4, false, false>), reinterpret_cast<const void*>(rerank_kernel<-4, false, true>),
+        reinterpret_cast<const void*>(rerank_kernel<-8, false, false>), reinterpret_cast<const void*>(rerank_kernel<-8, false, true>)};
     for (const void* kfn : kernels) {
         hipFuncAttributes attr;
         hipError_t e = hipFuncGetAttributes(&attr, kfn);

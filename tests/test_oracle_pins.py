@@ -346,36 +346,50 @@ def test_pair_lambda_score_equals_distance_to_reconstruction(tiny_pair):
             assert abs(s[t] - want) <= 1e-9 * max(want, 1e-30)
 
 
-def test_pair_lambda_codes_name_the_nearest_line(tiny_pair):
-    """Brute force over every centroid pair with the point-to-line distance from a least-squares
-    solve (not the projection formula the oracle uses)."""
+def test_pair_lambda_codes_are_nearest_code_points(tiny_pair):
+    """Brute force over every (pair, level): explicit reconstruction of all k1(k1-1)/2 x 256 points."""
     cfg, X, Y, ix = tiny_pair
     ds = cfg.D // cfg.M
     pairs = Q.centroid_pairs(cfg.k1)
+    lam = Q.lambda_of_level(np.arange(256))[:, None]
     for t in range(0, cfg.N, 487):
         x = X[ix.ids[t]].astype(np.float64)
         for m in range(cfg.M):
             cen = B.subpart_centroids(ix.C1, ix.M, m)
             xs = x[m * ds:(m + 1) * ds]
-            best, best_pi, best_lam = np.inf, -1, 0.0
+            best, best_code = np.inf, None
             for pi, (i, j) in enumerate(pairs):
-                u = (cen[j] - cen[i])[:, None]
-                sol, res, rank, _ = np.linalg.lstsq(u, xs - cen[i], rcond=None)
-                err = float(np.sum((xs - cen[i] - u[:, 0] * sol[0]) ** 2))
-                if rank == 1 and err < best * (1 - 1e-12):
-                    best, best_pi, best_lam = err, pi, float(sol[0])
-            assert ix.codes[t, 2 * m] == best_pi
-            lam_q = float(Q.lambda_of_level(ix.codes[t, 2 * m + 1]))
-            if -0.5 <= best_lam <= 191.0 / 128:
-                assert abs(lam_q - best_lam) <= 0.5 / 128 + 1e-12
-            else:
-                assert ix.codes[t, 2 * m + 1] in (0, 255)
+                pts = (1.0 - lam) * cen[i][None] + lam * cen[j][None]          # 256 points of this line
+                e = np.sum((pts - xs[None]) ** 2, axis=1)
+                lv = int(np.argmin(e))
+                if e[lv] < best:
+                    best, best_code = float(e[lv]), (pi, lv)
+            got = (int(ix.codes[t, 2 * m]), int(ix.codes[t, 2 * m + 1]))
+            if got != best_code:                                               # only an exact tie may differ
+                i, j = pairs[got[0]]
+                p = (1.0 - lam[got[1], 0]) * cen[i] + lam[got[1], 0] * cen[j]
+                assert abs(float(np.sum((p - xs) ** 2)) - best) <= 1e-12 * max(best, 1e-30), (t, m, got, best_code)
+
+
+def test_pair_lambda_beats_nearest_centroid_and_table_of_same_lines(tiny_pair, tiny):
+    """Every centroid is a code point (lambda = 0 or 1 of a line through it), so the error can never
+    exceed the distance to the nearest level-1 centroid of the sub-part."""
+    cfg, X, Y, ix = tiny_pair
+    ds = cfg.D // cfg.M
+    for t in range(0, cfg.N, 97):
+        x = X[ix.ids[t]].astype(np.float64)
+        xr = Q.reconstruct(ix, ix.codes[t])
+        for m in range(cfg.M):
+            cen = B.subpart_centroids(ix.C1, ix.M, m)
+            xs = x[m * ds:(m + 1) * ds]
+            nearest = float(np.min(np.sum((cen - xs[None]) ** 2, axis=1)))
+            assert float(np.sum((xr[m * ds:(m + 1) * ds] - xs) ** 2)) <= nearest * (1 + 1e-12) + 1e-12
 
 
 def test_pair_lambda_grid_and_pair_numbering():
-    assert Q.lambda_of_level(64) == 0.0 and Q.lambda_of_level(192) == 1.0
-    assert Q.lambda_of_level(0) == -0.5 and Q.lambda_of_level(255) == 191.0 / 128
-    assert list(Q.level_of_lambda([-10.0, 10.0, 0.0, 1.0, 0.5 / 128, 0.49 / 128, -0.51 / 128])) == [0, 255, 64, 192, 65, 64, 63]
+    assert Q.lambda_of_level(96) == 0.0 and Q.lambda_of_level(128) == 1.0
+    assert Q.lambda_of_level(0) == -3.0 and Q.lambda_of_level(255) == 159.0 / 32
+    assert list(Q.level_of_lambda([-10.0, 10.0, 0.0, 1.0, 0.5 / 32, 0.49 / 32, -0.51 / 32])) == [0, 255, 96, 128, 97, 96, 95]
     for k1 in (2, 5, 16, 23):
         pairs = Q.centroid_pairs(k1)
         assert len(pairs) == k1 * (k1 - 1) // 2
@@ -390,9 +404,9 @@ def test_pair_lambda_point_on_a_segment_is_reproduced(rng):
     ds = D // M
     x = np.zeros(D)
     want = []
-    for m, (i, j, level) in enumerate([(0, 3, 96), (1, 2, 64 + 128), (4, 5, 70), (2, 5, 10)]):
+    for m, (i, j, level) in enumerate([(0, 3, 104), (1, 2, 96 + 32), (4, 5, 99), (2, 5, 10)]):
         cen = B.subpart_centroids(C1, M, m)
-        lam = (level - 64) / 128
+        lam = (level - 96) / 32
         x[m * ds:(m + 1) * ds] = (1 - lam) * cen[i] + lam * cen[j]
         want += [Q.centroid_pairs(k1).index((i, j)), level]
     code = B.encode_pair_lambda(x[None], C1, M)[0]
