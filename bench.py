@@ -411,7 +411,7 @@ def main():
             cen = torch.from_numpy(tr["C1"][p_][:, lo_:lo_ + ds_]).to(dev)
             if code_format:
                 ij = pair_ij[codes_e[:, 2 * m]]
-                lam_ = ((codes_e[:, 2 * m + 1].float() - 96.0) / 32.0)[:, None]
+                lam_ = ((codes_e[:, 2 * m + 1].float() - 96.0) / 16.0)[:, None]
                 rec = (1.0 - lam_) * cen[ij[:, 0]] + lam_ * cen[ij[:, 1]]
             else:
                 ti_ = torch.from_numpy(tr["tbl_i"][m].astype(np.int64)).to(dev)

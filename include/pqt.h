@@ -53,7 +53,7 @@ typedef struct pqt_index pqt_index;   /* opaque; owns all device and host memory
  *   PQT_CODES_PAIR_LAMBDA  the tuple stored directly in "1+1 bytes" per sub-part (Sec. 3.3): byte 2m is
  *                          the number of the centroid pair i < j in lexicographic order
  *                          (i (2 k1 - i - 1) / 2 + j - i - 1; needs k1 (k1 - 1) / 2 <= 256), byte 2m+1 the
- *                          level of lambda = (level - 96) / 32, i.e. -3 .. 4.97 in steps of 1/32;
+ *                          level of lambda = (level - 96) / 16, i.e. -6 .. 9.94 in steps of 1/16;
  *                          2M bytes per vector.  The score is Eq. 9
  *                          evaluated per candidate; the line table is not used and may be NULL.
  */

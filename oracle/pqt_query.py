@@ -277,11 +277,12 @@ def build_lut(a, tbl_i, tbl_j, tbl_lam, cc):
 
 # Code format 1 stores the triple of Eq. 7 itself: one byte numbers the centroid pair i < j in
 # lexicographic order, one byte is the level of lambda on a fixed grid.  (The paper gives "1+1 bytes"
-# but neither the numbering nor the grid; the grid below has 0 and 1 on it and reaches from three
-# segment lengths before c_i to four beyond c_j: on data like the paper's a third of the projections
-# fall outside [-0.5, 1.5], almost none outside [-3, 5].)
+# but neither the numbering nor the grid; the grid below has 0 and 1 on it and reaches from six
+# segment lengths before c_i to nine beyond c_j: on data like the paper's a third of the projections
+# fall outside [-0.5, 1.5] and, with short sub-parts, some beyond [-3, 5]; a step of 1/16 moves a point
+# by at most 1/32 of the segment, far below the quantisation error itself.)
 LAMBDA_ZERO_LEVEL = 96
-LAMBDA_LEVELS_PER_UNIT = 32
+LAMBDA_LEVELS_PER_UNIT = 16
 
 
 def lambda_of_level(level):

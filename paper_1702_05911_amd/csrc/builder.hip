@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kEncodeThreads) void encode_kernel(const float* a, 
 }
 
 // (pair, lambda) codes (Sec. 3.3 "Offline computation"; Eq. 7 stored directly).  A code stands for the
-// point (1 - lambda) c_i + lambda c_j with lambda = (level - 96) / 32; a sub-vector gets the code of
+// point (1 - lambda) c_i + lambda c_j with lambda = (level - 96) / 16; a sub-vector gets the code of
 // the nearest such point.  One wavefront per vector, up to four centroid pairs per lane.  With b^2, a^2
 // the sub-vector's own distances to c_i, c_j and c^2 = ||c_i - c_j||^2, the projection on the line is
 // at (b^2 - a^2 + c^2) / (2 c^2); the level nearest to it (clamped to a byte) is the line's nearest
@@ -86,8 +86,8 @@ __global__ __launch_bounds__(kEncodeThreads) void encode_pairs_kernel(const floa
             if (!(e.kc > 0.0f)) continue;
             const float b2 = av[m * k1 + (e.ij & 0xffu)], a2 = av[m * k1 + ((e.ij >> 8) & 0xffu)];
             const float proj = ((b2 - a2) + e.kc) / (2.0f * e.kc);
-            const float level = fminf(fmaxf(floorf(fmaf(proj, 32.0f, 96.5f)), 0.0f), 255.0f);
-            const float lam = fmaf(level, 0.03125f, -3.0f);
+            const float level = fminf(fmaxf(floorf(fmaf(proj, 16.0f, 96.5f)), 0.0f), 255.0f);
+            const float lam = fmaf(level, 0.0625f, -6.0f);
             const float dist = fmaf(fmaf(lam, lam, -lam), e.kc, fmaf(lam, a2 - b2, b2));
             const unsigned long long key = ((unsigned long long)mono_key(dist) << 32) | (unsigned)c;
             if (key < best) {

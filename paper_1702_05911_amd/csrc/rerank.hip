@@ -140,11 +140,11 @@ struct RunCursor {
 };
 
 // (pair, lambda level) codes: the summand of Eq. 9 for one sub-part from the pair's LDS entry
-// (b^2, a^2 - b^2, c^2) and the level; lambda = (level - 96) / 32 is exact in fp32.
+// (b^2, a^2 - b^2, c^2) and the level; lambda = (level - 96) / 16 is exact in fp32.
 constexpr int kPairLambda = -1;      // MW < 0 selects this code format: -1 any M (byte loads), else -(words per code)
 __device__ __forceinline__ float pair_lambda_term(const float4* plut, int shift, int m, uint32_t pair, uint32_t level) {
     const float4 e = plut[(m << shift) + pair];
-    const float lam = fmaf((float)level, 0.03125f, -3.0f);
+    const float lam = fmaf((float)level, 0.0625f, -6.0f);
     return fmaf(fmaf(lam, lam, -lam), e.z, fmaf(lam, e.y, e.x));
 }
 

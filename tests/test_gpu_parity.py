@@ -467,9 +467,9 @@ def test_pair_lambda_native_builder(pqt, tiny_pair, tmp_path):
             lam, _ = B.line_projection(xs, cen[i], cen[j])
             level = int(nix.codes[t, 2 * m + 1])
             if 0 < level < 255:                                               # the level nearest to the projection
-                assert abs(float(Q.lambda_of_level(level)) - lam) <= 0.5 / 32 + 1e-4
+                assert abs(float(Q.lambda_of_level(level)) - lam) <= 0.5 / 16 + 1e-4
             else:
-                assert lam < -2.98 or lam > 4.95
+                assert lam < -5.96 or lam > 9.9
             same_pair += int(nix.codes[t, 2 * m] == want[2 * m] and level == want[2 * m + 1])
             total += 1
     assert same_pair >= 0.99 * total

@@ -387,9 +387,9 @@ def test_pair_lambda_beats_nearest_centroid_and_table_of_same_lines(tiny_pair, t
 
 
 def test_pair_lambda_grid_and_pair_numbering():
-    assert Q.lambda_of_level(96) == 0.0 and Q.lambda_of_level(128) == 1.0
-    assert Q.lambda_of_level(0) == -3.0 and Q.lambda_of_level(255) == 159.0 / 32
-    assert list(Q.level_of_lambda([-10.0, 10.0, 0.0, 1.0, 0.5 / 32, 0.49 / 32, -0.51 / 32])) == [0, 255, 96, 128, 97, 96, 95]
+    assert Q.lambda_of_level(96) == 0.0 and Q.lambda_of_level(112) == 1.0
+    assert Q.lambda_of_level(0) == -6.0 and Q.lambda_of_level(255) == 159.0 / 16
+    assert list(Q.level_of_lambda([-10.0, 10.0, 0.0, 1.0, 0.5 / 16, 0.49 / 16, -0.51 / 16])) == [0, 255, 96, 112, 97, 96, 95]
     for k1 in (2, 5, 16, 23):
         pairs = Q.centroid_pairs(k1)
         assert len(pairs) == k1 * (k1 - 1) // 2
@@ -404,9 +404,9 @@ def test_pair_lambda_point_on_a_segment_is_reproduced(rng):
     ds = D // M
     x = np.zeros(D)
     want = []
-    for m, (i, j, level) in enumerate([(0, 3, 104), (1, 2, 96 + 32), (4, 5, 99), (2, 5, 10)]):
+    for m, (i, j, level) in enumerate([(0, 3, 100), (1, 2, 96 + 16), (4, 5, 99), (2, 5, 10)]):
         cen = B.subpart_centroids(C1, M, m)
-        lam = (level - 96) / 32
+        lam = (level - 96) / 16
         x[m * ds:(m + 1) * ds] = (1 - lam) * cen[i] + lam * cen[j]
         want += [Q.centroid_pairs(k1).index((i, j)), level]
     code = B.encode_pair_lambda(x[None], C1, M)[0]
