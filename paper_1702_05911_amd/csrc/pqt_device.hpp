@@ -344,41 +344,6 @@ __device__ __forceinline__ void block_sort_lds(unsigned long long* keys, int n, 
     else block_sort_chunks<8>(keys, n, tid, nthreads);
 }
 
-// Exclusive prefix sum over data[0..n) in LDS, in place, by the whole workgroup.
-// part needs blockDim.x + 1 entries.  Returns the total.  Ends with a barrier.
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t* data, int n, uint32_t* part) {
-    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & (kWave - 1);
-    const int chunk = (n + nt - 1) / nt;
-    const int lo = min(tid * chunk, n), hi = min(lo + chunk, n);
-    uint32_t s = 0;
-    for (int e = lo; e < hi; ++e) s += data[e];
-    part[tid] = s;
-    __syncthreads();
-    if (tid < kWave) {                            // the first wavefront scans the per-thread sums
-        const int per = nt / kWave;
-        uint32_t ls = 0;
-        for (int i = 0; i < per; ++i) ls += part[lane * per + i];
-        const uint32_t incl = wave_inclusive_sum(ls, lane);
-        uint32_t run = incl - ls;
-        for (int i = 0; i < per; ++i) {
-            const uint32_t v = part[lane * per + i];
-            part[lane * per + i] = run;           // exclusive prefix of thread lane*per+i
-            run += v;
-        }
-        if (lane == kWave - 1) part[nt] = incl;   // grand total
-    }
-    __syncthreads();
-    s = part[tid];
-    const uint32_t total = part[nt];
-    for (int e = lo; e < hi; ++e) {
-        const uint32_t v = data[e];
-        data[e] = s;
-        s += v;
-    }
-    __syncthreads();
-    return total;
-}
-
 __host__ __device__ inline int next_pow2(int v) {
     int p = 1;
     while (p < v) p <<= 1;

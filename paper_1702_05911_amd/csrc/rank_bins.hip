@@ -7,11 +7,12 @@
 // The first T tuples of the order (sum, r1, r2) are found without a priority queue: a pair
 // (r1, r2) can only be among the first T if (r1+1)(r2+1) <= T, because every pair that is
 // component-wise smaller precedes it.  Only that hyperbolic region (about T ln T pairs) is ever
-// evaluated.  A head pass (one wavefront per query) ranks the first 64 tuples, which is enough
-// for most queries to fill the candidate budget; the full pass handles the rest: if the region
-// fits the sort buffer it is sorted directly, otherwise the T-th smallest key is found by a
-// radix select over the region (keys recomputed on the fly, never stored) and only the T
-// smallest are collected and sorted.
+// evaluated.  A head pass (one wavefront per query) ranks the first 32, then 64, then 128 tuples and
+// stops as soon as the candidate budget is filled, which it is for nearly every query; the full pass
+// handles the rest: if the region fits the sort buffer it is sorted directly, otherwise the T-th
+// smallest key is located by a histogram over the key range (keys recomputed on the fly, never
+// stored; an exact radix select when the keys tie heavily) and only the T smallest are collected
+// and sorted.
 #include "rank_device.hpp"
 
 namespace pqt {

@@ -3,7 +3,7 @@
 // the w closest clusters per part, the level-2 distances to their children, and the sorted
 // (distance, leaf) lists per part.
 //
-// One workgroup of 256 threads handles a tile of 16 queries.
+// One workgroup (256, 512 or 1024 threads for 1, 2 or 4 tree parts) handles a tile of 16 queries.
 //   * level 1 is a dense contraction [16 x ds] . [ds x k1] per sub-part on the matrix cores
 //     (v_mfma_f32_16x16x4_f32, fp32 in, fp32 accumulate) with ||q||^2 + ||c||^2 - 2 q.c;
 //   * the per-part distance is the sum of its sub-part distances in ascending sub-part order;
@@ -12,7 +12,8 @@
 //     w clusters), done on the vector ALU with direct squared differences: one wavefront
 //     per (query, part), one lane per child;
 //   * each list is sorted as 64-bit keys (ordered distance bits, leaf id) by a bitonic
-//     network in LDS.
+//     network in registers (in LDS for lists of more than 256 entries or part dimensions that
+//     are not a multiple of four).
 #include "pqt_device.hpp"
 #include "pqt_kernels.hpp"
 
