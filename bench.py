@@ -101,18 +101,18 @@ def measured_traffic(kernel, workload, w):
 
 
 def _oracle_worker(args):
-    path, Y, k, w, lo, hi = args
+    path, Y, k, w, lo, hi, order = args
     from oracle import pqt_index_io, pqt_query
     ix = pqt_index_io.read_index(path)
     t0 = time.perf_counter()
     res = []
     for q in range(lo, hi):
-        tr = pqt_query.query(ix, Y[q], k, w, with_margins=False)
+        tr = pqt_query.query(ix, Y[q], k, w, with_margins=False, order_method=order)
         res.append(tr.out_ids)
     return time.perf_counter() - t0, res
 
 
-def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16):
+def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16, order="fullsort"):
     """The CPU oracle, as it stands, on a bounded sample of the same queries and the same index
     file, one process per host core.  Also cross-checks the GPU ids on that sample."""
     import multiprocessing as mp
@@ -120,13 +120,13 @@ def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16):
     cores = min(len(os.sched_getaffinity(0)), max_procs)
     # size the sample from one timed query
     t0 = time.perf_counter()
-    _oracle_worker((path, Y_host, k, w, 0, 1))
+    _oracle_worker((path, Y_host, k, w, 0, 1, order))
     per_q = max(time.perf_counter() - t0, 1e-3)
     n = int(max(cores, min(Y_host.shape[0], budget_s / per_q * cores)))
     n -= n % cores
     n = max(n, cores) if Y_host.shape[0] >= cores else Y_host.shape[0]
     bounds = [(i * n) // cores for i in range(cores + 1)]
-    jobs = [(path, Y_host, k, w, bounds[i], bounds[i + 1]) for i in range(cores) if bounds[i + 1] > bounds[i]]
+    jobs = [(path, Y_host, k, w, bounds[i], bounds[i + 1], order) for i in range(cores) if bounds[i + 1] > bounds[i]]
     t0 = time.perf_counter()
     with mp.get_context("spawn").Pool(len(jobs)) as pool:
         outs = pool.map(_oracle_worker, jobs)
@@ -169,6 +169,9 @@ def main():
                     help="re-rank code format: one byte per sub-part naming a table entry (default), or two bytes "
                          "holding (centroid pair, lambda level) as in Sec. 3.3; with --M or --sweep-w also prints the "
                          "codes' distortion")
+    ap.add_argument("--order", choices=("summed", "static"), default="summed",
+                    help="bin proposal order: by summed level-2 distance (default) or the paper's fixed anisotropic "
+                         "orders for ten slopes (two tree parts, unhashed bins)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline", action="store_true",
                     help="also for the 100M / 1B workloads (writes the index to a file for the oracle's processes)")
@@ -224,6 +227,8 @@ def main():
                                        H=cfg.H, T=cfg.T, C=cfg.C, train_n=cfg.train_n, device=0,
                                        chunk_rows=(1 << 20) if in_hbm_only else (1 << 18), observer=observe,
                                        code_format=code_format)
+    if args.order == "static":
+        pqt.pqt_set_bin_order(index, pqt.PQT_ORDER_STATIC_SLOPES)
     runs = torch.diff(pqt.pqt_index_export(index, ("offsets",))["offsets"])
     occupancy = {"nonempty_slots": int((runs > 0).sum()), "max_run": int(runs.max()),
                  "mean_run_nonempty": float(runs[runs > 0].float().mean())}
@@ -328,7 +333,8 @@ def main():
     stages = [
         {"kernel": "traverse_kernel", "ms": stage_ms[0], "bound": "mfma", "achieved": trav_flops / (stage_ms[0] * 1e-3) / 1e12,
          "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s", "hbm_GBs": trav_bytes / (stage_ms[0] * 1e-3) / 1e9},
-        {"kernel": "rank_head_kernel" if cfg.P == 2 else "rank_kernel", "ms": stage_ms[1], "bound": "alu",
+        {"kernel": "rank_static_kernel" if args.order == "static" else "rank_head_kernel" if cfg.P == 2 else "rank_kernel",
+         "ms": stage_ms[1], "bound": "alu",
          "achieved": rank_ops / (stage_ms[1] * 1e-3) / 1e12, "peak": VALU_PEAK_TOPS, "unit": "T compare-exchange/s",
          "note": "compare-exchanges of the first ranking level only; register/ALU work, no HBM or MFMA roofline applies"},
         {"kernel": "rerank_kernel", "ms": stage_ms[2], "bound": "hbm", "achieved": rerank_bytes / (stage_ms[2] * 1e-3) / 1e9,
@@ -347,7 +353,7 @@ def main():
     stages[2]["lds_lookup_frac"] = stages[2]["lds_lookups_per_s"] / (256 * 32 * 2.4e9)
     dom = max(stages, key=lambda s: s["ms"])
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                "unit": dom["unit"], "frac": dom["frac"], "traffic": None if (code_format or args.M) else measured_traffic(dom["kernel"], cfg.name, w)}
+                "unit": dom["unit"], "frac": dom["frac"], "traffic": None if (code_format or args.M or args.order == "static") else measured_traffic(dom["kernel"], cfg.name, w)}
 
     ms_per_step = elapsed / args.steps * 1e3
     result = {
@@ -357,7 +363,8 @@ def main():
         "ms_per_step_with_stage_events": elapsed_profiled / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: N={cfg.N} D={cfg.D} nq={cfg.nq} P={cfg.P} k1={cfg.k1} k2={cfg.k2} "
-                               f"M={cfg.M} H={cfg.H} w={w} T={cfg.T} C={cfg.C} k={cfg.k}" + (" codes=(pair,lambda)" if code_format else ""),
+                               f"M={cfg.M} H={cfg.H} w={w} T={cfg.T} C={cfg.C} k={cfg.k}" + (" codes=(pair,lambda)" if code_format else "")
+                               + (" order=static-slopes" if args.order == "static" else ""),
                    "queries_per_call": B, "mean_candidates": mean_cand, "mean_runs": mean_runs, **occupancy},
         "recall": rec, "tuples_needed": tuples_needed, "stage_ms": stage_ms, "stages": stages, "roofline": roofline, "setup_s": setup_s,
         "measured_peaks": {"hbm_read_GBs": hbm_meas, "mfma_f32_TFLOPs": mfma_meas,
@@ -376,7 +383,8 @@ def main():
         result["latency_us_per_call"] = (time.perf_counter() - t0) / ncalls * 1e6
     if path is not None and not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(path, Y.cpu().numpy(), cfg.k, w, out_ids.cpu().numpy(),
-                                              max_procs=4 if cfg.N > 200_000_000 else 16)
+                                              max_procs=4 if cfg.N > 200_000_000 else 16,
+                                              order="static" if args.order == "static" else "fullsort")
     else:
         result["cpu_baseline"] = None
     sweep = []

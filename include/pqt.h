@@ -183,6 +183,25 @@ int pqt_index_info(const pqt_index* index, pqt_info* out);
 int pqt_set_budget(pqt_index* index, uint32_t T_bins, uint32_t C_candidates);
 
 /*
+ * pqt_set_bin_order -- the sequence in which neighbouring bins are proposed (Sec. 3.2 "Bin
+ * Proposal Heuristic").
+ *   PQT_ORDER_SUMMED_DISTANCE (default)  rank tuples by their summed level-2 distance: the
+ *       sequence the paper calls optimal (the priority-queue order of its reference [4]).
+ *   PQT_ORDER_STATIC_SLOPES  the paper's fixed anisotropic heuristic: ten pre-computed orders
+ *       of the rank pairs, one per slope 1.08^k, k = -5..4, nothing sorted per query.  The paper
+ *       prints neither the weighted norm nor how a query picks its slope; here the order for
+ *       slope s ranks pairs (v1, v2), counted from 1, by v1^2 + (s v2)^2 (ties by (v1, v2)), and
+ *       a query takes slope index #{ j in 1..9 : g2 > 1.08^(j-5.5) g1 } (fp32), where
+ *       g_p = L_p[min(w*k2 - 1, 8)] - L_p[0] is the rise of its sorted level-2 list of part p.
+ *       Two tree parts and H = (k1*k2)^2 only (PQT_EUNSUPPORTED otherwise).  The tables are
+ *       rebuilt inside the next query call whenever w*k2 or T changed.
+ * PQT_EINVAL for a null index or an unknown order.
+ */
+#define PQT_ORDER_SUMMED_DISTANCE 0
+#define PQT_ORDER_STATIC_SLOPES   1
+int pqt_set_bin_order(pqt_index* index, int order);
+
+/*
  * pqt_query_batch -- the online phase for nq queries.
  *   queries   device, nq x D row-major fp32
  *   k         results per query, 1 <= k <= min(C, PQT_MAX_K)

@@ -214,6 +214,65 @@ def bin_order(Ld, T, method="fullsort", truncate_pairs=False):
     raise ValueError("bin order is defined for P in {1, 2, 4}")
 
 
+# ---------------------------------------------------------------------------
+# O4'  the fixed anisotropic traversal order                    (Sec. 3.2 "Bin Proposal Heuristic")
+# ---------------------------------------------------------------------------
+# The paper replaces the priority-queue order by pre-computed orders of the rank pairs for ten
+# slopes 1.08^k, k = -5..4, one of which is used per query.  It prints neither the weighted norm nor
+# the rule that picks the slope; the readings below are this build's:
+#   * order for slope s: rank pairs v = (v1, v2), counted from 1, ascending by v1^2 + (s v2)^2 --
+#     s = 1 is the isotropic order by ||v||_2, a smaller s admits higher ranks in the second part
+#     as the paper describes for 1.08^-5 -- ties by (v1, v2);
+#   * slope of a query: how far each sorted level-2 list has risen by a reference rank,
+#     g_p = L_p[r0] - L_p[0] with r0 = min(R - 1, 8); the list that rises more slowly should be
+#     advanced faster, so the slope nearest to g_2 / g_1 in the geometric sense is taken:
+#     index = number of j in 1..9 with g_2 > 1.08^(j - 5.5) g_1, compared in the lists' own precision.
+N_SLOPES = 10
+SLOPE_REFERENCE_RANK = 8
+
+
+def slopes():
+    """1.08^(i - 5), i = 0..9, by repeated multiplication / division (no pow)."""
+    up, down = [1.0], [1.0]
+    for _ in range(4):
+        up.append(up[-1] * 1.08)
+    for _ in range(5):
+        down.append(down[-1] / 1.08)
+    return np.array(down[:0:-1] + up, dtype=np.float64)
+
+
+def slope_thresholds(dtype=np.float32):
+    """1.08^(j - 5.5), j = 1..9: the boundaries between neighbouring slopes."""
+    return (slopes()[1:] / np.sqrt(1.08)).astype(dtype)
+
+
+def choose_slope(L1, L2):
+    """Index 0..9 of the slope for one query; arithmetic in the dtype of the lists."""
+    dt = L1.dtype.type
+    r0 = min(L1.shape[0] - 1, SLOPE_REFERENCE_RANK)
+    g1, g2 = dt(L1[r0] - L1[0]), dt(L2[r0] - L2[0])
+    return int(sum(1 for t in slope_thresholds(L1.dtype) if g2 > dt(t * g1)))
+
+
+def static_order(R, T, slope):
+    """First min(T, R^2) rank pairs (a, b), counted from 0, ascending by ((a+1)^2 + (slope (b+1))^2, a, b)."""
+    a, b = np.meshgrid(np.arange(R), np.arange(R), indexing="ij")
+    a, b = a.ravel(), b.ravel()
+    key = (a + 1.0) ** 2 + (slope * (b + 1.0)) ** 2
+    o = np.lexsort((b, a, key))[:T]
+    return np.stack([a[o], b[o]], axis=1).astype(np.int64)
+
+
+def bin_order_static(Ld, T):
+    """Two tree parts: the rank tuples of the pre-computed order for this query's slope, and the
+    summed distances of those tuples (they are not what the order is sorted by)."""
+    if len(Ld) != 2:
+        raise ValueError("the fixed traversal order is defined here for two tree parts")
+    k = choose_slope(Ld[0], Ld[1])
+    tup = static_order(Ld[0].shape[0], T, slopes()[k])
+    return tup, (Ld[0][tup[:, 0]] + Ld[1][tup[:, 1]])
+
+
 def linear_bin(leaf_ids, k1k2):
     """Multi-index (Eq. 5) -> one unsigned integer, part 1 most significant."""
     lin = 0
@@ -404,6 +463,7 @@ def _rel_gap(lo, hi):
 
 def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_method="fullsort",
           with_margins=True):
+    # order_method "static": the fixed anisotropic order of O4' instead of the order by summed distance
     """One query through O1..O8.  With exact_rerank (needs the raw vectors X) the scores
     of O6-O7 are replaced by exact squared distances (step (3) of the PQ pipelines in
     Sec. 1; the paper's PQT_2 of Table 1)."""
@@ -415,7 +475,11 @@ def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_meth
     tr.sel = select_clusters(tr.d1, w)
     d2, ids2 = level2_distances(y, index.C2, tr.sel)
     tr.Ld, tr.Lid = sort_level2(d2, ids2)
-    tr.tuples, tr.keys = bin_order([tr.Ld[p] for p in range(index.P)], T, method=order_method)
+    if order_method == "static":
+        tr.tuples, tr.keys = bin_order_static([tr.Ld[p] for p in range(index.P)], T)
+        with_margins = False           # the margins describe decisions of the order by summed distance
+    else:
+        tr.tuples, tr.keys = bin_order([tr.Ld[p] for p in range(index.P)], T, method=order_method)
     tr.slots = propose_bins(tr.tuples, tr.Lid, index.k1 * index.k2, index.H, index.offsets)
     tr.cand_pos = gather_candidates(tr.slots, index.offsets, C)
     tr.cand_ids = index.ids[tr.cand_pos].astype(np.int64)

@@ -51,6 +51,7 @@ class _Arrays(ctypes.Structure):
 
 PQT_HOST, PQT_DEVICE = 0, 1
 PQT_CODES_TABLE, PQT_CODES_PAIR_LAMBDA = 0, 1
+PQT_ORDER_SUMMED_DISTANCE, PQT_ORDER_STATIC_SLOPES = 0, 1
 
 
 class _Taps(ctypes.Structure):
@@ -84,6 +85,8 @@ def load_library(path=LIB_PATH):
     lib.pqt_index_info.restype = ci
     lib.pqt_set_budget.argtypes = [vp, ctypes.c_uint32, ctypes.c_uint32]
     lib.pqt_set_budget.restype = ci
+    lib.pqt_set_bin_order.argtypes = [vp, ci]
+    lib.pqt_set_bin_order.restype = ci
     lib.pqt_query_batch.argtypes = [vp, vp, i64, ci, ci, vp, vp, vp]
     lib.pqt_query_batch.restype = ci
     lib.pqt_query_batch_debug.argtypes = [vp, vp, i64, ci, ci, vp, vp, vp, ctypes.POINTER(_Taps)]
@@ -197,6 +200,9 @@ class Index:
 
     def set_budget(self, T, C):
         _check(_lib.pqt_set_budget(self._h, int(T), int(C)))
+
+    def set_bin_order(self, order):
+        _check(_lib.pqt_set_bin_order(self._h, int(order)))
 
     def _buffers(self, queries, k):
         if queries.dtype != torch.float32 or not queries.is_cuda or not queries.is_contiguous() or queries.dim() != 2:
@@ -398,6 +404,10 @@ def pqt_index_info(index):
 
 def pqt_set_budget(index, T_bins, C_candidates):
     index.set_budget(T_bins, C_candidates)
+
+
+def pqt_set_bin_order(index, order):
+    index.set_bin_order(order)
 
 
 def pqt_query_batch(index, queries, k, w, out_ids=None, out_dists=None, stream=None):

@@ -465,7 +465,7 @@ void pqt_index_free(pqt_index* ix) {
     (void)hipFree(ix->vectors_owned); (void)hipFree(ix->ws_short_ids); (void)hipFree(ix->ws_short_dists);
     (void)hipFree(ix->vector_norms); (void)hipFree(ix->bf_qnorm); (void)hipFree(ix->bf_dist); (void)hipFree(ix->bf_best);
     (void)hipFree(ix->C1); (void)hipFree(ix->c1n); (void)hipFree(ix->C2); (void)hipFree(ix->C2t); (void)hipFree(ix->table);
-    (void)hipFree(ix->offsets); (void)hipFree(ix->ids); (void)hipFree(ix->codes);
+    (void)hipFree(ix->offsets); (void)hipFree(ix->ids); (void)hipFree(ix->codes); (void)hipFree(ix->static_table);
     ix->free_workspace();
     for (hipEvent_t e : ix->events) (void)hipEventDestroy(e);
     delete ix;
@@ -542,10 +542,35 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     if (tp.lut && ix->code_format == PQT_CODES_PAIR_LAMBDA)
         return fail(PQT_EINVAL, "pqt_query_batch_debug: the lut tap is the table of the one-byte code format");
     const bool rerank_taps = tp.n_cand || tp.cand_ids || tp.scores || tp.lut || tp.n_slots;
-    const bool head = pqt::rank_has_head(ra);
+    const bool fixed_order = ix->bin_order == PQT_ORDER_STATIC_SLOPES;
+    const bool head = !fixed_order && pqt::rank_has_head(ra);
     // the few queries the head pass cannot finish are ranked in full by their re-rank workgroup
     const bool fuse = head && !rerank_taps && can_fuse_ranking(ix, k, w);
-    HIP_TRY(pqt::launch_rank(ra, stream, fuse));
+    if (fixed_order) {
+        if (ix->static_R != R || ix->static_T != (int)ix->T) {          // tables for this list length and T
+            std::vector<uint32_t> table;
+            try {
+                ix->static_Tn = pqt::make_static_order(R, (int)ix->T, table, ix->static_thr);
+            } catch (const std::bad_alloc&) {
+                return fail(PQT_ENOMEM, "host allocation failed");
+            }
+            HIP_TRY(hipStreamSynchronize(stream));                      // an earlier batch may still read the old tables
+            (void)hipFree(ix->static_table);
+            ix->static_table = nullptr;
+            ix->static_R = ix->static_T = 0;
+            HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->static_table), table.size() * sizeof(uint32_t)));
+            HIP_TRY(hipMemcpy(ix->static_table, table.data(), table.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+            ix->static_R = R;
+            ix->static_T = (int)ix->T;
+        }
+        pqt::StaticOrder so;
+        so.table = ix->static_table;
+        so.Tn = ix->static_Tn;
+        for (int j = 0; j < pqt::kStaticSlopes - 1; ++j) so.thr[j] = ix->static_thr[j];
+        HIP_TRY(pqt::launch_rank_static(ra, so, stream));
+    } else {
+        HIP_TRY(pqt::launch_rank(ra, stream, fuse));
+    }
     if (ev) HIP_TRY(hipEventRecord(ev[2], stream));
 
     pqt::RerankArgs ca;
@@ -576,6 +601,16 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
         HIP_TRY(hipMemcpy2DAsync(tp.n_slots, sizeof(uint32_t), ix->ws_meta, sizeof(uint2), sizeof(uint32_t), (size_t)nq,
                                  hipMemcpyDeviceToDevice, stream));
     }
+    return PQT_OK;
+}
+
+int pqt_set_bin_order(pqt_index* ix, int order) {
+    if (!ix) return fail(PQT_EINVAL, "pqt_set_bin_order: null index");
+    if (order != PQT_ORDER_SUMMED_DISTANCE && order != PQT_ORDER_STATIC_SLOPES)
+        return fail(PQT_EINVAL, "pqt_set_bin_order: order %d", order);
+    if (order == PQT_ORDER_STATIC_SLOPES && (ix->P != 2 || ix->hashed))
+        return fail(PQT_EUNSUPPORTED, "pqt_set_bin_order: the fixed order needs two tree parts and H = (k1*k2)^2");
+    ix->bin_order = order;
     return PQT_OK;
 }
 

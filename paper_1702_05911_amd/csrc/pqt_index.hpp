@@ -82,6 +82,11 @@ struct pqt_index {
     uint32_t* ws_counters = nullptr;   // 2 words
     uint32_t* ws_order = nullptr;      // nq words
     uint64_t bytes_workspace = 0;
+    // fixed traversal order (pqt_set_bin_order): tables for lists of static_R entries and static_T tuples
+    int bin_order = 0;
+    uint32_t* static_table = nullptr;
+    int static_R = 0, static_T = 0, static_Tn = 0;
+    float static_thr[pqt::kStaticSlopes - 1] = {};
     // stage timing
     bool profiling = false;
     int prof_calls = 0;

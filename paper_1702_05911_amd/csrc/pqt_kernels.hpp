@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace pqt {
 
 constexpr int kQueryTile = 16;          // queries per workgroup of the traversal kernel (MFMA rows)
@@ -75,6 +77,19 @@ bool rank_has_head(const RankArgs& a);
 // defer_full: only the head pass is launched; the caller runs the full pass of the unfinished
 // queries elsewhere (inside the re-rank kernel).  Needs rank_has_head(a).
 hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full);
+
+// The fixed anisotropic traversal order (Sec. 3.2 "Bin Proposal Heuristic"): ten pre-computed orders of
+// the rank pairs, one per slope 1.08^k, k = -5..4; a query takes the one whose slope matches how fast
+// its two lists rise.  Two tree parts, unhashed bins.
+constexpr int kStaticSlopes = 10;
+struct StaticOrder {
+    const uint32_t* table;     // kStaticSlopes x Tn entries r1 << 16 | r2 (device)
+    int Tn;                    // min(T, R^2)
+    float thr[kStaticSlopes - 1];   // 1.08^(j - 5.5), j = 1..9: boundaries between neighbouring slopes
+};
+// host: the tables for lists of R entries and T tuples; returns Tn
+int make_static_order(int R, int T, std::vector<uint32_t>& table, float thr[kStaticSlopes - 1]);
+hipError_t launch_rank_static(const RankArgs& a, const StaticOrder& so, hipStream_t s);
 
 struct RerankArgs {
     int64_t nq;

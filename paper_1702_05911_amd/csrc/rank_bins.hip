@@ -13,6 +13,9 @@
 // smallest key is located by a histogram over the key range (keys recomputed on the fly, never
 // stored; an exact radix select when the keys tie heavily) and only the T smallest are collected
 // and sorted.
+#include <algorithm>
+#include <cmath>
+
 #include "rank_device.hpp"
 
 namespace pqt {
@@ -251,6 +254,113 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
         const int64_t q = L.force ? (int64_t)item : (int64_t)g.order[item];
         rank_query<0, false, 8>(g, L, q, smem, nullptr, nullptr, nullptr);
     }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Fixed traversal order (Sec. 3.2 "Bin Proposal Heuristic": pre-computed orders for ten slopes
+// 1.08^k instead of the order by summed distance).  The paper prints neither the weighted norm nor
+// the rule that picks a slope; here the order for slope s ranks the pairs v = (v1, v2), counted from
+// 1, by v1^2 + (s v2)^2 (ties by (v1, v2)), and a query takes the slope nearest (geometrically) to
+// g2 / g1, g_p = L_p[min(R-1, 8)] - L_p[0]: the list that rises more slowly is advanced faster.
+// One wavefront per query walks its table 64 tuples at a time and stops when the runs fill C.
+// ------------------------------------------------------------------------------------------------
+constexpr int kStaticThreads = 256;
+constexpr int kSlopeReferenceRank = 8;
+
+__global__ __launch_bounds__(kStaticThreads) void rank_static_kernel(RankArgs g, StaticOrder so) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t q = (int64_t)blockIdx.x * (kStaticThreads / kWave) + threadIdx.x / kWave;
+    if (q >= g.nq) return;
+    const int R = g.R, T = g.T;
+    const uint32_t C = (uint32_t)g.C;
+    const float* L1 = g.L_d + q * 2 * R;
+    const float* L2 = L1 + R;
+    const uint32_t* I1 = g.L_id + q * 2 * R;
+    const uint32_t* I2 = I1 + R;
+    const int r0 = R - 1 < kSlopeReferenceRank ? R - 1 : kSlopeReferenceRank;
+    const float g1 = L1[r0] - L1[0], g2 = L2[r0] - L2[0];
+    int k = 0;
+#pragma unroll
+    for (int j = 0; j < kStaticSlopes - 1; ++j) k += (g2 > so.thr[j] * g1) ? 1 : 0;
+    const uint32_t* tab = so.table + (size_t)k * so.Tn;
+    const bool every_tuple = g.tuples || g.tuple_keys || g.n_tuples;      // taps want them all
+    uint32_t total = 0, nruns = 0;
+    for (int base = 0; base < so.Tn; base += kWave) {
+        const int t = base + lane;
+        uint32_t len = 0, o0 = 0;
+        unsigned long long slot = 0;
+        if (t < so.Tn) {
+            const uint32_t ab = tab[t];
+            const uint32_t a = ab >> 16, b = ab & 0xffffu;
+            slot = (unsigned long long)I1[a] * g.k1k2 + I2[b];
+            o0 = g.offsets[slot];
+            len = g.offsets[slot + 1] - o0;
+            if (g.tuples) {
+                uint16_t* tp = g.tuples + ((size_t)q * T + t) * 4;
+                tp[0] = (uint16_t)a; tp[1] = (uint16_t)b; tp[2] = 0; tp[3] = 0;
+            }
+            if (g.tuple_keys) g.tuple_keys[(size_t)q * T + t] = L1[a] + L2[b];
+        }
+        const uint32_t incl = wave_inclusive_sum(len, lane);
+        const uint32_t start = total + incl - len;
+        const bool emit = len > 0 && start < C;
+        const unsigned long long mask = __ballot(emit);
+        if (emit) {
+            const uint32_t idx = nruns + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+            g.runs[(size_t)q * T + idx] = make_uint2(o0, start);
+            if (g.slots) g.slots[(size_t)q * T + idx] = slot;
+        }
+        nruns += (uint32_t)__popcll(mask);
+        total += (uint32_t)__shfl((int)incl, kWave - 1, kWave);
+        if (total >= C && !every_tuple) break;                  // same for the whole wavefront
+    }
+    if (lane == 0) {
+        g.meta[q] = make_uint2(nruns, total < C ? total : C);
+        if (g.n_tuples) g.n_tuples[q] = (uint32_t)so.Tn;
+    }
+}
+
+int make_static_order(int R, int T, std::vector<uint32_t>& table, float thr[kStaticSlopes - 1]) {
+#pragma clang fp contract(off)
+    const long all = (long)R * R;
+    const int Tn = (int)((long)T < all ? (long)T : all);
+    double slope[kStaticSlopes];
+    slope[5] = 1.0;
+    for (int i = 6; i < kStaticSlopes; ++i) slope[i] = slope[i - 1] * 1.08;
+    for (int i = 4; i >= 0; --i) slope[i] = slope[i + 1] / 1.08;
+    const double root = std::sqrt(1.08);
+    for (int j = 1; j < kStaticSlopes; ++j) thr[j - 1] = (float)(slope[j] / root);
+    struct Item {
+        double key;
+        uint32_t ab;
+    };
+    // a pair can only be among the first Tn of an order that grows in both ranks if (a+1)(b+1) <= Tn
+    std::vector<Item> items;
+    table.assign((size_t)kStaticSlopes * Tn, 0u);
+    for (int i = 0; i < kStaticSlopes; ++i) {
+        items.clear();
+        for (int a = 0; a < R && a < Tn; ++a) {
+            const int nb = region_row_count(a, R, Tn);
+            for (int b = 0; b < nb; ++b) {
+                const double x = a + 1.0, y = slope[i] * (b + 1.0);
+                const double xx = x * x, yy = y * y;
+                items.push_back(Item{xx + yy, ((uint32_t)a << 16) | (uint32_t)b});
+            }
+        }
+        std::sort(items.begin(), items.end(), [](const Item& l, const Item& r) {
+            return l.key != r.key ? l.key < r.key : l.ab < r.ab;           // (key, a, b)
+        });
+        for (int t = 0; t < Tn; ++t) table[(size_t)i * Tn + t] = items[(size_t)t].ab;
+    }
+    return Tn;
+}
+
+hipError_t launch_rank_static(const RankArgs& a, const StaticOrder& so, hipStream_t s) {
+    if (a.nq <= 0) return hipSuccess;
+    if (a.P != 2 || a.hashed || !so.table || so.Tn < 1 || so.Tn > a.T) return hipErrorInvalidValue;
+    constexpr int per = kStaticThreads / kWave;
+    hipLaunchKernelGGL(rank_static_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kStaticThreads), 0, s, a, so);
+    return hipGetLastError();
 }
 
 RankOffsets rank_offsets(int P, int R, int T, int hashed) {

@@ -39,17 +39,19 @@ def _run_debug(pqt, gix, Y, k, w):
     return PU.to_np(ids), PU.to_np(dists), {n: PU.to_np(t) for n, t in taps.items()}
 
 
-def _stagewise(pqt, ix, path, Y, k, w, T, C, exact=False, must_match_all=False):
+def _stagewise(pqt, ix, path, Y, k, w, T, C, exact=False, must_match_all=False, order="fullsort"):
     gix = pqt.pqt_index_load(path, 0)
     try:
         pqt.pqt_set_budget(gix, T, C)
+        if order == "static":
+            pqt.pqt_set_bin_order(gix, pqt.PQT_ORDER_STATIC_SLOPES)
         ids, dists, taps = _run_debug(pqt, gix, Y, k, w)
     finally:
         pqt.pqt_index_free(gix)
     same = decided = 0
     for q in range(Y.shape[0]):
         print(f"query {q}", flush=True)
-        tr = PU.check_query_stages(ix, Y[q], taps, q, k, w, T, C, ids, dists, exact=exact)
+        tr = PU.check_query_stages(ix, Y[q], taps, q, k, w, T, C, ids, dists, exact=exact, order=order)
         y64 = Y[q].astype(np.float64)
         scale = float(np.dot(y64, y64) + np.max(np.sum(ix.C1.astype(np.float64) ** 2, axis=2)) * ix.P)
         s, d = PU.end_to_end_agreement(tr, ids[q], dists[q], scale)
@@ -475,6 +477,55 @@ def test_pair_lambda_native_builder(pqt, tiny_pair, tmp_path):
     assert same_pair >= 0.99 * total
     same, _ = _stagewise(pqt, nix, path, Y[:30], cfg.k, cfg.w, cfg.T, cfg.C)
     assert same >= 27
+
+
+def test_static_slope_order(pqt, tiny, tmp_path, rng):
+    """pqt_set_bin_order(PQT_ORDER_STATIC_SLOPES): the tuples are the pre-computed order of the slope the
+    oracle picks from the GPU's own lists (bit for bit), everything downstream as usual; switching back
+    restores the default answers; unsupported for hashed or four-part indexes."""
+    import torch
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    same, _ = _stagewise(pqt, ix, path, Y[:40], cfg.k, cfg.w, cfg.T, cfg.C, order="static")
+    assert same >= 36
+    for k, w, T, C in ((5, 1, 1, 7), (10, 2, 37, 50), (cfg.k, cfg.k1, cfg.T, cfg.C)):      # ragged tails, R = all leaves
+        _stagewise(pqt, ix, path, Y[:6], k, w, T, C, order="static")
+    # every slope occurs: scale the second half of the query so that one list rises faster or slower
+    slopes = set()
+    for f in (0.05, 0.3, 0.6, 0.8, 0.9, 1.0, 1.1, 1.3, 1.7, 3.0, 20.0):
+        y = Y[:4].copy()
+        y[:, cfg.D // 2:] *= f
+        tr = Q.query(ix, y[0], cfg.k, cfg.w, order_method="static")
+        slopes.add(Q.choose_slope(tr.Ld[0].astype(np.float32), tr.Ld[1].astype(np.float32)))
+        _stagewise(pqt, ix, path, y, cfg.k, cfg.w, cfg.T, cfg.C, order="static")
+    assert len(slopes) >= 6, slopes
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        yq = torch.from_numpy(Y[:50]).cuda()
+        ids0, d0 = pqt.pqt_query_batch(gix, yq, cfg.k, cfg.w)
+        pqt.pqt_set_bin_order(gix, pqt.PQT_ORDER_STATIC_SLOPES)
+        ids1, _ = pqt.pqt_query_batch(gix, yq, cfg.k, cfg.w)
+        pqt.pqt_set_bin_order(gix, pqt.PQT_ORDER_SUMMED_DISTANCE)
+        ids2, d2 = pqt.pqt_query_batch(gix, yq, cfg.k, cfg.w)
+        torch.cuda.synchronize()
+        assert torch.equal(ids0, ids2) and torch.equal(d0, d2)
+        assert not torch.equal(ids0, ids1)                        # the two orders visit different bins
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_set_bin_order(gix, 7)
+        assert e.value.code == pqt.PQT_EINVAL
+    finally:
+        pqt.pqt_index_free(gix)
+    hashed = B.build_index(X[:3000], cfg.P, cfg.k1, cfg.k2, cfg.M, H=1009, T=cfg.T, C=cfg.C, iters=3)
+    hpath = str(tmp_path / "hashed.pqt")
+    IO.write_index(hpath, hashed)
+    gix = pqt.pqt_index_load(hpath, 0)
+    try:
+        with pytest.raises(pqt.PqtError) as e:
+            pqt.pqt_set_bin_order(gix, pqt.PQT_ORDER_STATIC_SLOPES)
+        assert e.value.code == pqt.PQT_EUNSUPPORTED
+    finally:
+        pqt.pqt_index_free(gix)
 
 
 def test_brute_force(pqt, tiny, tmp_path):

@@ -331,6 +331,75 @@ def test_exact_short_list_rerank_is_brute_force_on_the_list(tiny, rng):
     assert np.array_equal(ids_all, bf_ids) and np.array_equal(d_all, bf_d)
 
 
+# ---- the fixed anisotropic traversal order (Sec. 3.2 "Bin Proposal Heuristic") -------------------
+def test_static_order_slopes_are_the_papers():
+    s = Q.slopes()
+    assert s.shape == (10,) and s[5] == 1.0                        # ten slopes 1.08^k, k = -5 .. 4
+    assert np.allclose(s, [1.08 ** k for k in range(-5, 5)], rtol=1e-14, atol=0)
+    thr = Q.slope_thresholds(np.float64)
+    assert thr.shape == (9,) and np.all(s[:-1] < thr) and np.all(thr < s[1:])
+    assert np.allclose(thr * thr, s[:-1] * s[1:], rtol=1e-14, atol=0)       # geometric midpoints
+
+
+def test_static_order_is_a_valid_traversal(rng):
+    """No duplicates; a pair never comes before a pair that is smaller in both ranks; slope 1 is the
+    isotropic order by the Euclidean norm of the 1-based rank vector; slopes s and 1/s mirror each other."""
+    import math
+    for R, T in ((4, 16), (7, 30), (16, 100), (32, 1024)):
+        for i, s in enumerate(Q.slopes()):
+            tup = Q.static_order(R, T, s)
+            assert tup.shape == (min(T, R * R), 2)
+            seen = set()
+            for a, b in tup.tolist():
+                assert (a, b) not in seen
+                assert (a == 0 or (a - 1, b) in seen) and (b == 0 or (a, b - 1) in seen)
+                seen.add((a, b))
+        iso = sorted(((a, b) for a in range(R) for b in range(R)), key=lambda v: (math.hypot(v[0] + 1, v[1] + 1), v))
+        got = [tuple(v) for v in Q.static_order(R, T, 1.0).tolist()]
+        # hypot rounds; integer squared norms decide exactly
+        assert [(a + 1) ** 2 + (b + 1) ** 2 for a, b in got] == [(a + 1) ** 2 + (b + 1) ** 2 for a, b in iso[:len(got)]]
+        lo, hi = Q.slopes()[2], Q.slopes()[8]                       # 1.08^-3 and 1.08^3
+        A = Q.static_order(R, R * R, lo)
+        Bm = Q.static_order(R, R * R, hi)
+        ka = (A[:, 0] + 1.0) ** 2 + (lo * (A[:, 1] + 1.0)) ** 2
+        n = min(T, R * R)
+        if n < R * R and ka[n - 1] < ka[n] * (1 - 1e-9):            # no tie at the cut: the sets mirror
+            assert {(a, b) for a, b in A[:n].tolist()} == {(b, a) for a, b in Bm[:n].tolist()}
+    few = Q.static_order(32, 200, Q.slopes()[0])
+    many = Q.static_order(32, 200, Q.slopes()[9])
+    assert few[:, 1].max() > few[:, 0].max() and many[:, 0].max() > many[:, 1].max()   # smaller slope: deeper into part 2
+
+
+def test_static_order_slope_choice():
+    base = np.arange(20, dtype=np.float32) ** 1.5
+    assert Q.choose_slope(base, base) == 5                           # same rise: slope 1
+    assert Q.choose_slope(3.0 * base + 7.0, 3.0 * base + 1.0) == 5   # offsets and a common scale do not matter
+    assert Q.choose_slope(base, 0.0 * base) == 0                     # list 2 flat: go deep into part 2
+    assert Q.choose_slope(0.0 * base, base) == 9
+    for k in range(-5, 5):
+        assert Q.choose_slope(base, np.float32(1.08 ** k) * base) == k + 5
+        assert Q.choose_slope(base.astype(np.float64), (1.08 ** k) * base.astype(np.float64)) == k + 5
+    assert Q.choose_slope(base[:1], base[:1]) == 0                   # a single entry: nothing rises
+
+
+def test_static_order_costs_at_least_the_summed_distance_order(tiny):
+    """The order by summed distance takes the T smallest sums; any other order's first T sums add up to
+    at least as much, and for T = R^2 both visit everything."""
+    cfg, X, Y, ix = tiny
+    for q in range(10):
+        tr = Q.query(ix, Y[q], cfg.k, cfg.w, with_margins=False)
+        for T in (1, 10, 100):
+            _, ke = Q.bin_order([tr.Ld[0], tr.Ld[1]], T)
+            ts, ks = Q.bin_order_static([tr.Ld[0], tr.Ld[1]], T)
+            assert ks.shape == ke.shape and ks.sum() >= ke.sum() * (1 - 1e-12)
+            assert np.allclose(ks, tr.Ld[0][ts[:, 0]] + tr.Ld[1][ts[:, 1]])
+        R = tr.Ld[0].shape[0]
+        te, _ = Q.bin_order([tr.Ld[0], tr.Ld[1]], R * R)
+        ts, _ = Q.bin_order_static([tr.Ld[0], tr.Ld[1]], R * R)
+        assert {tuple(t) for t in te.tolist()} == {tuple(t) for t in ts.tolist()}
+        assert tuple(ts[0]) == (0, 0)                                # the best bin first (Sec. 3.2)
+
+
 # ---- codes stored as (centroid pair, lambda level): Eq. 7 directly -----------------------------
 def test_pair_lambda_score_equals_distance_to_reconstruction(tiny_pair):
     cfg, X, Y, ix = tiny_pair
