@@ -699,16 +699,9 @@ def test_sift_full_size_index_is_valid(sift_full):
     assert mism <= 4          # the fp32 builder may settle a near-tie differently from float64
 
 
-@pytest.mark.parametrize("w", [8, 1])
-def test_sift_full_size_parity(pqt, sift_full, w):
-    import torch
-    cfg, X, Y, path, ix = sift_full
-    gix = pqt.pqt_index_load(path, 0)
-    try:
-        ids, dists, taps = _run_debug(pqt, gix, Y, cfg.k, w)
-    finally:
-        pqt.pqt_index_free(gix)
-    # properties on every query
+def _full_size_check(pqt, gix, ix, cfg, Y, w, order="fullsort", label="sift"):
+    """Properties on every query of the batch bench.py times, and the oracle stage by stage on a sample."""
+    ids, dists, taps = _run_debug(pqt, gix, Y, cfg.k, w)
     nc = taps["n_cand"].astype(np.int64)
     assert np.all(nc <= cfg.C) and np.all(nc > 0)
     for q in range(cfg.nq):
@@ -718,20 +711,71 @@ def test_sift_full_size_parity(pqt, sift_full, w):
         assert np.array_equal(ids[q][:len(o)], cid[o]), f"query {q}: top-k is not the k smallest (score, id)"
         assert np.array_equal(dists[q][:len(o)], sc[o])
         assert len(set(cid.tolist())) == n
-    # the oracle, stage by stage, on a sample
     same = decided = 0
     sample = list(range(0, cfg.nq, 417))
     for q in sample:
-        print(f"w={w} query {q}", flush=True)
-        tr = PU.check_query_stages(ix, Y[q], taps, q, cfg.k, w, cfg.T, cfg.C, ids, dists)
+        print(f"{label} w={w} query {q}", flush=True)
+        tr = PU.check_query_stages(ix, Y[q], taps, q, cfg.k, w, cfg.T, cfg.C, ids, dists, order=order)
         y64 = Y[q].astype(np.float64)
         scale = float(np.dot(y64, y64) + np.max(np.sum(ix.C1.astype(np.float64) ** 2, axis=2)) * ix.P)
         s, d = PU.end_to_end_agreement(tr, ids[q], dists[q], scale)
         assert s or not d, f"query {q}: margins above threshold but ids differ"
         same += s
         decided += d
-    print(f"sift w={w}: {same}/{len(sample)} sampled queries identical to the float64 oracle, {decided} decided")
+    print(f"{label} w={w}: {same}/{len(sample)} sampled queries identical to the float64 oracle, {decided} decided")
     assert same >= 0.8 * len(sample)
+
+
+@pytest.mark.parametrize("w", [8, 1])
+def test_sift_full_size_parity(pqt, sift_full, w):
+    cfg, X, Y, path, ix = sift_full
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        _full_size_check(pqt, gix, ix, cfg, Y, w)
+    finally:
+        pqt.pqt_index_free(gix)
+
+
+def test_sift_full_size_static_order(pqt, sift_full):
+    cfg, X, Y, path, ix = sift_full
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        pqt.pqt_set_bin_order(gix, pqt.PQT_ORDER_STATIC_SLOPES)
+        _full_size_check(pqt, gix, ix, cfg, Y, cfg.w, order="static", label="sift static order")
+    finally:
+        pqt.pqt_index_free(gix)
+
+
+def test_sift_full_size_pair_lambda_codes(pqt, sift_full, tmp_path):
+    """The same codebooks and database with (pair, lambda) codes from the library's streaming builder."""
+    import torch
+    cfg, X, Y, path, ix = sift_full
+    params = dict(N=cfg.N, H=ix.H, D=ix.D, P=ix.P, k1=ix.k1, k2=ix.k2, M=ix.M, T=ix.T, C=ix.C,
+                  C1=ix.C1, C2=ix.C2, cc=ix.cc, code_format=1)
+    b = pqt.pqt_builder_create(params, 0)
+    try:
+        for lo in range(0, cfg.N, 1 << 18):
+            pqt.pqt_builder_add(b, torch.from_numpy(X[lo:lo + (1 << 18)]).cuda())
+            torch.cuda.synchronize()
+        gix = pqt.pqt_builder_finish(b)
+    finally:
+        pqt.pqt_builder_free(b)
+    ppath = str(tmp_path / "sift_pair.pqt")
+    try:
+        pqt.pqt_index_save(gix, ppath)
+        pix = IO.read_index(ppath)
+        off = pix.offsets.astype(np.int64)
+        assert pix.code_format == 1 and off[0] == 0 and off[-1] == cfg.N and np.all(np.diff(off) >= 0)
+        assert np.array_equal(np.sort(pix.ids), np.arange(cfg.N, dtype=np.uint32))
+        # the same bins as the index of the other builder, up to fp32 near-ties
+        slot_a = np.empty(cfg.N, np.int64)
+        slot_a[pix.ids] = np.repeat(np.arange(pix.H), np.diff(off))
+        slot_b = np.empty(cfg.N, np.int64)
+        slot_b[ix.ids] = np.repeat(np.arange(ix.H), np.diff(ix.offsets.astype(np.int64)))
+        assert np.mean(slot_a != slot_b) <= 2e-3
+        _full_size_check(pqt, gix, pix, cfg, Y, cfg.w, label="sift pair codes")
+    finally:
+        pqt.pqt_index_free(gix)
 
 
 @pytest.fixture(scope="module")
