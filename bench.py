@@ -151,6 +151,7 @@ def main():
     ap.add_argument("--nq", type=int, default=None, help="queries per step (default: the workload's)")
     ap.add_argument("--T", type=int, default=None, help="bin tuples examined per query (default: the workload's)")
     ap.add_argument("--C", type=int, default=None, help="candidate budget per query (default: the workload's)")
+    ap.add_argument("--k", type=int, default=None, help="results per query (default: the workload's)")
     ap.add_argument("--exact", type=int, default=0, metavar="K_SHORT",
                     help="also time pqt_query_batch_exact: exact re-ranking of the first K_SHORT results (the raw "
                          "vectors stay in HBM, one byte per element for the integer-valued workloads)")
@@ -197,6 +198,8 @@ def main():
         cfg = cfg.with_(T=args.T)
     if args.C:
         cfg = cfg.with_(C=args.C)
+    if args.k:
+        cfg = cfg.with_(k=args.k)
     if args.M:
         cfg = cfg.with_(M=args.M)
     w = args.w or cfg.w

@@ -127,6 +127,13 @@ __global__ void histogram_kernel(const uint32_t* slots, uint64_t n, uint32_t* co
     if (i < n) atomicAdd(&counts[slots[i]], 1u);
 }
 
+// number of slots that hold at least one vector (one atomic per wavefront)
+__global__ void count_nonempty_kernel(const uint32_t* counts, uint64_t n, unsigned long long* out) {
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned long long mask = __ballot(i < n && counts[i] > 0);
+    if ((threadIdx.x & (kWave - 1)) == 0 && mask) atomicAdd(out, (unsigned long long)__popcll(mask));
+}
+
 // codes_out[i] = codes_in[order[i]], one thread per row of M bytes
 __global__ void permute_codes_kernel(const uint8_t* in, const uint32_t* order, uint64_t n, int M, uint8_t* out) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -301,6 +308,17 @@ int pqt_builder_finish(pqt_builder* b, pqt_index** out) {
     BUILD_TRY(hipMalloc(reinterpret_cast<void**>(&offsets), sizeof(uint32_t) * ((size_t)ix->H + 1)));
     BUILD_TRY(hipMemset(counts, 0, sizeof(uint32_t) * ((size_t)ix->H + 1)));
     hipLaunchKernelGGL(pqt::histogram_kernel, dim3(nb), dim3(tb), 0, 0, b->slots, N, counts);
+    unsigned long long* nonempty_dev = nullptr;
+    unsigned long long nonempty = 0;
+    BUILD_TRY(hipMalloc(reinterpret_cast<void**>(&nonempty_dev), sizeof(unsigned long long)));
+    hipError_t ce = hipMemset(nonempty_dev, 0, sizeof(unsigned long long));
+    if (ce == hipSuccess) {
+        hipLaunchKernelGGL(pqt::count_nonempty_kernel, dim3((unsigned)((ix->H + tb - 1) / tb)), dim3(tb), 0, 0, counts,
+                           (uint64_t)ix->H, nonempty_dev);
+        ce = hipMemcpy(&nonempty, nonempty_dev, sizeof(nonempty), hipMemcpyDeviceToHost);
+    }
+    (void)hipFree(nonempty_dev);
+    BUILD_TRY(ce);
     temp_bytes = 0;
     BUILD_TRY(hipcub::DeviceScan::ExclusiveSum(nullptr, temp_bytes, counts, offsets, (size_t)ix->H + 1));
     BUILD_TRY(hipMalloc(&temp, temp_bytes ? temp_bytes : 1));
@@ -319,6 +337,7 @@ int pqt_builder_finish(pqt_builder* b, pqt_index** out) {
     ix->codes = codes_out;
     ix->bytes_index += (uint64_t)N * (4 + ix->code_bytes());
     ix->N = N;
+    ix->nonempty_slots = nonempty;
     ix->free_workspace();                 // sized for the builder's chunks and w = 1
     (void)hipFree(b->slots); (void)hipFree(b->codes); (void)hipFree(b->leaf);
     b->slots = nullptr; b->codes = nullptr; b->leaf = nullptr;

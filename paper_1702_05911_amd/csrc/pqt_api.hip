@@ -89,17 +89,30 @@ int upload(Tp** dev, const void* src, size_t bytes, hipMemcpyKind kind, uint64_t
     return PQT_OK;
 }
 
-// workgroup size of the re-rank kernel (PQT_RERANK_THREADS overrides: 256, 512 or 1024)
-int rerank_threads(const pqt_index* ix) {
+// Workgroup size of the re-rank kernel and candidates per thread: the fewest threads that hold the
+// candidate budget (a thread keeps the keys of its candidates in registers; fewer threads per query
+// leave room for more queries per compute unit).  PQT_RERANK_THREADS asks for more threads.
+int rerank_threads(const pqt_index* ix, int* keys_per_thread = nullptr) {
     static const int forced = [] {
         const char* e = getenv("PQT_RERANK_THREADS");
         const int v = e ? atoi(e) : 0;
         return (v == 256 || v == 512 || v == 1024) ? v : 0;
     }();
-    // the exact-selection fallback borrows the LUT area (M*1024 bytes) for one word per thread
-    const int cap = (int)ix->M * 256 < 256 ? 256 : (int)ix->M * 256;
-    int t = forced ? forced : (ix->C >= 2048 ? 512 : 256);
-    return t < cap ? t : cap;
+    int t, kpt;
+    pqt::rerank_shape((int)ix->C, (int)ix->M, (int)ix->code_format, &t, &kpt);
+    if (keys_per_thread) *keys_per_thread = kpt;
+    return forced > t ? forced : t;
+}
+
+// Runs of a query the re-rank workgroup keeps in LDS: twice what the candidate budget needs at the
+// index's mean run length, as a power of two (the kernel clamps it to 64..T and reads longer lists
+// from memory).
+int rerank_runs_in_lds(const pqt_index* ix) {
+    const double mean_run = ix->nonempty_slots ? (double)ix->N / (double)ix->nonempty_slots : 1.0;
+    const double want = 2.0 * (double)ix->C / (mean_run < 1.0 ? 1.0 : mean_run);
+    int r = 64;
+    while (r < (int)ix->T && (double)r < want) r *= 2;
+    return r;
 }
 
 // Can the re-rank kernel also run the full bin ranking of the queries the head pass leaves over?
@@ -110,7 +123,8 @@ bool can_fuse_ranking(const pqt_index* ix, int k, int w) {
     const int threads = rerank_threads(ix);
     const pqt::RankOffsets ro = pqt::rank_offsets(ix->P, R, ix->T, ix->hashed);
     if (ro.Tcap > pqt::rerank_fused_tuples_per_thread() * threads) return false;
-    return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total, (int)ix->code_format) <= g_lds_limit;
+    return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total, (int)ix->code_format,
+                                 rerank_runs_in_lds(ix)) <= g_lds_limit;
 }
 
 int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
@@ -118,7 +132,8 @@ int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
     const size_t l1 = pqt::traverse_lds_bytes(ix->D, ix->P, ix->k1, ix->k2, ix->M, w);
     const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed ? 1 : 2);   // 2: room for the slots tap
     const int threads = rerank_threads(ix);
-    const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0, (int)ix->code_format);
+    const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0, (int)ix->code_format,
+                                            rerank_runs_in_lds(ix));
     if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)
         return fail(PQT_EUNSUPPORTED,
                     "LDS budget exceeded (traverse %zu, rank %zu, rerank %zu bytes of %zu) for D=%u M=%u k1=%u R=%d T=%u C=%u",
@@ -207,8 +222,11 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
         off = off_copy.data();
     }
     if (off[0] != 0 || off[h.H] != h.N) return fail(PQT_EFORMAT, "offsets do not span the ids");
-    for (size_t s = 0; s < h.H; ++s)
+    uint64_t nonempty = 0;
+    for (size_t s = 0; s < h.H; ++s) {
         if (off[s + 1] < off[s]) return fail(PQT_EFORMAT, "offsets not monotone at slot %zu", s);
+        nonempty += off[s + 1] > off[s] ? 1 : 0;
+    }
     const size_t ntab = (size_t)h.M * 256;
     for (size_t e = 0; e < ntab && !pair_codes; ++e)
         if (h.tbl_i[e] >= h.k1 || h.tbl_j[e] >= h.k1) return fail(PQT_EFORMAT, "code table names centroid >= k1");
@@ -295,6 +313,7 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     ix->N = h.N; ix->H = h.H; ix->device = device;
     ix->hashed = (long double)h.H != K;
     ix->code_format = h.code_format;
+    ix->nonempty_slots = nonempty;
     try {
         ix->h_C1.assign(h.C1, h.C1 + (size_t)h.P * h.k1 * dp);
         ix->h_C2.assign(h.C2, h.C2 + (size_t)h.P * h.k1 * h.k2 * dp);
@@ -575,8 +594,9 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
 
     pqt::RerankArgs ca;
     ca.nq = nq; ca.M = ix->M; ca.k1 = ix->k1; ca.T = ix->T; ca.C = ix->C; ca.k = k;
-    ca.threads = rerank_threads(ix);
+    ca.threads = rerank_threads(ix, &ca.keys_per_thread);
     ca.code_format = (int)ix->code_format;
+    ca.runs_in_lds = rerank_runs_in_lds(ix);
     ca.a = ix->ws_a; ca.table = ix->table; ca.runs = ix->ws_runs; ca.meta = ix->ws_meta;
     ca.ids = ix->ids; ca.codes = ix->codes; ca.out_ids = out_ids; ca.out_dists = out_dists;
     ca.todo = ix->ws_order; ca.todo_count = ix->ws_counters;

@@ -43,6 +43,7 @@ struct pqt_index {
     uint64_t N = 0, H = 0;
     int device = 0;
     bool hashed = false;
+    uint64_t nonempty_slots = 0;       // slots that hold at least one vector
     uint32_t code_format = 0;          // PQT_CODES_TABLE or PQT_CODES_PAIR_LAMBDA
     uint32_t code_bytes() const { return M * (code_format == 1 ? 2u : 1u); }   // per vector
     // index arrays (device)

@@ -95,12 +95,16 @@ struct RerankArgs {
     int64_t nq;
     int M, k1, T, C, k;
     int threads;              // workgroup size (multiple of 64)
+    int keys_per_thread;      // candidates a thread scores; both from rerank_shape
     const float* a;           // nq x M x k1
     const CodeEntry* table;   // M x 256
     int code_format;          // 0: codes are entries of the table, one byte per sub-part;
                               // 1: two bytes per sub-part, (centroid pair, lambda level); the table is then
                               //    indexed by pair number and its kc field holds ||c_i - c_j||^2
     int pair_shift;           // code format 1: log2 of the LDS table's entries per sub-part (set by launch_rerank)
+    int runs_in_lds;          // runs of a query the workgroup keeps in LDS (at least 64, at most T); a longer list
+                              // is read from memory past that.  Sized from the index's mean run length so that
+                              // the common case fits without spending LDS (and thus resident queries) on it.
     const uint2* runs;
     const uint2* meta;
     const uint32_t* ids;
@@ -120,9 +124,13 @@ struct RerankArgs {
     float* lut;               // nq x M x 256
 };
 // rank_lds: LDS bytes of the full ranking pass when the kernel also runs it (0: it does not)
-size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format);
+size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format,
+                        int runs_in_lds);
 // tuples per thread the in-kernel ranking can hold: fusing needs min(T, R^2) <= that * threads
 int rerank_fused_tuples_per_thread();
+// workgroup size and candidates per thread of the re-rank kernel for a candidate budget C
+// (C <= threads * keys_per_thread; the fewest threads that hold the budget)
+void rerank_shape(int C, int M, int code_format, int* threads, int* keys_per_thread);
 // fused: the full ranking pass of the queries whose meta.x is kMetaTodo runs inside the kernel
 hipError_t launch_rerank(const RerankArgs& a, const RankArgs* fused, hipStream_t s);
 

@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffs
     const uint32_t count = L.force ? (uint32_t)g.nq : g.counters[0];
     for (uint32_t item = blockIdx.x; item < count; item += gridDim.x) {
         const int64_t q = L.force ? (int64_t)item : (int64_t)g.order[item];
-        rank_query<0, false, 8>(g, L, q, smem, nullptr, nullptr, nullptr);
+        rank_query<0, false, 8>(g, L, q, smem, nullptr);
     }
 }
 

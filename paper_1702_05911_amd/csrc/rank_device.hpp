@@ -195,13 +195,13 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
 }
 
 // The full ranking of query q.  PF: 0 = the number of tree parts is read from g.P, 2 = it is two
-// (the other cases are compiled out).  TO_LDS: the run list goes to out_src / out_start (LDS, T
-// entries) and out_counts[0..1] = (number of runs, number of candidates) instead of g.runs / g.meta.
+// (the other cases are compiled out).  The run list goes to g.runs.  TO_LDS: (number of runs, number
+// of candidates) go to out_counts[0..1] in LDS instead of g.meta (the caller goes on with the query).
 // MAXPER (2, 4 or 8): tuples a thread may have to hold, L.Tcap <= MAXPER * blockDim.x.
 // smem: the workgroup's LDS, laid out by L.  Every thread calls it; ends with a barrier.
 template <int PF, bool TO_LDS, int MAXPER>
 __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets& L, int64_t q, unsigned char* smem,
-                                           uint32_t* out_src, uint32_t* out_start, uint32_t* out_counts) {
+                                           uint32_t* out_counts) {
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + L.keys);
     unsigned long long* dkeys = keys;                       // (slot, position) keys reuse the sort buffer
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
@@ -342,13 +342,8 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
 #pragma unroll
         for (int i = 0; i < kMaxPer; ++i) {
             if (((flags >> i) & 1u) == 0) continue;
-            if (TO_LDS) {
-                out_src[idx] = o0[i];
-                out_start[idx] = first[i];
-            } else {
-                g.runs[(size_t)q * T + idx] = make_uint2(o0[i], first[i]);
-                if (g.slots) g.slots[(size_t)q * T + idx] = sslot[t0 + i];
-            }
+            g.runs[(size_t)q * T + idx] = make_uint2(o0[i], first[i]);
+            if (!TO_LDS && g.slots) g.slots[(size_t)q * T + idx] = sslot[t0 + i];
             ++idx;
         }
         if (tid == 0) {

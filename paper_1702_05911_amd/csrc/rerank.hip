@@ -9,90 +9,123 @@
 //     LDS) forwards; consecutive lanes read consecutive codes (coalesced), eight positions per
 //     thread in flight; the id array is only touched for the few survivors;
 //   * score = sum over m = 0..M-1, in that order, of LUT[m][code[m]] in fp32;
+//   * a thread scores at most twenty candidates and keeps their keys (ordered score bits) in
+//     registers through the selection: the kernel is bound by the latency of its dependent steps,
+//     so what counts is how many queries a compute unit has in flight, and that is set by the LDS
+//     a workgroup holds -- a key array in LDS would double it;
 //   * the k best by (score, id): one 1024-bin histogram over the ordered score bits between the
-//     smallest and largest score of the query; every wavefront locates the bin b that holds the
-//     k-th smallest; the positions in bins <= b (a superset of the answer, normally a few more
-//     than k) are compacted, their ids fetched, and the (score bits, id) keys ordered by counting
-//     ranks, four lanes per survivor.  If the superset does not fit (heavily tied scores) an
-//     exact radix select on score bits, then on ids, picks exactly k.
+//     smallest and largest score of the query; the first wavefront locates the bin b that holds the
+//     k-th smallest; the keys in bins <= b (a superset of the answer, normally a few more
+//     than k) are appended to a short list with their positions, their ids fetched, and the
+//     (score bits, id) keys sorted in registers.  If the superset does not fit (heavily tied
+//     scores) an exact radix select on score bits, then on ids, picks exactly k.
 #include "rank_device.hpp"
 
 namespace pqt {
 
 constexpr int kHistBits = 10;
 constexpr int kHistSize = 1 << kHistBits;
-constexpr int kCountRankMax = 512;   // survivors ordered by counting ranks up to this many, else bitonic
+constexpr int kCountRankMax = 32;    // survivors ordered by counting ranks up to this many, else sorted
 constexpr int kRunPrefetch = 64;     // runs fetched before the run count is known
-constexpr int kFusedPer = 2;         // tuples per thread the in-kernel bin ranking may hold (keeps registers low)
+constexpr int kFusedPer = 4;         // tuples per thread the in-kernel bin ranking may hold
+constexpr int kKeysPerThread = 20;   // candidates a thread scores; C <= kKeysPerThread * workgroup size
+constexpr int kRunsInLdsMin = 64;    // at least this many runs of a query are kept in LDS (see RerankArgs::runs_in_lds)
 
 struct RerankLds {
-    int kpad, scap;
-    uint32_t surv, spos, lut, a, run_src, run_start, skey, hist, misc, total;
+    int kpad, scap, rcap;
+    uint32_t surv, lut, a, run_src, run_start, hist, part, misc, total;
 };
 
 // (pair, lambda) codes: entries per sub-part in the LDS table of centroid pairs (128 while the pairs fit)
 static int pair_table_shift(int k1) { return k1 * (k1 - 1) / 2 <= 128 ? 7 : 8; }
 
-static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format) {
+static RerankLds rerank_layout(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format,
+                               int runs_in_lds) {
     RerankLds L;
-    (void)threads;
+    (void)C;
     L.kpad = next_pow2(k);
     L.scap = 2 * L.kpad < 256 ? 256 : 2 * L.kpad;
+    const int want = runs_in_lds < kRunsInLdsMin ? kRunsInLdsMin : runs_in_lds;
+    L.rcap = T < want ? T : want;
     size_t o = 0;
-    // at offset 0: lookups need no base register; also the scan scratch of the exact fallback.
+    // at offset 0: lookups need no base register.
     // One float per table entry, or (b^2, a^2 - b^2, c^2, -) per centroid pair for (pair, lambda) codes.
     L.lut = (uint32_t)o;       o += code_format == 1 ? sizeof(float4) * ((size_t)M << pair_table_shift(k1)) : sizeof(float) * M * 256;
-    L.skey = (uint32_t)o;      o += sizeof(uint32_t) * ((C + 3) & ~3);
     L.surv = (uint32_t)o;      o += sizeof(unsigned long long) * L.scap;
     L.hist = (uint32_t)o;      o += sizeof(uint32_t) * kHistSize;
+    L.part = (uint32_t)o;      o += sizeof(uint32_t) * threads;      // scan scratch of the exact selection
     // everything above is free while a workgroup runs the full bin ranking of its query, which uses
     // the first rank_lds bytes; the arrays below receive its result
     if (o < rank_lds) o = (rank_lds + 15) & ~size_t(15);
     L.a = (uint32_t)o;         o += sizeof(float) * M * k1;
-    L.run_src = (uint32_t)o;   o += sizeof(uint32_t) * T;
-    L.run_start = (uint32_t)o; o += sizeof(uint32_t) * (T + 1);
+    L.run_src = (uint32_t)o;   o += sizeof(uint32_t) * L.rcap;
+    L.run_start = (uint32_t)o; o += sizeof(uint32_t) * (L.rcap + 1);
     L.misc = (uint32_t)o;      o += sizeof(uint32_t) * 16;
-    L.spos = (uint32_t)o;      o += sizeof(uint16_t) * L.scap;
     o = (o + 15) & ~size_t(15);
     L.total = (uint32_t)o;
     return L;
 }
 
-size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format) {
-    return rerank_layout(M, k1, T, C, k, threads, rank_lds, code_format).total;
+size_t rerank_lds_bytes(int M, int k1, int T, int C, int k, int threads, size_t rank_lds, int code_format,
+                        int runs_in_lds) {
+    return rerank_layout(M, k1, T, C, k, threads, rank_lds, code_format, runs_in_lds).total;
 }
 
+void rerank_shape(int C, int M, int code_format, int* threads, int* keys_per_thread) {
+    int t = 256;
+    while (t < 1024 && C > kKeysPerThread * t) t *= 2;
+    (void)M;
+    (void)code_format;
+    *threads = t;
+    *keys_per_thread = kKeysPerThread;
+}
+
+// The run list of one query: the first rcap runs in LDS, any further ones in memory.  The LDS arrays
+// are named by their byte addresses (the kernels here have no static LDS, so the dynamic LDS starts
+// at address 0; the launcher checks that).
+typedef __attribute__((address_space(3))) const uint32_t lds_cuint;
+struct RunList {
+    uint32_t src, start;       // LDS addresses of run_src / run_start
+    const uint2* mem;          // runs of this query in memory
+    int rcap, nr;
+    uint32_t nc;
+    __device__ __forceinline__ uint32_t start_at(int r) const {   // r <= nr
+        return r < rcap || r == nr && nr <= rcap ? *reinterpret_cast<lds_cuint*>((uintptr_t)(start + 4u * (uint32_t)r))
+                                                 : (r < nr ? mem[r].y : nc);
+    }
+    __device__ __forceinline__ uint32_t src_at(int r) const {     // r < nr
+        return r < rcap ? *reinterpret_cast<lds_cuint*>((uintptr_t)(src + 4u * (uint32_t)r)) : mem[r].x;
+    }
+};
+
 // Position p of the candidate list -> position in ids/codes: the run r with
-// run_start[r] <= p < run_start[r+1], found in `steps` = ceil(log2(nr)) halvings.
-__device__ __forceinline__ uint32_t source_of(uint32_t p, int nr, int steps, const uint32_t* run_src,
-                                              const uint32_t* run_start) {
-    int lo = 0, hi = nr;
+// start(r) <= p < start(r+1), found in `steps` = ceil(log2(nr)) halvings.
+__device__ __forceinline__ uint32_t source_of(uint32_t p, int steps, const RunList& R) {
+    int lo = 0, hi = R.nr;
     for (int s = 0; s < steps; ++s) {
         const int mid = (lo + hi) >> 1;
-        const bool ge = run_start[mid] <= p;
+        const bool ge = R.start_at(mid) <= p;
         lo = ge ? mid : lo;
         hi = ge ? hi : mid;
     }
-    return run_src[lo] + (p - run_start[lo]);
+    return R.src_at(lo) + (p - R.start_at(lo));
 }
 
-// One pass of a most-significant-digit radix select (exact fallback).  Counts, among the n items
-// whose key agrees with `prefix` on the bits of `mask`, the digit (key >> shift) & (2^bits - 1);
-// finds the digit holding the item of 1-based rank `need`.  out[0] = digit, out[1] = rank inside
-// it, out[2] = size of the chosen digit's bucket.  All threads must call it; ends with a barrier.
-template <typename KeyFn>
-__device__ __forceinline__ void radix_select_pass(int n, uint32_t prefix, uint32_t mask, int shift, int bits,
-                                                  uint32_t need, uint32_t* hist, uint32_t* part,
-                                                  uint32_t* out, KeyFn get_key) {
+// One pass of a most-significant-digit radix select (exact fallback).  Counts, among the items whose
+// key agrees with `prefix` on the bits of `mask`, the digit (key >> shift) & (2^bits - 1); finds the
+// digit holding the item of 1-based rank `need`.  out[0] = digit, out[1] = rank inside it, out[2] =
+// size of the chosen digit's bucket.  each_key(f) calls f(key) for every item of the calling thread.
+// All threads must call it; ends with a barrier.
+template <typename EachKey>
+__device__ __forceinline__ void radix_select_pass(uint32_t prefix, uint32_t mask, int shift, int bits, uint32_t need,
+                                                  uint32_t* hist, uint32_t* part, uint32_t* out, EachKey each_key) {
     const int tid = threadIdx.x, nt = blockDim.x;
     const int nb = 1 << bits;
     for (int e = tid; e < nb; e += nt) hist[e] = 0;
     __syncthreads();
-    for (int p = tid; p < n; p += nt) {
-        bool valid;
-        const uint32_t key = get_key(p, valid);
-        if (valid && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
-    }
+    each_key([&](uint32_t key) {
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
+    });
     __syncthreads();
     const int chunk = (nb + nt - 1) / nt;
     const int lo = min(tid * chunk, nb), hi = min(lo + chunk, nb);
@@ -131,8 +164,8 @@ __device__ __forceinline__ float lut_at(int m, uint32_t c) {
 }
 
 // The run a thread's current candidate position lies in, kept in registers: positions of a thread
-// only grow, so the run only moves forwards and LDS is read only when a position crosses into the
-// next run.
+// only grow, so the run only moves forwards and the run list is read only when a position crosses
+// into another run.
 struct RunCursor {
     int run;
     uint32_t next_start;   // run_start[run + 1]
@@ -148,12 +181,12 @@ __device__ __forceinline__ float pair_lambda_term(const float4* plut, int shift,
     return fmaf(fmaf(lam, lam, -lam), e.z, fmaf(lam, e.y, e.x));
 }
 
-// Scores U candidate positions per thread (base + u*nt + tid).  CHECK: positions may pass nc.
+// Scores U candidate positions per thread (base + u*nt + tid) and leaves their keys (ordered score
+// bits) in key[0..U).  CHECK: positions may pass nc (their keys are left alone).
 template <int MW, int U, bool CHECK, bool TAPS>
 __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int base, int nc, int tid, int nt,
-                                            const float* lut, uint32_t* skey, const uint32_t* run_src,
-                                            const uint32_t* run_start, RunCursor& cur, uint32_t& kmin,
-                                            uint32_t& kmax) {
+                                            const float* lut, uint32_t* key, const RunList& R, RunCursor& cur,
+                                            uint32_t& kmin, uint32_t& kmax) {
     constexpr int NW = MW > 0 ? MW : (MW < -1 ? -MW : 0);      // code words fetched up front (0: byte loads)
     const int M = MW > 0 ? 4 * MW : (MW < -1 ? -2 * MW : g.M);
     uint32_t src[U];
@@ -162,14 +195,29 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
     for (int u = 0; u < U; ++u) {
         const uint32_t p = (uint32_t)(base + u * nt + tid);
         if (!CHECK || p < (uint32_t)nc) {
-            while (p >= cur.next_start) {                          // run_start[nr] = nc > p ends the walk
-                ++cur.run;
-                cur.next_start = run_start[cur.run + 1];
-                cur.delta = run_src[cur.run] - run_start[cur.run];
+            if (p >= cur.next_start) {
+                // usually the next run (long runs); otherwise the run is found by halving what is left of
+                // the list (short runs: a step of nt positions passes many of them)
+                int lo = cur.run + 1;
+                uint32_t next = R.start_at(lo + 1);
+                if (p >= next) {
+                    int hi = R.nr;                                  // start_at(lo) <= p < start_at(hi) = nc
+                    ++lo;
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        const bool ge = R.start_at(mid) <= p;
+                        lo = ge ? mid : lo;
+                        hi = ge ? hi : mid;
+                    }
+                    next = R.start_at(lo + 1);
+                }
+                cur.run = lo;
+                cur.next_start = next;
+                cur.delta = R.src_at(lo) - R.start_at(lo);
             }
             src[u] = p + cur.delta;
         } else {
-            src[u] = run_src[0];
+            src[u] = R.src_at(0);
         }
     }
     if (NW > 0) {
@@ -230,10 +278,10 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
             s = 0.0f;
             for (int m = 0; m < M; ++m) s += lut[m * 256 + code[m]];
         }
-        const uint32_t key = mono_key(s);
-        skey[p] = key;
-        kmin = min(kmin, key);
-        kmax = max(kmax, key);
+        const uint32_t ky = mono_key(s);
+        key[u] = ky;
+        kmin = min(kmin, ky);
+        kmax = max(kmax, ky);
         if (TAPS) {
             if (g.scores) g.scores[(size_t)q * g.C + p] = s;
             if (g.cand_ids) g.cand_ids[(size_t)q * g.C + p] = (int64_t)g.ids[src[u]];
@@ -242,20 +290,19 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
 }
 
 // MW = 32-bit words per code (M/4) for M in {4, 8, 16, 32}; 0 = any other M (byte loads);
-// kPairLambda = codes hold (centroid pair, lambda level) per sub-part, scored by Eq. 9 directly.
+// MW < 0 = codes hold (centroid pair, lambda level) per sub-part, scored by Eq. 9 directly.
 // FUSED: a query whose meta.x is kMetaTodo (the ranking head pass could not finish it) is first
-// ranked in full by this workgroup, which leaves the run list directly in LDS.
+// ranked in full by this workgroup.
 template <int MW, bool TAPS, bool FUSED>
-__global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs g, RerankLds L, RankArgs rk, RankOffsets RL) {
+__global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g, RerankLds L, RankArgs rk, RankOffsets RL) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* surv = reinterpret_cast<unsigned long long*>(smem + L.surv);
-    uint16_t* spos = reinterpret_cast<uint16_t*>(smem + L.spos);
     float* lut = reinterpret_cast<float*>(smem);                 // L.lut == 0
     float* sa = reinterpret_cast<float*>(smem + L.a);
     uint32_t* run_src = reinterpret_cast<uint32_t*>(smem + L.run_src);
     uint32_t* run_start = reinterpret_cast<uint32_t*>(smem + L.run_start);
-    uint32_t* skey = reinterpret_cast<uint32_t*>(smem + L.skey);
     uint32_t* hist = reinterpret_cast<uint32_t*>(smem + L.hist);
+    uint32_t* part = reinterpret_cast<uint32_t*>(smem + L.part);
     uint32_t* misc = reinterpret_cast<uint32_t*>(smem + L.misc);
 
     const int tid = threadIdx.x, nt = blockDim.x;
@@ -274,16 +321,16 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
         meta = g.meta[q];
         if (g.early > 0 && meta.x == kMetaTodo && meta.y < (uint32_t)g.early) return;   // an early workgroup has it
     }
-    bool ranked_here = false;
     if (FUSED && meta.x == kMetaTodo) {        // same for the whole workgroup
-        rank_query<2, true, kFusedPer>(rk, RL, q, smem, run_src, run_start, misc + kRanked);
+        // the run list goes to memory (this query's own rows), the counts come back through LDS
+        rank_query<2, true, kFusedPer>(rk, RL, q, smem, misc + kRanked);
         meta = make_uint2(misc[kRanked], misc[kRanked + 1]);
-        ranked_here = true;
     }
+    const uint2* qruns = g.runs + (size_t)q * T;
 
     // ---- issue every load that needs no other result first ------------------------------------------
     uint2 run0 = make_uint2(0u, 0u);
-    if (!ranked_here && tid < kRunPrefetch && tid < T) run0 = g.runs[(size_t)q * T + tid];
+    if (tid < kRunPrefetch && tid < L.rcap) run0 = qruns[tid];
     CodeEntry ent[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -296,31 +343,35 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
     const int nc = (int)meta.y;
     int steps = 0;
     while ((1 << steps) < nr) ++steps;
-    if (!ranked_here) {
-        if (tid < kRunPrefetch && tid < nr) {
-            run_src[tid] = run0.x;
-            run_start[tid] = run0.y;
-        }
-        for (int r = kRunPrefetch + tid; r < nr; r += nt) {
-            const uint2 run = g.runs[(size_t)q * T + r];
-            run_src[r] = run.x;
-            run_start[r] = run.y;
-        }
+    const int nr_lds = nr < L.rcap ? nr : L.rcap;
+    if (tid < kRunPrefetch && tid < nr_lds) {
+        run_src[tid] = run0.x;
+        run_start[tid] = run0.y;
+    }
+    for (int r = kRunPrefetch + tid; r < nr_lds; r += nt) {
+        const uint2 run = qruns[r];
+        run_src[r] = run.x;
+        run_start[r] = run.y;
     }
     if (tid == 0) {
-        run_start[nr] = (uint32_t)nc;
+        if (nr <= L.rcap) run_start[nr] = (uint32_t)nc;
         misc[kMin] = 0xffffffffu;
         misc[kMax] = 0u;
         misc[kNumSurv] = 0u;
     }
+    RunList R;
+    R.src = L.run_src; R.start = L.run_start; R.mem = qruns; R.rcap = L.rcap; R.nr = nr; R.nc = (uint32_t)nc;
     __syncthreads();
 
     // ---- LUT of Eq. 9 summands ------------------------------------------------------------------------
     for (int base = 0; base < nlut; base += nt * 4) {
-        if (base > 0) {
+        CodeEntry cur_ent[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cur_ent[u] = ent[u];
+        if (base + nt * 4 < nlut) {            // the next round's entries are fetched while this one is worked on
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int e = base + u * nt + tid;
+                const int e = base + (4 + u) * nt + tid;
                 ent[u] = g.table[e < nlut ? e : 0];
             }
         }
@@ -329,37 +380,48 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
             const int e = base + u * nt + tid;
             if (e >= nlut) continue;
             const int m = e >> 8;
-            const float b2 = sa[m * k1 + (ent[u].ij & 0xffu)];
-            const float a2 = sa[m * k1 + ((ent[u].ij >> 8) & 0xffu)];
+            const float b2 = sa[m * k1 + (cur_ent[u].ij & 0xffu)];
+            const float a2 = sa[m * k1 + ((cur_ent[u].ij >> 8) & 0xffu)];
             if (MW < 0) {
                 // entry = centroid pair number; its kc field holds c^2
                 const int pair = e & 255;
                 if (pair < (1 << g.pair_shift))
-                    reinterpret_cast<float4*>(lut)[(m << g.pair_shift) + pair] = make_float4(b2, a2 - b2, ent[u].kc, 0.0f);
+                    reinterpret_cast<float4*>(lut)[(m << g.pair_shift) + pair] = make_float4(b2, a2 - b2, cur_ent[u].kc, 0.0f);
                 continue;
             }
             // Eq. 9 rearranged: b^2 + lam (a^2 - b^2) + (lam^2 - lam) c^2, the last term folded per code value
-            const float v = fmaf(ent[u].lam, a2 - b2, b2) + ent[u].kc;
+            const float v = fmaf(cur_ent[u].lam, a2 - b2, b2) + cur_ent[u].kc;
             lut[e] = v;
             if (TAPS && g.lut) g.lut[(size_t)q * nlut + e] = v;
         }
     }
     __syncthreads();
 
-    // ---- scores ---------------------------------------------------------------------------------------
+    // ---- scores: candidate position u * nt + tid -> key[u] ----------------------------------------------
+    uint32_t key[kKeysPerThread];
+#pragma unroll
+    for (int u = 0; u < kKeysPerThread; ++u) key[u] = 0xffffffffu;
     uint32_t kmin = 0xffffffffu, kmax = 0u;
     if (nc > 0) {
         RunCursor cur;                         // positions of a thread only grow
         cur.run = 0;
-        cur.next_start = run_start[1];
-        cur.delta = run_src[0] - run_start[0];
-        int base = 0;
-        for (; base + 8 * nt <= nc; base += 8 * nt)
-            score_batch<MW, 8, false, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, cur, kmin, kmax);
-        for (; base + 4 * nt <= nc; base += 4 * nt)
-            score_batch<MW, 4, false, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, cur, kmin, kmax);
-        for (; base < nc; base += 4 * nt)
-            score_batch<MW, 4, true, TAPS>(g, q, base, nc, tid, nt, lut, skey, run_src, run_start, cur, kmin, kmax);
+        cur.next_start = R.start_at(1);
+        cur.delta = R.src_at(0) - R.start_at(0);
+        // eight positions in flight per thread; four when a code has four or more words (registers)
+        constexpr int UB = (MW >= 4 || MW <= -4) ? 4 : 8;
+        static_assert(kKeysPerThread % 4 == 0, "batches of four or eight");
+#pragma unroll
+        for (int b = 0; b * UB + UB <= kKeysPerThread; ++b) {
+            const int base = b * UB * nt;
+            if (base + UB * nt <= nc) score_batch<MW, UB, false, TAPS>(g, q, base, nc, tid, nt, lut, key + b * UB, R, cur, kmin, kmax);
+            else if (base < nc) score_batch<MW, UB, true, TAPS>(g, q, base, nc, tid, nt, lut, key + b * UB, R, cur, kmin, kmax);
+        }
+        if (kKeysPerThread % UB) {             // a last batch of four
+            constexpr int done = kKeysPerThread / UB * UB;
+            const int base = done * nt;
+            if (base + 4 * nt <= nc) score_batch<MW, 4, false, TAPS>(g, q, base, nc, tid, nt, lut, key + done, R, cur, kmin, kmax);
+            else if (base < nc) score_batch<MW, 4, true, TAPS>(g, q, base, nc, tid, nt, lut, key + done, R, cur, kmin, kmax);
+        }
     }
     if (TAPS && g.n_cand && tid == 0) g.n_cand[q] = (uint32_t)nc;
     kmin = wave_min_u32(kmin);
@@ -370,28 +432,26 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
     }
     __syncthreads();
 
-    // ---- the k smallest (score, id): positions of a superset of the answer -> spos --------------------
+    // ---- the k smallest (score, id): (key, position) of a superset of the answer -> surv ---------------
     const int kk = k < nc ? k : nc;           // results that exist
     int nsurv;
-    bool identity = false;                     // survivor e is candidate position e
     if (nc <= L.scap) {                        // few candidates: order all of them
+#pragma unroll
+        for (int u = 0; u < kKeysPerThread; ++u) {
+            const int p = u * nt + tid;
+            if (p < nc) surv[p] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
+        }
         nsurv = nc;
-        identity = true;
     } else {
         const uint32_t lo_key = misc[kMin];
         const uint32_t range = misc[kMax] - lo_key;
         const int width = 32 - __clz((int)(range | 1u));           // bits needed for range
         const int shift = width > kHistBits ? width - kHistBits : 0;   // (key - lo_key) >> shift < 1024
-        const uint4* skey4 = reinterpret_cast<const uint4*>(skey);
-        const int nc4 = nc >> 2;
-        for (int p4 = tid; p4 < nc4; p4 += nt) {                   // four keys per LDS read
-            const uint4 kq = skey4[p4];
-            atomicAdd(&hist[(kq.x - lo_key) >> shift], 1u);
-            atomicAdd(&hist[(kq.y - lo_key) >> shift], 1u);
-            atomicAdd(&hist[(kq.z - lo_key) >> shift], 1u);
-            atomicAdd(&hist[(kq.w - lo_key) >> shift], 1u);
+#pragma unroll
+        for (int u = 0; u < kKeysPerThread; ++u) {
+            if (u * nt >= nc) break;                                   // same for the whole workgroup
+            if (u * nt + tid < nc) atomicAdd(&hist[(key[u] - lo_key) >> shift], 1u);
         }
-        for (int p = 4 * nc4 + tid; p < nc; p += nt) atomicAdd(&hist[(skey[p] - lo_key) >> shift], 1u);
         __syncthreads();
         // the first wavefront finds the bin bsel with count(< bsel) < kk <= count(<= bsel)
         if (tid < kWave) {
@@ -409,27 +469,27 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
             // keys of the bins <= bsel are the keys <= thr
             const unsigned long long thr64 = (unsigned long long)lo_key + (((unsigned long long)bsel + 1ull) << shift) - 1ull;
             const uint32_t thr = thr64 > 0xffffffffull ? 0xffffffffu : (uint32_t)thr64;
-            for (int p4 = tid; p4 < nc4; p4 += nt) {
-                const uint4 kq = skey4[p4];
-                if (kq.x <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4);
-                if (kq.y <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4 + 1);
-                if (kq.z <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4 + 2);
-                if (kq.w <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)(4 * p4 + 3);
+#pragma unroll
+            for (int u = 0; u < kKeysPerThread; ++u) {
+                const int p = u * nt + tid;
+                if (u * nt >= nc) break;
+                if (p < nc && key[u] <= thr)
+                    surv[atomicAdd(&misc[kNumSurv], 1u)] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
             }
-            for (int p = 4 * nc4 + tid; p < nc; p += nt)
-                if (skey[p] <= thr) spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)p;
             nsurv = (int)count_le;
         } else {
             // exact selection: k-th smallest score key, then (only if that score is tied) the ids
             uint32_t* rout = misc + kRadix;
-            uint32_t* part = reinterpret_cast<uint32_t*>(lut);     // the LUT is no longer needed
             uint32_t prefix = 0, mask = 0, need = (uint32_t)kk, bucket = 0;
             const int shifts[4] = {22, 12, 2, 0};
             const int nbits[4] = {10, 10, 10, 2};
             __syncthreads();
             for (int pass = 0; pass < 4; ++pass) {
-                radix_select_pass(nc, prefix, mask, shifts[pass], nbits[pass], need, hist, part, rout,
-                                  [&](int p, bool& valid) { valid = true; return skey[p]; });
+                radix_select_pass(prefix, mask, shifts[pass], nbits[pass], need, hist, part, rout, [&](auto f) {
+#pragma unroll
+                    for (int u = 0; u < kKeysPerThread; ++u)
+                        if (u * nt + tid < nc) f(key[u]);
+                });
                 prefix |= rout[0] << shifts[pass];
                 mask |= ((1u << nbits[pass]) - 1u) << shifts[pass];
                 need = rout[1];
@@ -441,11 +501,13 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
             if (need < bucket) {
                 uint32_t iprefix = 0, imask = 0;
                 for (int pass = 0; pass < 4; ++pass) {
-                    radix_select_pass(nc, iprefix, imask, shifts[pass], nbits[pass], need, hist, part, rout,
-                                      [&](int p, bool& valid) {
-                                          valid = skey[p] == tau;
-                                          return valid ? g.ids[source_of((uint32_t)p, nr, steps, run_src, run_start)] : 0u;
-                                      });
+                    radix_select_pass(iprefix, imask, shifts[pass], nbits[pass], need, hist, part, rout, [&](auto f) {
+#pragma unroll
+                        for (int u = 0; u < kKeysPerThread; ++u) {
+                            const int p = u * nt + tid;
+                            if (p < nc && key[u] == tau) f(g.ids[source_of((uint32_t)p, steps, R)]);
+                        }
+                    });
                     iprefix |= rout[0] << shifts[pass];
                     imask |= ((1u << nbits[pass]) - 1u) << shifts[pass];
                     need = rout[1];
@@ -453,13 +515,12 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
                 }
                 id_cut = iprefix;
             }
-            for (int p = tid; p < nc; p += nt) {
-                const uint32_t key = skey[p];
-                if (key > tau) continue;
-                if (key == tau && id_cut != 0xffffffffu &&
-                    g.ids[source_of((uint32_t)p, nr, steps, run_src, run_start)] > id_cut)
-                    continue;
-                spos[atomicAdd(&misc[kNumSurv], 1u)] = (uint16_t)p;
+#pragma unroll
+            for (int u = 0; u < kKeysPerThread; ++u) {
+                const int p = u * nt + tid;
+                if (p >= nc || key[u] > tau) continue;
+                if (key[u] == tau && id_cut != 0xffffffffu && g.ids[source_of((uint32_t)p, steps, R)] > id_cut) continue;
+                surv[atomicAdd(&misc[kNumSurv], 1u)] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
             }
             nsurv = kk;
         }
@@ -467,38 +528,42 @@ __global__ __launch_bounds__(1024, FUSED ? 8 : 1) void rerank_kernel(RerankArgs 
     __syncthreads();
 
     // ---- fetch the survivors' ids: 64-bit keys (score bits, id) --------------------------------------------
+    // (one round of loads for the whole list: the thread that holds a surviving key does not fetch the id
+    // itself, or a wavefront would wait for memory once per key slot)
     for (int e = tid; e < nsurv; e += nt) {
-        const uint32_t p = identity ? (uint32_t)e : (uint32_t)spos[e];
-        const uint32_t id = g.ids[source_of(p, nr, steps, run_src, run_start)];
-        surv[e] = ((unsigned long long)skey[p] << 32) | id;
+        const unsigned long long kp = surv[e];
+        const uint32_t id = g.ids[source_of((uint32_t)kp, steps, R)];
+        surv[e] = (kp & 0xffffffff00000000ull) | id;
     }
     __syncthreads();
 
     // ---- order the survivors, write the first k ---------------------------------------------------------
     if (nsurv <= kCountRankMax) {
-        // rank = number of smaller keys (keys are unique); four adjacent lanes share one survivor
+        // a handful: rank = number of smaller keys (keys are unique); four adjacent lanes share one survivor
         const int sub = tid & 3;
         for (int e0 = 0; e0 < nsurv; e0 += nt / 4) {
             const int e = e0 + (tid >> 2);
             const bool valid = e < nsurv;
-            const unsigned long long key = valid ? surv[e] : 0ull;
+            const unsigned long long skey = valid ? surv[e] : 0ull;
             uint32_t rank = 0;
-            for (int j = sub; j < nsurv; j += 4) rank += (surv[j] < key) ? 1u : 0u;
+            for (int j = sub; j < nsurv; j += 4) rank += (surv[j] < skey) ? 1u : 0u;
             rank += quad_swap1(rank);
             rank += quad_swap2(rank);
             if (valid && sub == 0 && rank < (uint32_t)k) {
-                g.out_ids[(size_t)q * k + rank] = (int64_t)(uint32_t)key;
-                g.out_dists[(size_t)q * k + rank] = mono_inv((uint32_t)(key >> 32));
+                g.out_ids[(size_t)q * k + rank] = (int64_t)(uint32_t)skey;
+                g.out_dists[(size_t)q * k + rank] = mono_inv((uint32_t)(skey >> 32));
             }
         }
     } else {
-        const int npad = next_pow2(nsurv);
+        // sorted in registers, 64 keys per wavefront (comparisons grow as n log^2 n, not n^2)
+        const int npad = next_pow2(nsurv) < kWave ? kWave : next_pow2(nsurv);
         for (int e = nsurv + tid; e < npad; e += nt) surv[e] = ~0ull;
-        bitonic_sort_lds(surv, npad, tid, nt);
+        if (npad <= 4 * nt) block_sort_lds<4>(surv, npad, tid, nt);
+        else bitonic_sort_lds(surv, npad, tid, nt);            // more than four keys per thread: all in LDS
         for (int e = tid; e < kk; e += nt) {
-            const unsigned long long key = surv[e];
-            g.out_ids[(size_t)q * k + e] = (int64_t)(uint32_t)key;
-            g.out_dists[(size_t)q * k + e] = mono_inv((uint32_t)(key >> 32));
+            const unsigned long long skey = surv[e];
+            g.out_ids[(size_t)q * k + e] = (int64_t)(uint32_t)skey;
+            g.out_dists[(size_t)q * k + e] = mono_inv((uint32_t)(skey >> 32));
         }
     }
     for (int e = kk + tid; e < k; e += nt) {
@@ -545,8 +610,9 @@ hipError_t launch_rerank(const RerankArgs& a_in, const RankArgs* fused, hipStrea
         RL = rank_offsets(rk.P, rk.R, rk.T, rk.hashed);
         if (RL.Tcap > rerank_fused_tuples_per_thread() * a.threads) return hipErrorInvalidValue;
     }
+    if (a.keys_per_thread != kKeysPerThread || a.C > a.keys_per_thread * a.threads) return hipErrorInvalidValue;
     if (a.code_format == 1 && a.lut) return hipErrorInvalidValue;      // that tap is the one-byte format's table
-    const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads, fused ? RL.total : 0, a.code_format);
+    const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads, fused ? RL.total : 0, a.code_format, a.runs_in_lds);
     if (fused) launch_rerank_t<false, true>(a, L, rk, RL, s);
     else if (taps) launch_rerank_t<true, false>(a, L, rk, RL, s);
     else launch_rerank_t<false, false>(a, L, rk, RL, s);
