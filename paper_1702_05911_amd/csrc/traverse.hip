@@ -108,7 +108,11 @@ __device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, 
     }
 }
 
-__global__ __launch_bounds__(kTraverseMaxThreads) void traverse_kernel(TraverseArgs g) {
+// E: level-2 list entries per lane on the register path (lists of at most 64 * E entries from the
+// interleaved codebook), 0: the general path.  One kernel per E, so that the short-list kernels are not
+// held to the register count -- and with it the number of resident tiles -- of the long-list code.
+template <int E>
+__global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4)) void traverse_kernel(TraverseArgs g) {
     extern __shared__ __align__(16) unsigned char smem[];
     const TraverseLds L = traverse_layout(g.D, g.P, g.k1, g.k2, g.M, g.w);
     float* sq = reinterpret_cast<float*>(smem + L.off_q);
@@ -213,12 +217,10 @@ __global__ __launch_bounds__(kTraverseMaxThreads) void traverse_kernel(TraverseA
     __syncthreads();
 
     // ---- level 2: one wavefront per (query, part), one lane per child ---------------------------
-    if (g.C2t != nullptr && R <= 4 * kWave) {
+    if constexpr (E > 0) {
         // children of one cluster interleaved four dimensions at a time (C2t[p][i][d/4][j][4]): the
         // lanes of one cluster read consecutive 16-byte pieces; lists sorted in registers
-        if (R <= kWave) level2_lists<1>(g, q0, sq, L.qs, ssel);
-        else if (R <= 2 * kWave) level2_lists<2>(g, q0, sq, L.qs, ssel);
-        else level2_lists<4>(g, q0, sq, L.qs, ssel);
+        level2_lists<E>(g, q0, sq, L.qs, ssel);
         return;
     }
     unsigned long long* mykeys = skey + (size_t)wave * L.Rpad;
@@ -260,13 +262,23 @@ hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
     const size_t lds = traverse_lds_bytes(a.D, a.P, a.k1, a.k2, a.M, a.w);
     const unsigned blocks = (unsigned)((a.nq + kQueryTile - 1) / kQueryTile);
-    hipLaunchKernelGGL(traverse_kernel, dim3(blocks), dim3(traverse_threads(a.P)), lds, s, a);
+    const dim3 grid(blocks), block(traverse_threads(a.P));
+    const int R = a.w * a.k2;
+    if (a.C2t == nullptr || R > 4 * kWave) hipLaunchKernelGGL(traverse_kernel<0>, grid, block, lds, s, a);
+    else if (R <= kWave) hipLaunchKernelGGL(traverse_kernel<1>, grid, block, lds, s, a);
+    else if (R <= 2 * kWave) hipLaunchKernelGGL(traverse_kernel<2>, grid, block, lds, s, a);
+    else hipLaunchKernelGGL(traverse_kernel<4>, grid, block, lds, s, a);
     return hipGetLastError();
 }
 
 hipError_t configure_traverse(size_t max_dynamic_lds) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(traverse_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+    const void* kernels[] = {reinterpret_cast<const void*>(traverse_kernel<0>), reinterpret_cast<const void*>(traverse_kernel<1>),
+                             reinterpret_cast<const void*>(traverse_kernel<2>), reinterpret_cast<const void*>(traverse_kernel<4>)};
+    for (const void* kfn : kernels) {
+        const hipError_t e = hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace pqt
