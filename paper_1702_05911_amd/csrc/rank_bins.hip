@@ -134,17 +134,21 @@ struct HeadLevels {
 // One level: ranks the first T1 <= 64 * E tuples, probes their slots, and either writes the final run
 // list (returns 1), finds that more tuples are needed (returns 0), or -- on the last level -- lists the
 // query for the full pass (returns 1).
+// carry (E = 1): the 64 smallest keys of the table entries below e_begin, left by the level before
+// (+inf when e_begin = 0); the level only looks at the entries from e_begin on and leaves its own 64
+// smallest there.  The table is ordered by (a+1)(b+1), so the entries of a smaller T1 are a prefix.
 template <int E>
 __device__ __forceinline__ int head_level(const RankArgs& g, HeadLds& S, int64_t q, int lane, int R1, int T1,
-                                          int npairs, int Tn, bool last_level) {
+                                          int e_begin, int npairs, int Tn, bool last_level, unsigned long long& carry) {
     const int T = g.T;
     const uint32_t C = (uint32_t)g.C;
     // ---- the T1 smallest keys (ordered sum bits, a, b) of the region, ascending over (register, lane) ----
     unsigned long long best[E];
 #pragma unroll
     for (int r = 0; r < E; ++r) best[r] = ~0ull;
-    for (int blk = 0; blk * kWave < npairs; ++blk) {
-        const int e = blk * kWave + lane;
+    if (E == 1) best[0] = carry;
+    for (int base = e_begin; base < npairs; base += kWave) {
+        const int e = base + lane;
         unsigned long long cur[1] = {~0ull};
         if (e < npairs) {
             const unsigned a = kHeadPairTable.a[e], b = kHeadPairTable.b[e];
@@ -152,7 +156,7 @@ __device__ __forceinline__ int head_level(const RankArgs& g, HeadLds& S, int64_t
                 cur[0] = ((unsigned long long)mono_key(S.A[a] + S.B[b]) << 32) | (a << 16) | b;
         }
         wave_sort_chunk<1>(cur, lane, 0u);
-        if (blk == 0) {
+        if (base == 0) {
             best[0] = cur[0];
         } else {
             // the 64*E smallest of the ascending runs `best` and `cur` (padded with +inf to 64*E keys):
@@ -164,6 +168,8 @@ __device__ __forceinline__ int head_level(const RankArgs& g, HeadLds& S, int64_t
             wave_merge_chunk<E>(best, lane, 0u, 64u * E);
         }
     }
+
+    if (E == 1) carry = best[0];
 
     // ---- probe the first T1 tuples ---------------------------------------------------------------
     uint32_t o0[E], len[E];
@@ -238,9 +244,11 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
     }
     wave_lds_order();
     // levels whose tuple count does not grow are skipped (T smaller than 64 or 128)
-    if (head_level<1>(g, S, q, lane, R1, lv.T1[0], lv.npairs[0], Tn, lv.T1[1] == lv.T1[0])) return;
-    if (head_level<1>(g, S, q, lane, R1, lv.T1[1], lv.npairs[1], Tn, lv.T1[2] == lv.T1[1])) return;
-    head_level<2>(g, S, q, lane, R1, lv.T1[2], lv.npairs[2], Tn, true);
+    unsigned long long carry = ~0ull;
+    if (head_level<1>(g, S, q, lane, R1, lv.T1[0], 0, lv.npairs[0], Tn, lv.T1[1] == lv.T1[0], carry)) return;
+    // the second level adds the table entries between the two regions to the 64 smallest of the first
+    if (head_level<1>(g, S, q, lane, R1, lv.T1[1], lv.npairs[0], lv.npairs[1], Tn, lv.T1[2] == lv.T1[1], carry)) return;
+    head_level<2>(g, S, q, lane, R1, lv.T1[2], 0, lv.npairs[2], Tn, true, carry);
 }
 
 // ------------------------------------------------------------------------------------------------
