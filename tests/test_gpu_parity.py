@@ -195,6 +195,48 @@ def test_fewer_candidates_than_k_pads(pqt, tiny, tmp_path):
         assert nc < 50 and np.all(ids[q][nc:] == -1) and np.all(np.isinf(dists[q][nc:]))
 
 
+def test_large_candidate_budgets_change_the_workgroup_shape(pqt, tiny, tmp_path):
+    """The re-rank workgroup grows with the candidate budget (a thread holds at most twenty keys):
+    budgets on either side of 5120 and 10240, the largest one reaching every vector of the database."""
+    cfg, X, Y, ix = tiny
+    path = str(tmp_path / "tiny.pqt")
+    IO.write_index(path, ix)
+    T = (cfg.k1 * cfg.k2) ** 2                                     # every bin of the tiny tree
+    for C in (5120, 5121, 10240, 10241, 16384):
+        same, _ = _stagewise(pqt, ix, path, Y[:5], cfg.k, cfg.k1, T, C)
+        assert same >= 4
+    _stagewise(pqt, ix, path, Y[:3], 1000, cfg.k1, T, 16384)        # k large: the short list holds 2048 keys
+
+
+def test_more_runs_than_the_workgroup_keeps_in_lds(pqt, tmp_path):
+    """Two huge clusters and scattered single vectors: the mean run is long, so the workgroup keeps only
+    a short run list in LDS (twice what the budget needs at the mean run length), but a query among the
+    scattered vectors gathers from more runs than that and reads the rest of its list from memory."""
+    rng = np.random.default_rng(12345)
+    P, k1, k2, M, D, T, C = 2, 8, 4, 4, 16, 1024, 3000
+    centers = rng.normal(size=(2, D)) * 0.01 + np.array([[4.0] * D, [-4.0] * D])
+    big = np.repeat(centers, 4940, axis=0) + rng.normal(size=(9880, D)) * 1e-3
+    lone = rng.uniform(-1.5, 1.5, size=(120, D))
+    X = np.concatenate([big, lone]).astype(np.float32)
+    X = X[rng.permutation(X.shape[0])]
+    ix = B.build_index(X, P, k1, k2, M, T=T, C=C, train_n=None, iters=8)
+    mean_run = X.shape[0] / np.count_nonzero(np.diff(ix.offsets.astype(np.int64)))
+    kept = 64
+    while kept < T and kept < 2 * C / mean_run:
+        kept *= 2
+    Y = (lone[:12] + rng.normal(size=(12, D)) * 0.05).astype(np.float32)
+    path = str(tmp_path / "skew.pqt")
+    IO.write_index(path, ix)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        ids, dists, taps = _run_debug(pqt, gix, Y, 20, k1)
+    finally:
+        pqt.pqt_index_free(gix)
+    assert kept < T and int(taps["n_slots"].max()) > kept, "the case does not reach past the LDS run list"
+    for q in range(Y.shape[0]):
+        PU.check_query_stages(ix, Y[q], taps, q, 20, k1, T, C, ids, dists)
+
+
 def test_hashed_index_dedupes_slots(pqt, tiny, tmp_path):
     cfg, X, Y, ix = tiny
     ixh = B.build_index(X[:3000], cfg.P, cfg.k1, cfg.k2, cfg.M, H=97, T=256, C=1024, codebooks=(ix.C1, ix.C2),
