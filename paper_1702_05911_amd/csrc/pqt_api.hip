@@ -92,7 +92,7 @@ int upload(Tp** dev, const void* src, size_t bytes, hipMemcpyKind kind, uint64_t
 // Workgroup size of the re-rank kernel and candidates per thread: the fewest threads that hold the
 // candidate budget (a thread keeps the keys of its candidates in registers; fewer threads per query
 // leave room for more queries per compute unit).  PQT_RERANK_THREADS asks for more threads.
-int rerank_threads(const pqt_index* ix, int* keys_per_thread = nullptr) {
+int rerank_threads(const pqt_index* ix, int* keys_per_thread = nullptr, int64_t nq = -1) {
     static const int forced = [] {
         const char* e = getenv("PQT_RERANK_THREADS");
         const int v = e ? atoi(e) : 0;
@@ -101,6 +101,7 @@ int rerank_threads(const pqt_index* ix, int* keys_per_thread = nullptr) {
     int t, kpt;
     pqt::rerank_shape((int)ix->C, (int)ix->M, (int)ix->code_format, &t, &kpt);
     if (keys_per_thread) *keys_per_thread = kpt;
+    if (nq >= 0 && nq <= 1024) t = 1024;      // a small batch leaves the chip idle: more threads per query, answer sooner
     return forced > t ? forced : t;
 }
 
@@ -117,21 +118,21 @@ int rerank_runs_in_lds(const pqt_index* ix) {
 
 // Can the re-rank kernel also run the full bin ranking of the queries the head pass leaves over?
 // (two tree parts; few enough tuples per thread of the re-rank workgroup; the LDS of both fits)
-bool can_fuse_ranking(const pqt_index* ix, int k, int w) {
+bool can_fuse_ranking(const pqt_index* ix, int k, int w, int64_t nq) {
     if (ix->P != 2) return false;
     const int R = w * (int)ix->k2;
-    const int threads = rerank_threads(ix);
+    const int threads = rerank_threads(ix, nullptr, nq);
     const pqt::RankOffsets ro = pqt::rank_offsets(ix->P, R, ix->T, ix->hashed);
     if (ro.Tcap > pqt::rerank_fused_tuples_per_thread() * threads) return false;
     return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total, (int)ix->code_format,
                                  rerank_runs_in_lds(ix)) <= g_lds_limit;
 }
 
-int check_query_limits(const pqt_index* ix, int k, int w, size_t* lds_out) {
+int check_query_limits(const pqt_index* ix, int k, int w, int64_t nq, size_t* lds_out) {
     const int R = w * (int)ix->k2;
     const size_t l1 = pqt::traverse_lds_bytes(ix->D, ix->P, ix->k1, ix->k2, ix->M, w);
     const size_t l2 = pqt::rank_lds_bytes(ix->P, R, ix->T, ix->hashed ? 1 : 2);   // 2: room for the slots tap
-    const int threads = rerank_threads(ix);
+    const int threads = rerank_threads(ix, nullptr, nq);
     const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0, (int)ix->code_format,
                                             rerank_runs_in_lds(ix));
     if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)
@@ -520,7 +521,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
         return fail(PQT_EINVAL, "pqt_query_batch: w*k2=%lld exceeds %d", (long long)w * ix->k2, PQT_MAX_R);
     if (nq == 0) return PQT_OK;
     if (!queries || !out_ids || !out_dists) return fail(PQT_EINVAL, "pqt_query_batch: null buffer");
-    int rc = check_query_limits(ix, k, w, nullptr);
+    int rc = check_query_limits(ix, k, w, nq, nullptr);
     if (rc) return rc;
 
     DeviceGuard guard(ix->device);
@@ -564,7 +565,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     const bool fixed_order = ix->bin_order == PQT_ORDER_STATIC_SLOPES;
     const bool head = !fixed_order && pqt::rank_has_head(ra);
     // the few queries the head pass cannot finish are ranked in full by their re-rank workgroup
-    const bool fuse = head && !rerank_taps && can_fuse_ranking(ix, k, w);
+    const bool fuse = head && !rerank_taps && can_fuse_ranking(ix, k, w, nq);
     if (fixed_order) {
         if (ix->static_R != R || ix->static_T != (int)ix->T) {          // tables for this list length and T
             std::vector<uint32_t> table;
@@ -594,7 +595,7 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
 
     pqt::RerankArgs ca;
     ca.nq = nq; ca.M = ix->M; ca.k1 = ix->k1; ca.T = ix->T; ca.C = ix->C; ca.k = k;
-    ca.threads = rerank_threads(ix, &ca.keys_per_thread);
+    ca.threads = rerank_threads(ix, &ca.keys_per_thread, nq);
     ca.code_format = (int)ix->code_format;
     ca.runs_in_lds = rerank_runs_in_lds(ix);
     ca.a = ix->ws_a; ca.table = ix->table; ca.runs = ix->ws_runs; ca.meta = ix->ws_meta;

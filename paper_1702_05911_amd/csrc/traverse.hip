@@ -255,14 +255,19 @@ __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4))
     }
 }
 
-// one wavefront per four (query, part) lists of the tile
-static int traverse_threads(int P) { return P >= 4 ? 1024 : (P == 2 ? 512 : 256); }
+// One wavefront per four (query, part) lists of the tile when the batch fills the chip; a small batch
+// (at most one tile per compute unit) gets the largest workgroup, so that a wavefront has one or two
+// lists to work through and the call returns sooner.
+static int traverse_threads(int P, int64_t nq) {
+    if (nq <= 256 * kQueryTile) return kTraverseMaxThreads;
+    return P >= 4 ? 1024 : (P == 2 ? 512 : 256);
+}
 
 hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
     const size_t lds = traverse_lds_bytes(a.D, a.P, a.k1, a.k2, a.M, a.w);
     const unsigned blocks = (unsigned)((a.nq + kQueryTile - 1) / kQueryTile);
-    const dim3 grid(blocks), block(traverse_threads(a.P));
+    const dim3 grid(blocks), block(traverse_threads(a.P, a.nq));
     const int R = a.w * a.k2;
     if (a.C2t == nullptr || R > 4 * kWave) hipLaunchKernelGGL(traverse_kernel<0>, grid, block, lds, s, a);
     else if (R <= kWave) hipLaunchKernelGGL(traverse_kernel<1>, grid, block, lds, s, a);
