@@ -7,8 +7,9 @@
 //     a 128 x 128 tile of q.x with v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate), each wavefront a
 //     64 x 64 quarter as 4 x 4 MFMA tiles; operands are staged through LDS sixteen dimensions at a
 //     time (byte vectors are widened while staging); the epilogue forms ||q||^2 + ||x||^2 - 2 q.x.
-//   * bf_select_kernel: one workgroup per query scans its row of distances once, keeps what beats the
-//     k-th best so far in an LDS buffer, and re-selects the k best whenever the buffer fills.  Chunks
+//   * bf_select_kernel: one workgroup per query scans its row of distances once (16 bytes per thread
+//     and step), keeps what beats the k-th best so far in an LDS buffer, and re-selects the k best
+//     whenever the buffer may fill.  Chunks
 //     arrive in id order, so an equal distance that arrives later has the larger id and never wins.
 #include "pqt_device.hpp"
 #include "pqt_kernels.hpp"
@@ -126,7 +127,8 @@ __global__ __launch_bounds__(kBfThreads) void bf_distance_kernel(BruteArgs g, in
 }
 
 constexpr int kBfSelThreads = 512;
-constexpr int kBfBuf = 2048;       // pending entries the LDS buffer holds besides the k best
+constexpr int kBfBuf = 3840;       // pending entries the LDS buffer holds besides the k best (k <= 256:
+                                   // together at most 4096 keys, eight per thread of the sort)
 
 // best: nq x k keys (ordered distance bits << 32 | id), ascending, ~0 = none yet
 __global__ __launch_bounds__(kBfSelThreads) void bf_select_kernel(BruteArgs g, int64_t x0, int64_t nx, int first, int last) {
@@ -140,6 +142,48 @@ __global__ __launch_bounds__(kBfSelThreads) void bf_select_kernel(BruteArgs g, i
     if (tid == 0) counter[0] = 0;
     __syncthreads();
     uint32_t tau = (uint32_t)(keys[k - 1] >> 32);             // distance bits of the k-th best (all ones: none)
+    auto reselect = [&](uint32_t pending) {                     // keep the k smallest of the k best and the pending entries
+        const int n = k + (int)pending, npad = next_pow2(n) < 64 ? 64 : next_pow2(n);
+        for (int e = n + tid; e < npad; e += kBfSelThreads) keys[e] = ~0ull;
+        block_sort_lds<8>(keys, npad, tid, kBfSelThreads);
+        tau = (uint32_t)(keys[k - 1] >> 32);
+        if (tid == 0) counter[0] = 0;
+        __syncthreads();
+    };
+    if (g.chunk % 4 == 0) {
+        // rows are 16-byte aligned: four distances per thread and step, the next piece in flight while this
+        // one is examined; one barrier per 2048 distances
+        const float4* row4 = reinterpret_cast<const float4*>(row);
+        const int64_t n4 = (nx + 3) / 4;                       // a last partial piece stays inside the row
+        float4 next = tid < n4 ? row4[tid] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        for (int64_t b4 = 0; b4 < n4; b4 += kBfSelThreads) {
+            const int64_t i4 = b4 + tid;
+            const float4 v = next;
+            if (i4 + kBfSelThreads < n4) next = row4[i4 + kBfSelThreads];
+            const float vals[4] = {v.x, v.y, v.z, v.w};
+            uint32_t kb[4], cnt = 0;
+            bool tk[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                kb[c] = mono_key(vals[c]);
+                tk[c] = i4 < n4 && i4 * 4 + c < nx && kb[c] < tau;
+                cnt += tk[c] ? 1u : 0u;
+            }
+            const uint32_t incl = wave_inclusive_sum(cnt, lane);
+            const uint32_t total = (uint32_t)__shfl((int)incl, kWave - 1, kWave);
+            if (total) {                                        // same for the whole wavefront
+                uint32_t at = 0;
+                if (lane == kWave - 1) at = atomicAdd(counter, total);
+                at = (uint32_t)__shfl((int)at, kWave - 1, kWave) + incl - cnt;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (tk[c]) keys[k + at++] = ((unsigned long long)kb[c] << 32) | (uint32_t)(x0 + i4 * 4 + c);
+            }
+            __syncthreads();
+            const uint32_t pending = counter[0];
+            if (pending + 4 * kBfSelThreads > (uint32_t)kBfBuf || b4 + kBfSelThreads >= n4) reselect(pending);
+        }
+    } else
     for (int64_t base = 0; base < nx; base += kBfSelThreads) {
         const int64_t c = base + tid;
         bool take = false;
@@ -159,15 +203,7 @@ __global__ __launch_bounds__(kBfSelThreads) void bf_select_kernel(BruteArgs g, i
         }
         __syncthreads();
         const uint32_t pending = counter[0];
-        if (pending + kBfSelThreads > (uint32_t)kBfBuf || base + kBfSelThreads >= nx) {
-            // keep the k smallest of the k best and the pending entries
-            const int n = k + (int)pending, npad = next_pow2(n) < 64 ? 64 : next_pow2(n);
-            for (int e = n + tid; e < npad; e += kBfSelThreads) keys[e] = ~0ull;
-            block_sort_lds<8>(keys, npad, tid, kBfSelThreads);
-            tau = (uint32_t)(keys[k - 1] >> 32);
-            if (tid == 0) counter[0] = 0;
-            __syncthreads();
-        }
+        if (pending + kBfSelThreads > (uint32_t)kBfBuf || base + kBfSelThreads >= nx) reselect(pending);
     }
     if (last) {
         for (int e = tid; e < k; e += kBfSelThreads) {
