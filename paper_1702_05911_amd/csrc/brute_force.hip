@@ -6,7 +6,7 @@
 //   * bf_distance_kernel: a dense contraction on the matrix cores.  A workgroup of 256 threads computes
 //     a 128 x 128 tile of q.x with v_mfma_f32_16x16x4_f32 (fp32 in, fp32 accumulate), each wavefront a
 //     64 x 64 quarter as 4 x 4 MFMA tiles; operands are staged through LDS sixteen dimensions at a
-//     time (byte vectors are widened while staging); the epilogue forms ||q||^2 + ||x||^2 - 2 q.x.
+//     time (byte vectors are widened while staging; the next step's pieces are fetched during the MFMAs); the epilogue forms ||q||^2 + ||x||^2 - 2 q.x.
 //   * bf_select_kernel: one workgroup per query scans its row of distances once (16 bytes per thread
 //     and step), keeps what beats the k-th best so far in an LDS buffer, and re-selects the k best
 //     whenever the buffer may fill.  Chunks
@@ -58,13 +58,14 @@ __device__ __forceinline__ void load8(const uint8_t* p, bool aligned, float (&v)
     }
 }
 
+// A thread's piece of a 128-row x 16-dimension tile: row t/2, dimensions (t%2)*8 .. +8 of step k0, as
+// floats in registers; rows past nrows and dimensions past D are zero.
 template <typename Elem>
-__device__ __forceinline__ void stage_tile(const Elem* base, int64_t row0, int64_t nrows, int D, int k0, float* dst, int tid) {
-    // 128 rows x 16 dimensions; thread t takes row t/2, dimensions (t%2)*8 .. +8; rows past nrows and
-    // dimensions past D are zero
+__device__ __forceinline__ void fetch_piece(const Elem* base, int64_t row0, int64_t nrows, int D, int k0, int tid, float (&v)[8]) {
     const int r = tid >> 1, c0 = (tid & 1) * 8;
     const int64_t row = row0 + r;
-    float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int c = 0; c < 8; ++c) v[c] = 0.0f;
     if (row < nrows) {
         const Elem* p = base + (size_t)row * D + k0 + c0;
         if (k0 + c0 + 8 <= D) {
@@ -73,6 +74,9 @@ __device__ __forceinline__ void stage_tile(const Elem* base, int64_t row0, int64
             for (int c = 0; c < 8 && k0 + c0 + c < D; ++c) v[c] = (float)p[c];
         }
     }
+}
+__device__ __forceinline__ void store_piece(const float (&v)[8], float* dst, int tid) {
+    const int r = tid >> 1, c0 = (tid & 1) * 8;
 #pragma unroll
     for (int c = 0; c < 8; ++c) dst[r * kBfLdsStride + c0 + c] = v[c];
 }
@@ -92,11 +96,19 @@ __global__ __launch_bounds__(kBfThreads) void bf_distance_kernel(BruteArgs g, in
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    // the pieces of the next step are fetched into registers while the matrix cores work on this one
+    float pa[8], pb[8];
+    fetch_piece<float>(g.queries, q0, g.nq, g.D, 0, tid, pa);
+    fetch_piece<Elem>(X, c0, nx, g.D, 0, tid, pb);
     for (int k0 = 0; k0 < g.D; k0 += kBfKc) {
+        __syncthreads();                                        // the tiles of the step before are no longer read
+        store_piece(pa, As, tid);
+        store_piece(pb, Bs, tid);
         __syncthreads();
-        stage_tile<float>(g.queries, q0, g.nq, g.D, k0, As, tid);
-        stage_tile<Elem>(X, c0, nx, g.D, k0, Bs, tid);
-        __syncthreads();
+        if (k0 + kBfKc < g.D) {
+            fetch_piece<float>(g.queries, q0, g.nq, g.D, k0 + kBfKc, tid, pa);
+            fetch_piece<Elem>(X, c0, nx, g.D, k0 + kBfKc, tid, pb);
+        }
 #pragma unroll
         for (int kk = 0; kk < kBfKc; kk += 4) {
             float a[4], b[4];
