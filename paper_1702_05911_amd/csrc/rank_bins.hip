@@ -255,12 +255,17 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
 // Full pass: workgroups take the queries the head pass listed (or every query when forced).
 // ------------------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(kRankThreads) void rank_kernel(RankArgs g, RankOffsets L) {
+// MAXPER: tuples a thread may have to hold (T <= MAXPER * kRankThreads).  The variant for at most four is
+// compiled for 64 registers, so that two workgroups fit a compute unit: the pass is a chain of dependent
+// steps with many barriers, and a second resident query hides most of them.
+// PF: the number of tree parts when it is compiled in (4), 0: read from the arguments.
+template <int MAXPER, int PF = 0>
+__global__ __launch_bounds__(kRankThreads, MAXPER <= 4 ? 8 : 4) void rank_kernel(RankArgs g, RankOffsets L) {
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t count = L.force ? (uint32_t)g.nq : g.counters[0];
     for (uint32_t item = blockIdx.x; item < count; item += gridDim.x) {
         const int64_t q = L.force ? (int64_t)item : (int64_t)g.order[item];
-        rank_query<0, false, 8>(g, L, q, smem, nullptr);
+        rank_query<PF, false, MAXPER>(g, L, q, smem, nullptr);
     }
 }
 
@@ -410,12 +415,21 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
         if (e != hipSuccess || defer_full) return e;
     }
     const unsigned grid = head ? (unsigned)(a.nq < 1024 ? a.nq : 1024) : (unsigned)a.nq;
-    hipLaunchKernelGGL(rank_kernel, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
+    if (o.Tcap <= 4 * kRankThreads && a.P == 4)
+        hipLaunchKernelGGL((rank_kernel<4, 4>), dim3(grid), dim3(kRankThreads), o.total, s, a, o);
+    else if (o.Tcap <= 4 * kRankThreads) hipLaunchKernelGGL(rank_kernel<4>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
+    else hipLaunchKernelGGL(rank_kernel<8>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     return hipGetLastError();
 }
 
 hipError_t configure_rank(size_t max_dynamic_lds) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<4>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<4, 4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)max_dynamic_lds);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
 }
 
