@@ -237,6 +237,43 @@ def test_more_runs_than_the_workgroup_keeps_in_lds(pqt, tmp_path):
         PU.check_query_stages(ix, Y[q], taps, q, 20, k1, T, C, ids, dists)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes(pqt, tmp_path, seed):
+    """Seeded random index shapes and budgets inside the documented limits (tree parts, codebook sizes,
+    code bytes and format, hashing, bin order, w, T, C, k): every stage against the oracle."""
+    from workloads import tiny_mixture
+    rng = np.random.default_rng(1000 + seed)
+    P = int(rng.choice([1, 2, 2, 4]))
+    dp = int(rng.choice([4, 6, 8, 12]))                        # 6: not a multiple of four -> general level-2 path
+    D = P * dp
+    k1 = int(rng.choice([2, 3, 5, 8, 12]))
+    k2 = int(rng.choice([1, 2, 4, 7]))
+    per = [m for m in (1, 2, 4) if dp % m == 0]
+    M = P * int(rng.choice(per))
+    K = (k1 * k2) ** P
+    hashed = bool(rng.integers(0, 2)) and K > 64
+    H = int(rng.integers(17, min(K, 4096))) if hashed else K
+    if H > (1 << 22):                                          # keep the oracle's pointer array small
+        H = 4093
+    code_format = int(rng.integers(0, 2)) if k1 >= 2 else 0
+    N = int(rng.integers(500, 4000))
+    X = tiny_mixture(N, d=D, seed=50 + seed)
+    Y = tiny_mixture(10, d=D, seed=90 + seed)
+    w = int(rng.integers(1, k1 + 1))
+    R = w * k2
+    T = int(rng.integers(1, min(R ** P, 3000) + 1))
+    C = int(rng.integers(1, 2 * N))
+    C = min(C, 16384)
+    k = int(rng.integers(1, min(C, 300) + 1))
+    ix = B.build_index(X, P, k1, k2, M, H=H, T=T, C=C, iters=3, code_format=code_format)
+    path = str(tmp_path / f"rand{seed}.pqt")
+    IO.write_index(path, ix)
+    order = "static" if (P == 2 and H == K and rng.integers(0, 2)) else "fullsort"
+    print(f"seed {seed}: P={P} D={D} k1={k1} k2={k2} M={M} H={H} K={K} N={N} w={w} T={T} C={C} k={k} "
+          f"codes={code_format} order={order}", flush=True)
+    _stagewise(pqt, ix, path, Y, k, w, T, C, order=order)
+
+
 def test_hashed_index_dedupes_slots(pqt, tiny, tmp_path):
     cfg, X, Y, ix = tiny
     ixh = B.build_index(X[:3000], cfg.P, cfg.k1, cfg.k2, cfg.M, H=97, T=256, C=1024, codebooks=(ix.C1, ix.C2),
