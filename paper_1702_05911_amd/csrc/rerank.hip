@@ -181,10 +181,12 @@ __device__ __forceinline__ float pair_lambda_term(const float4* plut, int shift,
     return fmaf(fmaf(lam, lam, -lam), e.z, fmaf(lam, e.y, e.x));
 }
 
-// Scores U candidate positions per thread (base + u*nt + tid) and leaves their keys (ordered score
-// bits) in key[0..U).  CHECK: positions may pass nc (their keys are left alone).
+// Scores U candidate positions per thread (p0 + u * 64: a wavefront walks its own contiguous piece
+// of the candidate list, so a thread's next position is mostly in the same run or the one after)
+// and leaves their keys (ordered score bits) in key[0..U).  CHECK: positions may reach pend (their
+// keys are left alone).
 template <int MW, int U, bool CHECK, bool TAPS>
-__device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int base, int nc, int tid, int nt,
+__device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int p0, int pend,
                                             const float* lut, uint32_t* key, const RunList& R, RunCursor& cur,
                                             uint32_t& kmin, uint32_t& kmax) {
     constexpr int NW = MW > 0 ? MW : (MW < -1 ? -MW : 0);      // code words fetched up front (0: byte loads)
@@ -193,11 +195,11 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
     uint32_t cw[U][NW > 0 ? NW : 1];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t p = (uint32_t)(base + u * nt + tid);
-        if (!CHECK || p < (uint32_t)nc) {
+        const uint32_t p = (uint32_t)(p0 + u * kWave);
+        if (!CHECK || p < (uint32_t)pend) {
             if (p >= cur.next_start) {
-                // usually the next run (long runs); otherwise the run is found by halving what is left of
-                // the list (short runs: a step of nt positions passes many of them)
+                // usually the next run; otherwise the run is found by halving what is left of the list
+                // (a thread's first position, or short runs: a step of 64 positions passes several)
                 int lo = cur.run + 1;
                 uint32_t next = R.start_at(lo + 1);
                 if (p >= next) {
@@ -242,8 +244,8 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int p = base + u * nt + tid;
-        if (CHECK && p >= nc) continue;
+        const int p = p0 + u * kWave;
+        if (CHECK && p >= pend) continue;
         float s;
         if (MW > 0) {
             s = lut_at(0, cw[u][0] & 0xffu);               // sum in ascending m
@@ -397,7 +399,10 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     }
     __syncthreads();
 
-    // ---- scores: candidate position u * nt + tid -> key[u] ----------------------------------------------
+    // ---- scores: wavefront v owns positions [v * chunk, (v + 1) * chunk); position pos0 + u * 64 -> key[u] -----
+    const int chunk = ((nc + (nt >> 6) - 1) / (nt >> 6) + kWave - 1) & ~(kWave - 1);     // <= 64 * kKeysPerThread
+    const int pos0 = (tid >> 6) * chunk + lane;
+    const int pend = min(nc, ((tid >> 6) + 1) * chunk);      // this wavefront's positions end here
     uint32_t key[kKeysPerThread];
 #pragma unroll
     for (int u = 0; u < kKeysPerThread; ++u) key[u] = 0xffffffffu;
@@ -410,17 +415,18 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
         // eight positions in flight per thread; four when a code has four or more words (registers)
         constexpr int UB = (MW >= 4 || MW <= -4) ? 4 : 8;
         static_assert(kKeysPerThread % 4 == 0, "batches of four or eight");
+        const int wbase = pos0 - lane;         // the same for a wavefront: so is the choice of the variant
 #pragma unroll
         for (int b = 0; b * UB + UB <= kKeysPerThread; ++b) {
-            const int base = b * UB * nt;
-            if (base + UB * nt <= nc) score_batch<MW, UB, false, TAPS>(g, q, base, nc, tid, nt, lut, key + b * UB, R, cur, kmin, kmax);
-            else if (base < nc) score_batch<MW, UB, true, TAPS>(g, q, base, nc, tid, nt, lut, key + b * UB, R, cur, kmin, kmax);
+            const int base = wbase + b * UB * kWave;
+            if (base + UB * kWave <= pend) score_batch<MW, UB, false, TAPS>(g, q, base + lane, pend, lut, key + b * UB, R, cur, kmin, kmax);
+            else if (base < pend) score_batch<MW, UB, true, TAPS>(g, q, base + lane, pend, lut, key + b * UB, R, cur, kmin, kmax);
         }
         if (kKeysPerThread % UB) {             // a last batch of four
             constexpr int done = kKeysPerThread / UB * UB;
-            const int base = done * nt;
-            if (base + 4 * nt <= nc) score_batch<MW, 4, false, TAPS>(g, q, base, nc, tid, nt, lut, key + done, R, cur, kmin, kmax);
-            else if (base < nc) score_batch<MW, 4, true, TAPS>(g, q, base, nc, tid, nt, lut, key + done, R, cur, kmin, kmax);
+            const int base = wbase + done * kWave;
+            if (base + 4 * kWave <= pend) score_batch<MW, 4, false, TAPS>(g, q, base + lane, pend, lut, key + done, R, cur, kmin, kmax);
+            else if (base < pend) score_batch<MW, 4, true, TAPS>(g, q, base + lane, pend, lut, key + done, R, cur, kmin, kmax);
         }
     }
     if (TAPS && g.n_cand && tid == 0) g.n_cand[q] = (uint32_t)nc;
@@ -438,8 +444,8 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     if (nc <= L.scap) {                        // few candidates: order all of them
 #pragma unroll
         for (int u = 0; u < kKeysPerThread; ++u) {
-            const int p = u * nt + tid;
-            if (p < nc) surv[p] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
+            const int p = pos0 + u * kWave;
+            if (p < pend) surv[p] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
         }
         nsurv = nc;
     } else {
@@ -449,8 +455,8 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
         const int shift = width > kHistBits ? width - kHistBits : 0;   // (key - lo_key) >> shift < 1024
 #pragma unroll
         for (int u = 0; u < kKeysPerThread; ++u) {
-            if (u * nt >= nc) break;                                   // same for the whole workgroup
-            if (u * nt + tid < nc) atomicAdd(&hist[(key[u] - lo_key) >> shift], 1u);
+            if (u * kWave >= chunk) break;                             // same for the whole workgroup
+            if (pos0 + u * kWave < pend) atomicAdd(&hist[(key[u] - lo_key) >> shift], 1u);
         }
         __syncthreads();
         // the first wavefront finds the bin bsel with count(< bsel) < kk <= count(<= bsel)
@@ -471,9 +477,9 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
             const uint32_t thr = thr64 > 0xffffffffull ? 0xffffffffu : (uint32_t)thr64;
 #pragma unroll
             for (int u = 0; u < kKeysPerThread; ++u) {
-                const int p = u * nt + tid;
-                if (u * nt >= nc) break;
-                if (p < nc && key[u] <= thr)
+                const int p = pos0 + u * kWave;
+                if (u * kWave >= chunk) break;
+                if (p < pend && key[u] <= thr)
                     surv[atomicAdd(&misc[kNumSurv], 1u)] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
             }
             nsurv = (int)count_le;
@@ -488,7 +494,7 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
                 radix_select_pass(prefix, mask, shifts[pass], nbits[pass], need, hist, part, rout, [&](auto f) {
 #pragma unroll
                     for (int u = 0; u < kKeysPerThread; ++u)
-                        if (u * nt + tid < nc) f(key[u]);
+                        if (pos0 + u * kWave < pend) f(key[u]);
                 });
                 prefix |= rout[0] << shifts[pass];
                 mask |= ((1u << nbits[pass]) - 1u) << shifts[pass];
@@ -504,8 +510,8 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
                     radix_select_pass(iprefix, imask, shifts[pass], nbits[pass], need, hist, part, rout, [&](auto f) {
 #pragma unroll
                         for (int u = 0; u < kKeysPerThread; ++u) {
-                            const int p = u * nt + tid;
-                            if (p < nc && key[u] == tau) f(g.ids[source_of((uint32_t)p, steps, R)]);
+                            const int p = pos0 + u * kWave;
+                            if (p < pend && key[u] == tau) f(g.ids[source_of((uint32_t)p, steps, R)]);
                         }
                     });
                     iprefix |= rout[0] << shifts[pass];
@@ -517,8 +523,8 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
             }
 #pragma unroll
             for (int u = 0; u < kKeysPerThread; ++u) {
-                const int p = u * nt + tid;
-                if (p >= nc || key[u] > tau) continue;
+                const int p = pos0 + u * kWave;
+                if (p >= pend || key[u] > tau) continue;
                 if (key[u] == tau && id_cut != 0xffffffffu && g.ids[source_of((uint32_t)p, steps, R)] > id_cut) continue;
                 surv[atomicAdd(&misc[kNumSurv], 1u)] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
             }
