@@ -5,20 +5,26 @@
 //   * the per-query table LUT[m][c] of Eq. 9 summands is built in LDS from the level-1
 //     sub-part distances the traversal already produced (no new distance is computed);
 //   * codes are stored bin-major beside the ids, so the candidates of a proposed slot are one
-//     contiguous run: a thread's candidate positions only grow, so it walks the run starts (in
-//     LDS) forwards; consecutive lanes read consecutive codes (coalesced), eight positions per
-//     thread in flight; the id array is only touched for the few survivors;
+//     contiguous run.  A wavefront scores a contiguous piece of the candidate list, 64 positions
+//     (one window) after the other, consecutive lanes reading consecutive codes (coalesced),
+//     eight windows in flight; where runs are long (sixteen candidates or more on average) it
+//     walks the run list as one, with scalar control and one compare and select per run boundary,
+//     where they are short every thread searches the list for its own position.  The id array is
+//     only touched for the few survivors;
 //   * score = sum over m = 0..M-1, in that order, of LUT[m][code[m]] in fp32;
 //   * a thread scores at most twenty candidates and keeps their keys (ordered score bits) in
-//     registers through the selection: the kernel is bound by the latency of its dependent steps,
-//     so what counts is how many queries a compute unit has in flight, and that is set by the LDS
-//     a workgroup holds -- a key array in LDS would double it;
+//     registers through the selection: with eight workgroups per compute unit the vector ALU is
+//     busy most of the time on a cache-resident index, so what counts is the number of vector
+//     instructions per candidate and how many queries a compute unit has in flight, which is set
+//     by the LDS a workgroup holds -- a key array in LDS would double it;
 //   * the k best by (score, id): one 1024-bin histogram over the ordered score bits between the
 //     smallest and largest score of the query; the first wavefront locates the bin b that holds the
 //     k-th smallest; the keys in bins <= b (a superset of the answer, normally a few more
 //     than k) are appended to a short list with their positions, their ids fetched, and the
 //     (score bits, id) keys sorted in registers.  If the superset does not fit (heavily tied
 //     scores) an exact radix select on score bits, then on ids, picks exactly k.
+#include <type_traits>
+
 #include "rank_device.hpp"
 
 namespace pqt {
@@ -26,6 +32,7 @@ namespace pqt {
 constexpr int kHistBits = 10;
 constexpr int kHistSize = 1 << kHistBits;
 constexpr int kCountRankMax = 32;    // survivors ordered by counting ranks up to this many, else sorted
+constexpr int kWalkMinRun = 16;      // mean run length from which a wavefront walks the run list together
 constexpr int kRunPrefetch = 64;     // runs fetched before the run count is known
 constexpr int kFusedPer = 4;         // tuples per thread the in-kernel bin ranking may hold
 constexpr int kKeysPerThread = 20;   // candidates a thread scores; C <= kKeysPerThread * workgroup size
@@ -172,6 +179,61 @@ struct RunCursor {
     uint32_t delta;        // run_src[run] - run_start[run]: position in ids/codes = candidate position + delta
 };
 
+// Where a wavefront stands in the run list while it walks its piece of the candidate list, 64
+// positions (one window) at a time.  Lane l holds run blk0 + l of the list; r (the same in every
+// lane) is the first run that starts after the windows done so far, dcur the offset
+// run_src - run_start of run r - 1.  Everything that steers the walk is wavefront-uniform, so the
+// per-position work is one compare and one select per run boundary inside the window.
+struct WaveRuns {
+    uint32_t v_src, v_start;   // run blk0 + lane (v_start = 0xffffffff past the end of the list)
+    int blk0, r;
+    uint32_t dcur;
+    uint32_t next_s;           // start of run r, 0xffffffff when the list is used up
+    __device__ __forceinline__ void load(const RunList& R, int first, int lane) {
+        blk0 = first;
+        const int idx = first + lane;
+        v_start = 0xffffffffu;
+        v_src = 0u;
+        if (idx < R.nr) {
+            v_start = R.start_at(idx);
+            v_src = R.src_at(idx);
+        }
+    }
+    __device__ __forceinline__ void fetch_next(const RunList& R, int lane) {
+        if (r >= R.nr) {
+            next_s = 0xffffffffu;
+            return;
+        }
+        if (r - blk0 >= kWave) load(R, r & ~(kWave - 1), lane);
+        next_s = (uint32_t)__builtin_amdgcn_readlane((int)v_start, r - blk0);
+    }
+    // positions [wbase, ...) come next: r = number of runs that start at or before wbase (at least one)
+    __device__ __forceinline__ void seek(const RunList& R, uint32_t wbase, int lane) {
+        int b = 0;
+        while ((b + 1) * kWave < R.nr &&
+               (uint32_t)__builtin_amdgcn_readfirstlane((int)R.start_at((b + 1) * kWave)) <= wbase)
+            ++b;
+        load(R, b * kWave, lane);
+        const int cnt = __popcll(__ballot(v_start <= wbase));
+        r = b * kWave + cnt;
+        dcur = (uint32_t)__builtin_amdgcn_readlane((int)(v_src - v_start), cnt > 0 ? cnt - 1 : 0);
+        fetch_next(R, lane);
+    }
+    // offset of every lane's position wb + lane (wb: multiple of 64, not below the last window's);
+    // a window without a run boundary costs one scalar compare
+    __device__ __forceinline__ uint32_t window(const RunList& R, uint32_t wb, int lane) {
+        uint32_t delta = dcur;
+        while (next_s < wb + kWave) {
+            const uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)v_src, r - blk0) - next_s;
+            delta = wb + (uint32_t)lane >= next_s ? d : delta;
+            dcur = d;
+            ++r;
+            fetch_next(R, lane);
+        }
+        return delta;
+    }
+};
+
 // (pair, lambda level) codes: the summand of Eq. 9 for one sub-part from the pair's LDS entry
 // (b^2, a^2 - b^2, c^2) and the level; lambda = (level - 96) / 16 is exact in fp32.
 constexpr int kPairLambda = -1;      // MW < 0 selects this code format: -1 any M (byte loads), else -(words per code)
@@ -181,14 +243,15 @@ __device__ __forceinline__ float pair_lambda_term(const float4* plut, int shift,
     return fmaf(fmaf(lam, lam, -lam), e.z, fmaf(lam, e.y, e.x));
 }
 
-// Scores U candidate positions per thread (p0 + u * 64: a wavefront walks its own contiguous piece
-// of the candidate list, so a thread's next position is mostly in the same run or the one after)
-// and leaves their keys (ordered score bits) in key[0..U).  CHECK: positions may reach pend (their
-// keys are left alone).
-template <int MW, int U, bool CHECK, bool TAPS>
-__device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int p0, int pend,
-                                            const float* lut, uint32_t* key, const RunList& R, RunCursor& cur,
-                                            uint32_t& kmin, uint32_t& kmax) {
+// Scores U candidate positions per thread (wb + u * 64 + lane: a wavefront walks its own contiguous
+// piece of the candidate list, U windows of 64 positions at a time) and leaves their keys (ordered
+// score bits) in key[0..U).  CHECK: positions may reach pend (their keys are left alone).
+// WALK: the wavefront walks the run list (long runs); else every thread searches it (short runs).
+template <int MW, int U, bool CHECK, bool TAPS, bool WALK>
+__device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int wb, int lane, int pend,
+                                            const float* lut, uint32_t* key, const RunList& R, WaveRuns& wr,
+                                            RunCursor& cur, uint32_t& kmin, uint32_t& kmax) {
+    const int p0 = wb + lane;
     constexpr int NW = MW > 0 ? MW : (MW < -1 ? -MW : 0);      // code words fetched up front (0: byte loads)
     const int M = MW > 0 ? 4 * MW : (MW < -1 ? -2 * MW : g.M);
     uint32_t src[U];
@@ -196,7 +259,11 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t p = (uint32_t)(p0 + u * kWave);
-        if (!CHECK || p < (uint32_t)pend) {
+        if (WALK) {
+            const uint32_t delta = wr.window(R, (uint32_t)(wb + u * kWave), lane);
+            // a position past the end reads the first candidate of a run the wavefront holds
+            src[u] = (!CHECK || p < (uint32_t)pend) ? p + delta : (uint32_t)__builtin_amdgcn_readlane((int)wr.v_src, 0);
+        } else if (!CHECK || p < (uint32_t)pend) {
             if (p >= cur.next_start) {
                 // usually the next run; otherwise the run is found by halving what is left of the list
                 // (a thread's first position, or short runs: a step of 64 positions passes several)
@@ -341,8 +408,8 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     }
     for (int e = tid; e < M * k1; e += nt) sa[e] = g.a[(size_t)q * M * k1 + e];
     for (int e = tid; e < kHistSize; e += nt) hist[e] = 0;
-    const int nr = (int)meta.x;
-    const int nc = (int)meta.y;
+    const int nr = __builtin_amdgcn_readfirstlane((int)meta.x);     // the same in every thread
+    const int nc = __builtin_amdgcn_readfirstlane((int)meta.y);
     int steps = 0;
     while ((1 << steps) < nr) ++steps;
     const int nr_lds = nr < L.rcap ? nr : L.rcap;
@@ -408,25 +475,39 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     for (int u = 0; u < kKeysPerThread; ++u) key[u] = 0xffffffffu;
     uint32_t kmin = 0xffffffffu, kmax = 0u;
     if (nc > 0) {
-        RunCursor cur;                         // positions of a thread only grow
-        cur.run = 0;
-        cur.next_start = R.start_at(1);
-        cur.delta = R.src_at(0) - R.start_at(0);
+        const int wbase = __builtin_amdgcn_readfirstlane(pos0 - lane);    // the same for a wavefront
         // eight positions in flight per thread; four when a code has four or more words (registers)
         constexpr int UB = (MW >= 4 || MW <= -4) ? 4 : 8;
         static_assert(kKeysPerThread % 4 == 0, "batches of four or eight");
-        const int wbase = pos0 - lane;         // the same for a wavefront: so is the choice of the variant
+        WaveRuns wr;
+        RunCursor cur;                         // positions of a thread only grow
+        auto score_all = [&](auto walk) {
+            constexpr bool WALK = decltype(walk)::value;
 #pragma unroll
-        for (int b = 0; b * UB + UB <= kKeysPerThread; ++b) {
-            const int base = wbase + b * UB * kWave;
-            if (base + UB * kWave <= pend) score_batch<MW, UB, false, TAPS>(g, q, base + lane, pend, lut, key + b * UB, R, cur, kmin, kmax);
-            else if (base < pend) score_batch<MW, UB, true, TAPS>(g, q, base + lane, pend, lut, key + b * UB, R, cur, kmin, kmax);
-        }
-        if (kKeysPerThread % UB) {             // a last batch of four
-            constexpr int done = kKeysPerThread / UB * UB;
-            const int base = wbase + done * kWave;
-            if (base + 4 * kWave <= pend) score_batch<MW, 4, false, TAPS>(g, q, base + lane, pend, lut, key + done, R, cur, kmin, kmax);
-            else if (base < pend) score_batch<MW, 4, true, TAPS>(g, q, base + lane, pend, lut, key + done, R, cur, kmin, kmax);
+            for (int b = 0; b * UB + UB <= kKeysPerThread; ++b) {
+                const int base = wbase + b * UB * kWave;
+                if (base + UB * kWave <= pend)
+                    score_batch<MW, UB, false, TAPS, WALK>(g, q, base, lane, pend, lut, key + b * UB, R, wr, cur, kmin, kmax);
+                else if (base < pend)
+                    score_batch<MW, UB, true, TAPS, WALK>(g, q, base, lane, pend, lut, key + b * UB, R, wr, cur, kmin, kmax);
+            }
+            if (kKeysPerThread % UB) {         // a last batch of four
+                constexpr int done = kKeysPerThread / UB * UB;
+                const int base = wbase + done * kWave;
+                if (base + 4 * kWave <= pend)
+                    score_batch<MW, 4, false, TAPS, WALK>(g, q, base, lane, pend, lut, key + done, R, wr, cur, kmin, kmax);
+                else if (base < pend)
+                    score_batch<MW, 4, true, TAPS, WALK>(g, q, base, lane, pend, lut, key + done, R, wr, cur, kmin, kmax);
+            }
+        };
+        if (nr * kWalkMinRun <= nc) {          // runs long enough that a window of 64 positions meets few of them
+            wr.seek(R, (uint32_t)wbase, lane);
+            score_all(std::true_type{});
+        } else {
+            cur.run = 0;
+            cur.next_start = R.start_at(1);
+            cur.delta = R.src_at(0) - R.start_at(0);
+            score_all(std::false_type{});
         }
     }
     if (TAPS && g.n_cand && tid == 0) g.n_cand[q] = (uint32_t)nc;
