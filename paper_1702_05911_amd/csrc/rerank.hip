@@ -400,11 +400,16 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     // ---- issue every load that needs no other result first ------------------------------------------
     uint2 run0 = make_uint2(0u, 0u);
     if (tid < kRunPrefetch && tid < L.rcap) run0 = qruns[tid];
+    // table entries: a thread takes code value c = tid mod 256 of the sub-parts m0, m0 + ms, ... (m0 and ms
+    // are the same for a wavefront, so which sub-parts exist is decided by scalar code)
+    const int lut_c = tid & 255;
+    const int lut_m0 = __builtin_amdgcn_readfirstlane(tid >> 8), lut_ms = nt >> 8;
+    const int Mlut = MW > 0 ? 4 * MW : (MW < -1 ? -2 * MW : M);
     CodeEntry ent[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const int e = u * nt + tid;
-        ent[u] = g.table[e < nlut ? e : 0];
+        const int m = lut_m0 + u * lut_ms;
+        ent[u] = g.table[(m < Mlut ? m : 0) * 256 + lut_c];
     }
     for (int e = tid; e < M * k1; e += nt) sa[e] = g.a[(size_t)q * M * k1 + e];
     for (int e = tid; e < kHistSize; e += nt) hist[e] = 0;
@@ -433,29 +438,29 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     __syncthreads();
 
     // ---- LUT of Eq. 9 summands ------------------------------------------------------------------------
-    for (int base = 0; base < nlut; base += nt * 4) {
+    for (int mb = lut_m0; mb < Mlut; mb += 4 * lut_ms) {
         CodeEntry cur_ent[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) cur_ent[u] = ent[u];
-        if (base + nt * 4 < nlut) {            // the next round's entries are fetched while this one is worked on
+        if (mb + 4 * lut_ms < Mlut) {          // the next round's entries are fetched while this one is worked on
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int e = base + (4 + u) * nt + tid;
-                ent[u] = g.table[e < nlut ? e : 0];
+                const int m = mb + (4 + u) * lut_ms;
+                ent[u] = g.table[(m < Mlut ? m : 0) * 256 + lut_c];
             }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int e = base + u * nt + tid;
-            if (e >= nlut) continue;
-            const int m = e >> 8;
-            const float b2 = sa[m * k1 + (cur_ent[u].ij & 0xffu)];
-            const float a2 = sa[m * k1 + ((cur_ent[u].ij >> 8) & 0xffu)];
+            const int m = mb + u * lut_ms;
+            if (m >= Mlut) continue;              // (no early exit: the loop must unroll in full)
+            const int e = m * 256 + lut_c;
+            const float* sam = sa + m * k1;
+            const float b2 = sam[cur_ent[u].ij & 0xffu];
+            const float a2 = sam[(cur_ent[u].ij >> 8) & 0xffu];
             if (MW < 0) {
                 // entry = centroid pair number; its kc field holds c^2
-                const int pair = e & 255;
-                if (pair < (1 << g.pair_shift))
-                    reinterpret_cast<float4*>(lut)[(m << g.pair_shift) + pair] = make_float4(b2, a2 - b2, cur_ent[u].kc, 0.0f);
+                if (lut_c < (1 << g.pair_shift))
+                    reinterpret_cast<float4*>(lut)[(m << g.pair_shift) + lut_c] = make_float4(b2, a2 - b2, cur_ent[u].kc, 0.0f);
                 continue;
             }
             // Eq. 9 rearranged: b^2 + lam (a^2 - b^2) + (lam^2 - lam) c^2, the last term folded per code value
@@ -698,6 +703,7 @@ hipError_t launch_rerank(const RerankArgs& a_in, const RankArgs* fused, hipStrea
         if (RL.Tcap > rerank_fused_tuples_per_thread() * a.threads) return hipErrorInvalidValue;
     }
     if (a.keys_per_thread != kKeysPerThread || a.C > a.keys_per_thread * a.threads) return hipErrorInvalidValue;
+    if (a.threads % 256 != 0) return hipErrorInvalidValue;             // a thread builds the table entries of one code value
     if (a.code_format == 1 && a.lut) return hipErrorInvalidValue;      // that tap is the one-byte format's table
     const RerankLds L = rerank_layout(a.M, a.k1, a.T, a.C, a.k, a.threads, fused ? RL.total : 0, a.code_format, a.runs_in_lds);
     if (fused) launch_rerank_t<false, true>(a, L, rk, RL, s);
