@@ -561,12 +561,33 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
             // keys of the bins <= bsel are the keys <= thr
             const unsigned long long thr64 = (unsigned long long)lo_key + (((unsigned long long)bsel + 1ull) << shift) - 1ull;
             const uint32_t thr = thr64 > 0xffffffffull ? 0xffffffffu : (uint32_t)thr64;
+            if (thr != 0xffffffffu) {
+                // key slots without a candidate hold 0xffffffff > thr.  A wavefront counts its keys <= thr,
+                // reserves room for them with one atomic, then writes them: no wait for LDS per window
+                uint32_t mine = 0;
 #pragma unroll
-            for (int u = 0; u < kKeysPerThread; ++u) {
-                const int p = pos0 + u * kWave;
-                if (u * kWave >= chunk) break;
-                if (p < pend && key[u] <= thr)
-                    surv[atomicAdd(&misc[kNumSurv], 1u)] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
+                for (int u = 0; u < kKeysPerThread; ++u) mine += (uint32_t)__popcll(__ballot(key[u] <= thr));
+                uint32_t at = 0;
+                if (lane == 0 && mine) at = atomicAdd(&misc[kNumSurv], mine);
+                at = (uint32_t)__builtin_amdgcn_readfirstlane((int)at);
+#pragma unroll
+                for (int u = 0; u < kKeysPerThread; ++u) {
+                    const unsigned long long hm = __ballot(key[u] <= thr);
+                    if (hm == 0ull) continue;                          // the same for the wavefront
+                    if (key[u] <= thr) {
+                        const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(hm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hm, 0u));
+                        surv[at + below] = ((unsigned long long)key[u] << 32) | (uint32_t)(pos0 + u * kWave);
+                    }
+                    at += (uint32_t)__popcll(hm);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kKeysPerThread; ++u) {
+                    const int p = pos0 + u * kWave;
+                    if (u * kWave >= chunk) break;
+                    if (p < pend && key[u] <= thr)
+                        surv[atomicAdd(&misc[kNumSurv], 1u)] = ((unsigned long long)key[u] << 32) | (uint32_t)p;
+                }
             }
             nsurv = (int)count_le;
         } else {
