@@ -409,6 +409,12 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
             lv.T1[l] = o.Tcap < t ? o.Tcap : t;
             lv.npairs[l] = head_pair_count(lv.T1[l]);
         }
+        if (defer_full) {
+            // the re-rank workgroups rank what is left in full: the third level, one long chain of dependent
+            // steps in a single wavefront for a few queries, would only set the duration of this kernel
+            lv.T1[2] = lv.T1[1];
+            lv.npairs[2] = lv.npairs[1];
+        }
         hipLaunchKernelGGL(rank_head_kernel, dim3((unsigned)((a.nq + per - 1) / per)), dim3(kRankHeadThreads), 0, s, a,
                            o.Tcap, lv);
         hipError_t e = hipGetLastError();
