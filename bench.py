@@ -144,8 +144,9 @@ def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16, order
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default 2000, or 20 with --batch: a step then makes many calls)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default steps // 10)")
     ap.add_argument("--workload", default="sift")
     ap.add_argument("--w", type=int, default=None)
     ap.add_argument("--nq", type=int, default=None, help="queries per step (default: the workload's)")
@@ -184,6 +185,13 @@ def main():
         print("bench.py: this build runs on ONE GPU (a batch of queries needs no second one); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    # A step takes 0.15-2 ms, and the GPU's clocks need some milliseconds of work to settle: twenty steps
+    # right after the idle set-up read 8-10 % low, so the default is 2000 steps (under a second to a few
+    # seconds of timed work) after 200 untimed ones.
+    if args.steps is None:
+        args.steps = 20 if args.batch else 2000
+    if args.warmup is None:
+        args.warmup = max(3, args.steps // 10)
 
     import numpy as np
     import torch
