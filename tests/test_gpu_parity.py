@@ -237,6 +237,42 @@ def test_more_runs_than_the_workgroup_keeps_in_lds(pqt, tmp_path):
         PU.check_query_stages(ix, Y[q], taps, q, 20, k1, T, C, ids, dists)
 
 
+def test_many_medium_runs_are_walked_by_the_wavefront(pqt, tmp_path):
+    """Two huge clusters (so the workgroup keeps only 64 runs in LDS) and a few hundred small groups of
+    about twenty near-identical vectors: a query among the groups gathers from well over 64 runs whose
+    mean length is above sixteen, so a wavefront walks the run list as one, through several blocks of
+    64 runs, the later ones read from memory."""
+    rng = np.random.default_rng(4242)
+    P, k1, k2, M, D, T, C = 2, 8, 4, 4, 16, 1024, 3000
+    centers = rng.normal(size=(2, D)) * 0.01 + np.array([[4.0] * D, [-4.0] * D])
+    big = np.repeat(centers, 20000, axis=0) + rng.normal(size=(40000, D)) * 1e-3
+    spots = rng.uniform(-1.5, 1.5, size=(300, D))
+    groups = np.repeat(spots, 20, axis=0) + rng.normal(size=(6000, D)) * 1e-4
+    X = np.concatenate([big, groups]).astype(np.float32)
+    X = X[rng.permutation(X.shape[0])]
+    # the tree is trained on the groups and a few vectors of the big clusters, so that the groups spread over many bins
+    C1, C2 = B.train_tree(np.concatenate([groups, big[::2000]]).astype(np.float32), P, k1, k2, iters=8)
+    ix = B.build_index(X, P, k1, k2, M, T=T, C=C, codebooks=(C1, C2))
+    mean_run = X.shape[0] / np.count_nonzero(np.diff(ix.offsets.astype(np.int64)))
+    kept = 64
+    while kept < T and kept < 2 * C / mean_run:
+        kept *= 2
+    Y = (spots[:12] + rng.normal(size=(12, D)) * 0.05).astype(np.float32)
+    path = str(tmp_path / "groups.pqt")
+    IO.write_index(path, ix)
+    gix = pqt.pqt_index_load(path, 0)
+    try:
+        ids, dists, taps = _run_debug(pqt, gix, Y, 20, k1)
+    finally:
+        pqt.pqt_index_free(gix)
+    nr, nc = taps["n_slots"].astype(np.int64), taps["n_cand"].astype(np.int64)
+    print("runs per query", nr.tolist(), "candidates", nc.tolist(), "runs kept in LDS", kept, flush=True)
+    walked = (nr > 2 * 64) & (nc >= 16 * nr)
+    assert kept == 64 and walked.any(), "no query with more than two blocks of runs of mean length >= 16"
+    for q in range(Y.shape[0]):
+        PU.check_query_stages(ix, Y[q], taps, q, 20, k1, T, C, ids, dists)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_shapes(pqt, tmp_path, seed):
     """Seeded random index shapes and budgets inside the documented limits (tree parts, codebook sizes,
