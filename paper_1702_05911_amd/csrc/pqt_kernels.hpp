@@ -115,6 +115,9 @@ struct RerankArgs {
     const uint32_t* todo;
     const uint32_t* todo_count;
     int early;
+    // set by launch_rerank when the kernel ranks left-over queries: their first wavefront tries this many
+    // tuples (the pairs of the head-pass table up to mid_npairs) before the workgroup ranks in full
+    int mid_T1 = 0, mid_npairs = 0;
     int64_t* out_ids;         // nq x k
     float* out_dists;         // nq x k
     // taps (nullable)

@@ -25,7 +25,7 @@
 //     scores) an exact radix select on score bits, then on ids, picks exactly k.
 #include <type_traits>
 
-#include "rank_device.hpp"
+#include "rank_head_device.hpp"
 
 namespace pqt {
 
@@ -391,8 +391,25 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
         if (g.early > 0 && meta.x == kMetaTodo && meta.y < (uint32_t)g.early) return;   // an early workgroup has it
     }
     if (FUSED && meta.x == kMetaTodo) {        // same for the whole workgroup
-        // the run list goes to memory (this query's own rows), the counts come back through LDS
-        rank_query<2, true, kFusedPer>(rk, RL, q, smem, misc + kRanked);
+        // the run list goes to memory (this query's own rows), the counts come back through LDS.
+        // First the head pass's third level (128 tuples) by the first wavefront alone: few vector
+        // instructions, and nearly every left-over query is finished by it; the full ranking by the
+        // whole workgroup only if even those runs do not fill the candidate budget.
+        bool ranked = false;
+        if (g.mid_T1 > 0) {
+            if (tid < kWave) {
+                HeadLds& S = *reinterpret_cast<HeadLds*>(smem);
+                const int R1 = rk.R < kHeadT ? rk.R : kHeadT;
+                head_load_lists(rk, S, q, lane, R1);
+                unsigned long long carry = ~0ull;
+                const int r = head_level<2, true>(rk, S, q, lane, R1, g.mid_T1, 0, g.mid_npairs, RL.Tcap, true, carry, misc + kRanked);
+                if (lane == 0) misc[kRanked + 2] = r == 1 ? 1u : 0u;
+            }
+            __syncthreads();
+            ranked = misc[kRanked + 2] != 0u;
+            __syncthreads();
+        }
+        if (!ranked) rank_query<2, true, kFusedPer>(rk, RL, q, smem, misc + kRanked);
         meta = make_uint2(misc[kRanked], misc[kRanked + 1]);
     }
     const uint2* qruns = g.runs + (size_t)q * T;
@@ -722,6 +739,13 @@ hipError_t launch_rerank(const RerankArgs& a_in, const RankArgs* fused, hipStrea
         rk = *fused;
         RL = rank_offsets(rk.P, rk.R, rk.T, rk.hashed);
         if (RL.Tcap > rerank_fused_tuples_per_thread() * a.threads) return hipErrorInvalidValue;
+    }
+    if (fused) {
+        // the wavefront's two lists lie at the start of the workgroup's LDS (table, survivor list and
+        // histogram are not in use yet, and the arrays that receive the result come after them)
+        static_assert(sizeof(HeadLds) <= sizeof(uint32_t) * kHistSize, "the lists must end before the arrays that are live");
+        a.mid_T1 = RL.Tcap < kHeadT ? RL.Tcap : kHeadT;
+        a.mid_npairs = head_pair_count(a.mid_T1);
     }
     if (a.keys_per_thread != kKeysPerThread || a.C > a.keys_per_thread * a.threads) return hipErrorInvalidValue;
     if (a.threads % 256 != 0) return hipErrorInvalidValue;             // a thread builds the table entries of one code value
