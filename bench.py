@@ -26,6 +26,7 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
 # integer/compare work of the bin-ranking kernel runs on the vector ALU: 256 CUs x 4 SIMD16
 # x 16 lanes x 2.4 GHz = 39.3 T lane-ops/s (one 32-bit op per lane per clock)
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+VALU_ISSUE_PEAK_G = 256 * 4 * 2.4e9 / 4 / 1e9     # wave-level vector instructions per second, in G
 
 
 def make_data(cfg, device):
@@ -86,10 +87,11 @@ def recall_at(ids, gt, xs=(1, 10, 100)):
     return out
 
 
-def measured_traffic(kernel, workload, w):
+def measured_traffic(kernel, workload, w, field="bytes_per_launch"):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
     WRITE_SIZE runs, scaled by a copy kernel of known size), or None when there is no summary for
-    this kernel and workload.  Counters cannot be read from inside this process."""
+    this kernel and workload.  Counters cannot be read from inside this process.
+    field="valu_insts_per_launch": the wave-level vector instructions per launch (SQ_INSTS_VALU)."""
     path = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     try:
         with open(path) as f:
@@ -97,7 +99,7 @@ def measured_traffic(kernel, workload, w):
     except OSError:
         return None
     entry = table.get(f"{workload}:w{w}:{kernel}")
-    return None if entry is None else entry.get("bytes_per_launch")
+    return None if entry is None else entry.get(field)
 
 
 def _oracle_worker(args):
@@ -362,6 +364,15 @@ def main():
     # 256 CUs x 32 banks x 4 bytes x 2.4 GHz = 78.6 TB/s, i.e. 19.7 T look-ups/s without bank conflicts
     stages[2]["lds_lookups_per_s"] = nq * mean_cand * cfg.M / (stage_ms[2] * 1e-3)
     stages[2]["lds_lookup_frac"] = stages[2]["lds_lookups_per_s"] / (256 * 32 * 2.4e9)
+    # Vector instruction issue: a 64-lane instruction occupies its 16-lane SIMD for 4 cycles, so the chip
+    # issues at most 256 CUs x 4 SIMDs x 2.4 GHz / 4 = 614 G wave-instructions/s.  Instruction counts come
+    # from the committed counter run (same workload and launch shape), durations from this run.
+    if not (code_format or args.M or args.order == "static" or args.batch):
+        for s in stages:
+            n = measured_traffic(s["kernel"], cfg.name, w, "valu_insts_per_launch")
+            if n:
+                s["valu_issue"] = {"insts_per_launch": n, "achieved": n / (s["ms"] * 1e-3) / 1e9, "peak": VALU_ISSUE_PEAK_G,
+                                   "unit": "G wave-instructions/s", "frac": n / (s["ms"] * 1e-3) / 1e9 / VALU_ISSUE_PEAK_G}
     dom = max(stages, key=lambda s: s["ms"])
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
                 "unit": dom["unit"], "frac": dom["frac"], "traffic": None if (code_format or args.M or args.order == "static") else measured_traffic(dom["kernel"], cfg.name, w)}
