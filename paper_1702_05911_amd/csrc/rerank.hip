@@ -7,7 +7,7 @@
 //   * codes are stored bin-major beside the ids, so the candidates of a proposed slot are one
 //     contiguous run.  A wavefront scores a contiguous piece of the candidate list, 64 positions
 //     (one window) after the other, consecutive lanes reading consecutive codes (coalesced),
-//     eight windows in flight; where runs are long (sixteen candidates or more on average) it
+//     eight windows in flight; where runs are long (eight candidates or more on average) it
 //     walks the run list as one, with scalar control and one compare and select per run boundary,
 //     where they are short every thread searches the list for its own position.  The id array is
 //     only touched for the few survivors;
@@ -32,7 +32,7 @@ namespace pqt {
 constexpr int kHistBits = 10;
 constexpr int kHistSize = 1 << kHistBits;
 constexpr int kCountRankMax = 32;    // survivors ordered by counting ranks up to this many, else sorted
-constexpr int kWalkMinRun = 16;      // mean run length from which a wavefront walks the run list together
+constexpr int kWalkMinRun = 8;       // mean run length from which a wavefront walks the run list together
 constexpr int kRunPrefetch = 64;     // runs fetched before the run count is known
 constexpr int kFusedPer = 4;         // tuples per thread the in-kernel bin ranking may hold
 constexpr int kKeysPerThread = 20;   // candidates a thread scores; C <= kKeysPerThread * workgroup size
