@@ -84,18 +84,26 @@ size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R
 
 __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g, int Tn, HeadLevels lv) {
     __shared__ HeadLds lds[kRankHeadThreads / kWave];
+    __shared__ __align__(4) uint8_t tab_a[kHeadPairs], tab_b[kHeadPairs];      // the pair table: one load per thread
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t q = (int64_t)blockIdx.x * (kRankHeadThreads / kWave) + wave;
-    if (q >= g.nq) return;
+    static_assert(kHeadPairs % 4 == 0 && kHeadPairs / 4 <= kRankHeadThreads, "a word of each table half per thread");
+    if (threadIdx.x < kHeadPairs / 4) {
+        reinterpret_cast<uint32_t*>(tab_a)[threadIdx.x] = reinterpret_cast<const uint32_t*>(kHeadPairTable.a)[threadIdx.x];
+        reinterpret_cast<uint32_t*>(tab_b)[threadIdx.x] = reinterpret_cast<const uint32_t*>(kHeadPairTable.b)[threadIdx.x];
+    }
     HeadLds& S = lds[wave];
     const int R1 = g.R < kHeadT ? g.R : kHeadT;
-    head_load_lists(g, S, q, lane, R1);
+    if (q < g.nq) head_load_lists(g, S, q, lane, R1);
+    __syncthreads();
+    if (q >= g.nq) return;
     // levels whose tuple count does not grow are skipped (T smaller than 64 or 128)
     unsigned long long carry = ~0ull;
-    if (head_level<1>(g, S, q, lane, R1, lv.T1[0], 0, lv.npairs[0], Tn, lv.T1[1] == lv.T1[0], carry)) return;
+    if (head_level<1>(g, S, q, lane, R1, lv.T1[0], 0, lv.npairs[0], Tn, lv.T1[1] == lv.T1[0], carry, nullptr, tab_a, tab_b)) return;
     // the second level adds the table entries between the two regions to the 64 smallest of the first
-    if (head_level<1>(g, S, q, lane, R1, lv.T1[1], lv.npairs[0], lv.npairs[1], Tn, lv.T1[2] == lv.T1[1], carry)) return;
-    head_level<2>(g, S, q, lane, R1, lv.T1[2], 0, lv.npairs[2], Tn, true, carry);
+    if (head_level<1>(g, S, q, lane, R1, lv.T1[1], lv.npairs[0], lv.npairs[1], Tn, lv.T1[2] == lv.T1[1], carry, nullptr, tab_a, tab_b))
+        return;
+    head_level<2>(g, S, q, lane, R1, lv.T1[2], 0, lv.npairs[2], Tn, true, carry, nullptr, tab_a, tab_b);
 }
 
 // ------------------------------------------------------------------------------------------------

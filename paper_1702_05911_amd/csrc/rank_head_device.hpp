@@ -20,7 +20,7 @@ constexpr int kHeadPairs = 704;                // pairs (a, b) with (a+1)(b+1) <
 // product (so the pairs for a smaller T1 are a prefix), sorted in blocks of 64 across the lanes, and
 // folded into the T1 smallest.  No workgroup barrier; LDS only holds the two lists.
 // ------------------------------------------------------------------------------------------------
-struct HeadPairTable {
+struct alignas(16) HeadPairTable {
     uint8_t a[kHeadPairs], b[kHeadPairs];
 };
 constexpr HeadPairTable make_head_pair_table() {
@@ -68,7 +68,8 @@ struct HeadLevels {
 template <int E, bool TO_LDS = false>
 __device__ __forceinline__ int head_level(const RankArgs& g, HeadLds& S, int64_t q, int lane, int R1, int T1,
                                           int e_begin, int npairs, int Tn, bool last_level, unsigned long long& carry,
-                                          uint32_t* res = nullptr) {
+                                          uint32_t* res = nullptr, const uint8_t* tab_a = kHeadPairTable.a,
+                                          const uint8_t* tab_b = kHeadPairTable.b) {
     const int T = g.T;
     const uint32_t C = (uint32_t)g.C;
     // ---- the T1 smallest keys (ordered sum bits, a, b) of the region, ascending over (register, lane) ----
@@ -80,7 +81,7 @@ __device__ __forceinline__ int head_level(const RankArgs& g, HeadLds& S, int64_t
         const int e = base + lane;
         unsigned long long cur[1] = {~0ull};
         if (e < npairs) {
-            const unsigned a = kHeadPairTable.a[e], b = kHeadPairTable.b[e];
+            const unsigned a = tab_a[e], b = tab_b[e];        // (the table in memory, or the caller's copy in LDS)
             if (a < (unsigned)R1 && b < (unsigned)R1)
                 cur[0] = ((unsigned long long)mono_key(S.A[a] + S.B[b]) << 32) | (a << 16) | b;
         }
