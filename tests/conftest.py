@@ -13,6 +13,13 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (runs the HIP library)")
 
 
+def pytest_terminal_summary(terminalreporter):
+    """How many float comparisons of the GPU parity tests passed only through the absolute floor."""
+    pu = sys.modules.get("parity_util")
+    if pu is not None and pu.STATS.compared:
+        terminalreporter.write_line("parity tolerance (1e-4 relative + floor): " + pu.STATS.summary())
+
+
 @pytest.fixture(scope="session")
 def tiny():
     """Tiny workload: vectors, queries and an oracle-built index."""

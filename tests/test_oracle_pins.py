@@ -494,3 +494,104 @@ def test_pair_lambda_index_file_roundtrip(tiny_pair, tmp_path):
     assert back.code_format == 1 and np.array_equal(back.codes, ix.codes) and np.array_equal(back.ids, ix.ids)
     tr0, tr1 = Q.query(ix, Y[0], cfg.k, cfg.w), Q.query(back, Y[0], cfg.k, cfg.w)
     assert np.array_equal(tr0.out_ids, tr1.out_ids)
+
+
+# ---- bin order for four tree parts against its definition written out (Sec. 2.3, Sec. 3.2) ---------
+def _four_part_order_by_definition(L, T):
+    """All R^4 rank tuples ordered by the recursive definition: parts (1,2) and (3,4) are ranked as
+    two-part orders (fl32 sum, r, r'); a tuple's key is (fl32(s12 + s34), pos12, pos34) with pos the
+    position of its pair in those orders.  Plain Python, no call into the oracle."""
+    R = [len(l) for l in L]
+    o12 = sorted((np.float32(L[0][a] + L[1][b]), a, b) for a in range(R[0]) for b in range(R[1]))
+    o34 = sorted((np.float32(L[2][c] + L[3][d]), c, d) for c in range(R[2]) for d in range(R[3]))
+    pos12 = {(a, b): n for n, (_, a, b) in enumerate(o12)}
+    pos34 = {(c, d): n for n, (_, c, d) in enumerate(o34)}
+    items = []
+    for a in range(R[0]):
+        for b in range(R[1]):
+            for c in range(R[2]):
+                for d in range(R[3]):
+                    s = np.float32(o12[pos12[(a, b)]][0] + o34[pos34[(c, d)]][0])
+                    items.append((s, pos12[(a, b)], pos34[(c, d)], (a, b, c, d)))
+    items.sort(key=lambda it: it[:3])
+    return [it[3] for it in items[:T]], np.array([it[0] for it in items[:T]], dtype=np.float32)
+
+
+@pytest.mark.parametrize("integer", [False, True])
+def test_bin_order_four_parts_equals_definition(rng, integer):
+    """The four lists differ in length and scale, so exchanging any two parts (or the positions
+    in the two pair lists) changes the order."""
+    for lens in ((3, 4, 5, 2), (6, 6, 6, 6), (1, 7, 2, 3)):
+        if integer:
+            L = [np.sort(rng.integers(0, 6 + 3 * p, size=n)).astype(np.float32) for p, n in enumerate(lens)]
+        else:
+            L = [np.sort(rng.random(n) * (1.0 + p)).astype(np.float32) for p, n in enumerate(lens)]
+        total = int(np.prod(lens))
+        for T in (1, 5, total // 2, total, total + 3):
+            want_t, want_k = _four_part_order_by_definition(L, T)
+            for method in ("fullsort", "pq"):
+                for trunc in (False, True):
+                    got_t, got_k = Q.bin_order(L, T, method, truncate_pairs=trunc)
+                    assert [tuple(t) for t in got_t.tolist()] == want_t, (lens, T, method, trunc)
+                    assert np.array_equal(got_k.astype(np.float32), want_k)
+
+
+def test_linear_bin_is_row_major_part_one_most_significant():
+    """Eq. 5: the multi-index (id_1, .., id_P) as one number, part 1 most significant."""
+    assert Q.linear_bin([1, 2], 10) == 12
+    assert Q.linear_bin([2, 1], 10) == 21
+    assert Q.linear_bin([3, 0, 1], 7) == (3 * 7 + 0) * 7 + 1
+    assert Q.linear_bin([5], 9) == 5
+    assert Q.linear_bin([255, 255, 255, 255], 256) == 2 ** 32 - 1        # (16*16)^4 bins fit 32 bits (Sec. 3.2)
+    assert Q.linear_bin([1023, 1023, 1023, 1023], 1024) == 2 ** 40 - 1   # beyond 32 bits: plain integers
+
+
+def test_propose_bins_uses_part_one_as_the_high_digit():
+    """A hand-made pointer array in which only bin (leaf 1, leaf 2) = 1 * k1k2 + 2 holds vectors."""
+    k1k2 = 10
+    offsets = np.zeros(101, dtype=np.int64)
+    offsets[13:] = 4                                   # slot 12 holds four vectors
+    Lid = [np.array([1, 2]), np.array([2, 1])]
+    tuples = np.array([[0, 0], [1, 1], [0, 1], [1, 0]])     # leaves (1,2), (2,1), (1,1), (2,2)
+    assert Q.propose_bins(tuples, Lid, k1k2, 100, offsets).tolist() == [12]
+    # hashed to 7 slots: 12 % 7 = 5, 21 % 7 = 0, 11 % 7 = 4, 22 % 7 = 1
+    off7 = np.array([0, 1, 1, 1, 1, 3, 6, 6])          # slots 0, 4, 5 hold vectors
+    assert Q.propose_bins(tuples, Lid, k1k2, 7, off7).tolist() == [5, 0, 4]
+    # a slot is proposed once: 12 and 19 collide modulo 7
+    Lid2 = [np.array([1, 1]), np.array([2, 9])]
+    assert Q.propose_bins(np.array([[0, 0], [1, 1]]), Lid2, k1k2, 7, off7).tolist() == [5]
+
+
+def test_decision_margins_on_a_hand_made_trace():
+    """Every gap computed by hand: relative gap = (hi - lo) / max(|lo|, |hi|)."""
+    ix = Q.PQTIndex(D=4, P=2, k1=3, k2=2, M=2, N=9, H=36, T=3, C=5, C1=None, C2=None, tbl_i=None, tbl_j=None,
+                    tbl_lam=None, cc=None, offsets=None, ids=None, codes=None)
+    off = np.zeros(37, dtype=np.int64)
+    # bins: leaves (0,0) -> slot 0 holds 2 vectors, (0,1) -> slot 1 holds 4, (1,0) -> slot 6 holds 3
+    off[1:] = 2
+    off[2:] += 4
+    off[7:] += 3
+    ix.offsets = off
+    tr = Q.QueryTrace()
+    tr.d1 = np.array([[4.0, 1.0, 2.0], [8.0, 10.0, 9.0]])            # w = 2: gaps (4-2)/4 and (10-9)/10
+    tr.Ld = np.array([[1.0, 2.0, 5.0, 7.0], [0.5, 1.0, 4.0, 6.0]])
+    tr.Lid = np.array([[0, 1, 2, 3], [0, 1, 2, 3]])
+    # order by sum: (0,0)=1.5, (0,1)=2.0, (1,0)=2.5, (1,1)=3.0, ...
+    tr.tuples = np.array([[0, 0], [0, 1], [1, 0]])
+    tr.keys = np.array([1.5, 2.0, 2.5])
+    tr.slots = np.array([0, 1, 6])
+    tr.cand_ids = np.arange(5)
+    tr.scores = np.array([3.0, 1.0, 1.0, 2.0, 8.0])                 # sorted: 1, 1, 2, 3, 8
+    m = Q.decision_margins(ix, tr, k=3, w=2, T=3, C=5)
+    assert m["select"] == pytest.approx(min((4.0 - 2.0) / 4.0, (10.0 - 9.0) / 10.0))
+    assert m["tuples"] == pytest.approx((3.0 - 2.5) / 3.0)           # third key 2.5, the first unexamined 3.0
+    # runs 2 + 4 + 3 = 9 > C = 5: the cut falls into the second run (slot 1, key 2.0);
+    # its neighbours in the order have keys 1.5 and 2.5
+    assert m["budget"] == pytest.approx(min((2.0 - 1.5) / 2.0, (2.5 - 2.0) / 2.5))
+    # first k + 1 = 4 scores 1, 1, 2, 3: equal scores are skipped, gaps (2-1)/2 and (3-2)/3
+    assert m["topk"] == pytest.approx(1.0 / 3.0)
+    assert m["min"] == pytest.approx(0.1)
+    # nothing to decide: w = k1, T covers every tuple, budget not reached, one candidate
+    tr.scores, tr.cand_ids = np.array([2.0]), np.array([0])
+    m = Q.decision_margins(ix, tr, k=3, w=3, T=16, C=50)
+    assert m["select"] == np.inf and m["tuples"] == np.inf and m["budget"] == np.inf and m["topk"] == np.inf
