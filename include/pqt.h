@@ -23,6 +23,7 @@
 #ifndef PQT_H
 #define PQT_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -212,14 +213,38 @@ int pqt_set_bin_order(pqt_index* index, int order);
  *             (i.e. the exact squared distance to the line-quantised vector); tail +inf
  *   hip_stream  a hipStream_t (NULL = the default stream).  The call only enqueues work:
  *             it returns before the results exist and never synchronises the device,
- *             except when the library's workspace has to grow for a larger nq than seen
- *             before (one hipMalloc).  Same inputs give the same bytes.
+ *             except when the library's workspace has to grow (a larger nq, w * k2 or T than
+ *             any call before: it is freed and allocated anew, which waits for the device).
+ *             Same inputs give the same bytes.
  * Calls on one index must not overlap (they share the workspace).
  * Errors: PQT_EINVAL (null pointers with nq > 0, nq < 0, k or w out of range),
  * PQT_EUNSUPPORTED (LDS budget exceeded for this D/M/k1/R/T/C), PQT_ENOMEM, PQT_EHIP.
  */
 int pqt_query_batch(pqt_index* index, const float* queries, int64_t nq, int k, int w,
                     int64_t* out_ids, float* out_dists, void* hip_stream);
+
+/*
+ * pqt_query_batch_noalloc -- pqt_query_batch for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same results (bit for bit) as pqt_query_batch.  The per-batch workspace (level-1 distances, the
+ * sorted level-2 lists, run lists and counters of every query) is not the index's grown-on-demand
+ * allocation but a static array of pqt_noalloc_workspace_bytes() = 32 MiB of device memory that
+ * every GPU the library runs on holds until the process ends; the call allocates and frees nothing
+ * (no hipMalloc, hipFree, event or stream creation) and records no stage times.
+ *   - The workspace of one call is nq * (4 M k1 + 8 P w k2 + 8 T + 12) bytes plus rounding of each
+ *     of its seven arrays to 256 bytes; a call that needs more than the array holds returns
+ *     PQT_EINVAL and does nothing: send fewer queries per call (about 3,400 at M k1 = 128,
+ *     P w k2 = 128, T = 1024).
+ *   - With PQT_ORDER_STATIC_SLOPES the order tables for the current w * k2 and T must exist already
+ *     (any earlier pqt_query_batch with this w builds them), else PQT_EUNSUPPORTED.
+ *   - All calls on one GPU share the array, whichever index they use: calls that overlap in time
+ *     on one GPU (different streams or threads) race.  Nothing in it has to survive between calls;
+ *     what must start at zero is cleared by the first kernel of each call.
+ * Other errors as for pqt_query_batch.
+ */
+int pqt_query_batch_noalloc(pqt_index* index, const float* queries, int64_t nq, int k, int w,
+                            int64_t* out_ids, float* out_dists, void* hip_stream);
+size_t pqt_noalloc_workspace_bytes(void);
 
 /*
  * Exact re-ranking of a short list -- step (3) of the pipelines named in Sec. 1 of the paper
@@ -301,8 +326,9 @@ int pqt_query_batch_debug(pqt_index* index, const float* queries, int64_t nq, in
  * re-rank + top-k (with the full bin ranking of the queries the head pass left over), [3] exact
  * re-ranking of the short list (pqt_query_batch_exact only, else 0).
  * pqt_stage_times synchronises on the recorded events, adds up the elapsed milliseconds of
- * all calls since the last pqt_stage_times (at most 256 are kept) into ms[4], stores the
- * number of calls in *calls, and resets.  PQT_EINVAL on null arguments.
+ * all profiled calls since the last pqt_stage_times into ms[4], stores their number in *calls, and
+ * resets.  At most 4096 calls are profiled between two reads; later ones run unprofiled, and a
+ * call that fails is not counted.  PQT_EINVAL on null arguments.
  */
 int pqt_set_profiling(pqt_index* index, int enabled);
 int pqt_stage_times(pqt_index* index, float ms[4], int* calls);

@@ -18,7 +18,9 @@ PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -
 EXPORTS = (
     "pqt_index_load", "pqt_index_from_arrays", "pqt_index_save", "pqt_index_export", "pqt_builder_create", "pqt_builder_add",
     "pqt_builder_finish", "pqt_builder_free", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
-    "pqt_query_batch_debug", "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_brute_force", "pqt_measure_peaks", "pqt_set_profiling", "pqt_stage_times", "pqt_last_error",
+    "pqt_query_batch_debug", "pqt_query_batch_noalloc", "pqt_noalloc_workspace_bytes", "pqt_set_bin_order",
+    "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_brute_force", "pqt_measure_peaks", "pqt_set_profiling",
+    "pqt_stage_times", "pqt_last_error",
 )
 
 
@@ -91,6 +93,10 @@ def load_library(path=LIB_PATH):
     lib.pqt_query_batch.restype = ci
     lib.pqt_query_batch_debug.argtypes = [vp, vp, i64, ci, ci, vp, vp, vp, ctypes.POINTER(_Taps)]
     lib.pqt_query_batch_debug.restype = ci
+    lib.pqt_query_batch_noalloc.argtypes = [vp, vp, i64, ci, ci, vp, vp, vp]
+    lib.pqt_query_batch_noalloc.restype = ci
+    lib.pqt_noalloc_workspace_bytes.argtypes = []
+    lib.pqt_noalloc_workspace_bytes.restype = ctypes.c_size_t
     lib.pqt_index_set_vectors.argtypes = [vp, vp, ci, ci]
     lib.pqt_index_set_vectors.restype = ci
     lib.pqt_query_batch_exact.argtypes = [vp, vp, i64, ci, ci, ci, vp, vp, vp]
@@ -171,7 +177,9 @@ class Index:
             _lib.pqt_index_free(self._h)
             self._h = ctypes.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        if _lib is not None:               # module globals are cleared while the interpreter shuts down
+            self.close()
 
     def __enter__(self):
         return self
@@ -221,6 +229,19 @@ class Index:
         out_dists = dists_ if out_dists is None else out_dists
         _check(_lib.pqt_query_batch(self._h, queries.data_ptr(), nq, int(k), int(w), out_ids.data_ptr(),
                                     out_dists.data_ptr(), _stream_handle(stream)))
+        return out_ids, out_dists
+
+    def query_batch_noalloc(self, queries, k, w, out_ids, out_dists, stream=None):
+        """pqt_query_batch_noalloc: the caller brings the result tensors, nothing is allocated."""
+        if queries.dim() != 2 or queries.shape[1] != self._D or queries.dtype != torch.float32 or \
+                not queries.is_cuda or not queries.is_contiguous():
+            raise ValueError(f"queries must be a contiguous (nq, {self._D}) float32 CUDA tensor")
+        nq = queries.shape[0]
+        for t, dt in ((out_ids, torch.int64), (out_dists, torch.float32)):
+            if t.dtype != dt or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (nq, int(k)):
+                raise ValueError(f"results go to contiguous ({nq}, {k}) int64 / float32 CUDA tensors")
+        _check(_lib.pqt_query_batch_noalloc(self._h, queries.data_ptr(), nq, int(k), int(w), out_ids.data_ptr(),
+                                            out_dists.data_ptr(), _stream_handle(stream)))
         return out_ids, out_dists
 
     def query_batch_debug(self, queries, k, w, taps=_TAP_FIELDS, stream=None):
@@ -347,7 +368,9 @@ class Builder:
             _lib.pqt_builder_free(self._h)
             self._h = ctypes.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        if _lib is not None:
+            self.close()
 
 
 def pqt_measure_peaks(device=0):
@@ -412,6 +435,14 @@ def pqt_set_bin_order(index, order):
 
 def pqt_query_batch(index, queries, k, w, out_ids=None, out_dists=None, stream=None):
     return index.query_batch(queries, k, w, out_ids, out_dists, stream)
+
+
+def pqt_query_batch_noalloc(index, queries, k, w, out_ids, out_dists, stream=None):
+    return index.query_batch_noalloc(queries, k, w, out_ids, out_dists, stream)
+
+
+def pqt_noalloc_workspace_bytes():
+    return int(_lib.pqt_noalloc_workspace_bytes())
 
 
 def pqt_query_batch_debug(index, queries, k, w, taps=_TAP_FIELDS, stream=None):

@@ -37,11 +37,29 @@ using pqt_host::fail;
 
 namespace {
 
-constexpr int kMaxProfiledCalls = 256;
+constexpr int kMaxProfiledCalls = 4096;
 
-// Dynamic LDS a kernel may ask for: 160 KB once the runtime has accepted that ceiling for all
-// three kernels, else the 64 KB every HIP device grants without asking.
-size_t g_lds_limit = 64 * 1024;
+// The entry point that allocates nothing takes its per-batch workspace from this array instead of
+// hipMalloc.  Every GPU the library runs on holds its own copy at its own address (looked up once
+// per device); host code only ever uses that address, never the array's name.
+constexpr size_t kScratchBytes = 32u << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// address of `scratch` on the current device (which must be `device`); null on failure
+unsigned char* scratch_on_device(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[device] = static_cast<unsigned char*>(ptr);
+    }
+    return g_scratch_ptr[device];
+}
 
 }  // namespace
 
@@ -91,18 +109,13 @@ int upload(Tp** dev, const void* src, size_t bytes, hipMemcpyKind kind, uint64_t
 
 // Workgroup size of the re-rank kernel and candidates per thread: the fewest threads that hold the
 // candidate budget (a thread keeps the keys of its candidates in registers; fewer threads per query
-// leave room for more queries per compute unit).  PQT_RERANK_THREADS asks for more threads.
+// leave room for more queries per compute unit).
 int rerank_threads(const pqt_index* ix, int* keys_per_thread = nullptr, int64_t nq = -1) {
-    static const int forced = [] {
-        const char* e = getenv("PQT_RERANK_THREADS");
-        const int v = e ? atoi(e) : 0;
-        return (v == 256 || v == 512 || v == 1024) ? v : 0;
-    }();
     int t, kpt;
     pqt::rerank_shape((int)ix->C, (int)ix->M, (int)ix->code_format, &t, &kpt);
     if (keys_per_thread) *keys_per_thread = kpt;
     if (nq >= 0 && nq <= 1024) t = 1024;      // a small batch leaves the chip idle: more threads per query, answer sooner
-    return forced > t ? forced : t;
+    return t;
 }
 
 // Runs of a query the re-rank workgroup keeps in LDS: twice what the candidate budget needs at the
@@ -125,7 +138,7 @@ bool can_fuse_ranking(const pqt_index* ix, int k, int w, int64_t nq) {
     const pqt::RankOffsets ro = pqt::rank_offsets(ix->P, R, ix->T, ix->hashed);
     if (ro.Tcap > pqt::rerank_fused_tuples_per_thread() * threads) return false;
     return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total, (int)ix->code_format,
-                                 rerank_runs_in_lds(ix)) <= g_lds_limit;
+                                 rerank_runs_in_lds(ix)) <= ix->lds_limit;
 }
 
 int check_query_limits(const pqt_index* ix, int k, int w, int64_t nq, size_t* lds_out) {
@@ -135,10 +148,10 @@ int check_query_limits(const pqt_index* ix, int k, int w, int64_t nq, size_t* ld
     const int threads = rerank_threads(ix, nullptr, nq);
     const size_t l3 = pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, 0, (int)ix->code_format,
                                             rerank_runs_in_lds(ix));
-    if (l1 > g_lds_limit || l2 > g_lds_limit || l3 > g_lds_limit)
+    if (l1 > ix->lds_limit || l2 > ix->lds_limit || l3 > ix->lds_limit)
         return fail(PQT_EUNSUPPORTED,
                     "LDS budget exceeded (traverse %zu, rank %zu, rerank %zu bytes of %zu) for D=%u M=%u k1=%u R=%d T=%u C=%u",
-                    l1, l2, l3, g_lds_limit, ix->D, ix->M, ix->k1, R, ix->T, ix->C);
+                    l1, l2, l3, ix->lds_limit, ix->D, ix->M, ix->k1, R, ix->T, ix->C);
     if (lds_out) { lds_out[0] = l1; lds_out[1] = l2; lds_out[2] = l3; }
     return PQT_OK;
 }
@@ -147,10 +160,12 @@ int check_query_limits(const pqt_index* ix, int k, int w, int64_t nq, size_t* ld
 
 int pqt_host::ensure_workspace(pqt_index* ix, int64_t nq, int R) {
     if (nq <= ix->ws_nq && R <= ix->ws_R && (int)ix->T <= ix->ws_T) return PQT_OK;
-    ix->free_workspace();
+    // the new workspace covers the largest batch, list length and tuple count seen so far
     const int64_t n = nq > ix->ws_nq ? nq : ix->ws_nq;
     const int r = R > ix->ws_R ? R : ix->ws_R;
     const int t = (int)ix->T > ix->ws_T ? (int)ix->T : ix->ws_T;
+    ix->free_workspace();
+    ix->ws_R = ix->ws_T = 0;
     const size_t ba = sizeof(float) * (size_t)n * ix->M * ix->k1;
     const size_t bl = sizeof(float) * (size_t)n * ix->P * r;
     const size_t br = sizeof(uint2) * (size_t)n * t;
@@ -297,21 +312,24 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
             table[e].kc = (float)((lam * lam - lam) * (double)h.cc[(m * h.k1 + h.tbl_i[e]) * h.k1 + h.tbl_j[e]]);
         }
 
-    if (pqt::configure_traverse(pqt::kMaxLds) == hipSuccess && pqt::configure_rank(pqt::kMaxLds) == hipSuccess &&
-        pqt::configure_rerank(pqt::kMaxLds) == hipSuccess) {
-        g_lds_limit = pqt::kMaxLds;
-    } else {
+    // Dynamic LDS a kernel may ask for: 160 KB once the runtime has accepted that ceiling for all
+    // three kernels, else the 64 KB every HIP device grants without asking.
+    size_t lds_limit = pqt::kMaxLds;
+    if (pqt::configure_traverse(lds_limit) != hipSuccess || pqt::configure_rank(lds_limit) != hipSuccess ||
+        pqt::configure_rerank(lds_limit) != hipSuccess) {
         (void)hipGetLastError();
-        g_lds_limit = 64 * 1024;
-        HIP_TRY(pqt::configure_traverse(g_lds_limit));
-        HIP_TRY(pqt::configure_rank(g_lds_limit));
-        HIP_TRY(pqt::configure_rerank(g_lds_limit));
+        lds_limit = 64 * 1024;
+        HIP_TRY(pqt::configure_traverse(lds_limit));
+        HIP_TRY(pqt::configure_rank(lds_limit));
+        HIP_TRY(pqt::configure_rerank(lds_limit));
     }
+    (void)scratch_on_device(device);       // looked up now, so that the entry point that must not allocate finds it
 
     pqt_index* ix = new (std::nothrow) pqt_index();
     if (!ix) return fail(PQT_ENOMEM, "host allocation failed");
     ix->D = h.D; ix->P = h.P; ix->k1 = h.k1; ix->k2 = h.k2; ix->M = h.M; ix->T = h.T; ix->C = h.C;
     ix->N = h.N; ix->H = h.H; ix->device = device;
+    ix->lds_limit = lds_limit;
     ix->hashed = (long double)h.H != K;
     ix->code_format = h.code_format;
     ix->nonempty_slots = nonempty;
@@ -510,8 +528,45 @@ int pqt_set_budget(pqt_index* ix, uint32_t T_bins, uint32_t C_candidates) {
     return PQT_OK;
 }
 
-int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int64_t* out_ids,
-                          float* out_dists, void* hip_stream, const pqt_debug_taps* taps) {
+}  // extern "C"
+
+namespace {
+
+// The device buffers one batch works in (see pqt_index for their shapes).
+struct QueryWorkspace {
+    float* a;
+    float* Ld;
+    uint32_t* Lid;
+    uint2* runs;
+    uint2* meta;
+    uint32_t* counters;
+    uint32_t* order;
+};
+
+// Carves the workspace of nq queries out of `base` (256-byte aligned pieces); returns the bytes used.
+size_t carve_workspace(const pqt_index* ix, int64_t nq, int R, unsigned char* base, QueryWorkspace* ws) {
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        unsigned char* p = base ? base + o : nullptr;
+        o += (bytes + kAlign - 1) / kAlign * kAlign;
+        return p;
+    };
+    QueryWorkspace v;
+    v.a = reinterpret_cast<float*>(take(sizeof(float) * (size_t)nq * ix->M * ix->k1));
+    v.Ld = reinterpret_cast<float*>(take(sizeof(float) * (size_t)nq * ix->P * R));
+    v.Lid = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)nq * ix->P * R));
+    v.runs = reinterpret_cast<uint2*>(take(sizeof(uint2) * (size_t)nq * ix->T));
+    v.meta = reinterpret_cast<uint2*>(take(sizeof(uint2) * (size_t)nq));
+    v.counters = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * 2));
+    v.order = reinterpret_cast<uint32_t*>(take(sizeof(uint32_t) * (size_t)nq));
+    if (ws) *ws = v;
+    return o;
+}
+
+// The whole query path.  no_alloc: the workspace is the static scratch array and nothing may be
+// allocated (no workspace growth, no events, no upload of fixed-order tables).
+int run_query(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int64_t* out_ids, float* out_dists,
+                     void* hip_stream, const pqt_debug_taps* taps, bool no_alloc) {
     if (!ix) return fail(PQT_EINVAL, "pqt_query_batch: null index");
     if (nq < 0) return fail(PQT_EINVAL, "pqt_query_batch: nq=%lld < 0", (long long)nq);
     if (k < 1 || k > PQT_MAX_K || (uint32_t)k > ix->C)
@@ -519,6 +574,10 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     if (w < 1 || (uint32_t)w > ix->k1) return fail(PQT_EINVAL, "pqt_query_batch: w=%d outside 1..k1=%u", w, ix->k1);
     if ((int64_t)w * ix->k2 > PQT_MAX_R)
         return fail(PQT_EINVAL, "pqt_query_batch: w*k2=%lld exceeds %d", (long long)w * ix->k2, PQT_MAX_R);
+    static const pqt_debug_taps no_taps = {};
+    const pqt_debug_taps& tp = taps ? *taps : no_taps;
+    if (tp.lut && ix->code_format == PQT_CODES_PAIR_LAMBDA)
+        return fail(PQT_EINVAL, "pqt_query_batch_debug: the lut tap is the table of the one-byte code format");
     if (nq == 0) return PQT_OK;
     if (!queries || !out_ids || !out_dists) return fail(PQT_EINVAL, "pqt_query_batch: null buffer");
     int rc = check_query_limits(ix, k, w, nq, nullptr);
@@ -527,28 +586,55 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     DeviceGuard guard(ix->device);
     if (!guard.ok) return fail(PQT_EHIP, "cannot select GPU %d", ix->device);
     const int R = w * (int)ix->k2;
-    if ((rc = pqt_host::ensure_workspace(ix, nq, R))) return rc;
+    const bool fixed_order = ix->bin_order == PQT_ORDER_STATIC_SLOPES;
+    const bool tables_stale = fixed_order && (ix->static_R != R || ix->static_T != (int)ix->T);
+    QueryWorkspace ws;
+    if (no_alloc) {
+        unsigned char* base = scratch_on_device(ix->device);
+        if (!base) return fail(PQT_EHIP, "pqt_query_batch_noalloc: the scratch array of GPU %d cannot be located", ix->device);
+        const size_t need = carve_workspace(ix, nq, R, nullptr, nullptr);
+        if (need > kScratchBytes)
+            return fail(PQT_EINVAL,
+                        "pqt_query_batch_noalloc: nq=%lld needs %zu bytes of workspace (w*k2=%d, T=%u), the static scratch "
+                        "array holds %zu: send fewer queries per call",
+                        (long long)nq, need, R, ix->T, kScratchBytes);
+        if (tables_stale)
+            return fail(PQT_EUNSUPPORTED,
+                        "pqt_query_batch_noalloc: the fixed bin order needs new tables for w*k2=%d, T=%u: one pqt_query_batch "
+                        "call with this w builds them", R, ix->T);
+        carve_workspace(ix, nq, R, base, &ws);
+    } else {
+        if ((rc = pqt_host::ensure_workspace(ix, nq, R))) return rc;
+        ws = QueryWorkspace{ix->ws_a, ix->ws_Ld, ix->ws_Lid, ix->ws_runs, ix->ws_meta, ix->ws_counters, ix->ws_order};
+    }
     hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
-    static const pqt_debug_taps no_taps = {};
-    const pqt_debug_taps& tp = taps ? *taps : no_taps;
+
+    std::vector<uint32_t> static_host;                  // new fixed-order tables, built before anything is enqueued
+    if (tables_stale) {
+        try {
+            ix->static_Tn = pqt::make_static_order(R, (int)ix->T, static_host, ix->static_thr);
+        } catch (const std::bad_alloc&) {
+            return fail(PQT_ENOMEM, "host allocation failed");
+        }
+    }
 
     hipEvent_t* ev = nullptr;
     ix->last_events = nullptr;
-    if (ix->profiling && ix->prof_calls < kMaxProfiledCalls) {
+    if (!no_alloc && ix->profiling && ix->prof_calls < kMaxProfiledCalls) {
         while ((int)ix->events.size() < 5 * (ix->prof_calls + 1)) {
             hipEvent_t e;
             HIP_TRY(hipEventCreate(&e));
             ix->events.push_back(e);
         }
         ev = &ix->events[5 * ix->prof_calls];
-        ix->prof_calls++;
     }
+    // from here on every failure leaves the events of this call unused: the call is counted at the end
 
     pqt::TraverseArgs ta;
     ta.queries = queries; ta.nq = nq;
     ta.D = ix->D; ta.P = ix->P; ta.k1 = ix->k1; ta.k2 = ix->k2; ta.M = ix->M; ta.w = w;
     ta.C1 = ix->C1; ta.c1n = ix->c1n; ta.C2 = ix->C2; ta.C2t = ix->C2t;
-    ta.a = ix->ws_a; ta.L_d = ix->ws_Ld; ta.L_id = ix->ws_Lid; ta.sel_tap = tp.sel; ta.counters = ix->ws_counters;
+    ta.a = ws.a; ta.L_d = ws.Ld; ta.L_id = ws.Lid; ta.sel_tap = tp.sel; ta.counters = ws.counters;
     if (ev) HIP_TRY(hipEventRecord(ev[0], stream));
     HIP_TRY(pqt::launch_traverse(ta, stream));
     if (ev) HIP_TRY(hipEventRecord(ev[1], stream));
@@ -556,30 +642,21 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     pqt::RankArgs ra;
     ra.nq = nq; ra.P = ix->P; ra.R = R; ra.T = ix->T; ra.C = ix->C;
     ra.k1k2 = ix->k1 * ix->k2; ra.H = ix->H; ra.hashed = ix->hashed ? 1 : 0;
-    ra.offsets = ix->offsets; ra.L_d = ix->ws_Ld; ra.L_id = ix->ws_Lid;
-    ra.runs = ix->ws_runs; ra.meta = ix->ws_meta; ra.counters = ix->ws_counters; ra.order = ix->ws_order;
+    ra.offsets = ix->offsets; ra.L_d = ws.Ld; ra.L_id = ws.Lid;
+    ra.runs = ws.runs; ra.meta = ws.meta; ra.counters = ws.counters; ra.order = ws.order;
     ra.n_tuples = tp.n_tuples; ra.tuples = tp.tuples; ra.tuple_keys = tp.tuple_keys; ra.slots = tp.slots;
-    if (tp.lut && ix->code_format == PQT_CODES_PAIR_LAMBDA)
-        return fail(PQT_EINVAL, "pqt_query_batch_debug: the lut tap is the table of the one-byte code format");
     const bool rerank_taps = tp.n_cand || tp.cand_ids || tp.scores || tp.lut || tp.n_slots;
-    const bool fixed_order = ix->bin_order == PQT_ORDER_STATIC_SLOPES;
     const bool head = !fixed_order && pqt::rank_has_head(ra);
     // the few queries the head pass cannot finish are ranked in full by their re-rank workgroup
     const bool fuse = head && !rerank_taps && can_fuse_ranking(ix, k, w, nq);
     if (fixed_order) {
-        if (ix->static_R != R || ix->static_T != (int)ix->T) {          // tables for this list length and T
-            std::vector<uint32_t> table;
-            try {
-                ix->static_Tn = pqt::make_static_order(R, (int)ix->T, table, ix->static_thr);
-            } catch (const std::bad_alloc&) {
-                return fail(PQT_ENOMEM, "host allocation failed");
-            }
+        if (tables_stale) {                                             // tables for this list length and T
             HIP_TRY(hipStreamSynchronize(stream));                      // an earlier batch may still read the old tables
             (void)hipFree(ix->static_table);
             ix->static_table = nullptr;
             ix->static_R = ix->static_T = 0;
-            HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->static_table), table.size() * sizeof(uint32_t)));
-            HIP_TRY(hipMemcpy(ix->static_table, table.data(), table.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
+            HIP_TRY(hipMalloc(reinterpret_cast<void**>(&ix->static_table), static_host.size() * sizeof(uint32_t)));
+            HIP_TRY(hipMemcpy(ix->static_table, static_host.data(), static_host.size() * sizeof(uint32_t), hipMemcpyHostToDevice));
             ix->static_R = R;
             ix->static_T = (int)ix->T;
         }
@@ -598,9 +675,9 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
     ca.threads = rerank_threads(ix, &ca.keys_per_thread, nq);
     ca.code_format = (int)ix->code_format;
     ca.runs_in_lds = rerank_runs_in_lds(ix);
-    ca.a = ix->ws_a; ca.table = ix->table; ca.runs = ix->ws_runs; ca.meta = ix->ws_meta;
+    ca.a = ws.a; ca.table = ix->table; ca.runs = ws.runs; ca.meta = ws.meta;
     ca.ids = ix->ids; ca.codes = ix->codes; ca.out_ids = out_ids; ca.out_dists = out_dists;
-    ca.todo = ix->ws_order; ca.todo_count = ix->ws_counters;
+    ca.todo = ws.order; ca.todo_count = ws.counters;
     ca.early = fuse ? (int)(nq < 1024 ? nq : 1024) : 0;   // unfinished queries first: they take longest
     ca.n_cand = tp.n_cand; ca.cand_ids = tp.cand_ids; ca.scores = tp.scores; ca.lut = tp.lut;
     HIP_TRY(pqt::launch_rerank(ca, fuse ? &ra : nullptr, stream));
@@ -608,22 +685,39 @@ int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k
         HIP_TRY(hipEventRecord(ev[3], stream));
         HIP_TRY(hipEventRecord(ev[4], stream));     // moved behind the exact re-rank when that runs
         ix->last_events = ev;
+        ix->prof_calls++;                           // all five events of this call are recorded
     }
 
     // taps that are plain copies of workspace arrays
     if (tp.a)
-        HIP_TRY(hipMemcpyAsync(tp.a, ix->ws_a, sizeof(float) * (size_t)nq * ix->M * ix->k1, hipMemcpyDeviceToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(tp.a, ws.a, sizeof(float) * (size_t)nq * ix->M * ix->k1, hipMemcpyDeviceToDevice, stream));
     if (tp.L_d)
-        HIP_TRY(hipMemcpyAsync(tp.L_d, ix->ws_Ld, sizeof(float) * (size_t)nq * ix->P * R, hipMemcpyDeviceToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(tp.L_d, ws.Ld, sizeof(float) * (size_t)nq * ix->P * R, hipMemcpyDeviceToDevice, stream));
     if (tp.L_id)
-        HIP_TRY(hipMemcpyAsync(tp.L_id, ix->ws_Lid, sizeof(uint32_t) * (size_t)nq * ix->P * R, hipMemcpyDeviceToDevice, stream));
+        HIP_TRY(hipMemcpyAsync(tp.L_id, ws.Lid, sizeof(uint32_t) * (size_t)nq * ix->P * R, hipMemcpyDeviceToDevice, stream));
     if (tp.n_slots) {
         // number of proposed slots = meta.x; strided copy of the first word of every meta pair
-        HIP_TRY(hipMemcpy2DAsync(tp.n_slots, sizeof(uint32_t), ix->ws_meta, sizeof(uint2), sizeof(uint32_t), (size_t)nq,
+        HIP_TRY(hipMemcpy2DAsync(tp.n_slots, sizeof(uint32_t), ws.meta, sizeof(uint2), sizeof(uint32_t), (size_t)nq,
                                  hipMemcpyDeviceToDevice, stream));
     }
     return PQT_OK;
 }
+
+}  // namespace
+
+extern "C" {
+
+int pqt_query_batch_debug(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int64_t* out_ids,
+                          float* out_dists, void* hip_stream, const pqt_debug_taps* taps) {
+    return run_query(ix, queries, nq, k, w, out_ids, out_dists, hip_stream, taps, false);
+}
+
+int pqt_query_batch_noalloc(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int64_t* out_ids,
+                            float* out_dists, void* hip_stream) {
+    return run_query(ix, queries, nq, k, w, out_ids, out_dists, hip_stream, nullptr, true);
+}
+
+size_t pqt_noalloc_workspace_bytes(void) { return kScratchBytes; }
 
 int pqt_set_bin_order(pqt_index* ix, int order) {
     if (!ix) return fail(PQT_EINVAL, "pqt_set_bin_order: null index");
@@ -637,7 +731,7 @@ int pqt_set_bin_order(pqt_index* ix, int order) {
 
 int pqt_query_batch(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int64_t* out_ids,
                     float* out_dists, void* hip_stream) {
-    return pqt_query_batch_debug(ix, queries, nq, k, w, out_ids, out_dists, hip_stream, nullptr);
+    return run_query(ix, queries, nq, k, w, out_ids, out_dists, hip_stream, nullptr, false);
 }
 
 int pqt_index_set_vectors(pqt_index* ix, const void* vectors, int elem_bytes, int location) {
@@ -756,7 +850,10 @@ int pqt_stage_times(pqt_index* ix, float ms[4], int* calls) {
     if (!ix || !ms || !calls) return fail(PQT_EINVAL, "pqt_stage_times: null argument");
     DeviceGuard guard(ix->device);
     ms[0] = ms[1] = ms[2] = ms[3] = 0.0f;
-    for (int c = 0; c < ix->prof_calls; ++c) {
+    const int n = ix->prof_calls;
+    ix->prof_calls = 0;                              // also when reading an event fails below
+    *calls = 0;
+    for (int c = 0; c < n; ++c) {
         hipEvent_t* ev = &ix->events[5 * c];
         HIP_TRY(hipEventSynchronize(ev[4]));
         for (int s = 0; s < 4; ++s) {
@@ -765,8 +862,7 @@ int pqt_stage_times(pqt_index* ix, float ms[4], int* calls) {
             ms[s] += t;
         }
     }
-    *calls = ix->prof_calls;
-    ix->prof_calls = 0;
+    *calls = n;
     return PQT_OK;
 }
 

@@ -42,6 +42,7 @@ struct pqt_index {
     uint32_t D = 0, P = 0, k1 = 0, k2 = 0, M = 0, T = 0, C = 0;
     uint64_t N = 0, H = 0;
     int device = 0;
+    size_t lds_limit = 64 * 1024;      // dynamic LDS the query kernels may ask for on this device
     bool hashed = false;
     uint64_t nonempty_slots = 0;       // slots that hold at least one vector
     uint32_t code_format = 0;          // PQT_CODES_TABLE or PQT_CODES_PAIR_LAMBDA
