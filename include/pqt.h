@@ -121,11 +121,44 @@ typedef struct pqt_index_arrays {
 int pqt_index_from_arrays(const pqt_index_arrays* arrays, int location, int device, pqt_index** out);
 
 /*
+ * pqt_train -- everything that is learned from a sample (Sec. 3.1 "Training the codebook", Sec. 3.3
+ * "Offline computation"), on GPU `device`:
+ *   C1   level-1 product quantiser: per tree part, k1 centroids by `iters` Lloyd iterations (Sec. 2.1)
+ *        on the part's slice of the n training vectors.  Start: k1 vectors at evenly spaced places of
+ *        the sample; ties in the assignment go to the smaller centroid number; an empty cell is
+ *        re-seeded with the vector farthest from its centroid.
+ *   C2   level-2 quantisers: inside each level-1 cell, k2 centroids trained the same way on the
+ *        sub-vectors assigned to the cell (the sub-vectors themselves, not residuals).  A cell with
+ *        at most k2 members keeps them as centroids, the remaining centroids repeat their mean (the
+ *        cell's own centroid when it is empty).
+ *   cc   ||[c_s]_m - [c_t]_m||^2 for every re-rank sub-part m and pair of level-1 centroids (Sec. 3.3).
+ *   tbl_i, tbl_j, tbl_lambda   the 256 line code points of every sub-part (PQT_CODES_TABLE): each of
+ *        the first n_table training sub-vectors votes for the line through two level-1 centroids
+ *        that it is nearest to (projection error from its own level-1 distances, fp32); lines get
+ *        code points in proportion to their votes (largest-remainder rounding), placed at the
+ *        (t + 1/2) / count quantiles of the projection parameters seen on the line; entries ordered
+ *        by (i, j, lambda).  n_table = 0 (or k1 = 1) leaves the table at zeros and the three pointers
+ *        may be NULL ((pair, lambda) codes need no table).
+ * vectors: device, n x D row-major fp32 (unchanged).  The six outputs are HOST buffers of the shapes
+ * listed for pqt_index_from_arrays, owned by the caller.  Synchronous: returns when they are filled.
+ * The same inputs give the same bytes.  Errors: PQT_EINVAL (null, n = 0, n_table > n, inconsistent
+ * sizes), PQT_EUNSUPPORTED (sizes beyond the kernel limits), PQT_ENOMEM, PQT_EHIP.
+ */
+typedef struct pqt_train_params {
+    uint32_t D, P, k1, k2, M;
+    uint32_t iters;      /* Lloyd iterations per quantiser                       */
+    uint64_t n;          /* training vectors                                     */
+    uint64_t n_table;    /* the first n_table of them vote for the line table    */
+} pqt_train_params;
+int pqt_train(const pqt_train_params* params, const float* vectors, int device, float* C1, float* C2,
+              uint8_t* tbl_i, uint8_t* tbl_j, float* tbl_lambda, float* cc, void* hip_stream);
+
+/*
  * Streaming index construction on the GPU -- the per-vector part of the offline phase
  * (Sec. 3.1: every database vector is sorted into its bin by the tree; Sec. 3.3 "Offline
  * computation": its line-quantisation code; Sec. 4: ids sorted by bin, pointer array from a
- * histogram and a prefix sum).  The codebooks and the line-code table are trained by the
- * caller (a few Lloyd iterations on a sample) and passed in `params`, whose N is the number
+ * histogram and a prefix sum).  The codebooks and the line-code table (pqt_train, or the
+ * caller's own) are passed in `params`, whose N is the number
  * of vectors that will be added and whose offsets / ids / codes are ignored.
  *   pqt_builder_create  copies the codebooks to GPU `device`.
  *   pqt_builder_add     takes n more vectors (device, n x D row-major fp32; they get the next

@@ -16,7 +16,7 @@ PQT_OK = 0
 PQT_EINVAL, PQT_EIO, PQT_EFORMAT, PQT_ENOMEM, PQT_EHIP, PQT_EUNSUPPORTED = -1, -2, -3, -4, -5, -6
 
 EXPORTS = (
-    "pqt_index_load", "pqt_index_from_arrays", "pqt_index_save", "pqt_index_export", "pqt_builder_create", "pqt_builder_add",
+    "pqt_index_load", "pqt_index_from_arrays", "pqt_index_save", "pqt_index_export", "pqt_train", "pqt_builder_create", "pqt_builder_add",
     "pqt_builder_finish", "pqt_builder_free", "pqt_index_free", "pqt_index_info", "pqt_set_budget", "pqt_query_batch",
     "pqt_query_batch_debug", "pqt_query_batch_noalloc", "pqt_noalloc_workspace_bytes", "pqt_set_bin_order",
     "pqt_index_set_vectors", "pqt_query_batch_exact", "pqt_brute_force", "pqt_measure_peaks", "pqt_set_profiling",
@@ -51,6 +51,11 @@ class _Arrays(ctypes.Structure):
                [("code_format", ctypes.c_uint32)]
 
 
+class _TrainParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in ("D", "P", "k1", "k2", "M", "iters")] + \
+               [("n", ctypes.c_uint64), ("n_table", ctypes.c_uint64)]
+
+
 PQT_HOST, PQT_DEVICE = 0, 1
 PQT_CODES_TABLE, PQT_CODES_PAIR_LAMBDA = 0, 1
 PQT_ORDER_SUMMED_DISTANCE, PQT_ORDER_STATIC_SLOPES = 0, 1
@@ -73,6 +78,8 @@ def load_library(path=LIB_PATH):
     lib.pqt_index_export.restype = ci
     lib.pqt_index_save.argtypes = [vp, ctypes.c_char_p]
     lib.pqt_index_save.restype = ci
+    lib.pqt_train.argtypes = [ctypes.POINTER(_TrainParams), vp, ci, vp, vp, vp, vp, vp, vp, vp]
+    lib.pqt_train.restype = ci
     lib.pqt_builder_create.argtypes = [ctypes.POINTER(_Arrays), ci, ctypes.POINTER(vp)]
     lib.pqt_builder_create.restype = ci
     lib.pqt_builder_add.argtypes = [vp, vp, i64, vp]
@@ -399,6 +406,24 @@ def pqt_index_export(index, names=("offsets",)):
 
 def pqt_index_save(index, path):
     index.save(path)
+
+
+def pqt_train(vectors, *, P, k1, k2, M, iters=20, n_table=None, stream=None):
+    """pqt_train.  vectors: contiguous (n, D) float32 CUDA tensor.  Returns the trained arrays as NumPy
+    arrays named as the index arrays: C1, C2, tbl_i, tbl_j, tbl_lam, cc."""
+    import numpy as np
+    if vectors.dtype != torch.float32 or not vectors.is_cuda or not vectors.is_contiguous() or vectors.dim() != 2:
+        raise ValueError("vectors must be a contiguous 2-D float32 CUDA tensor")
+    n, D = vectors.shape
+    n_table = n if n_table is None else min(int(n_table), n)
+    out = dict(C1=np.zeros((P, k1, D // P), np.float32), C2=np.zeros((P, k1, k2, D // P), np.float32),
+               tbl_i=np.zeros((M, 256), np.uint8), tbl_j=np.zeros((M, 256), np.uint8),
+               tbl_lam=np.zeros((M, 256), np.float32), cc=np.zeros((M, k1, k1), np.float32))
+    tp = _TrainParams(D=int(D), P=int(P), k1=int(k1), k2=int(k2), M=int(M), iters=int(iters), n=int(n), n_table=int(n_table))
+    _check(_lib.pqt_train(ctypes.byref(tp), vectors.data_ptr(), vectors.device.index or 0, out["C1"].ctypes.data,
+                          out["C2"].ctypes.data, out["tbl_i"].ctypes.data, out["tbl_j"].ctypes.data,
+                          out["tbl_lam"].ctypes.data, out["cc"].ctypes.data, _stream_handle(stream)))
+    return out
 
 
 def pqt_builder_create(params, device=0):

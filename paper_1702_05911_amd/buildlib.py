@@ -5,7 +5,7 @@ import tempfile
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ("pqt_api.hip", "traverse.hip", "rank_bins.hip", "rerank.hip", "exact_rerank.hip", "builder.hip", "brute_force.hip", "peaks.hip")
+SOURCES = ("pqt_api.hip", "traverse.hip", "rank_bins.hip", "rerank.hip", "exact_rerank.hip", "builder.hip", "train.hip", "brute_force.hip", "peaks.hip")
 OUTPUT = os.path.join(HERE, "libpqt.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 instructions are kept off for all device code

@@ -508,6 +508,75 @@ def test_native_builder(pqt, tiny, tmp_path):
     assert same >= 27
 
 
+def _distortion(Xp, cen):
+    return float(np.mean(np.min(B.sqdist_matrix(Xp, cen), axis=1)))
+
+
+def test_training_on_the_gpu(pqt, tiny):
+    """pqt_train: after one Lloyd iteration every centroid is the mean of the vectors nearest to the start
+    centroids (vectors at evenly spaced places of the sample, of the cell for level 2), checked with the
+    oracle's distance routine; after twenty the distortion matches the oracle's own Lloyd training; the
+    line table is ordered by (i, j, lambda), shares the 256 code points out in proportion to the votes
+    the oracle counts, and places them inside the range of the lambdas voted on each line."""
+    import torch
+    cfg, X, Y, _ = tiny
+    P, k1, k2, M, D = cfg.P, cfg.k1, cfg.k2, cfg.M, cfg.D
+    dp, ds, n = D // P, D // M, 6000
+    Xd = torch.from_numpy(X[:n]).cuda()
+    one = pqt.pqt_train(Xd, P=P, k1=k1, k2=k2, M=M, iters=1, n_table=0)
+    again = pqt.pqt_train(Xd, P=P, k1=k1, k2=k2, M=M, iters=1, n_table=0)
+    for name in one:
+        assert np.array_equal(one[name], again[name]), f"{name}: training is not deterministic"
+    for p in range(P):
+        Xp = X[:n, p * dp:(p + 1) * dp].astype(np.float64)
+        start = Xp[(np.arange(k1) * n) // k1]
+        lab = np.argmin(B.sqdist_matrix(Xp, start), axis=1)
+        for i in range(k1):
+            np.testing.assert_allclose(one["C1"][p, i], Xp[lab == i].mean(axis=0), rtol=1e-5, atol=1e-6)
+        # level 2: cells of the finished level-1 quantiser, each trained on its own members
+        lab1 = np.argmin(B.sqdist_matrix(Xp, one["C1"][p].astype(np.float64)), axis=1)
+        for i in range(k1):
+            sub = Xp[lab1 == i]
+            if sub.shape[0] <= k2:
+                continue
+            start2 = sub[(np.arange(k2) * sub.shape[0]) // k2]
+            lab2 = np.argmin(B.sqdist_matrix(sub, start2), axis=1)
+            for j in range(k2):
+                if np.any(lab2 == j):
+                    np.testing.assert_allclose(one["C2"][p, i, j], sub[lab2 == j].mean(axis=0), rtol=1e-5, atol=1e-6)
+    full = pqt.pqt_train(Xd, P=P, k1=k1, k2=k2, M=M, iters=20, n_table=n)
+    oC1, oC2 = B.train_tree(X[:n], P, k1, k2, iters=20)
+    for p in range(P):
+        Xp = X[:n, p * dp:(p + 1) * dp].astype(np.float64)
+        g, o = _distortion(Xp, full["C1"][p].astype(np.float64)), _distortion(Xp, oC1[p].astype(np.float64))
+        print(f"part {p}: level-1 distortion GPU {g:.6f} oracle {o:.6f}", flush=True)
+        assert abs(g - o) <= 0.01 * o
+        g2 = _distortion(Xp, full["C2"][p].reshape(k1 * k2, dp).astype(np.float64))
+        o2 = _distortion(Xp, oC2[p].reshape(k1 * k2, dp).astype(np.float64))
+        assert g2 <= 1.03 * o2 and g2 < g
+    np.testing.assert_allclose(full["cc"], B.pair_table(full["C1"], M), rtol=1e-6, atol=1e-9)
+    pairs = Q.centroid_pairs(k1)
+    for m in range(M):
+        ti, tj, tl = full["tbl_i"][m], full["tbl_j"][m], full["tbl_lam"][m]
+        ent = list(zip(ti.tolist(), tj.tolist(), tl.tolist()))
+        assert ent == sorted(ent) and all(i < j < k1 for i, j, _ in ent)
+        bp, bl, _ = B.best_lines(X[:n, m * ds:(m + 1) * ds].astype(np.float64), B.subpart_centroids(full["C1"], M, m))
+        use = np.bincount(bp, minlength=len(pairs))
+        got = np.zeros(len(pairs), np.int64)
+        for i, j, _ in ent:
+            got[pairs.index((i, j))] += 1
+        quota = use * 256.0 / use.sum()
+        # largest-remainder shares lie within one of the exact quota; an fp32 near-tie may move a vote or two
+        assert got.sum() == 256 and np.all(np.abs(got - quota) <= 1.0 + 256.0 * 3 / n), (m, np.max(np.abs(got - quota)))
+        for q in np.nonzero(got)[0]:
+            lams = bl[bp == q]
+            mine = tl[(ti == pairs[q][0]) & (tj == pairs[q][1])]
+            assert lams.size and mine.min() >= lams.min() - 1e-3 and mine.max() <= lams.max() + 1e-3
+    with pytest.raises(pqt.PqtError) as e:
+        pqt.pqt_train(Xd, P=3, k1=k1, k2=k2, M=M)
+    assert e.value.code in (pqt.PQT_EINVAL, pqt.PQT_EUNSUPPORTED)
+
+
 def test_pair_lambda_codes(pqt, tiny_pair, tmp_path):
     """Codes stored as (centroid pair, lambda level): stage-wise parity of the query path on an
     oracle-built index; the lut tap is refused; a pair byte beyond the last pair is a format error."""
@@ -791,8 +860,8 @@ def test_error_codes(pqt, tiny, tmp_path):
 # ---- full size, in the launch configuration bench.py times -------------------------------------------
 @pytest.fixture(scope="module")
 def sift_full(pqt, tmp_path_factory):
-    """SIFT-shaped 1M x 128 database, 10,000 queries, index built by the package's builder on the
-    GPU (the index is input data for both sides; its validity is checked below)."""
+    """SIFT-shaped 1M x 128 database, 10,000 queries, index trained and built by the library
+    (pqt_train, pqt_builder_*; the index is input data for both sides; its validity is checked below)."""
     import torch
     from workloads import CONFIGS, sift_like_tables, sift_like_torch
     from paper_1702_05911_amd import builder
@@ -803,7 +872,7 @@ def sift_full(pqt, tmp_path_factory):
     Y = sift_like_torch(0, cfg.nq, d=cfg.D, seed=cfg.query_seed, tables=tables, device=dev)
     path = str(tmp_path_factory.mktemp("sift") / "sift.pqt")
     builder.build_index(path, X, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M, H=cfg.H, T=cfg.T, C=cfg.C,
-                        train_n=cfg.train_n, device=dev)
+                        train_n=cfg.train_n, device=0, chunk_rows=1 << 18).close()
     return cfg, X.cpu().numpy(), Y.cpu().numpy(), path, IO.read_index(path)
 
 
@@ -970,7 +1039,7 @@ def test_large_and_billion_parameter_shape(pqt, tmp_path, k1):
 @pytest.fixture(scope="module")
 def gist_full(pqt, tmp_path_factory):
     """GIST-shaped 1M x 960 database, 1,000 queries, P = 4 with H = K = 2^28 bin slots (the pointer
-    array alone is 1 GiB, so its probes are real HBM accesses); index built by the package's builder."""
+    array alone is 1 GiB, so its probes are real HBM accesses); index trained and built by the library."""
     import torch
     from workloads import CONFIGS, gist_like_torch
     from paper_1702_05911_amd import builder
@@ -980,7 +1049,7 @@ def gist_full(pqt, tmp_path_factory):
     Y = gist_like_torch(0, cfg.nq, d=cfg.D, seed=cfg.query_seed + 100, device=dev)
     path = str(tmp_path_factory.mktemp("gist") / "gist.pqt")
     builder.build_index(path, X, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M, H=cfg.H, T=cfg.T, C=cfg.C,
-                        train_n=cfg.train_n, device=dev)
+                        train_n=cfg.train_n, device=0, chunk_rows=1 << 18).close()
     Xh, Yh = X.cpu().numpy(), Y.cpu().numpy()
     del X, Y
     torch.cuda.empty_cache()

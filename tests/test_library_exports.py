@@ -46,24 +46,11 @@ def test_binding_uses_the_same_names():
     assert rc == b.PQT_EIO
 
 
-def test_product_builder_output_satisfies_the_oracle_definitions(tiny, tmp_path):
-    """The package's fp32 builder is separate code; its index must be a valid PQT index by the
-    oracle's definitions: bins partition X, every id sits in slot m(x), codes are nearest code points."""
-    import numpy as np
-    from oracle import pqt_build as B, pqt_index_io as IO
+def test_offline_driver_holds_no_arithmetic():
+    """The package's offline driver only marshals arguments: training, binning and encoding are the
+    library's (pqt_train, pqt_builder_*)."""
+    import inspect
     from paper_1702_05911_amd import builder
-    cfg, X, Y, _ = tiny
-    path = str(tmp_path / "prod.pqt")
-    builder.build_index(path, X, P=cfg.P, k1=cfg.k1, k2=cfg.k2, M=cfg.M, T=cfg.T, C=cfg.C, device="cpu")
-    ix = IO.read_index(path)
-    off = ix.offsets.astype(np.int64)
-    assert off[0] == 0 and off[-1] == cfg.N and np.all(np.diff(off) >= 0)
-    assert np.array_equal(np.sort(ix.ids), np.arange(cfg.N))
-    np.testing.assert_allclose(ix.cc, B.pair_table(ix.C1, ix.M), rtol=1e-6)
-    mism = 0
-    for t in range(0, cfg.N, 41):
-        slot = int(np.searchsorted(off, t, side="right")) - 1
-        x = X[ix.ids[t]]
-        mism += slot != B.bin_slot(x, ix.C1, ix.C2, ix.H)
-        mism += not np.array_equal(ix.codes[t], B.encode_vector(x, ix.C1, ix.M, ix.tbl_i, ix.tbl_j, ix.tbl_lam))
-    assert mism <= 2          # fp32 vs fp64 near-ties only
+    src = inspect.getsource(builder)
+    for banned in ("torch.cdist", ".argmin(", ".min(", "@", "bincount", "index_add", "cumsum", "torch.sort", "numpy"):
+        assert banned not in src, banned
