@@ -103,7 +103,8 @@ def measured_traffic(kernel, workload, w, field="bytes_per_launch"):
 
 
 def _oracle_worker(args):
-    path, Y, k, w, lo, hi, order = args
+    path, Y, k, w, lo, hi, order, gpu_ids = args
+    import numpy as np
     from oracle import pqt_index_io, pqt_query
     ix = pqt_index_io.read_index(path)
     t0 = time.perf_counter()
@@ -111,7 +112,25 @@ def _oracle_worker(args):
     for q in range(lo, hi):
         tr = pqt_query.query(ix, Y[q], k, w, with_margins=False, order_method=order)
         res.append(tr.out_ids)
-    return time.perf_counter() - t0, res
+    work = time.perf_counter() - t0
+    # untimed: a query whose ids differ from the GPU's is run again with the oracle's decision margins; it
+    # counts as a decided mismatch if every set-changing decision had a relative margin above 1e-5 (then
+    # fp32 rounding cannot explain the difference)
+    differing = decided = 0
+    if gpu_ids is not None and order != "static":
+        for q in range(lo, hi):
+            if not np.array_equal(res[q - lo], gpu_ids[q]):
+                differing += 1
+                tr = pqt_query.query(ix, Y[q], k, w, with_margins=True, order_method=order)
+                decided += int(tr.margins["min"] > 1e-5)
+    return work, res, differing, decided
+
+
+def under_profiler():
+    """rocprofv3 preloads a library that initialises the GPU in every process it starts; sixteen oracle
+    workers on top of the benchmark exceed what a GPU machine allows, so the CPU baseline is skipped then."""
+    env = os.environ
+    return any(k.startswith(("ROCPROF", "ROCP_", "ROCPROFILER")) for k in env) or "rocprof" in env.get("LD_PRELOAD", "")
 
 
 def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16, order="fullsort"):
@@ -122,13 +141,13 @@ def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16, order
     cores = min(len(os.sched_getaffinity(0)), max_procs)
     # size the sample from one timed query
     t0 = time.perf_counter()
-    _oracle_worker((path, Y_host, k, w, 0, 1, order))
+    _oracle_worker((path, Y_host, k, w, 0, 1, order, None))
     per_q = max(time.perf_counter() - t0, 1e-3)
     n = int(max(cores, min(Y_host.shape[0], budget_s / per_q * cores)))
     n -= n % cores
     n = max(n, cores) if Y_host.shape[0] >= cores else Y_host.shape[0]
     bounds = [(i * n) // cores for i in range(cores + 1)]
-    jobs = [(path, Y_host, k, w, bounds[i], bounds[i + 1], order) for i in range(cores) if bounds[i + 1] > bounds[i]]
+    jobs = [(path, Y_host, k, w, bounds[i], bounds[i + 1], order, gpu_ids) for i in range(cores) if bounds[i + 1] > bounds[i]]
     t0 = time.perf_counter()
     with mp.get_context("spawn").Pool(len(jobs)) as pool:
         outs = pool.map(_oracle_worker, jobs)
@@ -140,16 +159,24 @@ def cpu_baseline(path, Y_host, k, w, gpu_ids, budget_s=20.0, max_procs=16, order
             "sample": f"first {n} of {Y_host.shape[0]} queries, float64 NumPy oracle, {len(jobs)} processes "
                       f"(wall {wall:.1f}s incl. start-up)",
             "single_core_queries_per_s": 1.0 / per_q,
-            "gpu_ids_identical_on_sample": agree}
+            "gpu_ids_identical_on_sample": agree,
+            "queries_differing": int(sum(o[2] for o in outs)),
+            # of those, the ones whose oracle decision margins all exceed 1e-5 relative (must be 0: every
+            # difference is then a near-tie that fp32 and float64 settle differently)
+            "decided_mismatches": int(sum(o[3] for o in outs))}
 
 
-def main():
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None,
                     help="timed steps (default 2000, or 20 with --batch: a step then makes many calls)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default steps // 10)")
     ap.add_argument("--workload", default="sift")
+    ap.add_argument("--also", default=None, metavar="W1,W2,..",
+                    help="further workloads measured after the headline one and reported as sub-records under "
+                         "\"hbm_resident\" (default: large -- 100M vectors, 800 MB of codes: the index does not fit the "
+                         "caches -- when the headline workload is sift; none otherwise; pass an empty string for none)")
     ap.add_argument("--w", type=int, default=None)
     ap.add_argument("--nq", type=int, default=None, help="queries per step (default: the workload's)")
     ap.add_argument("--T", type=int, default=None, help="bin tuples examined per query (default: the workload's)")
@@ -194,14 +221,21 @@ def main():
         args.steps = 20 if args.batch else 2000
     if args.warmup is None:
         args.warmup = max(3, args.steps // 10)
+    return args
 
+
+def run_workload(args, workload, primary, peaks):
+    """One workload end to end: data, index (trained and built by the library), timed steps, stage times,
+    recall, rooflines.  primary: the headline workload (gets the CPU baseline and every optional extra);
+    otherwise a sub-record with the timing, recall and rooflines only.  peaks: (HBM GB/s, MFMA TFLOP/s)
+    measured on this machine before any timed loop."""
     import numpy as np
     import torch
     from workloads import CONFIGS
     from paper_1702_05911_amd import builder
     import paper_1702_05911_amd.binding as pqt
 
-    cfg = CONFIGS[args.workload]
+    cfg = CONFIGS[workload]
     if args.nq:
         cfg = cfg.with_(nq=args.nq)
     if args.T:
@@ -223,7 +257,7 @@ def main():
     gt = ExactNN(Y[:n_gt])
 
     raw_dtype = torch.uint8 if cfg.kind == "sift" else torch.float32
-    raw = torch.empty((cfg.N, cfg.D), dtype=raw_dtype, device=dev) if (args.exact or args.brute_force) else None
+    raw = torch.empty((cfg.N, cfg.D), dtype=raw_dtype, device=dev) if (primary and (args.exact or args.brute_force)) else None
 
     def observe(start, Xc):
         gt.update(start, Xc)
@@ -246,11 +280,10 @@ def main():
     occupancy = {"nonempty_slots": int((runs > 0).sum()), "max_run": int(runs.max()),
                  "mean_run_nonempty": float(runs[runs > 0].float().mean())}
     del runs
-    tmp = tempfile.mkdtemp(prefix="pqt_bench_")
-    path = os.path.join(tmp, f"{cfg.name}.pqt")
-    if in_hbm_only and not args.cpu_baseline:
-        path = None
-    else:
+    tmp = path = None
+    if primary and not (in_hbm_only and not args.cpu_baseline) and not args.no_cpu_baseline and not under_profiler():
+        tmp = tempfile.mkdtemp(prefix="pqt_bench_")
+        path = os.path.join(tmp, f"{cfg.name}.pqt")
         pqt.pqt_index_save(index, path)        # the oracle's processes read the same index from this file
     del X
     torch.cuda.empty_cache()
@@ -354,7 +387,7 @@ def main():
          "peak": HBM_PEAK_GBS, "unit": "GB/s",
          "note": "includes the full bin ranking of the queries the head pass leaves over (two tree parts)"},
     ]
-    hbm_meas, mfma_meas = pqt.pqt_measure_peaks(0)       # streaming read of 4 GiB; loop of independent MFMAs
+    hbm_meas, mfma_meas = peaks                          # streaming read of 4 GiB; loop of independent MFMAs
     for s in stages:
         s["frac"] = s["achieved"] / s["peak"]
         meas = {"hbm": hbm_meas, "mfma": mfma_meas}.get(s["bound"])
@@ -372,14 +405,20 @@ def main():
             n = measured_traffic(s["kernel"], cfg.name, w, "valu_insts_per_launch")
             if n:
                 s["valu_issue"] = {"insts_per_launch": n, "achieved": n / (s["ms"] * 1e-3) / 1e9, "peak": VALU_ISSUE_PEAK_G,
-                                   "unit": "G wave-instructions/s", "frac": n / (s["ms"] * 1e-3) / 1e9 / VALU_ISSUE_PEAK_G}
+                                   "unit": "G wave-instructions/s", "frac": n / (s["ms"] * 1e-3) / 1e9 / VALU_ISSUE_PEAK_G,
+                                   "source": "insts_per_launch: profiles/pmc_traffic.json (rocprofv3 --pmc SQ_INSTS_VALU, "
+                                             "a separate run); duration: this run"}
     dom = max(stages, key=lambda s: s["ms"])
+    traffic = None if (code_format or args.M or args.order == "static") else measured_traffic(dom["kernel"], cfg.name, w)
     roofline = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                "unit": dom["unit"], "frac": dom["frac"], "traffic": None if (code_format or args.M or args.order == "static") else measured_traffic(dom["kernel"], cfg.name, w)}
+                "unit": dom["unit"], "frac": dom["frac"], "traffic": traffic,
+                "traffic_source": None if traffic is None else
+                "profiles/pmc_traffic.json (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, separate runs of the same command)",
+                "launch_us": dom["ms"] * 1e3, "algorithmic_bytes_per_launch": rerank_bytes if dom["bound"] == "hbm" else None}
 
     ms_per_step = elapsed / args.steps * 1e3
     result = {
-        "metric": "queries/sec at fixed Recall@1/@100 (1M x 128-shaped); per-stage % roofline",
+        "metric": "queries/sec at fixed Recall@1/@100 (1M x 128 and 1B x 128-shaped); per-stage % roofline",
         "value": cfg.nq * args.steps / elapsed, "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step,
         "ms_per_step_with_stage_events": elapsed_profiled / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
@@ -403,14 +442,19 @@ def main():
             pqt.pqt_query_batch(index, Y[o:o + B], cfg.k, w, out_ids[o:o + B], out_d[o:o + B])
             torch.cuda.synchronize()
         result["latency_us_per_call"] = (time.perf_counter() - t0) / ncalls * 1e6
-    if path is not None and not args.no_cpu_baseline:
+    if not primary:
+        result["cpu_baseline"] = None
+    elif under_profiler():
+        result["cpu_baseline"] = None
+        print("[bench] a profiler is attached: the CPU baseline (sixteen worker processes) is skipped", file=sys.stderr)
+    elif path is not None and not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(path, Y.cpu().numpy(), cfg.k, w, out_ids.cpu().numpy(),
                                               max_procs=4 if cfg.N > 200_000_000 else 16,
                                               order="static" if args.order == "static" else "fullsort")
     else:
         result["cpu_baseline"] = None
     sweep = []
-    for wx in [int(v) for v in args.sweep_w.split(",") if v]:
+    for wx in [int(v) for v in args.sweep_w.split(",") if v and primary]:
         pqt.pqt_query_batch(index, Y, cfg.k, wx, out_ids, out_d)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -424,7 +468,7 @@ def main():
         result["w_sweep"] = sweep
         pqt.pqt_query_batch(index, Y, cfg.k, w, out_ids, out_d)
         torch.cuda.synchronize()
-    if args.M or args.sweep_w:
+    if primary and (args.M or args.sweep_w):
         # mean squared error of the stored codes against the vectors they stand for (Table 3's distortion):
         # reconstruction per Sec. 3.3 from the exported codes, on the first 100,000 database ids
         ex = pqt.pqt_index_export(index, ("ids", "codes"))
@@ -455,7 +499,7 @@ def main():
                                 "vectors": int(pick.numel()), "M": cfg.M, "code_bytes": code_bytes}
         del ex
     extra = []
-    for Bx in [int(v) for v in args.also_batches.split(",") if v]:
+    for Bx in [int(v) for v in args.also_batches.split(",") if v and primary]:
         ncall = -(-cfg.nq // Bx)
         reps = max(1, min(args.steps, 20000 // ncall))
 
@@ -480,7 +524,7 @@ def main():
                       "us_per_call_queued": el / reps / ncall * 1e6, "latency_us_per_call": lat * 1e6})
     if extra:
         result["batches"] = extra
-    if args.exact:
+    if args.exact and primary:
         # exact re-ranking of the first K_SHORT results (the paper's PQT_2): HBM-bound gather of raw rows
         ks = args.exact
         pqt.pqt_index_set_vectors(index, raw)
@@ -504,7 +548,7 @@ def main():
                            "roofline": {"kernel": "exact_rerank_kernel", "bound": "hbm",
                                         "achieved": ebytes / (ems[3] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                                         "unit": "GB/s", "frac": ebytes / (ems[3] * 1e-3) / 1e9 / HBM_PEAK_GBS}}
-    if args.brute_force:
+    if args.brute_force and primary:
         pqt.pqt_index_set_vectors(index, raw)
         bf_ids, bf_d = pqt.pqt_brute_force(index, Y, cfg.k)          # warm-up: workspace and database norms
         torch.cuda.synchronize()
@@ -524,6 +568,31 @@ def main():
                                               "unit": "TFLOP/s", "frac": flops / (bf_ms * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS,
                                               "note": "whole call (distance and selection kernels)"}}
     pqt.pqt_index_free(index)
+    del index, Y, out_ids, out_d
+    torch.cuda.empty_cache()
+    if tmp is not None:
+        import shutil
+        shutil.rmtree(tmp, ignore_errors=True)
+    return result
+
+
+def main():
+    args = parse_args()
+    import paper_1702_05911_amd.binding as pqt
+    # Measured ceilings first: about a second of streaming reads and matrix-core work, which also brings the
+    # clocks up from idle before anything is timed (twenty steps straight after an idle set-up read 8-10 % low).
+    peaks = pqt.pqt_measure_peaks(0)
+    result = run_workload(args, args.workload, True, peaks)
+    also = args.also if args.also is not None else ("large" if args.workload == "sift" and not args.batch else "")
+    extra = {}
+    for name in [v for v in also.split(",") if v]:
+        print(f"[bench] sub-record: {name}", file=sys.stderr, flush=True)
+        sub = run_workload(args, name, False, peaks)
+        extra[name] = {key: sub[key] for key in ("value", "unit", "ms_per_step", "steps", "warmup", "dtype", "config", "recall",
+                                                 "stage_ms", "stages", "roofline", "tuples_needed", "setup_s")}
+    if extra:
+        # the index of the headline workload (8 MB of codes) lives in the caches; these do not
+        result["hbm_resident"] = extra
     print(json.dumps(result))
 
 
