@@ -5,7 +5,11 @@ import tempfile
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ("pqt_api.hip", "traverse.hip", "rank_bins.hip", "rerank.hip", "exact_rerank.hip", "builder.hip", "train.hip", "brute_force.hip", "peaks.hip")
+SOURCES = ("pqt_api.hip", "traverse.hip", "rank_bins.hip", "rerank.hip",
+           # the re-rank kernel, one translation unit per code width (they compile side by side)
+           "rerank_table2.hip", "rerank_table0.hip", "rerank_table1.hip", "rerank_table4.hip", "rerank_table8.hip",
+           "rerank_pair_bytes.hip", "rerank_pair2.hip", "rerank_pair4.hip", "rerank_pair8.hip",
+           "exact_rerank.hip", "builder.hip", "train.hip", "brute_force.hip", "peaks.hip")
 OUTPUT = os.path.join(HERE, "libpqt.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 instructions are kept off for all device code
@@ -15,7 +19,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 def build_library(verbose=False, jobs=None):
     """One hipcc process per source file (they are independent translation units), then the link."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    jobs = jobs or min(len(SOURCES), os.cpu_count() or 1, 8)
+    jobs = jobs or min(len(SOURCES), os.cpu_count() or 1, 16)
     log = []
 
     def run(cmd):
