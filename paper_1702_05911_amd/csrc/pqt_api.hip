@@ -13,6 +13,7 @@
 #include <string>
 #include <vector>
 
+#include "pqt_host.hpp"
 #include "pqt_index.hpp"
 
 namespace pqt_host {
@@ -76,28 +77,13 @@ __global__ void max_even_byte_kernel(const uint8_t* codes, uint64_t n, uint32_t*
     atomicMax(out, worst);
 }
 
-struct FileHeader {
-    char magic[8];
-    uint32_t version, D, P, k1, k2, M;
-    uint64_t N, H;
-    uint32_t T, C, offset_bits, code_format;
-};
-static_assert(sizeof(FileHeader) == 64, "header prefix is 64 bytes");
+using pqt_host::FileHeader;
 
 struct FileCloser {
     void operator()(FILE* f) const {
         if (f) fclose(f);
     }
 };
-
-// Reads `bytes` at the next 256-byte boundary of the file.
-bool read_section(FILE* f, void* dst, size_t bytes) {
-    long pos = ftell(f);
-    if (pos < 0) return false;
-    long pad = (long)((kAlign - (size_t)pos % kAlign) % kAlign);
-    if (pad && fseek(f, pad, SEEK_CUR) != 0) return false;
-    return bytes == 0 || fread(dst, 1, bytes, f) == bytes;
-}
 
 template <typename Tp>
 int upload(Tp** dev, const void* src, size_t bytes, hipMemcpyKind kind, uint64_t* account) {
@@ -198,25 +184,11 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
         (!pair_codes && (!a->tbl_i || !a->tbl_j || !a->tbl_lambda)))
         return fail(PQT_EINVAL, "pqt_index_from_arrays: null array");
     const pqt_index_arrays& h = *a;
-    if (h.D == 0 || h.P == 0 || h.k1 == 0 || h.k2 == 0 || h.M == 0 || h.H == 0 || h.D % h.P || h.D % h.M ||
-        h.M % h.P)
-        return fail(PQT_EFORMAT, "inconsistent sizes D=%u P=%u k1=%u k2=%u M=%u", h.D, h.P, h.k1, h.k2, h.M);
-    if (!(h.P == 1 || h.P == 2 || h.P == 4)) return fail(PQT_EUNSUPPORTED, "P=%u: only 1, 2 or 4 tree parts", h.P);
-    if (h.k1 > PQT_MAX_K1 || h.k2 > PQT_MAX_R || h.M > 64 || h.D > 8192)
-        return fail(PQT_EUNSUPPORTED, "k1=%u k2=%u M=%u D=%u beyond the kernel limits", h.k1, h.k2, h.M, h.D);
-    if (h.N >= 0xffffffffull || h.H >= 0xffffffffull)
-        return fail(PQT_EUNSUPPORTED, "N=%llu H=%llu: 32-bit ids and slots only", (unsigned long long)h.N,
-                    (unsigned long long)h.H);
-    long double K = 1;
-    for (uint32_t p = 0; p < h.P; ++p) K *= (long double)h.k1 * h.k2;
-    if (K >= 18446744073709551616.0L)
-        return fail(PQT_EUNSUPPORTED, "(k1*k2)^P = %Lg bins do not fit 64-bit bin numbers", K);
-    if ((long double)h.H > K) return fail(PQT_EFORMAT, "H exceeds the number of bins");
-    if (h.T < 1 || h.T > PQT_MAX_T || h.C < 1 || h.C > PQT_MAX_C)
-        return fail(PQT_EFORMAT, "default budgets T=%u C=%u out of range", h.T, h.C);
+    std::string why;
+    bool hashed = false;
+    int vrc = pqt_host::check_sizes(h.D, h.P, h.k1, h.k2, h.M, h.N, h.H, h.T, h.C, h.code_format, &hashed, why);
+    if (vrc != PQT_OK) return fail(vrc, "%s", why.c_str());
     const uint32_t npairs = h.k1 * (h.k1 - 1) / 2;
-    if (pair_codes && (h.k1 < 2 || npairs > 256))
-        return fail(PQT_EUNSUPPORTED, "k1=%u: (pair, lambda) codes number the %u centroid pairs in one byte", h.k1, npairs);
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev)
@@ -237,33 +209,24 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
         HIP_TRY(hipMemcpy(off_copy.data(), h.offsets, off_copy.size() * 4, hipMemcpyDeviceToHost));
         off = off_copy.data();
     }
-    if (off[0] != 0 || off[h.H] != h.N) return fail(PQT_EFORMAT, "offsets do not span the ids");
     uint64_t nonempty = 0;
-    for (size_t s = 0; s < h.H; ++s) {
-        if (off[s + 1] < off[s]) return fail(PQT_EFORMAT, "offsets not monotone at slot %zu", s);
-        nonempty += off[s + 1] > off[s] ? 1 : 0;
-    }
+    vrc = pqt_host::check_arrays(h.k1, h.M, h.N, h.H, h.code_format, off, h.tbl_i, h.tbl_j,
+                                 location == PQT_HOST ? h.codes : nullptr, &nonempty, why);
+    if (vrc != PQT_OK) return fail(vrc, "%s", why.c_str());
     const size_t ntab = (size_t)h.M * 256;
-    for (size_t e = 0; e < ntab && !pair_codes; ++e)
-        if (h.tbl_i[e] >= h.k1 || h.tbl_j[e] >= h.k1) return fail(PQT_EFORMAT, "code table names centroid >= k1");
     const size_t code_bytes = (size_t)h.M * (pair_codes ? 2 : 1);
-    if (pair_codes && h.N > 0) {       // every pair byte must name a pair
+    if (pair_codes && h.N > 0 && location == PQT_DEVICE) {       // every pair byte must name a pair (codes on the GPU)
         uint32_t worst = 0;
-        if (location == PQT_HOST) {
-            for (size_t v = 0; v < (size_t)h.N; ++v)
-                for (size_t m = 0; m < h.M; ++m) worst = std::max<uint32_t>(worst, h.codes[v * code_bytes + 2 * m]);
-        } else {
-            uint32_t* dmax = nullptr;
-            HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dmax), sizeof(uint32_t)));
-            hipError_t e = hipMemset(dmax, 0, sizeof(uint32_t));
-            if (e == hipSuccess) {
-                hipLaunchKernelGGL(max_even_byte_kernel, dim3(1024), dim3(256), 0, 0, h.codes, (uint64_t)h.N * h.M, dmax);
-                e = hipGetLastError();
-            }
-            if (e == hipSuccess) e = hipMemcpy(&worst, dmax, sizeof(uint32_t), hipMemcpyDeviceToHost);
-            (void)hipFree(dmax);
-            if (e != hipSuccess) return fail(PQT_EHIP, "checking the codes: %s", hipGetErrorString(e));
+        uint32_t* dmax = nullptr;
+        HIP_TRY(hipMalloc(reinterpret_cast<void**>(&dmax), sizeof(uint32_t)));
+        hipError_t e = hipMemset(dmax, 0, sizeof(uint32_t));
+        if (e == hipSuccess) {
+            hipLaunchKernelGGL(max_even_byte_kernel, dim3(1024), dim3(256), 0, 0, h.codes, (uint64_t)h.N * h.M, dmax);
+            e = hipGetLastError();
         }
+        if (e == hipSuccess) e = hipMemcpy(&worst, dmax, sizeof(uint32_t), hipMemcpyDeviceToHost);
+        (void)hipFree(dmax);
+        if (e != hipSuccess) return fail(PQT_EHIP, "checking the codes: %s", hipGetErrorString(e));
         if (worst >= npairs) return fail(PQT_EFORMAT, "a code names centroid pair %u of %u", worst, npairs);
     }
 
@@ -330,7 +293,7 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
     ix->D = h.D; ix->P = h.P; ix->k1 = h.k1; ix->k2 = h.k2; ix->M = h.M; ix->T = h.T; ix->C = h.C;
     ix->N = h.N; ix->H = h.H; ix->device = device;
     ix->lds_limit = lds_limit;
-    ix->hashed = (long double)h.H != K;
+    ix->hashed = hashed;
     ix->code_format = h.code_format;
     ix->nonempty_slots = nonempty;
     try {
@@ -371,48 +334,13 @@ int pqt_index_from_arrays(const pqt_index_arrays* a, int location, int device, p
 int pqt_index_load(const char* path, int device, pqt_index** out) {
     if (!path || !out) return fail(PQT_EINVAL, "pqt_index_load: null argument");
     *out = nullptr;
-    std::unique_ptr<FILE, FileCloser> f(fopen(path, "rb"));
-    if (!f) return fail(PQT_EIO, "cannot open '%s'", path);
-    unsigned char hdr[kAlign];
-    if (fread(hdr, 1, kAlign, f.get()) != kAlign) return fail(PQT_EFORMAT, "'%s': truncated header", path);
-    FileHeader h;
-    memcpy(&h, hdr, sizeof(h));
-    if (memcmp(h.magic, "PQTIDX1\0", 8) != 0) return fail(PQT_EFORMAT, "'%s': bad magic", path);
-    if (h.version != 1 || h.offset_bits != 32 || h.code_format > PQT_CODES_PAIR_LAMBDA)
-        return fail(PQT_EFORMAT, "'%s': unsupported version", path);
-    // the sizes the arrays are read with must be sane before anything is allocated
-    // (pqt_index_from_arrays repeats these checks for callers that bring their own arrays)
-    if (h.D == 0 || h.P == 0 || h.k1 == 0 || h.k2 == 0 || h.M == 0 || h.H == 0 || h.D % h.P || h.D % h.M ||
-        h.M % h.P)
-        return fail(PQT_EFORMAT, "'%s': inconsistent sizes D=%u P=%u k1=%u k2=%u M=%u", path, h.D, h.P, h.k1,
-                    h.k2, h.M);
-    if (h.k1 > PQT_MAX_K1 || h.k2 > PQT_MAX_R || h.M > 64 || h.D > 8192 || h.N >= 0xffffffffull ||
-        h.H >= 0xffffffffull)
-        return fail(PQT_EUNSUPPORTED, "'%s': k1=%u k2=%u M=%u D=%u N=%llu H=%llu beyond the kernel limits", path,
-                    h.k1, h.k2, h.M, h.D, (unsigned long long)h.N, (unsigned long long)h.H);
-
-    const size_t dp = h.D / h.P;
-    std::vector<float> C1, C2, lam, cc;
-    std::vector<uint8_t> ti, tj, codes;
-    std::vector<uint32_t> offsets, ids;
-    try {
-        C1.resize((size_t)h.P * h.k1 * dp);
-        C2.resize((size_t)h.P * h.k1 * h.k2 * dp);
-        ti.resize((size_t)h.M * 256); tj.resize((size_t)h.M * 256); lam.resize((size_t)h.M * 256);
-        cc.resize((size_t)h.M * h.k1 * h.k1);
-        offsets.resize((size_t)h.H + 1);
-        ids.resize((size_t)h.N);
-        codes.resize((size_t)h.N * h.M * (h.code_format == PQT_CODES_PAIR_LAMBDA ? 2 : 1));
-    } catch (const std::bad_alloc&) {
-        return fail(PQT_ENOMEM, "host allocation failed while reading '%s'", path);
-    }
-    if (!read_section(f.get(), C1.data(), C1.size() * 4) || !read_section(f.get(), C2.data(), C2.size() * 4) ||
-        !read_section(f.get(), ti.data(), ti.size()) || !read_section(f.get(), tj.data(), tj.size()) ||
-        !read_section(f.get(), lam.data(), lam.size() * 4) || !read_section(f.get(), cc.data(), cc.size() * 4) ||
-        !read_section(f.get(), offsets.data(), offsets.size() * 4) || !read_section(f.get(), ids.data(), ids.size() * 4) ||
-        !read_section(f.get(), codes.data(), codes.size()))
-        return fail(PQT_EFORMAT, "'%s': truncated", path);
-
+    pqt_host::IndexFile h;
+    std::string why;
+    const int frc = pqt_host::read_index_file(path, h, why);
+    if (frc != PQT_OK) return fail(frc, "%s", why.c_str());
+    std::vector<float>&C1 = h.C1, &C2 = h.C2, &lam = h.lam, &cc = h.cc;
+    std::vector<uint8_t>&ti = h.ti, &tj = h.tj, &codes = h.codes;
+    std::vector<uint32_t>&offsets = h.offsets, &ids = h.ids;
     pqt_index_arrays a = {};
     a.N = h.N; a.H = h.H; a.D = h.D; a.P = h.P; a.k1 = h.k1; a.k2 = h.k2; a.M = h.M; a.T = h.T; a.C = h.C;
     a.C1 = C1.data(); a.C2 = C2.data(); a.tbl_i = ti.data(); a.tbl_j = tj.data(); a.tbl_lambda = lam.data();

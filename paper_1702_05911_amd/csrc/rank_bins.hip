@@ -16,6 +16,7 @@
 #include <algorithm>
 #include <cmath>
 
+#include "pqt_host.hpp"
 #include "rank_head_device.hpp"
 
 namespace pqt {
@@ -189,38 +190,8 @@ __global__ __launch_bounds__(kStaticThreads) void rank_static_kernel(RankArgs g,
 }
 
 int make_static_order(int R, int T, std::vector<uint32_t>& table, float thr[kStaticSlopes - 1]) {
-#pragma clang fp contract(off)
-    const long all = (long)R * R;
-    const int Tn = (int)((long)T < all ? (long)T : all);
-    double slope[kStaticSlopes];
-    slope[5] = 1.0;
-    for (int i = 6; i < kStaticSlopes; ++i) slope[i] = slope[i - 1] * 1.08;
-    for (int i = 4; i >= 0; --i) slope[i] = slope[i + 1] / 1.08;
-    const double root = std::sqrt(1.08);
-    for (int j = 1; j < kStaticSlopes; ++j) thr[j - 1] = (float)(slope[j] / root);
-    struct Item {
-        double key;
-        uint32_t ab;
-    };
-    // a pair can only be among the first Tn of an order that grows in both ranks if (a+1)(b+1) <= Tn
-    std::vector<Item> items;
-    table.assign((size_t)kStaticSlopes * Tn, 0u);
-    for (int i = 0; i < kStaticSlopes; ++i) {
-        items.clear();
-        for (int a = 0; a < R && a < Tn; ++a) {
-            const int nb = region_row_count(a, R, Tn);
-            for (int b = 0; b < nb; ++b) {
-                const double x = a + 1.0, y = slope[i] * (b + 1.0);
-                const double xx = x * x, yy = y * y;
-                items.push_back(Item{xx + yy, ((uint32_t)a << 16) | (uint32_t)b});
-            }
-        }
-        std::sort(items.begin(), items.end(), [](const Item& l, const Item& r) {
-            return l.key != r.key ? l.key < r.key : l.ab < r.ab;           // (key, a, b)
-        });
-        for (int t = 0; t < Tn; ++t) table[(size_t)i * Tn + t] = items[(size_t)t].ab;
-    }
-    return Tn;
+    static_assert(kStaticSlopes == pqt_host::kSlopes, "one table per slope");
+    return pqt_host::make_static_order(R, T, table, thr);
 }
 
 hipError_t launch_rank_static(const RankArgs& a, const StaticOrder& so, hipStream_t s) {
