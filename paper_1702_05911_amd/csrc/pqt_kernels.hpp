@@ -11,6 +11,7 @@ namespace pqt {
 constexpr int kQueryTile = 16;          // queries per workgroup of the traversal kernel (MFMA rows)
 constexpr int kTraverseMaxThreads = 1024; // workgroup size grows with the number of tree parts
 constexpr int kRankThreads = 1024;        // full ranking pass: one workgroup per query
+constexpr int kRankThreadsFourParts = 512;  // the same for four tree parts (up to 4096 tuples)
 constexpr int kRankHeadThreads = 256;     // head pass: one wavefront per query
 constexpr size_t kMaxLds = 160 * 1024;  // LDS per workgroup on gfx950
 

@@ -247,8 +247,15 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
         if (e != hipSuccess || defer_full) return e;
     }
     const unsigned grid = head ? (unsigned)(a.nq < 1024 ? a.nq : 1024) : (unsigned)a.nq;
-    if (o.Tcap <= 4 * kRankThreads && a.P == 4)
-        hipLaunchKernelGGL((rank_kernel<4, 4>), dim3(grid), dim3(kRankThreads), o.total, s, a, o);
+    // Four tree parts: the pass is a chain of dependent steps, so what counts is how many queries a compute
+    // unit works on at once: workgroups of 512 threads (four fit where two of 1024 did) as long as a thread
+    // then holds at most eight tuples.
+    if (a.P == 4 && o.Tcap <= 4 * kRankThreadsFourParts)
+        hipLaunchKernelGGL((rank_kernel<4, 4>), dim3(grid), dim3(kRankThreadsFourParts), o.total, s, a, o);
+    else if (a.P == 4 && o.Tcap <= 8 * kRankThreadsFourParts)
+        hipLaunchKernelGGL((rank_kernel<8, 4>), dim3(grid), dim3(kRankThreadsFourParts), o.total, s, a, o);
+    else if (a.P == 4)
+        hipLaunchKernelGGL((rank_kernel<8, 4>), dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     else if (o.Tcap <= 4 * kRankThreads) hipLaunchKernelGGL(rank_kernel<4>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     else hipLaunchKernelGGL(rank_kernel<8>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     return hipGetLastError();
@@ -259,6 +266,9 @@ hipError_t configure_rank(size_t max_dynamic_lds) {
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<4, 4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)max_dynamic_lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8, 4>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)max_dynamic_lds);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8>),
