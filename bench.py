@@ -175,8 +175,9 @@ def parse_args():
     ap.add_argument("--workload", default="sift")
     ap.add_argument("--also", default=None, metavar="W1,W2,..",
                     help="further workloads measured after the headline one and reported as sub-records under "
-                         "\"hbm_resident\" (default: large -- 100M vectors, 800 MB of codes: the index does not fit the "
-                         "caches -- when the headline workload is sift; none otherwise; pass an empty string for none)")
+                         "\"hbm_resident\" (default: large,billion -- 100M and 1B vectors, 0.8 and 8 GB of codes: indexes "
+                         "that do not fit the caches; the 1B one takes a minute to build -- when the headline workload "
+                         "is sift; none otherwise; pass an empty string for none)")
     ap.add_argument("--w", type=int, default=None)
     ap.add_argument("--nq", type=int, default=None, help="queries per step (default: the workload's)")
     ap.add_argument("--T", type=int, default=None, help="bin tuples examined per query (default: the workload's)")
@@ -583,7 +584,7 @@ def main():
     # clocks up from idle before anything is timed (twenty steps straight after an idle set-up read 8-10 % low).
     peaks = pqt.pqt_measure_peaks(0)
     result = run_workload(args, args.workload, True, peaks)
-    also = args.also if args.also is not None else ("large" if args.workload == "sift" and not args.batch else "")
+    also = args.also if args.also is not None else ("large,billion" if args.workload == "sift" and not args.batch else "")
     extra = {}
     for name in [v for v in also.split(",") if v]:
         print(f"[bench] sub-record: {name}", file=sys.stderr, flush=True)
