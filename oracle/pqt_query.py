@@ -462,8 +462,10 @@ def _rel_gap(lo, hi):
 
 
 def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_method="fullsort",
-          with_margins=True):
+          with_margins=True, truncate_pairs=False):
     # order_method "static": the fixed anisotropic order of O4' instead of the order by summed distance
+    # truncate_pairs: bin_order's option (four parts: the pair lists cut at T before the final merge, the
+    # same order by construction; lists of 128 are out of reach of the full form)
     """One query through O1..O8.  With exact_rerank (needs the raw vectors X) the scores
     of O6-O7 are replaced by exact squared distances (step (3) of the PQ pipelines in
     Sec. 1; the paper's PQT_2 of Table 1)."""
@@ -479,7 +481,8 @@ def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_meth
         tr.tuples, tr.keys = bin_order_static([tr.Ld[p] for p in range(index.P)], T)
         with_margins = False           # the margins describe decisions of the order by summed distance
     else:
-        tr.tuples, tr.keys = bin_order([tr.Ld[p] for p in range(index.P)], T, method=order_method)
+        tr.tuples, tr.keys = bin_order([tr.Ld[p] for p in range(index.P)], T, method=order_method,
+                                       truncate_pairs=truncate_pairs)
     tr.slots = propose_bins(tr.tuples, tr.Lid, index.k1 * index.k2, index.H, index.offsets)
     tr.cand_pos = gather_candidates(tr.slots, index.offsets, C)
     tr.cand_ids = index.ids[tr.cand_pos].astype(np.int64)
@@ -493,11 +496,11 @@ def query(index, y, k, w, T=None, C=None, X=None, exact_rerank=False, order_meth
         tr.scores = score_codes(tr.lut, index.codes[tr.cand_pos])
     tr.out_ids, tr.out_dists = top_k(tr.scores, tr.cand_ids, k)
     if with_margins:
-        tr.margins = decision_margins(index, tr, k, w, T, C)
+        tr.margins = decision_margins(index, tr, k, w, T, C, truncate_pairs=truncate_pairs)
     return tr
 
 
-def decision_margins(index, tr, k, w, T, C):
+def decision_margins(index, tr, k, w, T, C, truncate_pairs=False):
     """Relative gaps at the decisions that can change the *set* of returned ids or their
     order: the w-th vs (w+1)-th level-1 distance per part, the last examined vs first
     unexamined bin key, the keys around the run that the candidate budget cuts, and the
@@ -515,7 +518,7 @@ def decision_margins(index, tr, k, w, T, C):
     for p in range(index.P):
         total *= tr.Ld.shape[1]
     if T < total:
-        _, keys = bin_order([tr.Ld[p] for p in range(index.P)], T + 1)
+        _, keys = bin_order([tr.Ld[p] for p in range(index.P)], T + 1, truncate_pairs=truncate_pairs)
         g = _rel_gap(keys[T - 1], keys[T])
     m["tuples"] = g
     # C boundary: keys of the emitted slots around the truncated run

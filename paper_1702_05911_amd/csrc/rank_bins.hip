@@ -33,7 +33,7 @@ int rank_region_size(int R, int T) { return (int)region_size(R, R, T); }
 
 struct RankLds {
     int Tcap;    // tuples examined: min(T, R^P)
-    int cap;     // sort buffer entries: next_pow2(Tcap), at least 64
+    int cap;     // sort buffer: next_pow2(Tcap), at least 64 (the buffer holds kKeySlack entries more)
     int npair;   // P = 4: length of each of the two pair lists, min(T, R^2)
     int nreg;    // size of the hyperbolic region of the final ranking (P = 2, 4)
     int nreg_pair;   // P = 4: region size of each pair ranking
@@ -66,7 +66,7 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
         L.nreg = (int)region_size(L.npair, L.npair, L.Tcap);
     }
     size_t o = 0;
-    L.off_keys = o;  o += sizeof(unsigned long long) * L.cap;
+    L.off_keys = o;  o += sizeof(unsigned long long) * (L.cap + kKeySlack);
     L.off_hist = o;  o += sizeof(uint32_t) * kSelBins;
     L.off_Ld = o;    o += sizeof(float) * P * R;
     L.off_Lid = o;   o += sizeof(uint32_t) * P * R;
@@ -115,13 +115,14 @@ __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g,
 // compiled for 64 registers, so that two workgroups fit a compute unit: the pass is a chain of dependent
 // steps with many barriers, and a second resident query hides most of them.
 // PF: the number of tree parts when it is compiled in (4), 0: read from the arguments.
-template <int MAXPER, int PF = 0>
-__global__ __launch_bounds__(kRankThreads, MAXPER <= 4 ? 8 : 4) void rank_kernel(RankArgs g, RankOffsets L) {
+template <int MAXPER, int PF = 0, int MODE = kRankPlace>
+__global__ __launch_bounds__(PF == 4 && MAXPER <= 4 ? kRankThreadsFourParts : kRankThreads,
+                             MAXPER > 4 ? 4 : (PF == 4 ? 6 : 8)) void rank_kernel(RankArgs g, RankOffsets L) {
     extern __shared__ __align__(16) unsigned char smem[];
     const uint32_t count = L.force ? (uint32_t)g.nq : g.counters[0];
     for (uint32_t item = blockIdx.x; item < count; item += gridDim.x) {
         const int64_t q = L.force ? (int64_t)item : (int64_t)g.order[item];
-        rank_query<PF, false, MAXPER>(g, L, q, smem, nullptr);
+        rank_query<PF, false, MAXPER, MODE>(g, L, q, smem, nullptr);
     }
 }
 
@@ -250,13 +251,22 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
     // Four tree parts: the pass is a chain of dependent steps, so what counts is how many queries a compute
     // unit works on at once: workgroups of 512 threads (four fit where two of 1024 did) as long as a thread
     // then holds at most eight tuples.
-    if (a.P == 4 && o.Tcap <= 4 * kRankThreadsFourParts)
-        hipLaunchKernelGGL((rank_kernel<4, 4>), dim3(grid), dim3(kRankThreadsFourParts), o.total, s, a, o);
-    else if (a.P == 4 && o.Tcap <= 8 * kRankThreadsFourParts)
-        hipLaunchKernelGGL((rank_kernel<8, 4>), dim3(grid), dim3(kRankThreadsFourParts), o.total, s, a, o);
-    else if (a.P == 4)
-        hipLaunchKernelGGL((rank_kernel<8, 4>), dim3(grid), dim3(kRankThreads), o.total, s, a, o);
-    else if (o.Tcap <= 4 * kRankThreads) hipLaunchKernelGGL(rank_kernel<4>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
+    if (a.P == 4) {
+        const int threads = o.Tcap <= 8 * kRankThreadsFourParts ? kRankThreadsFourParts : kRankThreads;
+        // the kernel whose region walks deal out units of a row instead of rows (see for_region) where the three
+        // rankings of a query would otherwise wait for their first wavefront: 1.3 = a unit's cost against a row's
+        const WalkCost pair = walk_cost(a.R, a.R, o.npair, threads / kWave);
+        const WalkCost last = walk_cost(o.npair, o.npair, o.Tcap, threads / kWave);
+        const bool even = 10 * (2 * pair.rows_dealt + last.rows_dealt) > 13 * (2 * pair.units_dealt + last.units_dealt);
+        constexpr int kEven = kRankPlace | kRankEven;
+        if (o.Tcap <= 4 * kRankThreadsFourParts) {
+            if (even) hipLaunchKernelGGL((rank_kernel<4, 4, kEven>), dim3(grid), dim3(threads), o.total, s, a, o);
+            else hipLaunchKernelGGL((rank_kernel<4, 4>), dim3(grid), dim3(threads), o.total, s, a, o);
+        } else {
+            if (even) hipLaunchKernelGGL((rank_kernel<8, 4, kEven>), dim3(grid), dim3(threads), o.total, s, a, o);
+            else hipLaunchKernelGGL((rank_kernel<8, 4>), dim3(grid), dim3(threads), o.total, s, a, o);
+        }
+    } else if (o.Tcap <= 4 * kRankThreads) hipLaunchKernelGGL(rank_kernel<4>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     else hipLaunchKernelGGL(rank_kernel<8>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     return hipGetLastError();
 }
@@ -270,6 +280,12 @@ hipError_t configure_rank(size_t max_dynamic_lds) {
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8, 4>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)max_dynamic_lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<4, 4, kRankPlace | kRankEven>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8, 4, kRankPlace | kRankEven>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);

@@ -16,29 +16,91 @@ constexpr int kSelBits = 10;
 constexpr int kSelBins = 1 << kSelBits;
 constexpr int kMidT = 128;         // tuples ranked first by the full pass; all T only if they do not fill C
 constexpr int kRegionSplit = 64;   // rows below it are walked along b, the rest of the region along a
+constexpr int kBinRankMax = 64;    // placing keys by histogram bin: most keys a bin may hold (each is ranked against its bin)
+constexpr int kKeySlack = 64;      // entries of the key buffer beyond its power-of-two capacity (the last bin's excess)
+constexpr int kRankPlace = 1, kRankEven = 2;   // options of rank_pairs / rank_query
 
 // Calls f(ordered sum bits, a, b) for every pair of the region {a < nA, b < nB, (a+1)(b+1) <= Tn},
 // each pair once, spread over the workgroup.  Rows a < kRegionSplit are walked along b (they are
 // long); the remaining pairs have b < Tn / (kRegionSplit + 1) and are walked along a, so lanes stay
 // busy in the thin tail of the hyperbola as well.
-template <typename F>
+// Whole rows are dealt out to the wavefronts, or -- BAL -- units of 64 consecutive entries of a row: lane
+// i holds the number of units of row i, a prefix sum over the lanes numbers the units, and a wavefront
+// finds the row of its next unit with one ballot.  That costs a few instructions per unit and pays where
+// the first rows are many times longer than the rest (long lists, few tuples), so that with whole rows
+// most wavefronts would wait for the one that holds row 0; the host picks the kernel (walk_cost).
+template <bool BAL, typename F>
 __device__ __forceinline__ void for_region(const float* A, int nA, const float* B, int nB, int Tn, int wave,
                                            int lane, F&& f) {
     const int nwaves = (int)blockDim.x / kWave;
     const int rows = min(min(nA, Tn), kRegionSplit);
+    const int cols = nA > kRegionSplit ? min(nB, Tn / (kRegionSplit + 1)) : 0;
+    if (BAL && cols <= kWave) {
+        {
+            const int cnt = lane < rows ? region_row_count(lane, nB, Tn) : 0;
+            const uint32_t units = (uint32_t)(cnt + kWave - 1) / kWave;
+            const uint32_t incl = wave_inclusive_sum(units, lane);
+            const int total = __builtin_amdgcn_readlane((int)incl, kWave - 1);
+            for (int u = wave; u < total; u += nwaves) {
+                const int a = __builtin_amdgcn_readfirstlane(__popcll(__ballot(incl <= (uint32_t)u)));
+                const int first = __builtin_amdgcn_readlane((int)(incl - units), a);
+                const int n = __builtin_amdgcn_readlane(cnt, a);
+                const int b = (u - first) * kWave + lane;
+                const float da = A[a];
+                if (b < n) f(mono_key(da + B[b]), (uint32_t)a, (uint32_t)b);
+            }
+        }
+        if (cols > 0) {
+            const int hi = lane < cols ? min(nA, Tn / (lane + 1)) : kRegionSplit;     // column `lane`: a in [kRegionSplit, hi)
+            const int cnt = hi - kRegionSplit;
+            const uint32_t units = (uint32_t)(cnt + kWave - 1) / kWave;
+            const uint32_t incl = wave_inclusive_sum(units, lane);
+            const int total = __builtin_amdgcn_readlane((int)incl, kWave - 1);
+            for (int u = wave; u < total; u += nwaves) {
+                const int b = __builtin_amdgcn_readfirstlane(__popcll(__ballot(incl <= (uint32_t)u)));
+                const int first = __builtin_amdgcn_readlane((int)(incl - units), b);
+                const int end = __builtin_amdgcn_readlane(hi, b);
+                const int a = kRegionSplit + (u - first) * kWave + lane;
+                const float db = B[b];
+                if (a < end) f(mono_key(A[a] + db), (uint32_t)a, (uint32_t)b);
+            }
+        }
+        return;
+    }
     for (int a = wave; a < rows; a += nwaves) {
         const int cnt = region_row_count(a, nB, Tn);
         const float da = A[a];
         for (int b = lane; b < cnt; b += kWave) f(mono_key(da + B[b]), (uint32_t)a, (uint32_t)b);
     }
-    if (nA > kRegionSplit) {
-        const int cols = min(nB, Tn / (kRegionSplit + 1));
-        for (int b = wave; b < cols; b += nwaves) {
-            const int hi = min(nA, Tn / (b + 1));
-            const float db = B[b];
-            for (int a = kRegionSplit + lane; a < hi; a += kWave) f(mono_key(A[a] + db), (uint32_t)a, (uint32_t)b);
-        }
+    for (int b = wave; b < cols; b += nwaves) {
+        const int hi = min(nA, Tn / (b + 1));
+        const float db = B[b];
+        for (int a = kRegionSplit + lane; a < hi; a += kWave) f(mono_key(A[a] + db), (uint32_t)a, (uint32_t)b);
     }
+}
+
+// Host side of the choice above: the wave-iterations of the busiest wavefront when whole rows (columns)
+// are dealt out (.x), and an even share of the units (.y).
+struct WalkCost { long rows_dealt, units_dealt; };
+__host__ inline WalkCost walk_cost(int nA, int nB, int Tn, int nwaves) {
+    const int rows = nA < Tn ? (nA < kRegionSplit ? nA : kRegionSplit) : (Tn < kRegionSplit ? Tn : kRegionSplit);
+    const int cols = nA > kRegionSplit ? (nB < Tn / (kRegionSplit + 1) ? nB : Tn / (kRegionSplit + 1)) : 0;
+    long total = 0, first_wave = 0;
+    for (int a = 0; a < rows; ++a) {
+        const int u = (region_row_count(a, nB, Tn) + kWave - 1) / kWave;
+        total += u;
+        if (a % nwaves == 0) first_wave += u;
+    }
+    for (int b = 0; b < cols; ++b) {
+        const int hi = nA < Tn / (b + 1) ? nA : Tn / (b + 1);
+        const int u = (hi - kRegionSplit + kWave - 1) / kWave;
+        total += u;
+        if (b % nwaves == 0) first_wave += u;
+    }
+    WalkCost c;
+    c.rows_dealt = first_wave;
+    c.units_dealt = cols > kWave ? first_wave : (total + nwaves - 1) / nwaves;
+    return c;
 }
 
 // Appends `key` to keys[] for every lane with take set; one LDS atomic per wavefront instruction.
@@ -55,24 +117,114 @@ __device__ __forceinline__ void wave_append(bool take, unsigned long long key, u
 
 // Leaves in keys[0..Tn) the first Tn pairs (a, b) of two ascending lists A[0..nA), B[0..nB) in the
 // order (fl32(A[a] + B[b]), a, b), as sorted keys (ordered sum bits << 32 | a << 16 | b).
-// Tn <= nA * nB; nreg = size of the region (a+1)(b+1) <= Tn; cap = entries of keys[] (a power of two
-// >= Tn).  If the region fits it is sorted directly; otherwise the Tn-th smallest key is found by a
-// radix select over the region (sums recomputed in every pass, never stored), ties at that key are cut
-// by (a, b), and only the Tn smallest are collected and sorted.  All threads call it; ends with a barrier.
-template <int MAXE>
+// Tn <= nA * nB; nreg = size of the region (a+1)(b+1) <= Tn; cap = a power of two >= Tn, keys[] holds
+// cap + kKeySlack entries.  If the region fits it is sorted directly.  Otherwise the keys are placed by
+// counting: a 1024-bin histogram over the range that can hold the Tn-th key, a prefix sum that makes
+// every bin's count its first position, a second walk that drops each key into its bin's range, and a
+// last step in which every key counts the smaller keys of its own bin -- no comparison network.  Where a
+// bin is too full for that (heavy ties) the Tn-th smallest key is found by a radix select over the region
+// (sums recomputed in every pass, never stored), ties at that key are cut by (a, b), and only the Tn
+// smallest are collected and sorted.  part: 16 words for the prefix sum.  All threads call it; ends with
+// a barrier.
+// MODE: kRankPlace = place by bin where possible (without it: the select-and-sort path only, which needs
+// fewer registers where the ranking is a rarely taken branch of a larger kernel); kRankEven = the region
+// walks deal out units instead of rows.
+template <int MAXE, int MODE>
 __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* B, int nB, int Tn, int nreg,
-                                           int cap, unsigned long long* keys, uint32_t* hist, uint32_t* misc) {
+                                           int cap, unsigned long long* keys, uint32_t* hist, uint32_t* misc,
+                                           uint32_t* part) {
+    constexpr bool BAL = (MODE & kRankEven) != 0;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, nt = blockDim.x;
     uint32_t tau = 0xffffffffu, a_cut = 0xffffffffu, b_cut = 0xffffffffu;
     const bool all = nreg <= (next_pow2(Tn) < 64 ? 64 : next_pow2(Tn));   // sorting the region costs no more than sorting Tn keys
+    if (!all && (MODE & kRankPlace) != 0) {
+        // ---- placing by bin -----------------------------------------------------------------------------
+        // An upper bound of the Tn-th smallest key: the largest key of any rectangle a < sa, b < sb with
+        // sa * sb >= Tn is its corner's (both lists ascend, rounding is monotone), and at least Tn keys are
+        // not above it.  Rectangles sa = 1, 2, 4, .. and sa = nA; the smallest corner bounds the histogram.
+        const uint32_t lo_key = mono_key(A[0] + B[0]);
+        uint32_t up_key;
+        {
+            int sa = lane < 31 ? (1 << min(lane, 30)) : nA;
+            if (lane >= 31 || sa > nA) sa = nA;
+            const int sb = (Tn + sa - 1) / sa;
+            up_key = sb <= nB ? mono_key(A[sa - 1] + B[sb - 1]) : 0xffffffffu;
+            up_key = wave_min_u32(up_key);               // sa = nA always qualifies: Tn <= nA * nB
+        }
+        const uint32_t prange = up_key - lo_key;
+        const int pwidth = 32 - __clz((int)(prange | 1u));
+        const int pshift = pwidth > kSelBits ? pwidth - kSelBits : 0;
+        for (int e = tid; e < kSelBins; e += nt) hist[e] = 0;
+        if (tid == 0) misc[5] = 0;                       // a bin too full to rank, or more keys than keys[] holds
+        __syncthreads();
+        for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+            if (k32 <= up_key) atomicAdd(&hist[(k32 - lo_key) >> pshift], 1u);
+        });
+        __syncthreads();
+        {
+            // counts -> first positions, in place; the thread that owns the bin of the Tn-th key notes it
+            const int bpt = kSelBins / nt;               // bins per thread (nt divides 1024)
+            uint32_t sum = 0;
+            for (int j = 0; j < bpt; ++j) sum += hist[tid * bpt + j];
+            uint32_t total;
+            uint32_t c = block_exclusive_sum(sum, part, total);
+            for (int j = 0; j < bpt; ++j) {
+                const uint32_t cnt = hist[tid * bpt + j];
+                hist[tid * bpt + j] = c;
+                if (c < (uint32_t)Tn) {
+                    if (cnt > (uint32_t)kBinRankMax) misc[5] = 1;
+                    if ((uint32_t)Tn <= c + cnt) {
+                        misc[2] = (uint32_t)(tid * bpt + j);
+                        misc[3] = c;
+                        misc[4] = cnt;
+                        if (c + cnt > (uint32_t)(cap + kKeySlack)) misc[5] = 1;
+                    }
+                }
+                c += cnt;
+            }
+        }
+        __syncthreads();
+        if (misc[5] == 0) {
+            const uint32_t bsel = misc[2], nkeys = misc[3] + misc[4];
+            for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+                if (k32 > up_key) return;
+                const uint32_t bin = (k32 - lo_key) >> pshift;
+                if (bin > bsel) return;
+                keys[atomicAdd(&hist[bin], 1u)] = ((unsigned long long)k32 << 32) | (a << 16) | b;
+            });
+            __syncthreads();
+            // hist[b] is now the end of bin b (the start of bin b + 1) for every b <= bsel
+            unsigned long long mine[MAXE + 1];
+            uint32_t place[MAXE + 1];
+#pragma unroll
+            for (int i = 0; i < MAXE + 1; ++i) {
+                const uint32_t e = (uint32_t)(tid + i * nt);
+                place[i] = 0xffffffffu;
+                if (e >= nkeys) continue;
+                const unsigned long long key = keys[e];
+                const uint32_t bin = ((uint32_t)(key >> 32) - lo_key) >> pshift;
+                const uint32_t first = bin ? hist[bin - 1] : 0u, end = hist[bin];
+                uint32_t r = first;
+                for (uint32_t x = first; x < end; ++x) r += keys[x] < key ? 1u : 0u;
+                mine[i] = key;
+                place[i] = r;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < MAXE + 1; ++i)
+                if (place[i] < (uint32_t)Tn) keys[place[i]] = mine[i];
+            __syncthreads();
+            return;
+        }
+    }
     if (!all) {
-        // ---- usual case: one histogram over the range of the region's keys ----------------------------
+        // ---- a bin was too full (or no placing): one histogram over the range of the region's keys ---
+        const uint32_t lo_key = mono_key(A[0] + B[0]);
         // The region's smallest key is A[0]+B[0]; its largest is the last key of some row (both lists
         // ascend).  1024 bins over that range: the bin holding the Tn-th key is found, the
         // keys of lower bins go straight to keys[], the keys of that bin (a handful) to a side buffer
         // that reuses the histogram, is sorted, and gives its first Tn - (lower count).
         constexpr int kTailCap = kSelBins / 2;           // 64-bit entries the histogram's memory holds
-        const uint32_t lo_key = mono_key(A[0] + B[0]);
         if (tid < 2) misc[tid] = 0;                      // [0] range maximum, [1] unused here
         for (int e = tid; e < kSelBins; e += nt) hist[e] = 0;
         __syncthreads();
@@ -89,7 +241,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         const uint32_t range = hi_key - lo_key;
         const int width = 32 - __clz((int)(range | 1u));
         const int shift = width > kSelBits ? width - kSelBits : 0;
-        for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+        for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
             atomicAdd(&hist[(k32 - lo_key) >> shift], 1u);
         });
         __syncthreads();
@@ -108,7 +260,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         const uint32_t bsel = misc[2], below = misc[3], inbin = misc[4];
         if (inbin <= (uint32_t)kTailCap) {
             unsigned long long* tail = reinterpret_cast<unsigned long long*>(hist);
-            for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+            for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
                 const uint32_t bin = (k32 - lo_key) >> shift;
                 const unsigned long long key = ((unsigned long long)k32 << 32) | (a << 16) | b;
                 wave_append(bin < bsel, key, keys, &misc[0], lane);
@@ -135,7 +287,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
             __syncthreads();
             const int sh = shifts[pass];
             const uint32_t dm = (1u << nbits[pass]) - 1u;
-            for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+            for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
                 if ((k32 & mask) == prefix) atomicAdd(&hist[(k32 >> sh) & dm], 1u);
             });
             __syncthreads();
@@ -155,7 +307,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
             auto pass = [&](auto&& digit_of) {           // digit_of(k32, a, b) -> bin or 0xffffffff (skip)
                 for (int e = tid; e < kSelBins; e += nt) hist[e] = 0;
                 __syncthreads();
-                for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+                for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
                     const uint32_t d = digit_of(k32, a, b);
                     if (d != 0xffffffffu) atomicAdd(&hist[d], 1u);
                 });
@@ -182,7 +334,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
     }
     if (tid == 0) misc[0] = 0;
     __syncthreads();
-    for_region(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+    for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
         bool take = all || k32 < tau;
         if (!all && k32 == tau) take = a_cut == 0xffffffffu || a < a_cut || (a == a_cut && b <= b_cut);
         wave_append(take, ((unsigned long long)k32 << 32) | (a << 16) | b, keys, &misc[0], lane);
@@ -199,7 +351,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
 // of candidates) go to out_counts[0..1] in LDS instead of g.meta (the caller goes on with the query).
 // MAXPER (2, 4 or 8): tuples a thread may have to hold, L.Tcap <= MAXPER * blockDim.x.
 // smem: the workgroup's LDS, laid out by L.  Every thread calls it; ends with a barrier.
-template <int PF, bool TO_LDS, int MAXPER>
+template <int PF, bool TO_LDS, int MAXPER, int MODE>
 __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets& L, int64_t q, unsigned char* smem,
                                            uint32_t* out_counts) {
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(smem + L.keys);
@@ -237,21 +389,29 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
                 keys[e] = ((unsigned long long)mono_key(sLd[e]) << 32) | (unsigned)e;
             __syncthreads();                 // the list is already sorted by (distance, id)
         } else if (P == 2) {
-            rank_pairs<MAXPER>(sLd, R, sLd + R, R, Tn, attempt == 0 ? L.nreg_mid : L.nreg, L.cap, keys, hist, misc);
+            rank_pairs<MAXPER, MODE>(sLd, R, sLd + R, R, Tn, attempt == 0 ? L.nreg_mid : L.nreg, L.cap, keys, hist, misc,
+                                     part);
         } else {
-            // parts (1,2) and (3,4) first; then pairs of positions in those two lists
+            // parts (1,2) and (3,4) first; then pairs of positions in those two lists.  One loop, so that the
+            // ranking code exists once in the kernel: three copies of it do not fit the instruction cache.
             const int np = L.npair;
-            for (int half = 0; half < 2; ++half) {
-                rank_pairs<MAXPER>(sLd + 2 * half * R, R, sLd + (2 * half + 1) * R, R, np, L.nreg_pair, L.cap, keys, hist,
-                           misc);
-                for (int e = tid; e < np; e += nt) {
-                    const unsigned long long key = keys[e];
-                    ps[half * np + e] = mono_inv((uint32_t)(key >> 32));
-                    pt[half * np + e] = (uint32_t)key;
+#pragma nounroll
+            for (int stage = 0; stage < 3; ++stage) {
+                const bool last = stage == 2;
+                const float* A = last ? ps : sLd + 2 * stage * R;
+                const float* B = last ? ps + np : sLd + (2 * stage + 1) * R;
+                const int n = last ? np : R;
+                rank_pairs<MAXPER, MODE>(A, n, B, n, last ? Tn : np, last ? L.nreg : L.nreg_pair, L.cap, keys, hist, misc,
+                                         part);
+                if (!last) {
+                    for (int e = tid; e < np; e += nt) {
+                        const unsigned long long key = keys[e];
+                        ps[stage * np + e] = mono_inv((uint32_t)(key >> 32));
+                        pt[stage * np + e] = (uint32_t)key;
+                    }
+                    __syncthreads();
                 }
-                __syncthreads();
             }
-            rank_pairs<MAXPER>(ps, np, ps + np, np, Tn, L.nreg, L.cap, keys, hist, misc);
         }
 
         // ---- tuple -> bin number -> slot -> run of the inverted list ---------------------------

@@ -370,7 +370,7 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
             ranked = misc[kRanked + 2] != 0u;
             __syncthreads();
         }
-        if (!ranked) rank_query<2, true, kFusedPer>(rk, RL, q, smem, misc + kRanked);
+        if (!ranked) rank_query<2, true, kFusedPer, 0>(rk, RL, q, smem, misc + kRanked);
         meta = make_uint2(misc[kRanked], misc[kRanked + 1]);
     }
     const uint2* qruns = g.runs + (size_t)q * T;

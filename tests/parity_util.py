@@ -99,7 +99,8 @@ def to_np(t):
     return t.detach().cpu().numpy()
 
 
-def check_query_stages(ix, y, taps, q, k, w, T, C, out_ids, out_dists, exact=False, order="fullsort"):
+def check_query_stages(ix, y, taps, q, k, w, T, C, out_ids, out_dists, exact=False, order="fullsort",
+                       truncate_pairs=False):
     """ix: oracle PQTIndex (same file the GPU loaded); taps: dict of numpy arrays for the batch;
     q: row in the batch.  Raises AssertionError naming the stage.  Returns the oracle trace of the
     pure float64 run."""
@@ -108,7 +109,7 @@ def check_query_stages(ix, y, taps, q, k, w, T, C, out_ids, out_dists, exact=Fal
     y64 = np.asarray(y, dtype=np.float64)
     S = subpart_magnitudes(ix, y64)
     ka = kappa(ix.D // M)             # a[m][i]: accumulations over the D / M dimensions of a sub-part
-    tr = Q.query(ix, y, k, w, T=T, C=C, order_method=order)
+    tr = Q.query(ix, y, k, w, T=T, C=C, order_method=order, truncate_pairs=truncate_pairs)
 
     # ---- S1 level-1 sub-part distances (float) ---------------------------------------------------
     a_g = taps["a"][q]
@@ -138,7 +139,7 @@ def check_query_stages(ix, y, taps, q, k, w, T, C, out_ids, out_dists, exact=Fal
     if order == "static":        # the slope is chosen from the GPU's own fp32 lists, the table is fixed
         tup_r, keys_r = Q.bin_order_static([Ld_g[p].astype(np.float32) for p in range(P)], T)
     else:
-        tup_r, keys_r = Q.bin_order([Ld_g[p].astype(np.float32) for p in range(P)], T)
+        tup_r, keys_r = Q.bin_order([Ld_g[p].astype(np.float32) for p in range(P)], T, truncate_pairs=truncate_pairs)
     nt = int(taps["n_tuples"][q])
     assert nt == tup_r.shape[0], "S4 number of tuples"
     assert np.array_equal(taps["tuples"][q][:nt, :P].astype(np.int64), tup_r), "S4 tuple order"

@@ -39,7 +39,7 @@ def _run_debug(pqt, gix, Y, k, w):
     return PU.to_np(ids), PU.to_np(dists), {n: PU.to_np(t) for n, t in taps.items()}
 
 
-def _stagewise(pqt, ix, path, Y, k, w, T, C, exact=False, must_match_all=False, order="fullsort"):
+def _stagewise(pqt, ix, path, Y, k, w, T, C, exact=False, must_match_all=False, order="fullsort", truncate_pairs=False):
     gix = pqt.pqt_index_load(path, 0)
     try:
         pqt.pqt_set_budget(gix, T, C)
@@ -51,7 +51,8 @@ def _stagewise(pqt, ix, path, Y, k, w, T, C, exact=False, must_match_all=False, 
     same = decided = 0
     for q in range(Y.shape[0]):
         print(f"query {q}", flush=True)
-        tr = PU.check_query_stages(ix, Y[q], taps, q, k, w, T, C, ids, dists, exact=exact, order=order)
+        tr = PU.check_query_stages(ix, Y[q], taps, q, k, w, T, C, ids, dists, exact=exact, order=order,
+                                   truncate_pairs=truncate_pairs)
         s, d = PU.end_to_end_agreement(tr, ids[q], dists[q])
         if exact or must_match_all:
             assert s, f"query {q}: ids differ from the float64 oracle"
@@ -795,6 +796,26 @@ def test_four_part_index(pqt, tmp_path):
     path = str(tmp_path / "p4h.pqt")
     IO.write_index(path, ixh)
     _stagewise(pqt, ixh, path, Y[:12], 10, 2, 300, 1024)
+
+
+def test_four_part_long_lists(pqt, tmp_path):
+    """P = 4 with lists of 128 and 64 children and T = 1024: the pair lists are cut at T, the last ranking's
+    region has rows of 1024 entries beside rows of 16, so the kernel that deals out units of a row (not rows)
+    to its wavefronts runs, and the keys are placed by histogram bin; hashed and unhashed bins."""
+    from workloads import tiny_mixture
+    X = tiny_mixture(20000, d=32, seed=5)
+    Y = tiny_mixture(12, d=32, seed=6)
+    ixh = B.build_index(X, P=4, k1=16, k2=16, M=8, H=65537, T=1024, C=3000, iters=4)
+    path = str(tmp_path / "p4_long_hashed.pqt")
+    IO.write_index(path, ixh)
+    # (the oracle with its pair lists cut at T, which its pin test shows to be the same order: the uncut
+    # form sorts R^4 tuples)
+    _stagewise(pqt, ixh, path, Y, 10, 8, 1024, 3000, truncate_pairs=True)         # R = 128
+    _stagewise(pqt, ixh, path, Y[:6], 10, 4, 700, 1500, truncate_pairs=True)      # R = 64, T not a power of two
+    ix = B.build_index(X, P=4, k1=8, k2=8, M=8, T=1024, C=3000, iters=4)
+    path = str(tmp_path / "p4_long.pqt")
+    IO.write_index(path, ix)
+    _stagewise(pqt, ix, path, Y, 10, 8, 1024, 3000, truncate_pairs=True)          # R = 64, 2^24 bins, unhashed
 
 
 def test_four_part_exact_arithmetic_heavily_tied(pqt, tmp_path):
