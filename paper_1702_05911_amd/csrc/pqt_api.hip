@@ -121,7 +121,7 @@ bool can_fuse_ranking(const pqt_index* ix, int k, int w, int64_t nq) {
     if (ix->P != 2) return false;
     const int R = w * (int)ix->k2;
     const int threads = rerank_threads(ix, nullptr, nq);
-    const pqt::RankOffsets ro = pqt::rank_offsets(ix->P, R, ix->T, ix->hashed);
+    const pqt::RankOffsets ro = pqt::rank_offsets(ix->P, R, ix->T, ix->hashed, false);
     if (ro.Tcap > pqt::rerank_fused_tuples_per_thread() * threads) return false;
     return pqt::rerank_lds_bytes(ix->M, ix->k1, ix->T, ix->C, k, threads, ro.total, (int)ix->code_format,
                                  rerank_runs_in_lds(ix)) <= ix->lds_limit;

@@ -71,8 +71,10 @@ struct RankOffsets {   // LDS layout of the full ranking pass (computed once on 
 };
 // number of (r1, r2) pairs that can be among the first T of an R x R sum table
 int rank_region_size(int R, int T);
+// LDS of the stand-alone ranking kernel / layout of a ranking (place: with the room the stand-alone kernels
+// use for placing keys by bin; without: the ranking inside the re-rank kernel)
 size_t rank_lds_bytes(int P, int R, int T, int hashed);
-RankOffsets rank_offsets(int P, int R, int T, int hashed);
+RankOffsets rank_offsets(int P, int R, int T, int hashed, bool place);
 // does a head pass exist for these arguments (two tree parts, no taps of the ranking)?
 bool rank_has_head(const RankArgs& a);
 // defer_full: only the head pass is launched; the caller runs the full pass of the unfinished

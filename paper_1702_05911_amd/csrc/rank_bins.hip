@@ -33,7 +33,7 @@ int rank_region_size(int R, int T) { return (int)region_size(R, R, T); }
 
 struct RankLds {
     int Tcap;    // tuples examined: min(T, R^P)
-    int cap;     // sort buffer: next_pow2(Tcap), at least 64 (the buffer holds kKeySlack entries more)
+    int cap;     // sort buffer: next_pow2(Tcap), at least 64 (with `place` the buffer holds kKeySlack entries more)
     int npair;   // P = 4: length of each of the two pair lists, min(T, R^2)
     int nreg;    // size of the hyperbolic region of the final ranking (P = 2, 4)
     int nreg_pair;   // P = 4: region size of each pair ranking
@@ -44,7 +44,8 @@ struct RankLds {
 };
 
 // hashed: slots may repeat (their lengths and numbers go through LDS); 2: the slots tap also wants the numbers
-static RankLds rank_layout(int P, int R, int T, int hashed) {
+// place: room for placing the keys by bin (the stand-alone kernels; see rank_pairs)
+static RankLds rank_layout(int P, int R, int T, int hashed, bool place) {
     RankLds L;
     long total_tuples = 1;
     for (int p = 0; p < P; ++p) total_tuples = (total_tuples * R > (1L << 40)) ? (1L << 40) : total_tuples * R;
@@ -66,8 +67,8 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
         L.nreg = (int)region_size(L.npair, L.npair, L.Tcap);
     }
     size_t o = 0;
-    L.off_keys = o;  o += sizeof(unsigned long long) * (L.cap + kKeySlack);
-    L.off_hist = o;  o += sizeof(uint32_t) * kSelBins;
+    L.off_keys = o;  o += sizeof(unsigned long long) * (L.cap + (place ? kKeySlack : 0));
+    L.off_hist = o;  o += sizeof(uint32_t) * (place ? kPlaceBins : kSelBins);
     L.off_Ld = o;    o += sizeof(float) * P * R;
     L.off_Lid = o;   o += sizeof(uint32_t) * P * R;
     L.off_ps = o;    o += sizeof(float) * 2 * L.npair;        // summed distances of the two pair lists
@@ -80,7 +81,7 @@ static RankLds rank_layout(int P, int R, int T, int hashed) {
     return L;
 }
 
-size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed).total; }
+size_t rank_lds_bytes(int P, int R, int T, int hashed) { return rank_layout(P, R, T, hashed, true).total; }
 
 
 __global__ __launch_bounds__(kRankHeadThreads) void rank_head_kernel(RankArgs g, int Tn, HeadLevels lv) {
@@ -203,8 +204,8 @@ hipError_t launch_rank_static(const RankArgs& a, const StaticOrder& so, hipStrea
     return hipGetLastError();
 }
 
-RankOffsets rank_offsets(int P, int R, int T, int hashed) {
-    const RankLds L = rank_layout(P, R, T, hashed);
+RankOffsets rank_offsets(int P, int R, int T, int hashed, bool place) {
+    const RankLds L = rank_layout(P, R, T, hashed, place);
     RankOffsets o;
     o.Tcap = L.Tcap; o.cap = L.cap; o.npair = L.npair; o.nreg = L.nreg; o.nreg_pair = L.nreg_pair;
     o.Tmid = L.Tmid; o.nreg_mid = L.nreg_mid;
@@ -224,7 +225,7 @@ bool rank_has_head(const RankArgs& a) {
 
 hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
     if (a.nq <= 0) return hipSuccess;
-    RankOffsets o = rank_offsets(a.P, a.R, a.T, a.hashed ? 1 : (a.slots ? 2 : 0));
+    RankOffsets o = rank_offsets(a.P, a.R, a.T, a.hashed ? 1 : (a.slots ? 2 : 0), true);
     const bool head = rank_has_head(a);
     if (defer_full && !head) return hipErrorInvalidValue;
     o.force = head ? 0 : 1;

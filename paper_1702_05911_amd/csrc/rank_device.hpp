@@ -18,6 +18,9 @@ constexpr int kMidT = 128;         // tuples ranked first by the full pass; all 
 constexpr int kRegionSplit = 64;   // rows below it are walked along b, the rest of the region along a
 constexpr int kBinRankMax = 64;    // placing keys by histogram bin: most keys a bin may hold (each is ranked against its bin)
 constexpr int kKeySlack = 64;      // entries of the key buffer beyond its power-of-two capacity (the last bin's excess)
+constexpr int kPlaceBits = 11;
+constexpr int kPlaceBins = 1 << kPlaceBits;    // bins of the placing histogram (the select path uses the first kSelBins)
+constexpr int kPlaceMin = 256;     // regions up to this size are sorted as they are
 constexpr int kRankPlace = 1, kRankEven = 2;   // options of rank_pairs / rank_query
 
 // Calls f(ordered sum bits, a, b) for every pair of the region {a < nA, b < nB, (a+1)(b+1) <= Tn},
@@ -118,14 +121,14 @@ __device__ __forceinline__ void wave_append(bool take, unsigned long long key, u
 // Leaves in keys[0..Tn) the first Tn pairs (a, b) of two ascending lists A[0..nA), B[0..nB) in the
 // order (fl32(A[a] + B[b]), a, b), as sorted keys (ordered sum bits << 32 | a << 16 | b).
 // Tn <= nA * nB; nreg = size of the region (a+1)(b+1) <= Tn; cap = a power of two >= Tn, keys[] holds
-// cap + kKeySlack entries.  If the region fits it is sorted directly.  Otherwise the keys are placed by
-// counting: a 1024-bin histogram over the range that can hold the Tn-th key, a prefix sum that makes
-// every bin's count its first position, a second walk that drops each key into its bin's range, and a
-// last step in which every key counts the smaller keys of its own bin -- no comparison network.  Where a
-// bin is too full for that (heavy ties) the Tn-th smallest key is found by a radix select over the region
-// (sums recomputed in every pass, never stored), ties at that key are cut by (a, b), and only the Tn
-// smallest are collected and sorted.  part: 16 words for the prefix sum.  All threads call it; ends with
-// a barrier.
+// cap entries (cap + kKeySlack where keys are placed by bin).  A small region is sorted as it is.
+// Otherwise the keys are placed by counting: a 2048-bin histogram over the range that can hold the Tn-th
+// key, a prefix sum that makes every bin's count its first position, a second walk that drops each key
+// into its bin's range, and a last step in which every key counts the smaller keys of its own bin -- no
+// comparison network.  Where a bin is too full for that (heavy ties) the Tn-th smallest key is found by
+// a radix select over the region (sums recomputed in every pass, never stored), ties at that key are cut
+// by (a, b), and only the Tn smallest are collected and sorted.  part: 16 words for the prefix sum.  All
+// threads call it; ends with a barrier.
 // MODE: kRankPlace = place by bin where possible (without it: the select-and-sort path only, which needs
 // fewer registers where the ranking is a rarely taken branch of a larger kernel); kRankEven = the region
 // walks deal out units instead of rows.
@@ -137,7 +140,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, nt = blockDim.x;
     uint32_t tau = 0xffffffffu, a_cut = 0xffffffffu, b_cut = 0xffffffffu;
     const bool all = nreg <= (next_pow2(Tn) < 64 ? 64 : next_pow2(Tn));   // sorting the region costs no more than sorting Tn keys
-    if (!all && (MODE & kRankPlace) != 0) {
+    if ((MODE & kRankPlace) != 0 && nreg > kPlaceMin) {
         // ---- placing by bin -----------------------------------------------------------------------------
         // An upper bound of the Tn-th smallest key: the largest key of any rectangle a < sa, b < sb with
         // sa * sb >= Tn is its corner's (both lists ascend, rounding is monotone), and at least Tn keys are
@@ -153,8 +156,8 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         }
         const uint32_t prange = up_key - lo_key;
         const int pwidth = 32 - __clz((int)(prange | 1u));
-        const int pshift = pwidth > kSelBits ? pwidth - kSelBits : 0;
-        for (int e = tid; e < kSelBins; e += nt) hist[e] = 0;
+        const int pshift = pwidth > kPlaceBits ? pwidth - kPlaceBits : 0;
+        for (int e = tid; e < kPlaceBins; e += nt) hist[e] = 0;
         if (tid == 0) misc[5] = 0;                       // a bin too full to rank, or more keys than keys[] holds
         __syncthreads();
         for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
@@ -163,7 +166,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         __syncthreads();
         {
             // counts -> first positions, in place; the thread that owns the bin of the Tn-th key notes it
-            const int bpt = kSelBins / nt;               // bins per thread (nt divides 1024)
+            const int bpt = kPlaceBins / nt;             // bins per thread (nt a power of two, at most 1024)
             uint32_t sum = 0;
             for (int j = 0; j < bpt; ++j) sum += hist[tid * bpt + j];
             uint32_t total;

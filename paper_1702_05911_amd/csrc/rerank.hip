@@ -61,7 +61,7 @@ hipError_t launch_rerank(const RerankArgs& a_in, const RankArgs* fused, hipStrea
     if (fused) {
         if (taps || fused->P != 2) return hipErrorInvalidValue;
         rk = *fused;
-        RL = rank_offsets(rk.P, rk.R, rk.T, rk.hashed);
+        RL = rank_offsets(rk.P, rk.R, rk.T, rk.hashed, false);
         if (RL.Tcap > rerank_fused_tuples_per_thread() * a.threads) return hipErrorInvalidValue;
         // the wavefront's two lists lie at the start of the workgroup's LDS (table, survivor list and
         // histogram are not in use yet, and the arrays that receive the result come after them)
