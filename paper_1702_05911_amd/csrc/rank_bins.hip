@@ -250,23 +250,14 @@ hipError_t launch_rank(const RankArgs& a, hipStream_t s, bool defer_full) {
     }
     const unsigned grid = head ? (unsigned)(a.nq < 1024 ? a.nq : 1024) : (unsigned)a.nq;
     // Four tree parts: the pass is a chain of dependent steps, so what counts is how many queries a compute
-    // unit works on at once: workgroups of 512 threads (four fit where two of 1024 did) as long as a thread
-    // then holds at most eight tuples.
+    // unit works on at once: workgroups of 512 threads (their LDS lets three share a compute unit, which is
+    // also what the kernel's register budget is set for) as long as a thread then holds at most eight tuples.
     if (a.P == 4) {
         const int threads = o.Tcap <= 8 * kRankThreadsFourParts ? kRankThreadsFourParts : kRankThreads;
-        // the kernel whose region walks deal out units of a row instead of rows (see for_region) where the three
-        // rankings of a query would otherwise wait for their first wavefront: 1.3 = a unit's cost against a row's
-        const WalkCost pair = walk_cost(a.R, a.R, o.npair, threads / kWave);
-        const WalkCost last = walk_cost(o.npair, o.npair, o.Tcap, threads / kWave);
-        const bool even = 10 * (2 * pair.rows_dealt + last.rows_dealt) > 13 * (2 * pair.units_dealt + last.units_dealt);
-        constexpr int kEven = kRankPlace | kRankEven;
-        if (o.Tcap <= 4 * kRankThreadsFourParts) {
-            if (even) hipLaunchKernelGGL((rank_kernel<4, 4, kEven>), dim3(grid), dim3(threads), o.total, s, a, o);
-            else hipLaunchKernelGGL((rank_kernel<4, 4>), dim3(grid), dim3(threads), o.total, s, a, o);
-        } else {
-            if (even) hipLaunchKernelGGL((rank_kernel<8, 4, kEven>), dim3(grid), dim3(threads), o.total, s, a, o);
-            else hipLaunchKernelGGL((rank_kernel<8, 4>), dim3(grid), dim3(threads), o.total, s, a, o);
-        }
+        if (o.Tcap <= 4 * kRankThreadsFourParts)
+            hipLaunchKernelGGL((rank_kernel<4, 4>), dim3(grid), dim3(threads), o.total, s, a, o);
+        else
+            hipLaunchKernelGGL((rank_kernel<8, 4>), dim3(grid), dim3(threads), o.total, s, a, o);
     } else if (o.Tcap <= 4 * kRankThreads) hipLaunchKernelGGL(rank_kernel<4>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     else hipLaunchKernelGGL(rank_kernel<8>, dim3(grid), dim3(kRankThreads), o.total, s, a, o);
     return hipGetLastError();
@@ -282,12 +273,7 @@ hipError_t configure_rank(size_t max_dynamic_lds) {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8, 4>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)max_dynamic_lds);
     if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<4, 4, kRankPlace | kRankEven>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8, 4, kRankPlace | kRankEven>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
-    if (e != hipSuccess) return e;
+
     return hipFuncSetAttribute(reinterpret_cast<const void*>(rank_kernel<8>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)max_dynamic_lds);
 }

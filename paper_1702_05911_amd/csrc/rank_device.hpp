@@ -21,89 +21,44 @@ constexpr int kKeySlack = 64;      // entries of the key buffer beyond its power
 constexpr int kPlaceBits = 11;
 constexpr int kPlaceBins = 1 << kPlaceBits;    // bins of the placing histogram (the select path uses the first kSelBins)
 constexpr int kPlaceMin = 256;     // regions up to this size are sorted as they are
-constexpr int kRankPlace = 1, kRankEven = 2;   // options of rank_pairs / rank_query
+constexpr int kRankPlace = 1;      // option of rank_pairs / rank_query
 
 // Calls f(ordered sum bits, a, b) for every pair of the region {a < nA, b < nB, (a+1)(b+1) <= Tn},
 // each pair once, spread over the workgroup.  Rows a < kRegionSplit are walked along b (they are
 // long); the remaining pairs have b < Tn / (kRegionSplit + 1) and are walked along a, so lanes stay
 // busy in the thin tail of the hyperbola as well.
-// Whole rows are dealt out to the wavefronts, or -- BAL -- units of 64 consecutive entries of a row: lane
-// i holds the number of units of row i, a prefix sum over the lanes numbers the units, and a wavefront
-// finds the row of its next unit with one ballot.  That costs a few instructions per unit and pays where
-// the first rows are many times longer than the rest (long lists, few tuples), so that with whole rows
-// most wavefronts would wait for the one that holds row 0; the host picks the kernel (walk_cost).
-template <bool BAL, typename F>
+// BOUNDED: only pairs whose key is at most `bound` are wanted (f is still called for a few others and
+// tests the key itself): keys ascend along a row, so the wavefront leaves a row at the first 64 entries
+// without a wanted key -- the first rows are many times longer than the part of them that matters, and
+// without the bound most wavefronts would wait for the one that holds row 0.  (Dealing out units of 64
+// entries instead of rows evens the walk as well, at a few instructions per unit; with the bound it gained
+// nothing more: 0.765 against 0.766 ms per 10,000 queries on lists of 128.)
+template <bool BOUNDED, typename F>
 __device__ __forceinline__ void for_region(const float* A, int nA, const float* B, int nB, int Tn, int wave,
-                                           int lane, F&& f) {
+                                           int lane, uint32_t bound, F&& f) {
     const int nwaves = (int)blockDim.x / kWave;
     const int rows = min(min(nA, Tn), kRegionSplit);
-    const int cols = nA > kRegionSplit ? min(nB, Tn / (kRegionSplit + 1)) : 0;
-    if (BAL && cols <= kWave) {
-        {
-            const int cnt = lane < rows ? region_row_count(lane, nB, Tn) : 0;
-            const uint32_t units = (uint32_t)(cnt + kWave - 1) / kWave;
-            const uint32_t incl = wave_inclusive_sum(units, lane);
-            const int total = __builtin_amdgcn_readlane((int)incl, kWave - 1);
-            for (int u = wave; u < total; u += nwaves) {
-                const int a = __builtin_amdgcn_readfirstlane(__popcll(__ballot(incl <= (uint32_t)u)));
-                const int first = __builtin_amdgcn_readlane((int)(incl - units), a);
-                const int n = __builtin_amdgcn_readlane(cnt, a);
-                const int b = (u - first) * kWave + lane;
-                const float da = A[a];
-                if (b < n) f(mono_key(da + B[b]), (uint32_t)a, (uint32_t)b);
-            }
-        }
-        if (cols > 0) {
-            const int hi = lane < cols ? min(nA, Tn / (lane + 1)) : kRegionSplit;     // column `lane`: a in [kRegionSplit, hi)
-            const int cnt = hi - kRegionSplit;
-            const uint32_t units = (uint32_t)(cnt + kWave - 1) / kWave;
-            const uint32_t incl = wave_inclusive_sum(units, lane);
-            const int total = __builtin_amdgcn_readlane((int)incl, kWave - 1);
-            for (int u = wave; u < total; u += nwaves) {
-                const int b = __builtin_amdgcn_readfirstlane(__popcll(__ballot(incl <= (uint32_t)u)));
-                const int first = __builtin_amdgcn_readlane((int)(incl - units), b);
-                const int end = __builtin_amdgcn_readlane(hi, b);
-                const int a = kRegionSplit + (u - first) * kWave + lane;
-                const float db = B[b];
-                if (a < end) f(mono_key(A[a] + db), (uint32_t)a, (uint32_t)b);
-            }
-        }
-        return;
-    }
     for (int a = wave; a < rows; a += nwaves) {
         const int cnt = region_row_count(a, nB, Tn);
         const float da = A[a];
-        for (int b = lane; b < cnt; b += kWave) f(mono_key(da + B[b]), (uint32_t)a, (uint32_t)b);
+        for (int b = lane; b < cnt; b += kWave) {
+            const uint32_t k32 = mono_key(da + B[b]);
+            if (BOUNDED && __ballot(k32 <= bound) == 0) break;
+            f(k32, (uint32_t)a, (uint32_t)b);
+        }
     }
-    for (int b = wave; b < cols; b += nwaves) {
-        const int hi = min(nA, Tn / (b + 1));
-        const float db = B[b];
-        for (int a = kRegionSplit + lane; a < hi; a += kWave) f(mono_key(A[a] + db), (uint32_t)a, (uint32_t)b);
+    if (nA > kRegionSplit) {
+        const int cols = min(nB, Tn / (kRegionSplit + 1));
+        for (int b = wave; b < cols; b += nwaves) {
+            const int hi = min(nA, Tn / (b + 1));
+            const float db = B[b];
+            for (int a = kRegionSplit + lane; a < hi; a += kWave) {
+                const uint32_t k32 = mono_key(A[a] + db);
+                if (BOUNDED && __ballot(k32 <= bound) == 0) break;
+                f(k32, (uint32_t)a, (uint32_t)b);
+            }
+        }
     }
-}
-
-// Host side of the choice above: the wave-iterations of the busiest wavefront when whole rows (columns)
-// are dealt out (.x), and an even share of the units (.y).
-struct WalkCost { long rows_dealt, units_dealt; };
-__host__ inline WalkCost walk_cost(int nA, int nB, int Tn, int nwaves) {
-    const int rows = nA < Tn ? (nA < kRegionSplit ? nA : kRegionSplit) : (Tn < kRegionSplit ? Tn : kRegionSplit);
-    const int cols = nA > kRegionSplit ? (nB < Tn / (kRegionSplit + 1) ? nB : Tn / (kRegionSplit + 1)) : 0;
-    long total = 0, first_wave = 0;
-    for (int a = 0; a < rows; ++a) {
-        const int u = (region_row_count(a, nB, Tn) + kWave - 1) / kWave;
-        total += u;
-        if (a % nwaves == 0) first_wave += u;
-    }
-    for (int b = 0; b < cols; ++b) {
-        const int hi = nA < Tn / (b + 1) ? nA : Tn / (b + 1);
-        const int u = (hi - kRegionSplit + kWave - 1) / kWave;
-        total += u;
-        if (b % nwaves == 0) first_wave += u;
-    }
-    WalkCost c;
-    c.rows_dealt = first_wave;
-    c.units_dealt = cols > kWave ? first_wave : (total + nwaves - 1) / nwaves;
-    return c;
 }
 
 // Appends `key` to keys[] for every lane with take set; one LDS atomic per wavefront instruction.
@@ -130,13 +85,11 @@ __device__ __forceinline__ void wave_append(bool take, unsigned long long key, u
 // by (a, b), and only the Tn smallest are collected and sorted.  part: 16 words for the prefix sum.  All
 // threads call it; ends with a barrier.
 // MODE: kRankPlace = place by bin where possible (without it: the select-and-sort path only, which needs
-// fewer registers where the ranking is a rarely taken branch of a larger kernel); kRankEven = the region
-// walks deal out units instead of rows.
+// fewer registers where the ranking is a rarely taken branch of a larger kernel).
 template <int MAXE, int MODE>
 __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* B, int nB, int Tn, int nreg,
                                            int cap, unsigned long long* keys, uint32_t* hist, uint32_t* misc,
                                            uint32_t* part) {
-    constexpr bool BAL = (MODE & kRankEven) != 0;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave, nt = blockDim.x;
     uint32_t tau = 0xffffffffu, a_cut = 0xffffffffu, b_cut = 0xffffffffu;
     const bool all = nreg <= (next_pow2(Tn) < 64 ? 64 : next_pow2(Tn));   // sorting the region costs no more than sorting Tn keys
@@ -160,7 +113,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         for (int e = tid; e < kPlaceBins; e += nt) hist[e] = 0;
         if (tid == 0) misc[5] = 0;                       // a bin too full to rank, or more keys than keys[] holds
         __syncthreads();
-        for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+        for_region<true>(A, nA, B, nB, Tn, wave, lane, up_key, [&](uint32_t k32, uint32_t, uint32_t) {
             if (k32 <= up_key) atomicAdd(&hist[(k32 - lo_key) >> pshift], 1u);
         });
         __syncthreads();
@@ -189,7 +142,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         __syncthreads();
         if (misc[5] == 0) {
             const uint32_t bsel = misc[2], nkeys = misc[3] + misc[4];
-            for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+            for_region<true>(A, nA, B, nB, Tn, wave, lane, up_key, [&](uint32_t k32, uint32_t a, uint32_t b) {
                 if (k32 > up_key) return;
                 const uint32_t bin = (k32 - lo_key) >> pshift;
                 if (bin > bsel) return;
@@ -244,7 +197,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         const uint32_t range = hi_key - lo_key;
         const int width = 32 - __clz((int)(range | 1u));
         const int shift = width > kSelBits ? width - kSelBits : 0;
-        for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+        for_region<false>(A, nA, B, nB, Tn, wave, lane, 0u, [&](uint32_t k32, uint32_t, uint32_t) {
             atomicAdd(&hist[(k32 - lo_key) >> shift], 1u);
         });
         __syncthreads();
@@ -263,7 +216,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         const uint32_t bsel = misc[2], below = misc[3], inbin = misc[4];
         if (inbin <= (uint32_t)kTailCap) {
             unsigned long long* tail = reinterpret_cast<unsigned long long*>(hist);
-            for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+            for_region<false>(A, nA, B, nB, Tn, wave, lane, 0u, [&](uint32_t k32, uint32_t a, uint32_t b) {
                 const uint32_t bin = (k32 - lo_key) >> shift;
                 const unsigned long long key = ((unsigned long long)k32 << 32) | (a << 16) | b;
                 wave_append(bin < bsel, key, keys, &misc[0], lane);
@@ -290,7 +243,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
             __syncthreads();
             const int sh = shifts[pass];
             const uint32_t dm = (1u << nbits[pass]) - 1u;
-            for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t, uint32_t) {
+            for_region<false>(A, nA, B, nB, Tn, wave, lane, 0u, [&](uint32_t k32, uint32_t, uint32_t) {
                 if ((k32 & mask) == prefix) atomicAdd(&hist[(k32 >> sh) & dm], 1u);
             });
             __syncthreads();
@@ -310,7 +263,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
             auto pass = [&](auto&& digit_of) {           // digit_of(k32, a, b) -> bin or 0xffffffff (skip)
                 for (int e = tid; e < kSelBins; e += nt) hist[e] = 0;
                 __syncthreads();
-                for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+                for_region<false>(A, nA, B, nB, Tn, wave, lane, 0u, [&](uint32_t k32, uint32_t a, uint32_t b) {
                     const uint32_t d = digit_of(k32, a, b);
                     if (d != 0xffffffffu) atomicAdd(&hist[d], 1u);
                 });
@@ -337,7 +290,7 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
     }
     if (tid == 0) misc[0] = 0;
     __syncthreads();
-    for_region<BAL>(A, nA, B, nB, Tn, wave, lane, [&](uint32_t k32, uint32_t a, uint32_t b) {
+    for_region<false>(A, nA, B, nB, Tn, wave, lane, 0u, [&](uint32_t k32, uint32_t a, uint32_t b) {
         bool take = all || k32 < tau;
         if (!all && k32 == tau) take = a_cut == 0xffffffffu || a < a_cut || (a == a_cut && b <= b_cut);
         wave_append(take, ((unsigned long long)k32 << 32) | (a << 16) | b, keys, &misc[0], lane);
