@@ -570,6 +570,7 @@ int run_query(pqt_index* ix, const float* queries, int64_t nq, int k, int w, int
     pqt::RankArgs ra;
     ra.nq = nq; ra.P = ix->P; ra.R = R; ra.T = ix->T; ra.C = ix->C;
     ra.k1k2 = ix->k1 * ix->k2; ra.H = ix->H; ra.hashed = ix->hashed ? 1 : 0;
+    ra.H_inv = ix->H >= 2 ? (uint64_t)((((unsigned __int128)1) << 64) / ix->H) : 0;
     ra.offsets = ix->offsets; ra.L_d = ws.Ld; ra.L_id = ws.Lid;
     ra.runs = ws.runs; ra.meta = ws.meta; ra.counters = ws.counters; ra.order = ws.order;
     ra.n_tuples = tp.n_tuples; ra.tuples = tp.tuples; ra.tuple_keys = tp.tuple_keys; ra.slots = tp.slots;

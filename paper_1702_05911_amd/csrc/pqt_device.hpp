@@ -344,6 +344,16 @@ __device__ __forceinline__ void block_sort_lds(unsigned long long* keys, int n, 
     else block_sort_chunks<8>(keys, n, tid, nthreads);
 }
 
+// bin mod H (Sec. 4: the bin number is hashed into the pointer array) without a 64-bit division:
+// q' = floor(bin * floor(2^64 / H) / 2^64) is the quotient or one less, so one conditional subtraction
+// gives the exact remainder.  H_inv = 0 stands for H = 1.
+__device__ __forceinline__ unsigned long long slot_of_bin(unsigned long long bin, unsigned long long H,
+                                                          unsigned long long H_inv) {
+    if (H_inv == 0) return 0;
+    unsigned long long r = bin - __umul64hi(bin, H_inv) * H;
+    return r >= H ? r - H : r;
+}
+
 __host__ __device__ inline int next_pow2(int v) {
     int p = 1;
     while (p < v) p <<= 1;

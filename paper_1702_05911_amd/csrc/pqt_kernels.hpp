@@ -46,6 +46,7 @@ struct RankArgs {
     int P, R, T, C;
     uint32_t k1k2;
     uint64_t H;
+    uint64_t H_inv;           // floor(2^64 / H) for H >= 2 (slot_of_bin divides by multiplying), else 0
     int hashed;               // H != (k1*k2)^P: slots may repeat within a query
     const uint32_t* offsets;  // H+1
     const float* L_d;

@@ -402,7 +402,7 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
                 lin = lin * g.k1k2 + sLid[2 * R + r[2]];
                 lin = lin * g.k1k2 + sLid[3 * R + r[3]];
             }
-            const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+            const unsigned long long slot = g.hashed ? slot_of_bin(lin, g.H, g.H_inv) : lin;
             o0[i] = g.offsets[slot];
             len[i] = g.offsets[slot + 1] - o0[i];
             if (keep_slots) sslot[t] = (uint32_t)slot;

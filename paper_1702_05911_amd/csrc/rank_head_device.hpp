@@ -111,7 +111,7 @@ __device__ __forceinline__ int head_level(const RankArgs& g, HeadLds& S, int64_t
         if (t < T1) {
             const unsigned r1 = ((unsigned)best[r] >> 16) & 0xffffu, r2 = (unsigned)best[r] & 0xffffu;
             const unsigned long long lin = (unsigned long long)S.Aid[r1] * g.k1k2 + S.Bid[r2];
-            const unsigned long long slot = g.hashed ? (lin % g.H) : lin;
+            const unsigned long long slot = g.hashed ? slot_of_bin(lin, g.H, g.H_inv) : lin;
             o0[r] = g.offsets[slot];
             len[r] = g.offsets[slot + 1] - o0[r];
             S.slot[t] = (uint32_t)slot;
