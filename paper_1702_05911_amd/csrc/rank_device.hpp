@@ -38,8 +38,12 @@ __device__ __forceinline__ void for_region(const float* A, int nA, const float* 
                                            int lane, uint32_t bound, F&& f) {
     const int nwaves = (int)blockDim.x / kWave;
     const int rows = min(min(nA, Tn), kRegionSplit);
-    for (int a = wave; a < rows; a += nwaves) {
-        const int cnt = region_row_count(a, nB, Tn);
+    const int wv = __builtin_amdgcn_readfirstlane(wave);
+    // lane i holds the length of row i (and of column i below): one integer division per lane instead of one
+    // per row, which was a fifth of the pass's instructions
+    const int row_len = lane < rows ? region_row_count(lane, nB, Tn) : 0;
+    for (int a = wv; a < rows; a += nwaves) {
+        const int cnt = __builtin_amdgcn_readlane(row_len, a);
         const float da = A[a];
         for (int b = lane; b < cnt; b += kWave) {
             const uint32_t k32 = mono_key(da + B[b]);
@@ -49,8 +53,9 @@ __device__ __forceinline__ void for_region(const float* A, int nA, const float* 
     }
     if (nA > kRegionSplit) {
         const int cols = min(nB, Tn / (kRegionSplit + 1));
-        for (int b = wave; b < cols; b += nwaves) {
-            const int hi = min(nA, Tn / (b + 1));
+        const int col_end = (lane < cols && cols <= kWave) ? min(nA, Tn / (lane + 1)) : 0;
+        for (int b = wv; b < cols; b += nwaves) {
+            const int hi = cols <= kWave ? __builtin_amdgcn_readlane(col_end, b) : min(nA, Tn / (b + 1));
             const float db = B[b];
             for (int a = kRegionSplit + lane; a < hi; a += kWave) {
                 const uint32_t k32 = mono_key(A[a] + db);
