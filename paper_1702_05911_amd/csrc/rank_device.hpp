@@ -421,7 +421,43 @@ __device__ __forceinline__ void rank_query(const RankArgs& g, const RankOffsets&
         if (g.n_tuples && tid == 0) g.n_tuples[q] = (uint32_t)Tn;
 
         // ---- a slot proposed earlier in the order is skipped (hashed indexes only) --------------
-        if (g.hashed) {
+        const int tsize = 2 * next_pow2(Tn);                  // at most half full; fits the keys' memory (2 * cap words)
+        if (g.hashed && (MODE & kRankPlace) != 0 && tsize <= kPlaceBins) {
+            // a table of (slot, first tuple) entries with open addressing in the memory of the histogram and
+            // of the keys, both free by now: a tuple claims the entry of its slot (or finds it claimed for
+            // the same slot), the smallest tuple number of an entry wins, the others' runs get length 0
+            uint32_t* tslot = hist;
+            uint32_t* tfirst = reinterpret_cast<uint32_t*>(keys);
+            const int tshift = 32 - (31 - __clz(tsize));
+            __syncthreads();                                  // every keys[t] has been read
+            for (int e = tid; e < tsize; e += nt) {
+                tslot[e] = 0xffffffffu;                       // no slot has this number: H < 2^32
+                tfirst[e] = 0xffffffffu;
+            }
+            __syncthreads();
+            uint32_t at[kMaxPer];
+#pragma unroll
+            for (int i = 0; i < kMaxPer; ++i) {
+                const int t = t0 + i;
+                at[i] = 0;
+                if (i >= per || t >= Tn) continue;
+                const uint32_t sl = sslot[t];
+                uint32_t h = (sl * 2654435761u) >> tshift;
+                for (;;) {
+                    const uint32_t old = atomicCAS(&tslot[h], 0xffffffffu, sl);
+                    if (old == 0xffffffffu || old == sl) break;
+                    h = (h + 1) & (uint32_t)(tsize - 1);
+                }
+                atomicMin(&tfirst[h], (uint32_t)t);
+                at[i] = h;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < kMaxPer; ++i) {
+                const int t = t0 + i;
+                if (i < per && t < Tn && tfirst[at[i]] != (uint32_t)t) len[i] = 0;   // not the first of its slot
+            }
+        } else if (g.hashed) {
             __syncthreads();                                  // every keys[t] has been read
 #pragma unroll
             for (int i = 0; i < kMaxPer; ++i) {
