@@ -102,15 +102,18 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         // ---- placing by bin -----------------------------------------------------------------------------
         // An upper bound of the Tn-th smallest key: the largest key of any rectangle a < sa, b < sb with
         // sa * sb >= Tn is its corner's (both lists ascend, rounding is monotone), and at least Tn keys are
-        // not above it.  Rectangles sa = 1, 2, 4, .. and sa = nA; the smallest corner bounds the histogram.
+        // not above it.  Lane l tries the rectangles with sa = l + 1 and with sb = l + 1 (lane 63: sa = nA, which
+        // always qualifies because Tn <= nA * nB); the smallest corner bounds the histogram.
         const uint32_t lo_key = mono_key(A[0] + B[0]);
         uint32_t up_key;
         {
-            int sa = lane < 31 ? (1 << min(lane, 30)) : nA;
-            if (lane >= 31 || sa > nA) sa = nA;
-            const int sb = (Tn + sa - 1) / sa;
-            up_key = sb <= nB ? mono_key(A[sa - 1] + B[sb - 1]) : 0xffffffffu;
-            up_key = wave_min_u32(up_key);               // sa = nA always qualifies: Tn <= nA * nB
+            const int s1 = lane == kWave - 1 ? nA : min(lane + 1, nA);
+            const int o1 = (Tn + s1 - 1) / s1;
+            up_key = o1 <= nB ? mono_key(A[s1 - 1] + B[o1 - 1]) : 0xffffffffu;
+            const int s2 = min(lane + 1, nB);
+            const int o2 = (Tn + s2 - 1) / s2;
+            if (o2 <= nA) up_key = min(up_key, mono_key(A[o2 - 1] + B[s2 - 1]));
+            up_key = wave_min_u32(up_key);
         }
         const uint32_t prange = up_key - lo_key;
         const int pwidth = 32 - __clz((int)(prange | 1u));
@@ -147,11 +150,11 @@ __device__ __forceinline__ void rank_pairs(const float* A, int nA, const float* 
         __syncthreads();
         if (misc[5] == 0) {
             const uint32_t bsel = misc[2], nkeys = misc[3] + misc[4];
-            for_region<true>(A, nA, B, nB, Tn, wave, lane, up_key, [&](uint32_t k32, uint32_t a, uint32_t b) {
-                if (k32 > up_key) return;
-                const uint32_t bin = (k32 - lo_key) >> pshift;
-                if (bin > bsel) return;
-                keys[atomicAdd(&hist[bin], 1u)] = ((unsigned long long)k32 << 32) | (a << 16) | b;
+            // the last key of bin bsel bounds this walk more tightly than the first one's bound
+            const uint32_t last_key = min(up_key, lo_key + (((bsel + 1u) << pshift) - 1u));
+            for_region<true>(A, nA, B, nB, Tn, wave, lane, last_key, [&](uint32_t k32, uint32_t a, uint32_t b) {
+                if (k32 > last_key) return;
+                keys[atomicAdd(&hist[(k32 - lo_key) >> pshift], 1u)] = ((unsigned long long)k32 << 32) | (a << 16) | b;
             });
             __syncthreads();
             // hist[b] is now the end of bin b (the start of bin b + 1) for every b <= bsel
