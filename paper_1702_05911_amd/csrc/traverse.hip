@@ -28,7 +28,9 @@ struct TraverseLds {
     size_t off_q, off_a, off_d1, off_qn, off_sel, off_key, total;
 };
 
-__host__ __device__ inline TraverseLds traverse_layout(int D, int P, int k1, int k2, int M, int w) {
+// lists_in_lds: the general level-2 path sorts its lists in LDS; the register paths need no room for them
+// (16 KB at lists of 128 that would cost the large codebooks a resident workgroup)
+__host__ __device__ inline TraverseLds traverse_layout(int D, int P, int k1, int k2, int M, int w, bool lists_in_lds) {
     TraverseLds L;
     L.qs = (D + 4) & ~3;       // rows 16-byte aligned, stride not a multiple of 32 words when D is
     L.k1p = (k1 + 15) & ~15;
@@ -40,13 +42,13 @@ __host__ __device__ inline TraverseLds traverse_layout(int D, int P, int k1, int
     L.off_qn = o;  o += sizeof(float) * kQueryTile * M;
     L.off_sel = o; o += sizeof(int) * kQueryTile * P * w;
     o = (o + 7) & ~size_t(7);
-    L.off_key = o; o += sizeof(unsigned long long) * (kTraverseMaxThreads / kWave) * L.Rpad;
+    L.off_key = o; o += lists_in_lds ? sizeof(unsigned long long) * (kTraverseMaxThreads / kWave) * L.Rpad : 0;
     L.total = o;
     return L;
 }
 
 size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w) {
-    return traverse_layout(D, P, k1, k2, M, w).total;
+    return traverse_layout(D, P, k1, k2, M, w, true).total;      // the larger of the two layouts
 }
 
 // Level-2 lists of the tile's queries, E list entries per lane (R <= 64 * E), from the interleaved
@@ -114,7 +116,7 @@ __device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, 
 template <int E>
 __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4)) void traverse_kernel(TraverseArgs g) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const TraverseLds L = traverse_layout(g.D, g.P, g.k1, g.k2, g.M, g.w);
+    const TraverseLds L = traverse_layout(g.D, g.P, g.k1, g.k2, g.M, g.w, E == 0);
     float* sq = reinterpret_cast<float*>(smem + L.off_q);
     float* sa = reinterpret_cast<float*>(smem + L.off_a);
     float* sd1 = reinterpret_cast<float*>(smem + L.off_d1);
@@ -265,11 +267,12 @@ static int traverse_threads(int P, int64_t nq) {
 
 hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
-    const size_t lds = traverse_lds_bytes(a.D, a.P, a.k1, a.k2, a.M, a.w);
     const unsigned blocks = (unsigned)((a.nq + kQueryTile - 1) / kQueryTile);
     const dim3 grid(blocks), block(traverse_threads(a.P, a.nq));
     const int R = a.w * a.k2;
-    if (a.C2t == nullptr || R > 4 * kWave) hipLaunchKernelGGL(traverse_kernel<0>, grid, block, lds, s, a);
+    const bool general = a.C2t == nullptr || R > 4 * kWave;
+    const size_t lds = traverse_layout(a.D, a.P, a.k1, a.k2, a.M, a.w, general).total;
+    if (general) hipLaunchKernelGGL(traverse_kernel<0>, grid, block, lds, s, a);
     else if (R <= kWave) hipLaunchKernelGGL(traverse_kernel<1>, grid, block, lds, s, a);
     else if (R <= 2 * kWave) hipLaunchKernelGGL(traverse_kernel<2>, grid, block, lds, s, a);
     else hipLaunchKernelGGL(traverse_kernel<4>, grid, block, lds, s, a);
