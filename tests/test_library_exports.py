@@ -54,3 +54,26 @@ def test_offline_driver_holds_no_arithmetic():
     src = inspect.getsource(builder)
     for banned in ("torch.cdist", ".argmin(", ".min(", "@", "bincount", "index_add", "cumsum", "torch.sort", "numpy"):
         assert banned not in src, banned
+
+
+def test_slot_of_a_bin_by_reciprocal_multiplication():
+    """The kernels take a bin number modulo H (Sec. 4: bins are hashed into the pointer array) without a
+    division: r = bin - floor(bin * floor(2^64 / H) / 2^64) * H, then one conditional subtraction.  The same
+    integer arithmetic in Python must give bin % H for every H >= 2 and every 64-bit bin number, the
+    extreme ones included (the quotient estimate is the quotient or one less)."""
+    import random
+    rng = random.Random(7)
+    mask = (1 << 64) - 1
+    hs = [2, 3, 5, 997, 65537, 10_000_019, (1 << 31) - 1, (1 << 32) - 1, 1 << 20, (1 << 32) - 5]
+    hs += [rng.randrange(2, 1 << 32) for _ in range(200)]
+    for H in hs:
+        H_inv = (1 << 64) // H
+        bins = [0, 1, H - 1, H, H + 1, mask, mask - 1, (mask // H) * H, (mask // H) * H - 1, 1 << 36, (1 << 36) - 1]
+        bins += [rng.randrange(0, 1 << 64) for _ in range(200)] + [rng.randrange(0, 1 << 36) for _ in range(200)]
+        for b in bins:
+            q = (b * H_inv) >> 64
+            r = (b - q * H) & mask
+            assert r < 2 * H, (H, b)
+            if r >= H:
+                r -= H
+            assert r == b % H, (H, b)
