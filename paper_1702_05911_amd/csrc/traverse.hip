@@ -54,16 +54,17 @@ size_t traverse_lds_bytes(int D, int P, int k1, int k2, int M, int w) {
 // Level-2 lists of the tile's queries, E list entries per lane (R <= 64 * E), from the interleaved
 // codebook.  The distance is the plain sum of squared differences, dimensions in ascending order.
 template <int E>
-__device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, const float* sq, int qs, const int* ssel) {
+__device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, const float* sq, int qs, const int* ssel,
+                                             int pbase, int np) {
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int nwaves = (int)blockDim.x / kWave;
     const int P = g.P, k1 = g.k1, k2 = g.k2, w = g.w;
     const int dp = g.D / P, R = w * k2, nd4 = dp / 4;
     const float4* C2t = reinterpret_cast<const float4*>(g.C2t);
-    for (int job = wave; job < kQueryTile * P; job += nwaves) {
-        const int q = job / P, p = job - q * P;
+    for (int job = wave; job < kQueryTile * np; job += nwaves) {
+        const int q = job / np, p = pbase + (job - q * np);
         if (q0 + q >= g.nq) continue;                              // uniform per wavefront
-        const float4* yp = reinterpret_cast<const float4*>(sq + q * qs + p * dp);   // 16-byte aligned rows
+        const float4* yp = reinterpret_cast<const float4*>(sq + q * qs + (p - pbase) * dp);   // 16-byte aligned rows
         unsigned long long key[E];
         const float4* row[E];
         uint32_t leaf[E];
@@ -116,7 +117,12 @@ __device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, 
 template <int E>
 __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4)) void traverse_kernel(TraverseArgs g) {
     extern __shared__ __align__(16) unsigned char smem[];
-    const TraverseLds L = traverse_layout(g.D, g.P, g.k1, g.k2, g.M, g.w, E == 0);
+    // A grid with P rows splits every tile by tree part (small batches: see launch_traverse): the workgroup
+    // then stages, ranks and lists only part blockIdx.y; nothing in this kernel crosses parts.
+    const int np = gridDim.y > 1 ? 1 : g.P;                 // parts this workgroup handles ...
+    const int pbase = gridDim.y > 1 ? (int)blockIdx.y : 0;  // ... starting with this one
+    const int Dl = np * (g.D / g.P), dbase = pbase * (g.D / g.P);   // the dimensions it stages
+    const TraverseLds L = traverse_layout(Dl, g.P, g.k1, g.k2, g.M, g.w, E == 0);
     float* sq = reinterpret_cast<float*>(smem + L.off_q);
     float* sa = reinterpret_cast<float*>(smem + L.off_a);
     float* sd1 = reinterpret_cast<float*>(smem + L.off_d1);
@@ -131,21 +137,22 @@ __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4))
     const int D = g.D, P = g.P, k1 = g.k1, k2 = g.k2, M = g.M, w = g.w;
     const int dp = D / P, ds = D / M, per = M / P, R = w * k2;
     const int64_t q0 = (int64_t)blockIdx.x * kQueryTile;
-    if (g.counters && blockIdx.x == 0 && tid == 0) g.counters[0] = g.counters[1] = 0u;   // used by the bin ranking
+    if (g.counters && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) g.counters[0] = g.counters[1] = 0u;   // used by the bin ranking
 
     // ---- stage the query tile in LDS (rows past nq are zero) -------------------------------
-    for (int e = tid; e < kQueryTile * D; e += nthreads) {
-        int q = e / D, d = e - q * D;
+    for (int e = tid; e < kQueryTile * Dl; e += nthreads) {
+        int q = e / Dl, d = e - q * Dl;
         int64_t gq = q0 + q;
-        sq[q * L.qs + d] = (gq < g.nq) ? g.queries[gq * D + d] : 0.0f;
+        sq[q * L.qs + d] = (gq < g.nq) ? g.queries[gq * D + dbase + d] : 0.0f;
     }
     __syncthreads();
-    for (int e = tid; e < kQueryTile * M; e += nthreads) {
-        int q = e / M, m = e - q * M;
-        const float* row = sq + q * L.qs + m * ds;
+    const int Ml = np * per, mbase = pbase * per;           // the sub-parts of those parts
+    for (int e = tid; e < kQueryTile * Ml; e += nthreads) {
+        int q = e / Ml, m = mbase + (e - q * Ml);
+        const float* row = sq + q * L.qs + (m * ds - dbase);
         float s = 0.0f;
         for (int d = 0; d < ds; ++d) s = fmaf(row[d], row[d], s);
-        sqn[e] = s;
+        sqn[q * M + m] = s;
     }
     __syncthreads();
 
@@ -155,11 +162,11 @@ __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4))
     {
         const int ntiles = L.k1p / 16;
         const int row = lane & 15, kq = lane >> 4;
-        for (int job = wave; job < M * ntiles; job += nwaves) {
-            const int m = job / ntiles, nt = job - m * ntiles;
+        for (int job = wave; job < Ml * ntiles; job += nwaves) {
+            const int m = mbase + job / ntiles, nt = job % ntiles;
             const int p = m / per, lo = m * ds - p * dp;
             const int col = nt * 16 + row;            // centroid this lane feeds as B column
-            const float* arow = sq + row * L.qs + m * ds;
+            const float* arow = sq + row * L.qs + (m * ds - dbase);
             const float* brow = g.C1 + ((size_t)p * k1 + (col < k1 ? col : 0)) * dp + lo;
             v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
             // the centroid values of eight k-steps are fetched together, so that their latencies overlap
@@ -194,15 +201,16 @@ __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4))
     __syncthreads();
 
     // ---- per-part distances and the w closest clusters ------------------------------------------
-    for (int e = tid; e < kQueryTile * P * k1; e += nthreads) {
-        const int i = e % k1, qp = e / k1, p = qp % P, q = qp / P;
+    for (int e = tid; e < kQueryTile * np * k1; e += nthreads) {
+        const int i = e % k1, ql = e / k1, p = pbase + ql % np, q = ql / np;
         float s = sa[(q * M + p * per) * k1 + i];
         for (int m = p * per + 1; m < (p + 1) * per; ++m) s += sa[(q * M + m) * k1 + i];
-        sd1[e] = s;
+        sd1[(q * P + p) * k1 + i] = s;
     }
     __syncthreads();
-    for (int e = tid; e < kQueryTile * P * k1; e += nthreads) {
-        const int i = e % k1, qp = e / k1;
+    for (int e = tid; e < kQueryTile * np * k1; e += nthreads) {
+        const int i = e % k1, ql = e / k1;
+        const int qp = (ql / np) * P + pbase + ql % np;
         const float* row = sd1 + qp * k1;
         const unsigned long long me = ((unsigned long long)mono_key(row[i]) << 32) | (unsigned)i;
         int rank = 0;
@@ -222,13 +230,13 @@ __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4))
     if constexpr (E > 0) {
         // children of one cluster interleaved four dimensions at a time (C2t[p][i][d/4][j][4]): the
         // lanes of one cluster read consecutive 16-byte pieces; lists sorted in registers
-        level2_lists<E>(g, q0, sq, L.qs, ssel);
+        level2_lists<E>(g, q0, sq, L.qs, ssel, pbase, np);
         return;
     }
     unsigned long long* mykeys = skey + (size_t)wave * L.Rpad;
-    for (int job = wave; job < kQueryTile * P; job += nwaves) {   // same trip count for every wave
-        const int q = job / P, p = job - q * P;
-        const float* yp = sq + q * L.qs + p * dp;
+    for (int job = wave; job < kQueryTile * np; job += nwaves) {   // same trip count for every wave
+        const int q = job / np, p = pbase + (job - q * np);
+        const float* yp = sq + q * L.qs + (p - pbase) * dp;
         for (int e = lane; e < L.Rpad; e += kWave) {
             unsigned long long key = ~0ull;
             if (e < R) {
@@ -257,21 +265,24 @@ __global__ __launch_bounds__(kTraverseMaxThreads, E == 1 ? 8 : (E == 2 ? 6 : 4))
     }
 }
 
-// One wavefront per four (query, part) lists of the tile when the batch fills the chip; a small batch
-// (at most one tile per compute unit) gets the largest workgroup, so that a wavefront has one or two
-// lists to work through and the call returns sooner.
+// One wavefront per four (query, part) lists of the tile when the batch fills the chip.  A small batch (at
+// most one tile per compute unit) gets the largest workgroup and one workgroup per (tile, tree part), so
+// that more compute units take part, a wavefront has one list to work through and the call returns
+// sooner (1,000 queries of 960 dimensions with four parts: 63 tiles became 252 workgroups).
+static bool traverse_small_batch(int64_t nq) { return nq <= 256 * kQueryTile; }
 static int traverse_threads(int P, int64_t nq) {
-    if (nq <= 256 * kQueryTile) return kTraverseMaxThreads;
+    if (traverse_small_batch(nq)) return kTraverseMaxThreads;
     return P >= 4 ? 1024 : (P == 2 ? 512 : 256);
 }
 
 hipError_t launch_traverse(const TraverseArgs& a, hipStream_t s) {
     if (a.nq <= 0) return hipSuccess;
     const unsigned blocks = (unsigned)((a.nq + kQueryTile - 1) / kQueryTile);
-    const dim3 grid(blocks), block(traverse_threads(a.P, a.nq));
+    const bool by_part = traverse_small_batch(a.nq) && a.P > 1;
+    const dim3 grid(blocks, by_part ? a.P : 1), block(traverse_threads(a.P, a.nq));
     const int R = a.w * a.k2;
     const bool general = a.C2t == nullptr || R > 4 * kWave;
-    const size_t lds = traverse_layout(a.D, a.P, a.k1, a.k2, a.M, a.w, general).total;
+    const size_t lds = traverse_layout(by_part ? a.D / a.P : a.D, a.P, a.k1, a.k2, a.M, a.w, general).total;
     if (general) hipLaunchKernelGGL(traverse_kernel<0>, grid, block, lds, s, a);
     else if (R <= kWave) hipLaunchKernelGGL(traverse_kernel<1>, grid, block, lds, s, a);
     else if (R <= 2 * kWave) hipLaunchKernelGGL(traverse_kernel<2>, grid, block, lds, s, a);
