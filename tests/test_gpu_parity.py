@@ -796,6 +796,8 @@ def test_four_part_index(pqt, tmp_path):
     path = str(tmp_path / "p4h.pqt")
     IO.write_index(path, ixh)
     _stagewise(pqt, ixh, path, Y[:12], 10, 2, 300, 1024)
+    # more tuples than the table for repeated slots holds: they are found by sorting (slot, tuple) keys
+    _stagewise(pqt, ixh, path, Y[:6], 10, 3, 2500, 4000)
 
 
 def test_four_part_long_lists(pqt, tmp_path):
