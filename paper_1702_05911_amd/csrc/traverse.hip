@@ -79,20 +79,56 @@ __device__ __forceinline__ void level2_lists(const TraverseArgs& g, int64_t q0, 
             row[r] = C2t + ((size_t)p * k1 + i) * nd4 * k2 + j;
             acc[r] = 0.0f;
         }
-#pragma unroll 4
-        for (int d4 = 0; d4 < nd4; ++d4) {
-            const float4 y = yp[d4];
+        if constexpr (E >= 2) {
+            // the pieces of four steps are requested together and are operands of one empty statement, which
+            // keeps the compiler's scheduler from moving every load down to its use: left alone it waited for
+            // each 16-byte piece before it asked for the next, one request in flight per wavefront
+            for (int d0 = 0; d0 < nd4; d0 += 4) {
+                v4f c[E][4];
 #pragma unroll
-            for (int r = 0; r < E; ++r) {
-                const float4 c = row[r][(size_t)d4 * k2];
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int r = 0; r < E; ++r)
+                        c[r][u] = *reinterpret_cast<const v4f*>(row[r] + (size_t)(d0 + u < nd4 ? d0 + u : nd4 - 1) * k2);
+                if constexpr (E == 2)
+                    asm volatile("" : "+v"(c[0][0]), "+v"(c[0][1]), "+v"(c[0][2]), "+v"(c[0][3]),
+                                      "+v"(c[1][0]), "+v"(c[1][1]), "+v"(c[1][2]), "+v"(c[1][3]));
+                else
+                    asm volatile("" : "+v"(c[0][0]), "+v"(c[0][1]), "+v"(c[0][2]), "+v"(c[0][3]),
+                                      "+v"(c[1][0]), "+v"(c[1][1]), "+v"(c[1][2]), "+v"(c[1][3]),
+                                      "+v"(c[2][0]), "+v"(c[2][1]), "+v"(c[2][2]), "+v"(c[2][3]),
+                                      "+v"(c[3][0]), "+v"(c[3][1]), "+v"(c[3][2]), "+v"(c[3][3]));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (d0 + u < nd4) {                                // uniform
+                        const float4 y = yp[d0 + u];
+#pragma unroll
+                        for (int r = 0; r < E; ++r) {
+                            float diff = y.x - c[r][u][0];
+                            acc[r] = fmaf(diff, diff, acc[r]);
+                            diff = y.y - c[r][u][1];
+                            acc[r] = fmaf(diff, diff, acc[r]);
+                            diff = y.z - c[r][u][2];
+                            acc[r] = fmaf(diff, diff, acc[r]);
+                            diff = y.w - c[r][u][3];
+                            acc[r] = fmaf(diff, diff, acc[r]);
+                        }
+                    }
+                }
+            }
+        } else {
+#pragma unroll 4
+            for (int d4 = 0; d4 < nd4; ++d4) {
+                const float4 y = yp[d4];
+                const float4 c = row[0][(size_t)d4 * k2];
                 float diff = y.x - c.x;
-                acc[r] = fmaf(diff, diff, acc[r]);
+                acc[0] = fmaf(diff, diff, acc[0]);
                 diff = y.y - c.y;
-                acc[r] = fmaf(diff, diff, acc[r]);
+                acc[0] = fmaf(diff, diff, acc[0]);
                 diff = y.z - c.z;
-                acc[r] = fmaf(diff, diff, acc[r]);
+                acc[0] = fmaf(diff, diff, acc[0]);
                 diff = y.w - c.w;
-                acc[r] = fmaf(diff, diff, acc[r]);
+                acc[0] = fmaf(diff, diff, acc[0]);
             }
         }
 #pragma unroll
