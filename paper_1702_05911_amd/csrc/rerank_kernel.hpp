@@ -505,6 +505,9 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     // ---- the k smallest (score, id): (key, position) of a superset of the answer -> surv ---------------
     const int kk = k < nc ? k : nc;           // results that exist
     int nsurv;
+    bool by_bin = false;                       // the survivors can be placed by their histogram bin (see below)
+    uint32_t lo_key = 0;
+    int shift = 0;
     if (nc <= L.scap) {                        // few candidates: order all of them
 #pragma unroll
         for (int u = 0; u < kKeysPerThread; ++u) {
@@ -513,23 +516,32 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
         }
         nsurv = nc;
     } else {
-        const uint32_t lo_key = misc[kMin];
+        lo_key = misc[kMin];
         const uint32_t range = misc[kMax] - lo_key;
         const int width = 32 - __clz((int)(range | 1u));           // bits needed for range
-        const int shift = width > kHistBits ? width - kHistBits : 0;   // (key - lo_key) >> shift < 1024
+        shift = width > kHistBits ? width - kHistBits : 0;          // (key - lo_key) >> shift < 1024
 #pragma unroll
         for (int u = 0; u < kKeysPerThread; ++u) {
             if (u * kWave >= chunk) break;                             // same for the whole workgroup
             if (pos0 + u * kWave < pend) atomicAdd(&hist[(key[u] - lo_key) >> shift], 1u);
         }
         __syncthreads();
-        // the first wavefront finds the bin bsel with count(< bsel) < kk <= count(<= bsel)
-        if (tid < kWave) {
-            uint32_t bsel, below, inbin;
-            hist_locate(hist, (uint32_t)kk, lane, bsel, below, inbin);
-            if (tid == 0) {
-                misc[kSel] = bsel;
-                misc[kSelCount] = below + inbin;
+        // counts -> first positions, in place (a prefix sum by the whole workgroup); the thread that owns the
+        // bin bsel with count(< bsel) < kk <= count(<= bsel) notes it
+        {
+            const int bpt = kHistSize / nt;                        // 4, 2 or 1 bins per thread
+            uint32_t sum = 0;
+            for (int j = 0; j < bpt; ++j) sum += hist[tid * bpt + j];
+            uint32_t total;
+            uint32_t c = block_exclusive_sum(sum, part, total);
+            for (int j = 0; j < bpt; ++j) {
+                const uint32_t cnt = hist[tid * bpt + j];
+                hist[tid * bpt + j] = c;
+                if (c < (uint32_t)kk && (uint32_t)kk <= c + cnt) {
+                    misc[kSel] = (uint32_t)(tid * bpt + j);
+                    misc[kSelCount] = c + cnt;
+                }
+                c += cnt;
             }
         }
         __syncthreads();
@@ -539,6 +551,7 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
             // keys of the bins <= bsel are the keys <= thr
             const unsigned long long thr64 = (unsigned long long)lo_key + (((unsigned long long)bsel + 1ull) << shift) - 1ull;
             const uint32_t thr = thr64 > 0xffffffffull ? 0xffffffffu : (uint32_t)thr64;
+            by_bin = thr != 0xffffffffu && count_le <= (uint32_t)nt;
             if (thr != 0xffffffffu) {
                 // key slots without a candidate hold 0xffffffff > thr.  A wavefront counts its keys <= thr,
                 // reserves room for them with one atomic, then writes them: no wait for LDS per window
@@ -618,7 +631,39 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     }
     __syncthreads();
 
-    // ---- fetch the survivors' ids: 64-bit keys (score bits, id) --------------------------------------------
+    // ---- usual case: the survivors are placed by their histogram bin, no sort -----------------------------
+    // hist[] holds the first position of every bin among the sorted keys.  A thread takes one survivor,
+    // fetches its id, and drops the (score bits, id) key into its bin's range with one LDS atomic; then every
+    // key counts the smaller keys of its own bin (one to four entries) and that is its place in the output.
+    if (by_bin) {
+        const bool have = tid < nsurv;
+        unsigned long long mine = ~0ull;
+        uint32_t bin = 0;
+        if (have) {
+            const unsigned long long kp = surv[tid];
+            mine = (kp & 0xffffffff00000000ull) | g.ids[source_of((uint32_t)kp, steps, R)];
+            bin = ((uint32_t)(kp >> 32) - lo_key) >> shift;
+        }
+        __syncthreads();                       // every surv[] entry has been read
+        if (have) surv[atomicAdd(&hist[bin], 1u)] = mine;
+        __syncthreads();                       // hist[b] is now the end of bin b, the start of bin b + 1
+        if (have) {
+            const uint32_t first = bin ? hist[bin - 1] : 0u, end = hist[bin];
+            uint32_t r = first;
+            for (uint32_t x = first; x < end; ++x) r += surv[x] < mine ? 1u : 0u;
+            if (r < (uint32_t)kk) {
+                g.out_ids[(size_t)q * k + r] = (int64_t)(uint32_t)mine;
+                g.out_dists[(size_t)q * k + r] = mono_inv((uint32_t)(mine >> 32));
+            }
+        }
+        for (int e = kk + tid; e < k; e += nt) {
+            g.out_ids[(size_t)q * k + e] = (int64_t)-1;
+            g.out_dists[(size_t)q * k + e] = __builtin_inff();
+        }
+        return;
+    }
+
+    // ---- otherwise: fetch the survivors' ids: 64-bit keys (score bits, id) ------------------------------
     // (one round of loads for the whole list: the thread that holds a surviving key does not fetch the id
     // itself, or a wavefront would wait for memory once per key slot)
     for (int e = tid; e < nsurv; e += nt) {
