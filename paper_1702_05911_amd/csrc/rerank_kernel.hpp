@@ -383,9 +383,13 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     const int lut_c = tid & 255;
     const int lut_m0 = __builtin_amdgcn_readfirstlane(tid >> 8), lut_ms = nt >> 8;
     const int Mlut = MW > 0 ? 4 * MW : (MW < -1 ? -2 * MW : M);
-    CodeEntry ent[4];
+    // entries a thread fetches per round: with codes of up to eight bytes all of a thread's entries at once, so
+    // that no load is waited for inside the table phase (256 threads had two rounds of four)
+    constexpr int kEnt = (MW > 0 && MW <= 2) ? 8 : 4;
+    constexpr bool kOneRound = MW > 0 && 4 * MW <= kEnt;
+    CodeEntry ent[kEnt];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kEnt; ++u) {
         const int m = lut_m0 + u * lut_ms;
         ent[u] = g.table[(m < Mlut ? m : 0) * 256 + lut_c];
     }
@@ -416,35 +420,45 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     __syncthreads();
 
     // ---- LUT of Eq. 9 summands ------------------------------------------------------------------------
-    for (int mb = lut_m0; mb < Mlut; mb += 4 * lut_ms) {
-        CodeEntry cur_ent[4];
+    auto table_entry = [&](int m, const CodeEntry& ce) {
+        const int e = m * 256 + lut_c;
+        const float* sam = sa + m * k1;
+        const float b2 = sam[ce.ij & 0xffu];
+        const float a2 = sam[(ce.ij >> 8) & 0xffu];
+        if (MW < 0) {
+            // entry = centroid pair number; its kc field holds c^2
+            if (lut_c < (1 << g.pair_shift))
+                reinterpret_cast<float4*>(lut)[(m << g.pair_shift) + lut_c] = make_float4(b2, a2 - b2, ce.kc, 0.0f);
+            return;
+        }
+        // Eq. 9 rearranged: b^2 + lam (a^2 - b^2) + (lam^2 - lam) c^2, the last term folded per code value
+        const float v = fmaf(ce.lam, a2 - b2, b2) + ce.kc;
+        lut[e] = v;
+        if (TAPS && g.lut) g.lut[(size_t)q * nlut + e] = v;
+    };
+    if constexpr (kOneRound) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) cur_ent[u] = ent[u];
-        if (mb + 4 * lut_ms < Mlut) {          // the next round's entries are fetched while this one is worked on
+        for (int u = 0; u < kEnt; ++u) {
+            const int m = lut_m0 + u * lut_ms;
+            if (m < Mlut) table_entry(m, ent[u]);
+        }
+    } else {
+        for (int mb = lut_m0; mb < Mlut; mb += 4 * lut_ms) {
+            CodeEntry cur_ent[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cur_ent[u] = ent[u];
+            if (mb + 4 * lut_ms < Mlut) {          // the next round's entries are fetched while this one is worked on
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int m = mb + (4 + u) * lut_ms;
+                    ent[u] = g.table[(m < Mlut ? m : 0) * 256 + lut_c];
+                }
+            }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int m = mb + (4 + u) * lut_ms;
-                ent[u] = g.table[(m < Mlut ? m : 0) * 256 + lut_c];
+                const int m = mb + u * lut_ms;
+                if (m < Mlut) table_entry(m, cur_ent[u]);      // (no early exit: the loop must unroll in full)
             }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int m = mb + u * lut_ms;
-            if (m >= Mlut) continue;              // (no early exit: the loop must unroll in full)
-            const int e = m * 256 + lut_c;
-            const float* sam = sa + m * k1;
-            const float b2 = sam[cur_ent[u].ij & 0xffu];
-            const float a2 = sam[(cur_ent[u].ij >> 8) & 0xffu];
-            if (MW < 0) {
-                // entry = centroid pair number; its kc field holds c^2
-                if (lut_c < (1 << g.pair_shift))
-                    reinterpret_cast<float4*>(lut)[(m << g.pair_shift) + lut_c] = make_float4(b2, a2 - b2, cur_ent[u].kc, 0.0f);
-                continue;
-            }
-            // Eq. 9 rearranged: b^2 + lam (a^2 - b^2) + (lam^2 - lam) c^2, the last term folded per code value
-            const float v = fmaf(cur_ent[u].lam, a2 - b2, b2) + cur_ent[u].kc;
-            lut[e] = v;
-            if (TAPS && g.lut) g.lut[(size_t)q * nlut + e] = v;
         }
     }
     __syncthreads();
