@@ -324,7 +324,7 @@ __device__ __forceinline__ void score_batch(const RerankArgs& g, int64_t q, int 
 // FUSED: a query whose meta.x is kMetaTodo (the ranking head pass could not finish it) is first
 // ranked in full by this workgroup.
 template <int MW, bool TAPS, bool FUSED>
-__global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g, RerankLds L, RankArgs rk, RankOffsets RL) {
+__global__ __launch_bounds__(1024, TAPS ? 1 : ((MW >= 8 || MW <= -8) ? 4 : 8)) void rerank_kernel(RerankArgs g, RerankLds L, RankArgs rk, RankOffsets RL) {
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned long long* surv = reinterpret_cast<unsigned long long*>(smem + L.surv);
     float* lut = reinterpret_cast<float*>(smem);                 // L.lut == 0
@@ -473,8 +473,9 @@ __global__ __launch_bounds__(1024, TAPS ? 1 : 8) void rerank_kernel(RerankArgs g
     uint32_t kmin = 0xffffffffu, kmax = 0u;
     if (nc > 0) {
         const int wbase = __builtin_amdgcn_readfirstlane(pos0 - lane);    // the same for a wavefront
-        // eight positions in flight per thread; four when a code has four or more words (registers)
-        constexpr int UB = (MW >= 4 || MW <= -4) ? 4 : 8;
+        // eight positions in flight per thread; four when a code has four or more words or holds (pair, lambda)
+        // tuples, whose scoring needs the registers
+        constexpr int UB = (MW >= 4 || MW <= -2) ? 4 : 8;
         static_assert(kKeysPerThread % 4 == 0, "batches of four or eight");
         WaveRuns wr;
         RunCursor cur;                         // positions of a thread only grow
